@@ -1,0 +1,212 @@
+"""Python face of the CPU oracle (``ctkvr_oracle.c``) -- TEST INFRASTRUCTURE.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this package.  It never imports the GPU package and the
+GPU package never imports it.
+
+The functions below only marshal numpy arrays into the C routines; the
+arithmetic of the method lives in ``ctkvr_oracle.c`` where each routine cites
+the lines of the paper's Algorithm 1 / Algorithm 2 it follows.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ctkvr_oracle.c")
+_LIB = os.path.join(_HERE, "libctkvr_oracle.so")
+
+CFLAGS = ["-O2", "-mfma", "-mavx2", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra"]
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (contraction off: every fused multiply-add
+    in it is an explicit ``fmaf``/``fma``)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", *CFLAGS, "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        fp = ctypes.POINTER(ctypes.c_float)
+        dp = ctypes.POINTER(ctypes.c_double)
+        ip = ctypes.POINTER(ctypes.c_int32)
+        ci = ctypes.c_int
+        L.ctkvr_oracle_dot128.restype = ctypes.c_float
+        L.ctkvr_oracle_dot128.argtypes = [fp, fp]
+        L.ctkvr_oracle_inv_norm.restype = ctypes.c_float
+        L.ctkvr_oracle_inv_norm.argtypes = [fp]
+        L.ctkvr_oracle_exp.restype = ctypes.c_float
+        L.ctkvr_oracle_exp.argtypes = [ctypes.c_float]
+        L.ctkvr_oracle_log_fixed.restype = ctypes.c_double
+        L.ctkvr_oracle_log_fixed.argtypes = [ctypes.c_uint64]
+        L.ctkvr_oracle_build_lists.restype = None
+        L.ctkvr_oracle_build_lists.argtypes = [fp, fp, ci, ci, ci, ci, ci, ctypes.c_float, ip, ci, ip, fp]
+        L.ctkvr_oracle_inv_norms.restype = None
+        L.ctkvr_oracle_inv_norms.argtypes = [fp, ci, fp]
+        L.ctkvr_oracle_recall.restype = None
+        L.ctkvr_oracle_recall.argtypes = [fp, fp, ci, ci, ci, ci, fp, ip]
+        L.ctkvr_oracle_rerank_attend.restype = None
+        L.ctkvr_oracle_rerank_attend.argtypes = [fp, fp, fp, ip, ip, ci, ci, ci, ci, ci, ci, ci, ctypes.c_float,
+                                                 ip, ip, fp, ip, dp, dp]
+        L.ctkvr_oracle_num_threads.restype = ci
+        L.ctkvr_oracle_set_threads.argtypes = [ci]
+        _lib = L
+    return _lib
+
+
+def _f(a: np.ndarray):
+    assert a.dtype == np.float32 and a.flags.c_contiguous
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def _d(a: np.ndarray):
+    assert a.dtype == np.float64 and a.flags.c_contiguous
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _i(a: Optional[np.ndarray]):
+    if a is None:
+        return None
+    assert a.dtype == np.int32 and a.flags.c_contiguous
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def default_scale(d: int = 128) -> np.float32:
+    """1/sqrt(d) rounded once to fp32."""
+    return np.float32(1.0 / np.sqrt(np.float64(d)))
+
+
+# ---- primitives (exposed so the tests can pin them) ------------------------ #
+def dot128(a: np.ndarray, b: np.ndarray) -> np.float32:
+    a = np.ascontiguousarray(a, np.float32)
+    b = np.ascontiguousarray(b, np.float32)
+    assert a.shape == (128,) and b.shape == (128,)
+    return np.float32(lib().ctkvr_oracle_dot128(_f(a), _f(b)))
+
+
+def exp_c(x: float) -> np.float32:
+    return np.float32(lib().ctkvr_oracle_exp(ctypes.c_float(x)))
+
+
+def log_fixed(S: int) -> float:
+    return float(lib().ctkvr_oracle_log_fixed(ctypes.c_uint64(S)))
+
+
+def inv_norms(X: np.ndarray) -> np.ndarray:
+    X = np.ascontiguousarray(X, np.float32)
+    assert X.shape[-1] == 128
+    out = np.empty(X.shape[:-1], np.float32)
+    lib().ctkvr_oracle_inv_norms(_f(X), int(np.prod(X.shape[:-1])), _f(out))
+    return out
+
+
+# ---- Algorithm 1 ----------------------------------------------------------- #
+def centroids_last_c(q_tail: np.ndarray, C: int) -> np.ndarray:
+    """Algorithm 1 line 1: the last C prefill queries, as [h][C][d].
+    ``q_tail`` is [n_tail >= C][h][d] ending at the last prompt position."""
+    assert q_tail.shape[0] >= C
+    return np.ascontiguousarray(np.transpose(q_tail[q_tail.shape[0] - C:], (1, 0, 2)), np.float32)
+
+
+def build_lists(K: np.ndarray, Qc: np.ndarray, rho: int, scale: Optional[float] = None,
+                pairs: Optional[np.ndarray] = None, return_keys: bool = False):
+    """Algorithm 1 lines 2-4.  K [g][s][d], Qc [h][C][d] -> lists int32.
+    With ``pairs`` ([n][2] of (kv head, centroid)) only those lists are built,
+    returned as [n][rho]; otherwise [g][C][rho]."""
+    K = np.ascontiguousarray(K, np.float32)
+    Qc = np.ascontiguousarray(Qc, np.float32)
+    g, s, d = K.shape
+    h, C, _ = Qc.shape
+    assert d == 128 and h % g == 0 and 1 <= rho <= s
+    scale = default_scale(d) if scale is None else np.float32(scale)
+    if pairs is not None:
+        pairs = np.ascontiguousarray(pairs, np.int32).reshape(-1, 2)
+        n = pairs.shape[0]
+        shape = (n, rho)
+    else:
+        n = g * C
+        shape = (g, C, rho)
+    lists = np.empty(shape, np.int32)
+    keys = np.empty((n, s), np.float32) if return_keys else None
+    lib().ctkvr_oracle_build_lists(_f(K), _f(Qc), h, g, s, C, rho, ctypes.c_float(scale), _i(pairs), n,
+                                   _i(lists), _f(keys) if keys is not None else None)
+    return (lists, keys) if return_keys else lists
+
+
+# ---- Algorithm 2 ----------------------------------------------------------- #
+def recall(q: np.ndarray, Qc: np.ndarray, g: int, n_probe: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Algorithm 2 lines 1-3.  q [h][d], Qc [h][C][d] -> (Cos_kv [g][C], I^Q [g][C'] ascending)."""
+    q = np.ascontiguousarray(q, np.float32)
+    Qc = np.ascontiguousarray(Qc, np.float32)
+    h, C, d = Qc.shape
+    assert q.shape == (h, d) and d == 128 and 1 <= n_probe <= C
+    cos_kv = np.empty((g, C), np.float32)
+    probe = np.empty((g, n_probe), np.int32)
+    lib().ctkvr_oracle_recall(_f(q), _f(Qc), h, g, C, n_probe, _f(cos_kv), _i(probe))
+    return cos_kv, probe
+
+
+@dataclass
+class DecodeResult:
+    cos_kv: np.ndarray      # [g][C] fp32
+    probe: np.ndarray       # [g][C'] int32 ascending
+    cand: list              # per kv head: int32 array of the L recalled key ids, ascending
+    ncand: np.ndarray       # [g] int32
+    rerank_key: list        # per kv head: fp32 [L] max-over-group log-softmax over the recalled set
+    sel: np.ndarray         # [g][top_k] int32 ascending, -1 padded
+    out: np.ndarray         # [h][d] fp64
+    lse: np.ndarray         # [h] fp64
+
+
+def rerank_attend(q, K, V, lists, probe, top_k, scale=None):
+    """Algorithm 2 lines 4-9 given the probed centroid ids."""
+    q = np.ascontiguousarray(q, np.float32)
+    K = np.ascontiguousarray(K, np.float32)
+    V = np.ascontiguousarray(V, np.float32)
+    lists = np.ascontiguousarray(lists, np.int32)
+    probe = np.ascontiguousarray(probe, np.int32)
+    g, s, d = K.shape
+    h = q.shape[0]
+    _, C, rho = lists.shape
+    n_probe = probe.shape[1]
+    scale = default_scale(d) if scale is None else np.float32(scale)
+    Lmax = min(s, n_probe * rho)
+    cand = np.full((g, Lmax), -1, np.int32)
+    ncand = np.zeros(g, np.int32)
+    rkey = np.zeros((g, Lmax), np.float32)
+    sel = np.empty((g, top_k), np.int32)
+    out = np.empty((h, d), np.float64)
+    lse = np.empty(h, np.float64)
+    lib().ctkvr_oracle_rerank_attend(_f(q), _f(K), _f(V), _i(lists), _i(probe), h, g, s, C, rho, n_probe, top_k,
+                                     ctypes.c_float(scale), _i(cand), _i(ncand), _f(rkey), _i(sel), _d(out), _d(lse))
+    return cand, ncand, rkey, sel, out, lse
+
+
+def decode_step(q, K, V, Qc, lists, n_probe, top_k, scale=None) -> DecodeResult:
+    """Algorithm 2 lines 1-9 for one sequence and one decode query."""
+    g = K.shape[0]
+    cos_kv, probe = recall(q, Qc, g, n_probe)
+    cand, ncand, rkey, sel, out, lse = rerank_attend(q, K, V, lists, probe, top_k, scale)
+    return DecodeResult(cos_kv, probe, [cand[i, :ncand[i]].copy() for i in range(g)], ncand,
+                        [rkey[i, :ncand[i]].copy() for i in range(g)], sel, out, lse)
+
+
+def num_threads() -> int:
+    return int(lib().ctkvr_oracle_num_threads())
+
+
+def set_threads(n: int) -> None:
+    lib().ctkvr_oracle_set_threads(int(n))
