@@ -1,0 +1,184 @@
+/*
+ * ctkvr.h -- C ABI of the MI355X (gfx950) implementation of CTkvr's data-parallel
+ * hot path: the query-centroid inverted file built at prefill (Algorithm 1,
+ * lines 1-4 of the paper) and the per-decode-step centroid-then-token retrieval
+ * followed by sparse attention (Algorithm 2, lines 1-9).
+ *
+ * Notation (the paper's): b batch, h query heads, g KV heads, G = h/g, d head
+ * dimension, s context length, C query centroids per head, C' probed centroids
+ * (n_probe), rho keys per inverted list (list_len), rho' sparsity budget (top_k).
+ * Query heads i*G .. (i+1)*G-1 share KV head i (Section 3.1.1, footnote on
+ * grouped-query attention).
+ *
+ * Conventions
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller unless the
+ *     comment says HOST.  The library never frees caller memory and keeps no
+ *     reference to it after a call returns, except where stated.
+ *   - Work is enqueued on the HIP stream passed as `hip_stream` (a hipStream_t
+ *     cast to void*; NULL = the default stream).  ctkvr_decode_step does not
+ *     synchronise and does not allocate.
+ *   - Functions return CTKVR_OK (0) or a negative ctkvr_status; nothing is thrown
+ *     across the boundary.  ctkvr_last_error() gives a thread-local message for
+ *     the last non-OK return.  Argument errors are detected on the host before
+ *     anything is launched.
+ *   - The KV cache is paged: k_pages / v_pages are
+ *     [num_pages][g][page_size][d] elements of `dtype`; token t of sequence i
+ *     lives in page block_table[i*max_pages + t/page_size], slot t%page_size.
+ *   - head_dim must be 128 and G one of 1, 2, 4, 8, else CTKVR_EUNSUPPORTED.
+ *   - Selections break ties towards the lowest id and are reported in ascending
+ *     id order.
+ */
+#ifndef CTKVR_H
+#define CTKVR_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ctkvr_index ctkvr_index;   /* opaque: centroids, their inverse norms, inverted lists, workspace */
+
+typedef enum {
+    CTKVR_OK = 0,
+    CTKVR_EINVAL = -1,        /* bad argument (null pointer, C' > C, rho > s, h % g != 0, ...) */
+    CTKVR_ENOMEM = -2,        /* device or host allocation failed */
+    CTKVR_EHIP = -3,          /* a HIP runtime call failed */
+    CTKVR_EUNSUPPORTED = -4   /* valid in the paper, not supported by this build (head_dim != 128, ...) */
+} ctkvr_status;
+
+typedef enum { CTKVR_F32 = 0, CTKVR_BF16 = 1 } ctkvr_dtype;
+
+typedef enum {
+    CTKVR_CENTROID_LAST_C = 0,   /* Algorithm 1 line 1: the last C prompt queries */
+    CTKVR_CENTROID_KMEANS = 1    /* Lloyd iterations over the prompt queries replace line 1 only */
+} ctkvr_centroid_mode;
+
+typedef enum {
+    CTKVR_BUILD_EXACT = 0,   /* list scores in the fixed fp32 arithmetic of the decode path (bit-reproducible) */
+    CTKVR_BUILD_MFMA = 1     /* list scores on the matrix cores (bf16 inputs only); lists may differ from
+                                EXACT only for keys whose score ties the rho-th within rounding */
+} ctkvr_build_algo;
+
+typedef struct {
+    int32_t batch;           /* b */
+    int32_t n_q_heads;       /* h */
+    int32_t n_kv_heads;      /* g */
+    int32_t head_dim;        /* d, must be 128 */
+    int32_t page_size;       /* tokens per KV page (16 in the benchmark workloads) */
+    int32_t dtype;           /* ctkvr_dtype of q, K, V and the centroid table */
+    int32_t n_centroids;     /* C; 0 => per sequence C_i = ctx_len_i / centroid_div */
+    int32_t centroid_div;    /* used when n_centroids == 0 */
+    int32_t list_len;        /* rho  (Algorithm 1 line 4) */
+    int32_t n_probe;         /* C'   (Algorithm 2 line 3) */
+    int32_t top_k;           /* rho' (Algorithm 2 line 6) */
+    float   sm_scale;        /* softmax scale applied to q.k; 0 => 1/sqrt(head_dim) */
+    int32_t centroid_mode;   /* ctkvr_centroid_mode */
+    int32_t kmeans_iters;    /* Lloyd iterations when centroid_mode == KMEANS */
+    int32_t build_algo;      /* ctkvr_build_algo */
+    int32_t reserved;
+} ctkvr_params;
+
+/*
+ * Index construction at prefill (Algorithm 1, lines 1-4).
+ *   q_prefill   post-RoPE prompt queries, [total_rows][h][d] of `dtype`, sequences
+ *               concatenated; cu_seqlens (HOST, batch+1 entries) gives each
+ *               sequence's row range.  With q_is_tail = 1 a sequence contributes
+ *               only the queries of its last C_i prompt positions (all LAST_C needs);
+ *               with q_is_tail = 0 it contributes all ctx_len_i of them.
+ *   k_pages, block_table, max_pages   the paged key cache (see above).
+ *   ctx_lens    HOST, [batch]: s of every sequence.  The index is built over keys
+ *               0 .. s-1 and stays valid for decode steps over that frozen prefix.
+ *   init_pos    KMEANS only, DEVICE int32 [batch][g][C]: prompt positions whose
+ *               queries seed the centres (e.g. from k-means++ run by the caller).
+ * For every sequence, KV head and centroid j the list holds the rho keys with the
+ * largest max over the group's query heads of softmax_t(c_{h,j} . k_t * sm_scale)
+ * taken over all s keys (lines 2-4), ascending.
+ * On success *out_index owns device memory until ctkvr_free.  The call
+ * synchronises the stream before returning.
+ * Errors: EINVAL for null/inconsistent arguments (C_i < n_probe, rho > s_i, ...);
+ * EUNSUPPORTED for head_dim != 128, G not in {1,2,4,8}, MFMA build with f32 data.
+ */
+int ctkvr_build_index(const ctkvr_params *p, const void *q_prefill, const int32_t *cu_seqlens, int32_t q_is_tail,
+                      const void *k_pages, const int32_t *block_table, int32_t max_pages, const int32_t *ctx_lens,
+                      const int32_t *init_pos, void *hip_stream, ctkvr_index **out_index);
+
+/*
+ * Wrap an index built elsewhere (Algorithm 1's outputs) so that decode steps can
+ * run on it.  All pointers HOST: centroids [batch][h][C_max][d] of `dtype`
+ * (C_max = max_i C_i; rows j >= C_i unused), lists int32 [batch][g][C_max][rho]
+ * ascending key ids, ctx_lens [batch].  The data is copied; inverse centroid
+ * norms are recomputed on the device.
+ */
+int ctkvr_index_load(const ctkvr_params *p, const int32_t *ctx_lens, const void *centroids, const int32_t *lists,
+                     void *hip_stream, ctkvr_index **out_index);
+
+/*
+ * One decode step of retrieval + sparse attention for every sequence of the
+ * batch (Algorithm 2, lines 1-9):
+ *   lines 1-3  cosine of q_h to every centroid of head h, max over the group,
+ *              top-C' centroids per KV head;
+ *   line  4    union of their lists, deduplicated -> L recalled key ids;
+ *   lines 5-6  max over the group of softmax(q . K^Recall * sm_scale) over the
+ *              recalled keys, top-rho' key ids;
+ *   lines 7-9  softmax(q . K^sparse * sm_scale) V^sparse per query head.
+ *   q          [batch][h][d] post-RoPE, `dtype`.
+ *   out        fp32 [batch][h][d].
+ * Optional outputs (NULL to skip):
+ *   out_lse    fp32 [batch][h]: natural-log sum of exp of the scaled logits over
+ *              the selected keys (lets a caller merge a resident window later);
+ *   out_sel    int32 [batch][g][rho'] selected key ids ascending, -1 padded when L < rho';
+ *   out_ncand  int32 [batch][g]: L;
+ *   out_probe  int32 [batch][g][C'] probed centroid ids ascending.
+ * The KV cache must hold the same first ctx_len_i keys the index was built on.
+ * Asynchronous on hip_stream; uses the index's workspace, so steps on one index
+ * must not overlap.  Errors: EINVAL (null required pointer, max_pages too small).
+ */
+int ctkvr_decode_step(ctkvr_index *idx, const void *q, const void *k_pages, const void *v_pages,
+                      const int32_t *block_table, int32_t max_pages, float *out, float *out_lse, int32_t *out_sel,
+                      int32_t *out_ncand, int32_t *out_probe, void *hip_stream);
+
+/* Release an index (NULL is allowed).  Synchronises the device first. */
+void ctkvr_free(ctkvr_index *idx);
+
+/* Thread-local description of the last non-OK return of this library. */
+const char *ctkvr_last_error(void);
+
+/* ---- inspection (tests, tooling); each synchronises ----------------------- */
+typedef struct {
+    int32_t batch, n_q_heads, n_kv_heads, head_dim, dtype;
+    int32_t c_max;           /* centroid rows allocated per head */
+    int32_t list_len, n_probe, top_k;
+    int32_t l_stride;        /* candidate slots per (sequence, KV head): max_i min(s_i, C' * rho) */
+    int64_t index_bytes;     /* bytes of the inverted lists: b * g * C_max * rho * 4 */
+    int64_t device_bytes;    /* everything the index holds on the device */
+} ctkvr_index_info_t;
+
+int ctkvr_index_info(const ctkvr_index *idx, ctkvr_index_info_t *out);
+/* Copy out the inverted lists, int32 [batch][g][C_max][rho], to HOST memory. */
+int ctkvr_index_lists(const ctkvr_index *idx, int32_t *dst_host);
+/* Copy out the centroid table, [batch][h][C_max][d] of `dtype`, to HOST memory. */
+int ctkvr_index_centroids(const ctkvr_index *idx, void *dst_host);
+/* Recalled key ids of the last decode step, int32 [batch][g][l_stride] (first L valid), to HOST memory. */
+int ctkvr_index_last_candidates(const ctkvr_index *idx, int32_t *dst_host);
+
+/* ---- per-kernel timing (measurement aid) ----------------------------------- */
+/* The decode step runs CTKVR_N_STAGES kernels in this order:
+ * 0 centroid cosine, 1 probe select + list gather/dedup, 2 key scoring over the
+ * recalled ids, 3 softmax denominators, 4 rerank select, 5 sparse attention,
+ * 6 merge of the attention splits. */
+#define CTKVR_N_STAGES 7
+/* After this call every decode step on `idx` records a HIP event before its first
+ * kernel and after each kernel, for up to max_steps steps (0 disables and frees
+ * the events).  Recording adds work to the stream: use it for the breakdown, not
+ * for the headline step time. */
+int ctkvr_profile_enable(ctkvr_index *idx, int32_t max_steps);
+/* Synchronises, writes ms_host[step][stage] (fp32, CTKVR_N_STAGES per step) for
+ * the steps recorded since the last collect (at most capacity_steps), stores
+ * their number in *n_steps and restarts recording at step 0. */
+int ctkvr_profile_collect(ctkvr_index *idx, float *ms_host, int32_t capacity_steps, int32_t *n_steps);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CTKVR_H */

@@ -1,0 +1,319 @@
+// Fixed arithmetic of every quantity that decides an integer on the CTkvr path
+// (which centroids are probed -- Algorithm 2 line 3; which keys enter a list --
+// Algorithm 1 line 4; which keys survive the rerank -- Algorithm 2 line 6), and
+// the wave/block primitives built on it.  gfx950, wave64.
+//
+// A 128-element row is owned by 16 adjacent lanes, lane l holding elements
+// 8l..8l+7 (one 16-byte load for bf16).  A dot product is 16 lane-partials (a
+// sequential fmaf chain over the lane's 8 elements, starting from 0) combined by
+// a butterfly over the 16 lanes (xor 1, 2, 4, 8): a fixed balanced tree whose
+// value does not depend on which lane looks at it, because a + b == b + a.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ctkvr {
+
+constexpr int kD = 128;          // head dimension
+constexpr int kFixShift = 40;    // softmax denominators are summed in 2^-40 fixed point
+
+typedef uint16_t bf16_t;
+
+// ---- raw 8-element chunks ---------------------------------------------------
+template <typename T> struct Chunk;
+template <> struct Chunk<float> { float4 a, b; };
+template <> struct Chunk<bf16_t> { uint4 w; };
+
+__device__ __forceinline__ Chunk<float> load_chunk(const float *row, int lane16)
+{
+    const float4 *p = reinterpret_cast<const float4 *>(row + 8 * lane16);
+    Chunk<float> c;
+    c.a = p[0];
+    c.b = p[1];
+    return c;
+}
+__device__ __forceinline__ Chunk<bf16_t> load_chunk(const bf16_t *row, int lane16)
+{
+    Chunk<bf16_t> c;
+    c.w = *reinterpret_cast<const uint4 *>(row + 8 * lane16);
+    return c;
+}
+__device__ __forceinline__ void unpack(const Chunk<float> &c, float (&x)[8])
+{
+    x[0] = c.a.x; x[1] = c.a.y; x[2] = c.a.z; x[3] = c.a.w;
+    x[4] = c.b.x; x[5] = c.b.y; x[6] = c.b.z; x[7] = c.b.w;
+}
+__device__ __forceinline__ void unpack(const Chunk<bf16_t> &c, float (&x)[8])
+{
+    // bf16 -> fp32 is a 16-bit shift: exact
+    x[0] = __uint_as_float(c.w.x << 16); x[1] = __uint_as_float(c.w.x & 0xffff0000u);
+    x[2] = __uint_as_float(c.w.y << 16); x[3] = __uint_as_float(c.w.y & 0xffff0000u);
+    x[4] = __uint_as_float(c.w.z << 16); x[5] = __uint_as_float(c.w.z & 0xffff0000u);
+    x[6] = __uint_as_float(c.w.w << 16); x[7] = __uint_as_float(c.w.w & 0xffff0000u);
+}
+
+// ---- 16-lane butterfly sum ----------------------------------------------------
+// DPP controls: quad_perm[1,0,3,2] = 0xB1, quad_perm[2,3,0,1] = 0x4E,
+// row_half_mirror = 0x141, row_mirror = 0x140.  After the two quad steps the four
+// lanes of a quad agree, so mirroring within 8 (then 16) lanes pairs each quad
+// with the partner the xor-4 (xor-8) step of the butterfly would give it.
+template <int CTRL> __device__ __forceinline__ float dpp_f(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float group16_sum(float v)
+{
+    v = v + dpp_f<0xB1>(v);
+    v = v + dpp_f<0x4E>(v);
+    v = v + dpp_f<0x141>(v);
+    v = v + dpp_f<0x140>(v);
+    return v;
+}
+
+__device__ __forceinline__ float lane_partial(const float (&a)[8], const float (&b)[8])
+{
+    float acc = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc = __fmaf_rn(a[e], b[e], acc);
+    return acc;
+}
+
+// 1/|x| from the squared norm: IEEE sqrt and divide; 0 for the zero vector
+__device__ __forceinline__ float inv_norm_from_sq(float n2)
+{
+    return (n2 > 0.0f) ? (1.0f / sqrtf(n2)) : 0.0f;
+}
+
+// ---- exp / fixed point / log ---------------------------------------------------
+// exp(x), x <= 0: x = n ln2 + r, degree-7 Taylor polynomial in r, times 2^n.
+// Below -30 the term is under 2^-43 and cannot reach the 2^-40 grid: 0.
+__device__ __forceinline__ float exp_series(float x)
+{
+    if (!(x >= -30.0f)) return 0.0f;
+    const float kMagic = 12582912.0f;
+    float t = __fmaf_rn(x, 1.44269504088896341f, kMagic);
+    float n = t - kMagic;
+    float r = __fmaf_rn(n, -0.693145751953125f, x);
+    r = __fmaf_rn(n, -1.42860682030941723e-6f, r);
+    float p = 1.0f / 5040.0f;
+    p = __fmaf_rn(p, r, 1.0f / 720.0f);
+    p = __fmaf_rn(p, r, 1.0f / 120.0f);
+    p = __fmaf_rn(p, r, 1.0f / 24.0f);
+    p = __fmaf_rn(p, r, 1.0f / 6.0f);
+    p = __fmaf_rn(p, r, 0.5f);
+    p = __fmaf_rn(p, r, 1.0f);
+    p = __fmaf_rn(p, r, 1.0f);
+    float two_n = __uint_as_float((uint32_t)((int)n + 127) << 23);
+    return p * two_n;
+}
+
+// floor(e * 2^40), 0 <= e < 2, with fp32 and integer operations only
+__device__ __forceinline__ uint64_t to_fixed40(float e)
+{
+    float a = e * 65536.0f;                       // exact
+    uint32_t hi = (uint32_t)a;                    // floor
+    float rem = a - (float)hi;                    // exact, in [0, 1)
+    uint32_t lo = (uint32_t)(rem * 16777216.0f);  // floor(rem * 2^24)
+    return ((uint64_t)hi << 24) + lo;
+}
+
+// log(S * 2^-40), S >= 1: S = 2^k f, f in [sqrt(1/2), sqrt(2)); log f = 2 atanh((f-1)/(f+1))
+__device__ __forceinline__ double log_fixed40(uint64_t S)
+{
+    if (S == 0) return -__builtin_huge_val();
+    int k = 63 - __clzll((long long)S);
+    uint64_t mant = (k > 52) ? (S >> (k - 52)) : (S << (52 - k));
+    double f = (double)mant * 0x1p-52;
+    if (f > 1.4142135623730951) {
+        f = f * 0.5;
+        k += 1;
+    }
+    double u = (f - 1.0) / (f + 1.0);
+    double u2 = u * u;
+    double p = 1.0 / 23.0;
+#pragma unroll
+    for (int q = 21; q >= 1; q -= 2) p = fma(p, u2, 1.0 / (double)q);
+    return fma((double)(k - kFixShift), 0.6931471805599453, 2.0 * u * p);
+}
+
+// ---- order-preserving float <-> uint32 ----------------------------------------
+// +0.0f first so that -0 and +0 map to one key (they compare equal as floats).
+__device__ __forceinline__ uint32_t ordered_key(float x)
+{
+    uint32_t u = __float_as_uint(x + 0.0f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float ordered_value(uint32_t k)
+{
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
+// ---- wave / block helpers -------------------------------------------------------
+__device__ __forceinline__ int lane_id() { return __lane_id(); }
+
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v)
+{
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        uint32_t t = __shfl_up(v, o);
+        if (lane_id() >= o) v += t;
+    }
+    return v;
+}
+
+// Exclusive scan of one value per thread over the block; *total gets the sum.
+// s_tmp: at least NT/64 + 1 words.  Contains __syncthreads().
+template <int NT> __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *s_tmp, uint32_t *total)
+{
+    constexpr int NW = NT / 64;
+    uint32_t inc = wave_incl_scan(v);
+    int w = threadIdx.x >> 6;
+    __syncthreads();
+    if (lane_id() == 63) s_tmp[w] = inc;
+    __syncthreads();
+    if (w == 0) {
+        uint32_t t = (lane_id() < NW) ? s_tmp[lane_id()] : 0u;
+        uint32_t ti = wave_incl_scan(t);
+        if (lane_id() < NW) s_tmp[lane_id()] = ti - t;
+        if (lane_id() == NW - 1) s_tmp[NW] = ti;
+    }
+    __syncthreads();
+    uint32_t r = s_tmp[w] + inc - v;
+    *total = s_tmp[NW];
+    return r;
+}
+
+// ---- block-wide top-k selection ---------------------------------------------------
+// Among keys key(i), i in [0, n), pick the k largest, ties towards the lowest i,
+// and call emit(pos, i) with pos = rank of i among the picked in ascending i.
+// One block of NT threads; s_hist needs 2048 + NT/64 + 8 words.  Returns
+// min(n, k) to every thread.
+//
+// Method: MSB-first radix select on 11-bit digits, starting at the highest bit in
+// which the keys differ at all (one min/max pass), which finds the k-th largest
+// key T and how many keys equal to T still belong to the pick; then an ordered
+// compaction: each wave owns a contiguous range of i, counts, and after one scan
+// over the wave totals writes its picks in place -- no atomics decide an order.
+template <int NT, typename KeyFn, typename EmitFn>
+__device__ int block_select_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t *s_hist)
+{
+    constexpr int NW = NT / 64;
+    const int tid = threadIdx.x;
+    uint32_t *s_aux = s_hist + 2048;   // [0] lo, [1] hi, [2] bin, [3] remaining ; scan scratch after that
+    uint32_t *s_scan = s_aux + 4;
+    if (k >= n) {
+        for (int i = tid; i < n; i += NT) emit(i, i);
+        return n;
+    }
+    // pass 0: range of the keys
+    uint32_t lo = 0xffffffffu, hi = 0u;
+    for (int i = tid; i < n; i += NT) {
+        uint32_t kk = key(i);
+        lo = min(lo, kk);
+        hi = max(hi, kk);
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        lo = min(lo, (uint32_t)__shfl_xor(lo, o));
+        hi = max(hi, (uint32_t)__shfl_xor(hi, o));
+    }
+    __syncthreads();
+    if (tid == 0) { s_aux[0] = 0xffffffffu; s_aux[1] = 0u; }
+    __syncthreads();
+    if (lane_id() == 0) { atomicMin(&s_aux[0], lo); atomicMax(&s_aux[1], hi); }
+    __syncthreads();
+    lo = s_aux[0];
+    hi = s_aux[1];
+    uint32_t prefix = 0, pmask = 0;
+    uint32_t remaining = (uint32_t)k;
+    int bit = 0;   // number of still undecided low bits
+    if (lo != hi) {
+        int top = 31 - __clz((int)(lo ^ hi));
+        bit = top + 1;
+        pmask = (bit >= 32) ? 0u : ~((1u << bit) - 1u);
+        prefix = hi & pmask;
+    } else {
+        prefix = hi;
+        pmask = 0xffffffffu;
+    }
+    while (bit > 0) {
+        const int w = bit < 11 ? bit : 11;
+        const int shift = bit - w;
+        const uint32_t dmask = (1u << w) - 1u;
+        const int nbins = 1 << w;
+        __syncthreads();
+        for (int i = tid; i < 2048; i += NT) s_hist[i] = 0;
+        __syncthreads();
+        for (int i = tid; i < n; i += NT) {
+            uint32_t kk = key(i);
+            if ((kk & pmask) == prefix) atomicAdd(&s_hist[(kk >> shift) & dmask], 1u);
+        }
+        __syncthreads();
+        // walk the bins from the top: thread t owns the BPT bins below nbins - BPT*t
+        constexpr int BPT = 2048 / NT;
+        uint32_t c[BPT];
+        uint32_t mine = 0;
+#pragma unroll
+        for (int q = 0; q < BPT; ++q) {
+            int bq = nbins - 1 - (BPT * tid + q);
+            c[q] = (bq >= 0) ? s_hist[bq] : 0u;
+            mine += c[q];
+        }
+        uint32_t tot;
+        uint32_t before = block_excl_scan<NT>(mine, s_scan, &tot);
+#pragma unroll
+        for (int q = 0; q < BPT; ++q) {
+            int bq = nbins - 1 - (BPT * tid + q);
+            if (bq >= 0 && before < remaining && remaining <= before + c[q]) {
+                s_aux[2] = (uint32_t)bq;
+                s_aux[3] = remaining - before;
+            }
+            before += c[q];
+        }
+        __syncthreads();
+        prefix |= s_aux[2] << shift;
+        pmask |= dmask << shift;
+        remaining = s_aux[3];
+        bit = shift;
+    }
+    const uint32_t T = prefix;
+    const uint32_t need_eq = remaining;
+    // ordered compaction; wave wv owns [wv*per, min(n, (wv+1)*per))
+    const int wv = tid >> 6, ln = lane_id();
+    const int per = ((n + NW - 1) / NW + 63) & ~63;
+    const int beg = wv * per;
+    const int end = min(n, beg + per);
+    uint32_t cgt = 0, ceq = 0;
+    for (int i = beg + ln; i < end; i += 64) {
+        uint32_t kk = key(i);
+        cgt += (kk > T);
+        ceq += (kk == T);
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        cgt += __shfl_xor(cgt, o);
+        ceq += __shfl_xor(ceq, o);
+    }
+    // exclusive scan over waves of (gt, eq) counts, done by every thread redundantly from shared memory
+    __syncthreads();
+    if (ln == 0) { s_hist[2 * wv] = cgt; s_hist[2 * wv + 1] = ceq; }
+    __syncthreads();
+    uint32_t run_gt = 0, run_eq = 0;
+    for (int q = 0; q < wv; ++q) { run_gt += s_hist[2 * q]; run_eq += s_hist[2 * q + 1]; }
+    for (int base = beg; base < end; base += 64) {
+        int i = base + ln;
+        bool in = i < end;
+        uint32_t kk = in ? key(i) : 0u;
+        bool gt = in && kk > T, eq = in && kk == T;
+        uint64_t mg = __ballot(gt), me = __ballot(eq);
+        uint64_t below = (1ull << ln) - 1ull;
+        uint32_t gt_before = run_gt + (uint32_t)__popcll(mg & below);
+        uint32_t eq_before = run_eq + (uint32_t)__popcll(me & below);
+        if (gt || (eq && eq_before < need_eq)) emit((int)(gt_before + min(eq_before, need_eq)), i);
+        run_gt += (uint32_t)__popcll(mg);
+        run_eq += (uint32_t)__popcll(me);
+    }
+    return k;
+}
+
+}  // namespace ctkvr

@@ -1,0 +1,634 @@
+// Host side of the C ABI declared in include/ctkvr.h: argument checks, device
+// memory of the index and its workspace, kernel launches.  No computation of the
+// method happens on the host.
+#include "../../include/ctkvr.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "kernels.hpp"
+
+using namespace ctkvr;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                           \
+    do {                                                                                        \
+        hipError_t e_ = (expr);                                                                 \
+        if (e_ != hipSuccess)                                                                   \
+            return fail(e_ == hipErrorOutOfMemory ? CTKVR_ENOMEM : CTKVR_EHIP, "%s: %s", #expr, \
+                        hipGetErrorString(e_));                                                 \
+    } while (0)
+
+size_t elem_size(int dtype) { return dtype == CTKVR_BF16 ? 2 : 4; }
+
+}  // namespace
+
+struct ctkvr_index {
+    ctkvr_params p{};
+    int G = 0, c_max = 0, s_max = 0, l_stride = 0, page_shift = 0, nsplit = 0, units = 0;
+    float scale = 0.f;
+    std::vector<int32_t> ctx_lens, n_cent;
+    std::vector<void *> allocs;
+    size_t device_bytes = 0;
+    // index proper
+    void *centroids = nullptr;
+    float *inv_norm_c = nullptr;
+    int32_t *lists = nullptr;
+    int32_t *d_ctx_lens = nullptr, *d_n_cent = nullptr;
+    // decode workspace
+    float *cos = nullptr;
+    int32_t *probe = nullptr, *cand = nullptr, *ncand = nullptr, *sel = nullptr, *nsel = nullptr;
+    float *z = nullptr, *zsel = nullptr, *po = nullptr, *pm = nullptr, *pl = nullptr;
+    uint32_t *m_key = nullptr;
+    unsigned long long *S = nullptr;
+    size_t recall_lds = 0;
+    // per-kernel timing
+    std::vector<hipEvent_t> events;
+    int prof_max = 0, prof_step = 0;
+
+    template <typename P> int alloc(P **ptr, size_t bytes)
+    {
+        void *v = nullptr;
+        hipError_t e = hipMalloc(&v, bytes ? bytes : 16);
+        if (e != hipSuccess)
+            return fail(e == hipErrorOutOfMemory ? CTKVR_ENOMEM : CTKVR_EHIP, "hipMalloc(%zu): %s", bytes,
+                        hipGetErrorString(e));
+        allocs.push_back(v);
+        device_bytes += bytes;
+        *ptr = (P *)v;
+        return CTKVR_OK;
+    }
+    ~ctkvr_index()
+    {
+        for (void *v : allocs) (void)hipFree(v);
+        for (hipEvent_t e : events) (void)hipEventDestroy(e);
+    }
+    // event slot `stage` (0 = before the first kernel) of the step being recorded
+    void mark(int stage, hipStream_t st)
+    {
+        if (prof_step < prof_max) (void)hipEventRecord(events[(size_t)prof_step * (CTKVR_N_STAGES + 1) + stage], st);
+    }
+};
+
+namespace {
+
+#define TRY(expr)                    \
+    do {                             \
+        int rc_ = (expr);            \
+        if (rc_ != CTKVR_OK) return rc_; \
+    } while (0)
+
+int check_params(const ctkvr_params *p, const int32_t *ctx_lens)
+{
+    if (!p) return fail(CTKVR_EINVAL, "params is NULL");
+    if (!ctx_lens) return fail(CTKVR_EINVAL, "ctx_lens is NULL");
+    if (p->batch < 1 || p->n_q_heads < 1 || p->n_kv_heads < 1) return fail(CTKVR_EINVAL, "batch/heads must be >= 1");
+    if (p->n_q_heads % p->n_kv_heads) return fail(CTKVR_EINVAL, "n_q_heads %% n_kv_heads != 0");
+    if (p->head_dim != 128) return fail(CTKVR_EUNSUPPORTED, "head_dim %d: only 128 is supported", p->head_dim);
+    int G = p->n_q_heads / p->n_kv_heads;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return fail(CTKVR_EUNSUPPORTED, "group size %d: only 1, 2, 4, 8", G);
+    if (p->dtype != CTKVR_F32 && p->dtype != CTKVR_BF16) return fail(CTKVR_EINVAL, "unknown dtype %d", p->dtype);
+    if (p->page_size < 1 || p->page_size > 256 || (p->page_size & (p->page_size - 1)))
+        return fail(CTKVR_EUNSUPPORTED, "page_size %d: powers of two up to 256", p->page_size);
+    if (p->n_centroids < 0 || (p->n_centroids == 0 && p->centroid_div < 1))
+        return fail(CTKVR_EINVAL, "n_centroids = 0 needs centroid_div >= 1");
+    if (p->list_len < 1 || p->n_probe < 1 || p->top_k < 1) return fail(CTKVR_EINVAL, "list_len, n_probe, top_k must be >= 1");
+    if (p->n_probe > 1024) return fail(CTKVR_EUNSUPPORTED, "n_probe %d > 1024", p->n_probe);
+    if (p->centroid_mode != CTKVR_CENTROID_LAST_C && p->centroid_mode != CTKVR_CENTROID_KMEANS)
+        return fail(CTKVR_EINVAL, "unknown centroid_mode %d", p->centroid_mode);
+    if (p->build_algo != CTKVR_BUILD_EXACT && p->build_algo != CTKVR_BUILD_MFMA)
+        return fail(CTKVR_EINVAL, "unknown build_algo %d", p->build_algo);
+    if (!(p->sm_scale >= 0.0f)) return fail(CTKVR_EINVAL, "sm_scale must be >= 0");
+    for (int b = 0; b < p->batch; ++b) {
+        int s = ctx_lens[b];
+        if (s < 1 || s > (1 << 20)) return fail(s < 1 ? CTKVR_EINVAL : CTKVR_EUNSUPPORTED, "ctx_lens[%d] = %d outside 1..2^20", b, s);
+        int C = p->n_centroids ? p->n_centroids : s / p->centroid_div;
+        if (C < 1 || C > s) return fail(CTKVR_EINVAL, "sequence %d: %d centroids for %d tokens", b, C, s);
+        if (p->n_probe > C) return fail(CTKVR_EINVAL, "sequence %d: n_probe %d > centroids %d", b, p->n_probe, C);
+        if (p->list_len > s) return fail(CTKVR_EINVAL, "sequence %d: list_len %d > ctx_len %d", b, p->list_len, s);
+    }
+    return CTKVR_OK;
+}
+
+// allocate everything an index holds; fills the host-side geometry
+int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **out)
+{
+    ctkvr_index *ix = new (std::nothrow) ctkvr_index();
+    if (!ix) return fail(CTKVR_ENOMEM, "host allocation failed");
+    ix->p = *p;
+    const int B = p->batch, h = p->n_q_heads, g = p->n_kv_heads;
+    ix->G = h / g;
+    ix->scale = p->sm_scale > 0.0f ? p->sm_scale : (float)(1.0 / sqrt(128.0));
+    ix->page_shift = __builtin_ctz(p->page_size);
+    ix->units = B * g;
+    for (int b = 0; b < B; ++b) {
+        int s = ctx_lens[b];
+        int C = p->n_centroids ? p->n_centroids : s / p->centroid_div;
+        ix->ctx_lens.push_back(s);
+        ix->n_cent.push_back(C);
+        ix->c_max = std::max(ix->c_max, C);
+        ix->s_max = std::max(ix->s_max, s);
+        long lm = std::min<long>(s, (long)p->n_probe * p->list_len);
+        ix->l_stride = std::max<long>(ix->l_stride, lm);
+    }
+    ix->nsplit = (p->top_k + 63) / 64;
+    const size_t es = elem_size(p->dtype);
+    const size_t U = ix->units;
+    int rc = CTKVR_OK;
+    auto A = [&](auto **ptr, size_t bytes) {
+        if (rc == CTKVR_OK) rc = ix->alloc(ptr, bytes);
+    };
+    A(&ix->centroids, (size_t)B * h * ix->c_max * 128 * es);
+    A(&ix->inv_norm_c, (size_t)B * h * ix->c_max * 4);
+    A(&ix->lists, U * ix->c_max * p->list_len * 4);
+    A(&ix->d_ctx_lens, (size_t)B * 4);
+    A(&ix->d_n_cent, (size_t)B * 4);
+    A(&ix->cos, U * ix->c_max * 4);
+    A(&ix->probe, U * p->n_probe * 4);
+    A(&ix->cand, U * ix->l_stride * 4);
+    A(&ix->ncand, U * 4);
+    A(&ix->z, U * ix->l_stride * ix->G * 4);
+    A(&ix->m_key, U * ix->G * 4);
+    A(&ix->S, U * ix->G * 8);
+    A(&ix->sel, U * p->top_k * 4);
+    A(&ix->zsel, U * p->top_k * ix->G * 4);
+    A(&ix->nsel, U * 4);
+    A(&ix->po, (size_t)B * h * ix->nsplit * 128 * 4);
+    A(&ix->pm, (size_t)B * h * ix->nsplit * 4);
+    A(&ix->pl, (size_t)B * h * ix->nsplit * 4);
+    if (rc != CTKVR_OK) {
+        delete ix;
+        return rc;
+    }
+    ix->recall_lds = (size_t)(2080 + p->n_probe + (ix->s_max + 31) / 32) * 4;
+    if (ix->recall_lds > 160 * 1024) {
+        delete ix;
+        return fail(CTKVR_EUNSUPPORTED, "context too long for the in-LDS candidate bitmap");
+    }
+    hipError_t e = hipFuncSetAttribute((const void *)recall_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)ix->recall_lds);
+    if (e == hipSuccess) e = hipMemcpy(ix->d_ctx_lens, ix->ctx_lens.data(), (size_t)B * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(ix->d_n_cent, ix->n_cent.data(), (size_t)B * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemset(ix->lists, 0, U * ix->c_max * p->list_len * 4);
+    if (e == hipSuccess) e = hipMemset(ix->centroids, 0, (size_t)B * h * ix->c_max * 128 * es);
+    if (e != hipSuccess) {
+        delete ix;
+        return fail(CTKVR_EHIP, "index set-up: %s", hipGetErrorString(e));
+    }
+    *out = ix;
+    return CTKVR_OK;
+}
+
+Units decode_units(const ctkvr_index *ix)
+{
+    Units u{};
+    u.g = ix->p.n_kv_heads;
+    u.G = ix->G;
+    u.h = ix->p.n_q_heads;
+    u.build = 0;
+    u.unit0 = 0;
+    u.c_max = ix->c_max;
+    u.n_cent = ix->d_n_cent;
+    return u;
+}
+
+template <typename T> int launch_inv_norms(ctkvr_index *ix, hipStream_t st)
+{
+    size_t n = (size_t)ix->p.batch * ix->p.n_q_heads * ix->c_max;
+    inv_norm_kernel<T><<<dim3((unsigned)((n + 15) / 16)), 256, 0, st>>>((const T *)ix->centroids, n, ix->inv_norm_c);
+    HIP_TRY(hipGetLastError());
+    return CTKVR_OK;
+}
+
+// Algorithm 1 lines 2-4 in the decode path's own arithmetic: for chunks of
+// (sequence, KV head, centroid) units, score all keys, sum the denominators,
+// select the top-rho.
+template <typename T, int G>
+int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block_table, int max_pages, hipStream_t st)
+{
+    const int total_units = ix->units * ix->c_max;
+    const size_t per_unit = (size_t)ix->s_max * G * 4;
+    int chunk = (int)std::min<size_t>(total_units, std::max<size_t>(1, ((size_t)2 << 30) / per_unit));
+    chunk = std::min(chunk, 32768);
+    float *z = nullptr;
+    uint32_t *m_key = nullptr;
+    unsigned long long *S = nullptr;
+    HIP_TRY(hipMalloc((void **)&z, (size_t)chunk * per_unit));
+    hipError_t e1 = hipMalloc((void **)&m_key, (size_t)chunk * G * 4);
+    hipError_t e2 = hipMalloc((void **)&S, (size_t)chunk * G * 8);
+    int rc = CTKVR_OK;
+    if (e1 != hipSuccess || e2 != hipSuccess) rc = fail(CTKVR_ENOMEM, "build scratch allocation failed");
+    for (int u0 = 0; rc == CTKVR_OK && u0 < total_units; u0 += chunk) {
+        const int nu = std::min(chunk, total_units - u0);
+        Units u = decode_units(ix);
+        u.build = 1;
+        u.unit0 = u0;
+        fill_u32_kernel<<<dim3((unsigned)((nu * G * 3 + 255) / 256)), 256, 0, st>>>(m_key, 0u, (size_t)nu * G);
+        fill_u32_kernel<<<dim3((unsigned)((nu * G * 2 + 255) / 256)), 256, 0, st>>>((uint32_t *)S, 0u, (size_t)nu * G * 2);
+        ScoreArgs sa{};
+        sa.u = u;
+        sa.q = ix->centroids;
+        sa.qrows = ix->c_max;
+        sa.k = Paged{k_pages, block_table, max_pages, ix->page_shift};
+        sa.ctx_lens = ix->d_ctx_lens;
+        sa.cand = nullptr;
+        sa.ncand = nullptr;
+        sa.l_stride = ix->s_max;
+        sa.z = z;
+        sa.m_key = m_key;
+        sa.scale = ix->scale;
+        score_kernel<T, G><<<dim3((ix->s_max + 255) / 256, nu), 256, 0, st>>>(sa);
+        DenomArgs da{};
+        da.u = u;
+        da.ctx_lens = ix->d_ctx_lens;
+        da.ncand = nullptr;
+        da.l_stride = ix->s_max;
+        da.z = z;
+        da.m_key = m_key;
+        da.S = S;
+        denom_kernel<G><<<dim3((ix->s_max + 1023) / 1024, nu), 256, 0, st>>>(da);
+        SelectArgs se{};
+        se.u = u;
+        se.ctx_lens = ix->d_ctx_lens;
+        se.ncand = nullptr;
+        se.cand = nullptr;
+        se.l_stride = ix->s_max;
+        se.top_k = ix->p.list_len;
+        se.z = z;
+        se.m_key = m_key;
+        se.S = S;
+        se.sel = ix->lists;
+        rerank_select_kernel<G><<<dim3(nu), 1024, 0, st>>>(se);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) rc = fail(CTKVR_EHIP, "build launch: %s", hipGetErrorString(e));
+    }
+    hipError_t es = hipStreamSynchronize(st);
+    if (rc == CTKVR_OK && es != hipSuccess) rc = fail(CTKVR_EHIP, "build: %s", hipGetErrorString(es));
+    (void)hipFree(z);
+    (void)hipFree(m_key);
+    (void)hipFree(S);
+    return rc;
+}
+
+template <typename T>
+int build_lists_dispatch(ctkvr_index *ix, const void *k_pages, const int32_t *bt, int max_pages, hipStream_t st)
+{
+    switch (ix->G) {
+        case 1: return build_lists_exact<T, 1>(ix, k_pages, bt, max_pages, st);
+        case 2: return build_lists_exact<T, 2>(ix, k_pages, bt, max_pages, st);
+        case 4: return build_lists_exact<T, 4>(ix, k_pages, bt, max_pages, st);
+        default: return build_lists_exact<T, 8>(ix, k_pages, bt, max_pages, st);
+    }
+}
+
+template <typename T, int G>
+int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const void *v_pages, const int32_t *bt,
+                  int max_pages, float *out, float *out_lse, int32_t *out_sel, int32_t *out_ncand, int32_t *out_probe,
+                  hipStream_t st)
+{
+    const ctkvr_params &p = ix->p;
+    const int U = ix->units;
+    CosArgs ca{};
+    ca.q = q;
+    ca.centroids = ix->centroids;
+    ca.inv_norm_c = ix->inv_norm_c;
+    ca.n_cent = ix->d_n_cent;
+    ca.cos = ix->cos;
+    ca.m_key = ix->m_key;
+    ca.S = ix->S;
+    ca.g = p.n_kv_heads;
+    ca.h = p.n_q_heads;
+    ca.c_max = ix->c_max;
+    ix->mark(0, st);
+    centroid_cos_kernel<T, G><<<dim3((ix->c_max + 63) / 64, U), 256, 0, st>>>(ca);
+    ix->mark(1, st);
+
+    RecallArgs ra{};
+    ra.cos = ix->cos;
+    ra.lists = ix->lists;
+    ra.n_cent = ix->d_n_cent;
+    ra.ctx_lens = ix->d_ctx_lens;
+    ra.probe = ix->probe;
+    ra.cand = ix->cand;
+    ra.ncand = ix->ncand;
+    ra.out_probe = out_probe;
+    ra.out_ncand = out_ncand;
+    ra.g = p.n_kv_heads;
+    ra.c_max = ix->c_max;
+    ra.rho = p.list_len;
+    ra.n_probe = p.n_probe;
+    ra.l_stride = ix->l_stride;
+    recall_kernel<<<dim3(U), 1024, ix->recall_lds, st>>>(ra);
+    ix->mark(2, st);
+
+    Units u = decode_units(ix);
+    ScoreArgs sa{};
+    sa.u = u;
+    sa.q = q;
+    sa.qrows = 1;
+    sa.k = Paged{k_pages, bt, max_pages, ix->page_shift};
+    sa.ctx_lens = ix->d_ctx_lens;
+    sa.cand = ix->cand;
+    sa.ncand = ix->ncand;
+    sa.l_stride = ix->l_stride;
+    sa.z = ix->z;
+    sa.m_key = ix->m_key;
+    sa.scale = ix->scale;
+    score_kernel<T, G><<<dim3((ix->l_stride + 255) / 256, U), 256, 0, st>>>(sa);
+    ix->mark(3, st);
+
+    DenomArgs da{};
+    da.u = u;
+    da.ctx_lens = ix->d_ctx_lens;
+    da.ncand = ix->ncand;
+    da.l_stride = ix->l_stride;
+    da.z = ix->z;
+    da.m_key = ix->m_key;
+    da.S = ix->S;
+    denom_kernel<G><<<dim3((ix->l_stride + 1023) / 1024, U), 256, 0, st>>>(da);
+    ix->mark(4, st);
+
+    SelectArgs se{};
+    se.u = u;
+    se.ctx_lens = ix->d_ctx_lens;
+    se.ncand = ix->ncand;
+    se.cand = ix->cand;
+    se.l_stride = ix->l_stride;
+    se.top_k = p.top_k;
+    se.z = ix->z;
+    se.m_key = ix->m_key;
+    se.S = ix->S;
+    se.sel = ix->sel;
+    se.zsel = ix->zsel;
+    se.nsel = ix->nsel;
+    se.out_sel = out_sel;
+    rerank_select_kernel<G><<<dim3(U), 1024, 0, st>>>(se);
+    ix->mark(5, st);
+
+    AttnArgs aa{};
+    aa.v = Paged{v_pages, bt, max_pages, ix->page_shift};
+    aa.g = p.n_kv_heads;
+    aa.h = p.n_q_heads;
+    aa.top_k = p.top_k;
+    aa.nsplit = ix->nsplit;
+    aa.sel = ix->sel;
+    aa.nsel = ix->nsel;
+    aa.zsel = ix->zsel;
+    aa.po = ix->po;
+    aa.pm = ix->pm;
+    aa.pl = ix->pl;
+    aa.out = out;
+    aa.out_lse = out_lse;
+    sparse_attn_kernel<T, G><<<dim3(ix->nsplit, U), 256, 0, st>>>(aa);
+    ix->mark(6, st);
+    attn_merge_kernel<G><<<dim3(p.batch * p.n_q_heads), 128, 0, st>>>(aa);
+    ix->mark(7, st);
+    if (ix->prof_step < ix->prof_max) ix->prof_step++;
+    HIP_TRY(hipGetLastError());
+    return CTKVR_OK;
+}
+
+template <typename T>
+int decode_dispatch(ctkvr_index *ix, const void *q, const void *k, const void *v, const int32_t *bt, int mp, float *out,
+                    float *lse, int32_t *sel, int32_t *ncand, int32_t *probe, hipStream_t st)
+{
+    switch (ix->G) {
+        case 1: return decode_launch<T, 1>(ix, q, k, v, bt, mp, out, lse, sel, ncand, probe, st);
+        case 2: return decode_launch<T, 2>(ix, q, k, v, bt, mp, out, lse, sel, ncand, probe, st);
+        case 4: return decode_launch<T, 4>(ix, q, k, v, bt, mp, out, lse, sel, ncand, probe, st);
+        default: return decode_launch<T, 8>(ix, q, k, v, bt, mp, out, lse, sel, ncand, probe, st);
+    }
+}
+
+int min_pages_needed(const ctkvr_index *ix)
+{
+    return (ix->s_max + ix->p.page_size - 1) / ix->p.page_size;
+}
+
+}  // namespace
+
+#pragma GCC visibility push(default)
+extern "C" {
+
+const char *ctkvr_last_error(void) { return g_err.c_str(); }
+
+int ctkvr_build_index(const ctkvr_params *p, const void *q_prefill, const int32_t *cu_seqlens, int32_t q_is_tail,
+                      const void *k_pages, const int32_t *block_table, int32_t max_pages, const int32_t *ctx_lens,
+                      const int32_t *init_pos, void *hip_stream, ctkvr_index **out_index)
+{
+    if (!out_index) return fail(CTKVR_EINVAL, "out_index is NULL");
+    *out_index = nullptr;
+    TRY(check_params(p, ctx_lens));
+    if (!q_prefill || !cu_seqlens || !k_pages || !block_table) return fail(CTKVR_EINVAL, "a required pointer is NULL");
+    if (p->centroid_mode == CTKVR_CENTROID_KMEANS) return fail(CTKVR_EUNSUPPORTED, "k-means centroid mode is not built yet");
+    if (p->build_algo == CTKVR_BUILD_MFMA) return fail(CTKVR_EUNSUPPORTED, "MFMA list build is not built yet");
+    (void)init_pos;
+    std::vector<int32_t> first_row(p->batch);
+    for (int b = 0; b < p->batch; ++b) {
+        int s = ctx_lens[b];
+        int C = p->n_centroids ? p->n_centroids : s / p->centroid_div;
+        int rows = cu_seqlens[b + 1] - cu_seqlens[b];
+        int need = q_is_tail ? C : s;
+        if (rows != need)
+            return fail(CTKVR_EINVAL, "sequence %d: cu_seqlens gives %d query rows, expected %d", b, rows, need);
+        if (max_pages * p->page_size < s) return fail(CTKVR_EINVAL, "max_pages %d too small for ctx_len %d", max_pages, s);
+        first_row[b] = cu_seqlens[b] + rows - C;
+    }
+    ctkvr_index *ix = nullptr;
+    TRY(create_index(p, ctx_lens, &ix));
+    hipStream_t st = (hipStream_t)hip_stream;
+    int rc = CTKVR_OK;
+    int32_t *d_first = nullptr;
+    hipError_t e = hipMalloc((void **)&d_first, (size_t)p->batch * 4);
+    if (e == hipSuccess) e = hipMemcpy(d_first, first_row.data(), (size_t)p->batch * 4, hipMemcpyHostToDevice);
+    if (e != hipSuccess) rc = fail(CTKVR_EHIP, "build set-up: %s", hipGetErrorString(e));
+    if (rc == CTKVR_OK) {
+        dim3 grid(ix->c_max, p->n_q_heads, p->batch);
+        if (p->dtype == CTKVR_BF16) {
+            copy_centroids_kernel<bf16_t><<<grid, 128, 0, st>>>((const bf16_t *)q_prefill, d_first, ix->d_n_cent,
+                                                                 p->n_q_heads, ix->c_max, (bf16_t *)ix->centroids);
+            rc = launch_inv_norms<bf16_t>(ix, st);
+            if (rc == CTKVR_OK) rc = build_lists_dispatch<bf16_t>(ix, k_pages, block_table, max_pages, st);
+        } else {
+            copy_centroids_kernel<float><<<grid, 128, 0, st>>>((const float *)q_prefill, d_first, ix->d_n_cent,
+                                                                p->n_q_heads, ix->c_max, (float *)ix->centroids);
+            rc = launch_inv_norms<float>(ix, st);
+            if (rc == CTKVR_OK) rc = build_lists_dispatch<float>(ix, k_pages, block_table, max_pages, st);
+        }
+    }
+    if (rc == CTKVR_OK) {
+        e = hipStreamSynchronize(st);
+        if (e != hipSuccess) rc = fail(CTKVR_EHIP, "build: %s", hipGetErrorString(e));
+    }
+    if (d_first) (void)hipFree(d_first);
+    if (rc != CTKVR_OK) {
+        delete ix;
+        return rc;
+    }
+    *out_index = ix;
+    return CTKVR_OK;
+}
+
+int ctkvr_index_load(const ctkvr_params *p, const int32_t *ctx_lens, const void *centroids, const int32_t *lists,
+                     void *hip_stream, ctkvr_index **out_index)
+{
+    if (!out_index) return fail(CTKVR_EINVAL, "out_index is NULL");
+    *out_index = nullptr;
+    TRY(check_params(p, ctx_lens));
+    if (!centroids || !lists) return fail(CTKVR_EINVAL, "a required pointer is NULL");
+    ctkvr_index *ix = nullptr;
+    TRY(create_index(p, ctx_lens, &ix));
+    // every id a decode step may touch must be a valid key id of its sequence
+    const int g = p->n_kv_heads;
+    for (int b = 0; b < p->batch; ++b)
+        for (int kv = 0; kv < g; ++kv)
+            for (int j = 0; j < ix->n_cent[b]; ++j) {
+                const int32_t *l = lists + (((size_t)b * g + kv) * ix->c_max + j) * p->list_len;
+                for (int r = 0; r < p->list_len; ++r)
+                    if (l[r] < 0 || l[r] >= ix->ctx_lens[b]) {
+                        delete ix;
+                        return fail(CTKVR_EINVAL, "list (%d,%d,%d)[%d] = %d is not a key id of the sequence", b, kv, j, r, l[r]);
+                    }
+            }
+    hipStream_t st = (hipStream_t)hip_stream;
+    const size_t es = elem_size(p->dtype);
+    hipError_t e = hipMemcpy(ix->centroids, centroids, (size_t)p->batch * p->n_q_heads * ix->c_max * 128 * es,
+                             hipMemcpyHostToDevice);
+    if (e == hipSuccess)
+        e = hipMemcpy(ix->lists, lists, (size_t)ix->units * ix->c_max * p->list_len * 4, hipMemcpyHostToDevice);
+    int rc = CTKVR_OK;
+    if (e != hipSuccess) rc = fail(CTKVR_EHIP, "index upload: %s", hipGetErrorString(e));
+    if (rc == CTKVR_OK) rc = p->dtype == CTKVR_BF16 ? launch_inv_norms<bf16_t>(ix, st) : launch_inv_norms<float>(ix, st);
+    if (rc == CTKVR_OK) {
+        e = hipStreamSynchronize(st);
+        if (e != hipSuccess) rc = fail(CTKVR_EHIP, "index upload: %s", hipGetErrorString(e));
+    }
+    if (rc != CTKVR_OK) {
+        delete ix;
+        return rc;
+    }
+    *out_index = ix;
+    return CTKVR_OK;
+}
+
+int ctkvr_decode_step(ctkvr_index *idx, const void *q, const void *k_pages, const void *v_pages,
+                      const int32_t *block_table, int32_t max_pages, float *out, float *out_lse, int32_t *out_sel,
+                      int32_t *out_ncand, int32_t *out_probe, void *hip_stream)
+{
+    if (!idx) return fail(CTKVR_EINVAL, "index is NULL");
+    if (!q || !k_pages || !v_pages || !block_table || !out) return fail(CTKVR_EINVAL, "a required pointer is NULL");
+    if (max_pages < min_pages_needed(idx))
+        return fail(CTKVR_EINVAL, "max_pages %d < %d pages of the longest sequence", max_pages, min_pages_needed(idx));
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (idx->p.dtype == CTKVR_BF16)
+        return decode_dispatch<bf16_t>(idx, q, k_pages, v_pages, block_table, max_pages, out, out_lse, out_sel, out_ncand,
+                                       out_probe, st);
+    return decode_dispatch<float>(idx, q, k_pages, v_pages, block_table, max_pages, out, out_lse, out_sel, out_ncand,
+                                  out_probe, st);
+}
+
+void ctkvr_free(ctkvr_index *idx)
+{
+    if (!idx) return;
+    (void)hipDeviceSynchronize();
+    delete idx;
+}
+
+int ctkvr_profile_enable(ctkvr_index *idx, int32_t max_steps)
+{
+    if (!idx || max_steps < 0) return fail(CTKVR_EINVAL, "bad argument");
+    HIP_TRY(hipDeviceSynchronize());
+    for (hipEvent_t e : idx->events) (void)hipEventDestroy(e);
+    idx->events.clear();
+    idx->prof_max = idx->prof_step = 0;
+    for (size_t i = 0; i < (size_t)max_steps * (CTKVR_N_STAGES + 1); ++i) {
+        hipEvent_t e;
+        HIP_TRY(hipEventCreate(&e));
+        idx->events.push_back(e);
+    }
+    idx->prof_max = max_steps;
+    return CTKVR_OK;
+}
+
+int ctkvr_profile_collect(ctkvr_index *idx, float *ms_host, int32_t capacity_steps, int32_t *n_steps)
+{
+    if (!idx || !ms_host || !n_steps) return fail(CTKVR_EINVAL, "NULL argument");
+    HIP_TRY(hipDeviceSynchronize());
+    int n = std::min<int>(idx->prof_step, capacity_steps);
+    for (int s = 0; s < n; ++s)
+        for (int k = 0; k < CTKVR_N_STAGES; ++k) {
+            const hipEvent_t *ev = &idx->events[(size_t)s * (CTKVR_N_STAGES + 1)];
+            HIP_TRY(hipEventElapsedTime(&ms_host[(size_t)s * CTKVR_N_STAGES + k], ev[k], ev[k + 1]));
+        }
+    *n_steps = n;
+    idx->prof_step = 0;
+    return CTKVR_OK;
+}
+
+int ctkvr_index_info(const ctkvr_index *idx, ctkvr_index_info_t *out)
+{
+    if (!idx || !out) return fail(CTKVR_EINVAL, "NULL argument");
+    out->batch = idx->p.batch;
+    out->n_q_heads = idx->p.n_q_heads;
+    out->n_kv_heads = idx->p.n_kv_heads;
+    out->head_dim = idx->p.head_dim;
+    out->dtype = idx->p.dtype;
+    out->c_max = idx->c_max;
+    out->list_len = idx->p.list_len;
+    out->n_probe = idx->p.n_probe;
+    out->top_k = idx->p.top_k;
+    out->l_stride = idx->l_stride;
+    out->index_bytes = (int64_t)idx->units * idx->c_max * idx->p.list_len * 4;
+    out->device_bytes = (int64_t)idx->device_bytes;
+    return CTKVR_OK;
+}
+
+int ctkvr_index_lists(const ctkvr_index *idx, int32_t *dst_host)
+{
+    if (!idx || !dst_host) return fail(CTKVR_EINVAL, "NULL argument");
+    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipMemcpy(dst_host, idx->lists, (size_t)idx->units * idx->c_max * idx->p.list_len * 4, hipMemcpyDeviceToHost));
+    return CTKVR_OK;
+}
+
+int ctkvr_index_centroids(const ctkvr_index *idx, void *dst_host)
+{
+    if (!idx || !dst_host) return fail(CTKVR_EINVAL, "NULL argument");
+    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipMemcpy(dst_host, idx->centroids,
+                      (size_t)idx->p.batch * idx->p.n_q_heads * idx->c_max * 128 * elem_size(idx->p.dtype),
+                      hipMemcpyDeviceToHost));
+    return CTKVR_OK;
+}
+
+int ctkvr_index_last_candidates(const ctkvr_index *idx, int32_t *dst_host)
+{
+    if (!idx || !dst_host) return fail(CTKVR_EINVAL, "NULL argument");
+    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipMemcpy(dst_host, idx->cand, (size_t)idx->units * idx->l_stride * 4, hipMemcpyDeviceToHost));
+    return CTKVR_OK;
+}
+
+}  // extern "C"
+#pragma GCC visibility pop

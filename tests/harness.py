@@ -1,0 +1,128 @@
+"""Glue for the GPU parity tests: moves the seeded inputs to the device, builds
+the oracle's index and runs both sides on the same inputs.  No arithmetic of
+the method lives here."""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List, Optional
+
+import numpy as np
+
+import oracle
+from ctkvr_inputs import Batch, Workload, f32_to_bf16_bits
+
+REL_TOL = 2e-3   # max relative error of the attention output (bf16 inputs, fp32 accumulation)
+
+
+def torch_dtype(wl: Workload):
+    import torch
+    return torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+
+
+def to_dev(x: np.ndarray, wl: Workload):
+    """fp32 values (exactly representable in the workload dtype) -> device tensor of that dtype."""
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(x)).to(device="cuda", dtype=torch_dtype(wl))
+
+
+def params_of(wl: Workload, **over):
+    import paper_2512_15550_amd as ck
+    p = ck.Params(batch=wl.batch, n_q_heads=wl.h, n_kv_heads=wl.g, head_dim=wl.d, page_size=wl.page_size,
+                  dtype=ck.BF16 if wl.dtype == "bf16" else ck.F32, n_centroids=wl.n_centroids,
+                  centroid_div=wl.centroid_div, list_len=wl.list_len, n_probe=wl.n_probe, top_k=wl.top_k)
+    for k, v in over.items():
+        setattr(p, k, v)
+    return p
+
+
+@dataclass
+class DeviceBatch:
+    k_pages: object
+    v_pages: object
+    block_table: object
+    q_prefill: object       # concatenated tails [sum C_i][h][d]
+    cu_seqlens: np.ndarray
+    ctx_lens: np.ndarray
+
+
+def device_batch(bt: Batch) -> DeviceBatch:
+    import torch
+    wl = bt.wl
+    tails = [sq.q_tail[sq.q_tail.shape[0] - wl.centroids_of(sq.s):] for sq in bt.seqs]
+    cu = np.zeros(len(tails) + 1, np.int32)
+    cu[1:] = np.cumsum([t.shape[0] for t in tails])
+    return DeviceBatch(k_pages=to_dev(bt.paged.k_pages, wl), v_pages=to_dev(bt.paged.v_pages, wl),
+                       block_table=torch.from_numpy(bt.paged.block_table).cuda(),
+                       q_prefill=to_dev(np.concatenate(tails, axis=0), wl), cu_seqlens=cu,
+                       ctx_lens=bt.paged.ctx_lens.copy())
+
+
+@dataclass
+class OracleIndex:
+    Qc: List[np.ndarray]        # per sequence [h][C_i][d]
+    lists: List[np.ndarray]     # per sequence [g][C_i][rho]
+
+    def padded(self, wl: Workload):
+        """[B][h][C_max][d] centroid table (storage dtype) and [B][g][C_max][rho] lists, zero padded."""
+        c_max = max(q.shape[1] for q in self.Qc)
+        cen = np.zeros((len(self.Qc), wl.h, c_max, wl.d), np.float32)
+        lst = np.zeros((len(self.Qc), wl.g, c_max, wl.list_len), np.int32)
+        for b, (q, l) in enumerate(zip(self.Qc, self.lists)):
+            cen[b, :, :q.shape[1]] = q
+            lst[b, :, :l.shape[1]] = l
+        return (f32_to_bf16_bits(cen) if wl.dtype == "bf16" else cen), lst
+
+
+def oracle_index(bt: Batch) -> OracleIndex:
+    wl = bt.wl
+    Qc = [oracle.centroids_last_c(sq.q_tail, wl.centroids_of(sq.s)) for sq in bt.seqs]
+    lists = [oracle.build_lists(sq.K, q, wl.list_len) for sq, q in zip(bt.seqs, Qc)]
+    return OracleIndex(Qc, lists)
+
+
+def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """Per output row (one query head): max |got - ref| / max |ref|; returns the worst row."""
+    got = got.reshape(-1, got.shape[-1]).astype(np.float64)
+    ref = ref.reshape(-1, ref.shape[-1]).astype(np.float64)
+    return float(np.max(np.max(np.abs(got - ref), axis=1) / np.max(np.abs(ref), axis=1)))
+
+
+def run_decode_parity(bt: Batch, oi: OracleIndex, idx, db: DeviceBatch, steps: Optional[List[int]] = None,
+                      check_candidates: bool = True) -> dict:
+    """Run decode steps on the GPU index `idx` and on the oracle with index `oi`;
+    assert bit-equal integers and outputs within REL_TOL.  Returns statistics."""
+    import torch
+    import paper_2512_15550_amd as ck
+    wl = bt.wl
+    B, h, g, d = wl.batch, wl.h, wl.g, wl.d
+    steps = list(range(bt.seqs[0].q_decode.shape[0])) if steps is None else steps
+    out = torch.empty((B, h, d), dtype=torch.float32, device="cuda")
+    lse = torch.empty((B, h), dtype=torch.float32, device="cuda")
+    sel = torch.empty((B, g, wl.top_k), dtype=torch.int32, device="cuda")
+    ncand = torch.empty((B, g), dtype=torch.int32, device="cuda")
+    probe = torch.empty((B, g, wl.n_probe), dtype=torch.int32, device="cuda")
+    worst, worst_lse, alphas = 0.0, 0.0, []
+    for st in steps:
+        q = np.stack([sq.q_decode[st] for sq in bt.seqs])
+        ck.ctkvr_decode_step(idx, to_dev(q, wl), db.k_pages, db.v_pages, db.block_table, out, lse, sel, ncand, probe)
+        torch.cuda.synchronize()
+        g_out, g_lse = out.cpu().numpy(), lse.cpu().numpy()
+        g_sel, g_ncand, g_probe = sel.cpu().numpy(), ncand.cpu().numpy(), probe.cpu().numpy()
+        g_cand = ck.ctkvr_index_last_candidates(idx) if check_candidates else None
+        for b, sq in enumerate(bt.seqs):
+            r = oracle.decode_step(q[b], sq.K, sq.V, oi.Qc[b], oi.lists[b], wl.n_probe, wl.top_k)
+            tag = f"step {st} seq {b}"
+            assert np.array_equal(g_probe[b], r.probe), f"{tag}: probed centroids differ"
+            assert np.array_equal(g_ncand[b], r.ncand), f"{tag}: L differs {g_ncand[b]} vs {r.ncand}"
+            if check_candidates:
+                for kv in range(g):
+                    assert np.array_equal(g_cand[b, kv, :r.ncand[kv]], r.cand[kv]), f"{tag} kv {kv}: recalled ids differ"
+            assert np.array_equal(g_sel[b], r.sel), f"{tag}: selected ids differ ({int(np.sum(g_sel[b] != r.sel))} slots)"
+            e = rel_err(g_out[b], r.out)
+            assert e <= REL_TOL, f"{tag}: output relative error {e:.3e} > {REL_TOL}"
+            worst = max(worst, e)
+            el = float(np.max(np.abs(g_lse[b] - r.lse) / np.maximum(1.0, np.abs(r.lse))))
+            assert el <= 1e-4, f"{tag}: lse error {el:.3e}"
+            worst_lse = max(worst_lse, el)
+            alphas.append(float(np.mean(r.ncand)) / (wl.n_probe * wl.list_len))
+    return {"max_rel_err": worst, "max_lse_err": worst_lse, "alpha": float(np.mean(alphas))}

@@ -1,0 +1,159 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Integers (probed centroids, recalled ids, selected ids,
+list contents) must be bit-equal; attention outputs within 2e-3 relative."""
+import numpy as np
+import pytest
+
+import oracle
+from ctkvr_inputs import gen_batch, gen_lattice_sequence, paginate, small_workload, workload, Batch
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ck():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2512_15550_amd as ck
+    ck.load_library()
+    return ck
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+SMALL = [
+    # name, dtype, h, g, ctx_lens, C, div, C', rho, rho'
+    ("g4_bf16", "bf16", 8, 2, (1000,), 24, 0, 4, 96, 64),
+    ("g1_bf16", "bf16", 2, 2, (777,), 16, 0, 3, 80, 50),
+    ("g2_f32", "f32", 4, 2, (1500,), 20, 0, 5, 100, 70),
+    ("g8_bf16", "bf16", 8, 1, (2100,), 32, 0, 6, 128, 100),
+    ("ragged_batch", "bf16", 8, 2, (700, 1333, 2049, 5000), 0, 50, 4, 120, 90),
+    ("rerank_off", "bf16", 8, 2, (900,), 12, 0, 3, 60, 180),          # rho' >= L: every recalled key is kept
+    ("all_probed", "bf16", 4, 1, (640,), 8, 0, 8, 640, 640),           # C' = C, rho = s: dense attention
+    ("multi_tile", "bf16", 16, 4, (9000,), 96, 0, 12, 700, 300),       # L spans many 256-id tiles, ragged tail
+]
+
+
+@pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
+def test_decode_matches_oracle_on_shared_index(ck, case):
+    name, dtype, h, g, lens, C, div, n_probe, rho, top_k = case
+    wl = small_workload(name, dtype, h, g, lens, tuple(range(200, 200 + len(lens))), C, div, n_probe, rho, top_k, 3)
+    _say(f"[case {name}] generating")
+    bt = gen_batch(wl)
+    oi = H.oracle_index(bt)
+    db = H.device_batch(bt)
+    cen, lst = oi.padded(wl)
+    idx = ck.ctkvr_index_load(H.params_of(wl), db.ctx_lens, cen, lst)
+    _say(f"[case {name}] decode parity")
+    st = H.run_decode_parity(bt, oi, idx, db)
+    _say(f"[case {name}] ok {st}")
+    ck.ctkvr_free(idx)
+
+
+@pytest.mark.parametrize("case", SMALL[:5], ids=[c[0] for c in SMALL[:5]])
+def test_exact_build_matches_oracle_lists(ck, case):
+    name, dtype, h, g, lens, C, div, n_probe, rho, top_k = case
+    wl = small_workload(name, dtype, h, g, lens, tuple(range(300, 300 + len(lens))), C, div, n_probe, rho, top_k, 1)
+    bt = gen_batch(wl)
+    oi = H.oracle_index(bt)
+    db = H.device_batch(bt)
+    _say(f"[build {name}] building on the GPU")
+    idx = ck.ctkvr_build_index(H.params_of(wl), db.q_prefill, db.cu_seqlens, True, db.k_pages, db.block_table,
+                               db.ctx_lens)
+    lists = ck.ctkvr_index_lists(idx)
+    cen = ck.ctkvr_index_centroids(idx)
+    ref_cen, ref_lst = oi.padded(wl)
+    assert np.array_equal(cen, ref_cen), "centroid table differs from the last C prompt queries"
+    for b, sq in enumerate(bt.seqs):
+        Cb = wl.centroids_of(sq.s)
+        assert np.array_equal(lists[b, :, :Cb], oi.lists[b]), f"lists of sequence {b} differ"
+    info = ck.ctkvr_index_info(idx)
+    assert info["index_bytes"] == wl.batch * wl.g * info["c_max"] * wl.list_len * 4
+    st = H.run_decode_parity(bt, oi, idx, db)   # decode on the GPU-built index
+    _say(f"[build {name}] ok {st}")
+    ck.ctkvr_free(idx)
+
+
+def test_exact_ties_duplicated_keys_and_centroids(ck):
+    wl = small_workload("ties", "bf16", 4, 2, (512,), (400,), 8, 0, 3, 64, 40, 2)
+    bt = gen_batch(wl)
+    sq = bt.seqs[0]
+    sq.K[:, 256:512] = sq.K[:, 0:256]
+    sq.V[:, 256:512] = sq.V[:, 0:256]
+    sq.q_tail[4:8] = sq.q_tail[0:4]
+    bt = Batch(wl=wl, seqs=[sq], paged=paginate([sq], wl.page_size, 9))
+    oi = H.oracle_index(bt)
+    db = H.device_batch(bt)
+    idx = ck.ctkvr_build_index(H.params_of(wl), db.q_prefill, db.cu_seqlens, True, db.k_pages, db.block_table,
+                               db.ctx_lens)
+    assert np.array_equal(ck.ctkvr_index_lists(idx)[0], oi.lists[0])
+    H.run_decode_parity(bt, oi, idx, db)
+    ck.ctkvr_free(idx)
+
+
+def test_lattice_inputs_all_scores_exact(ck):
+    wl = small_workload("lattice", "bf16", 8, 2, (1200,), (500,), 16, 0, 4, 90, 60, 3)
+    sq = gen_lattice_sequence(500, 1200, 8, 2, 128, 16, 3)
+    bt = Batch(wl=wl, seqs=[sq], paged=paginate([sq], wl.page_size, 5))
+    oi = H.oracle_index(bt)
+    db = H.device_batch(bt)
+    idx = ck.ctkvr_build_index(H.params_of(wl), db.q_prefill, db.cu_seqlens, True, db.k_pages, db.block_table,
+                               db.ctx_lens)
+    assert np.array_equal(ck.ctkvr_index_lists(idx)[0], oi.lists[0])
+    H.run_decode_parity(bt, oi, idx, db)
+    ck.ctkvr_free(idx)
+
+
+def test_cfg1_tiny_fp32_end_to_end(ck):
+    wl = workload("cfg1")
+    bt = gen_batch(wl)
+    oi = H.oracle_index(bt)
+    db = H.device_batch(bt)
+    idx = ck.ctkvr_build_index(H.params_of(wl), db.q_prefill, db.cu_seqlens, True, db.k_pages, db.block_table,
+                               db.ctx_lens)
+    assert np.array_equal(ck.ctkvr_index_lists(idx)[0], oi.lists[0])
+    st = H.run_decode_parity(bt, oi, idx, db)
+    _say(f"[cfg1] {st}")
+    ck.ctkvr_free(idx)
+
+
+def test_cfg2_32k_decode_on_oracle_index(ck):
+    wl = workload("cfg2")
+    _say("[cfg2] generating inputs")
+    bt = gen_batch(wl, n_decode=6)
+    _say("[cfg2] oracle index build (CPU)")
+    oi = H.oracle_index(bt)
+    db = H.device_batch(bt)
+    cen, lst = oi.padded(wl)
+    idx = ck.ctkvr_index_load(H.params_of(wl), db.ctx_lens, cen, lst)
+    _say("[cfg2] decode parity")
+    st = H.run_decode_parity(bt, oi, idx, db)
+    _say(f"[cfg2] ok {st}")
+    ck.ctkvr_free(idx)
+    _say("[cfg2] GPU exact build vs oracle lists")
+    idx2 = ck.ctkvr_build_index(H.params_of(wl), db.q_prefill, db.cu_seqlens, True, db.k_pages, db.block_table,
+                                db.ctx_lens)
+    assert np.array_equal(ck.ctkvr_index_lists(idx2)[0], oi.lists[0])
+    ck.ctkvr_free(idx2)
+
+
+def test_bad_max_pages_is_an_error_not_a_fault(ck):
+    import torch
+    wl = small_workload("err", "bf16", 4, 2, (300,), (1,), 8, 0, 2, 32, 16, 1)
+    bt = gen_batch(wl)
+    db = H.device_batch(bt)
+    oi = H.oracle_index(bt)
+    cen, lst = oi.padded(wl)
+    idx = ck.ctkvr_index_load(H.params_of(wl), db.ctx_lens, cen, lst)
+    out = torch.empty((1, 4, 128), dtype=torch.float32, device="cuda")
+    short = db.block_table[:, :5].contiguous()
+    with pytest.raises(ck.CtkvrError):
+        ck.ctkvr_decode_step(idx, H.to_dev(bt.seqs[0].q_decode[:1], wl), db.k_pages, db.v_pages, short, out)
+    bad = lst.copy()
+    bad[0, 0, 0, 0] = 300
+    with pytest.raises(ck.CtkvrError):
+        ck.ctkvr_index_load(H.params_of(wl), db.ctx_lens, cen, bad)
+    ck.ctkvr_free(idx)
