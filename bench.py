@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Benchmark of the CTkvr decode hot path on one MI355X.
+
+A "step" is one pass of the whole path -- centroid scoring, top-C' probe,
+list gather + dedup, exact q.K over the recalled keys, top-rho' rerank, sparse
+attention -- over one batch of decode queries of the named synthetic workload,
+with the index, the paged KV cache and all queries already resident in HBM.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg4|cfg1]
+
+prints ONE JSON line.  The CPU oracle is timed beside it on a bounded sample
+(reported baseline, not the target).  Everything is single-GPU: --gpus above 1
+exits with a message.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def step_bytes(wl, C, L_sum_per_seq, e):
+    """Algorithmic bytes one decode step must move for one sequence: centroid table
+    and inverse norms, the probed lists, each recalled key row once per KV head,
+    block-table entries, the selected value rows, q in and o out."""
+    h, g, d = wl.h, wl.g, wl.d
+    return (h * C * d * e + h * C * 4 + g * wl.n_probe * wl.list_len * 4 + L_sum_per_seq * d * e
+            + (L_sum_per_seq + g * wl.top_k) * 4 + g * wl.top_k * d * e + 2 * h * d * 4)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--mode", default="graph", choices=["graph", "eager"])
+    ap.add_argument("--cpu-steps", type=int, default=None, help="decode steps of the CPU oracle sample (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2512_15550_amd as ck
+    from ctkvr_inputs import gen_batch, workload
+    from tests import harness as H   # device upload helpers only
+
+    ck.load_library()
+    torch.cuda.set_device(0)
+    wl = workload(args.workload)
+    K = args.steps if args.steps is not None else max(1, wl.n_decode)
+    W = args.warmup
+    n_q = max(1, min(wl.n_decode, K))
+    t0 = time.time()
+    bt = gen_batch(wl, n_decode=n_q)
+    db = H.device_batch(bt)
+    B, h, g, d = wl.batch, wl.h, wl.g, wl.d
+    e = 2 if wl.dtype == "bf16" else 4
+    q_all = H.to_dev(np.stack([np.stack([sq.q_decode[i] for sq in bt.seqs]) for i in range(n_q)]), wl)  # [n_q][B][h][d]
+    t_gen = time.time() - t0
+
+    torch.cuda.synchronize()
+    t0 = time.time()
+    idx = ck.ctkvr_build_index(H.params_of(wl), db.q_prefill, db.cu_seqlens, True, db.k_pages, db.block_table,
+                               db.ctx_lens)
+    torch.cuda.synchronize()
+    build_ms = (time.time() - t0) * 1e3
+
+    out = torch.empty((B, h, d), dtype=torch.float32, device="cuda")
+    ncand = torch.zeros((K, B, g), dtype=torch.int32, device="cuda")
+
+    def run_steps(n, first=0, record=True):
+        for i in range(n):
+            ck.ctkvr_decode_step(idx, q_all[(first + i) % n_q], db.k_pages, db.v_pages, db.block_table, out,
+                                 out_ncand=ncand[i] if record else None)
+
+    # ---- warm-up -----------------------------------------------------------------
+    run_steps(W, record=False)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps -------------------------------------------
+    mode = args.mode
+    graph = None
+    if mode == "graph":
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph, stream=side):
+                    run_steps(K)
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            graph.replay()            # untimed: first replay uploads the graph
+            torch.cuda.synchronize()
+        except Exception as exc:      # capture not possible: time plain launches instead
+            print(f"bench.py: graph capture failed ({exc}); timing eager launches", file=sys.stderr)
+            graph, mode = None, "eager"
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    if graph is not None:
+        graph.replay()
+    else:
+        run_steps(K)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    us_per_step = dt / K * 1e6
+    out_timed = out.clone()
+    L = ncand.cpu().numpy().astype(np.int64)          # [K][B][g]
+
+    # the last step's output must equal an eager run of the same query (graph replays are checked, not trusted)
+    ck.ctkvr_decode_step(idx, q_all[(K - 1) % n_q], db.k_pages, db.v_pages, db.block_table, out)
+    torch.cuda.synchronize()
+    if not torch.equal(out, out_timed):
+        raise SystemExit("bench.py: timed-region output differs from an eager re-run of the same step")
+
+    # ---- per-kernel durations with HIP events on the launch stream, same K steps ----
+    ck.ctkvr_profile_enable(idx, K)
+    run_steps(K, record=False)
+    stage_ms = ck.ctkvr_profile_collect(idx, K)
+    ck.ctkvr_profile_enable(idx, 0)
+    stage_us = {n: float(stage_ms[:, i].mean() * 1e3) for i, n in enumerate(ck.STAGE_NAMES)}
+
+    # ---- bytes --------------------------------------------------------------------
+    L_step = L.sum(axis=2)                             # [K][B] recalled keys per sequence (all KV heads)
+    bytes_step = np.array([sum(step_bytes(wl, wl.centroids_of(s), int(L_step[k, b]), e)
+                               for b, s in enumerate(wl.ctx_lens)) for k in range(K)], dtype=np.float64)
+    achieved = float(bytes_step.mean() / (dt / K)) / 1e9
+    score_bytes = float(L.sum(axis=(1, 2)).mean()) * (d * e + 8)   # key row + its id + its block-table entry
+    score_gbps = score_bytes / (stage_us["score"] * 1e-6) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_score_{wl.name}.json")
+    if os.path.exists(tpath):
+        with open(tpath) as fh:
+            traffic = json.load(fh).get("traffic_bytes_per_launch")
+
+    # ---- CPU oracle on a bounded sample (reported baseline) -------------------------
+    cpu = None
+    n_cpu = args.cpu_steps if args.cpu_steps is not None else {"cfg1": 4, "cfg2": 64, "cfg3": 2, "cfg4": 2}.get(wl.name, 4)
+    if n_cpu > 0:
+        import oracle
+        nb = B if wl.name in ("cfg1", "cfg2") else 1   # long configs: first sequence only, scaled to the batch
+        t0 = time.time()
+        Qc = [oracle.centroids_last_c(sq.q_tail, wl.centroids_of(sq.s)) for sq in bt.seqs[:nb]]
+        if wl.name in ("cfg1", "cfg2"):
+            lists = [oracle.build_lists(sq.K, q, wl.list_len) for sq, q in zip(bt.seqs[:nb], Qc)]
+        else:   # building the full oracle index would take minutes: only the probed lists are built, untimed
+            lists = None
+        t_obuild = time.time() - t0
+        n_cpu = min(n_cpu, n_q)
+        t_dec = 0.0
+        for i in range(n_cpu):
+            for b in range(nb):
+                sq = bt.seqs[b]
+                qv = sq.q_decode[i]
+                if lists is not None:
+                    t1 = time.perf_counter()
+                    oracle.decode_step(qv, sq.K, sq.V, Qc[b], lists[b], wl.n_probe, wl.top_k)
+                    t_dec += time.perf_counter() - t1
+                else:
+                    t1 = time.perf_counter()
+                    cosv, probe = oracle.recall(qv, Qc[b], g, wl.n_probe)
+                    t_dec += time.perf_counter() - t1
+                    pairs = np.array([[kv, j] for kv in range(g) for j in probe[kv]], np.int32)
+                    lst = np.zeros((g, Qc[b].shape[1], wl.list_len), np.int32)
+                    built = oracle.build_lists(sq.K, Qc[b], wl.list_len, pairs=pairs)
+                    for (kv, j), row in zip(pairs, built):
+                        lst[kv, j] = row
+                    t1 = time.perf_counter()
+                    oracle.rerank_attend(qv, sq.K, sq.V, lst, probe, wl.top_k)
+                    t_dec += time.perf_counter() - t1
+        cpu_us = t_dec / n_cpu * 1e6 * (B / nb)
+        cpu = {"value": cpu_us, "unit": "us/step", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"{n_cpu} decode steps of {wl.name} on {nb} of {B} sequences"
+                         + ("" if nb == B else f", scaled x{B // nb}") + f"; oracle index build {t_obuild:.1f} s not included"}
+
+    rec = {
+        "metric": "decode retrieval+sparse-attn us/step (and achieved HBM GB/s)",
+        "value": us_per_step, "unit": "us/step", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": us_per_step / 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "storage_dtype": wl.dtype, "batch": B, "q_heads": h, "kv_heads": g,
+                   "ctx_lens": wl.ctx_lens if B <= 4 else [min(wl.ctx_lens), max(wl.ctx_lens)],
+                   "centroids": wl.n_centroids or f"ctx/{wl.centroid_div}", "n_probe": wl.n_probe,
+                   "list_len": wl.list_len, "top_k": wl.top_k, "launch": mode},
+        "tokens_per_s": B / (dt / K), "tokens_per_s_32_layers": B / (dt / K) / 32,
+        "achieved_GBps": achieved, "hbm_frac": achieved / HBM_PEAK_GBPS,
+        "algorithmic_bytes_per_step": float(bytes_step.mean()),
+        "L_recall_mean": float(L.mean()), "alpha": float(L.mean()) / (wl.n_probe * wl.list_len),
+        "index_build_ms": build_ms, "stage_us": stage_us,
+        "roofline": {"kernel": "score_kernel", "bound": "hbm", "achieved": score_gbps, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": score_gbps / HBM_PEAK_GBPS, "traffic": traffic,
+                     "bytes_per_launch": score_bytes, "avg_us": stage_us["score"]},
+        "cpu_baseline": cpu,
+        "input_gen_s": t_gen,
+    }
+    ck.ctkvr_free(idx)
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()
