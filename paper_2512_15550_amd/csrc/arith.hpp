@@ -186,32 +186,68 @@ template <int NT> __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v
 // ---- block-wide top-k selection ---------------------------------------------------
 // Among keys key(i), i in [0, n), pick the k largest, ties towards the lowest i,
 // and call emit(pos, i) with pos = rank of i among the picked in ascending i.
-// One block of NT threads; s_hist needs 2048 + NT/64 + 8 words.  Returns
-// min(n, k) to every thread.
+// One block of NT threads; s_hist needs 2048 + 64 words.  Returns min(n, k) to
+// every thread.
+//
+// Layout: wave w owns the contiguous ids [w*per, (w+1)*per), lane-strided inside,
+// per = a multiple of 64 covering n/NW.  With KPT > 0 each thread keeps its keys
+// in KPT registers (needs n <= NT*KPT) and key() is called once per id; with
+// KPT == 0 key() is called again in every pass.
 //
 // Method: MSB-first radix select on 11-bit digits, starting at the highest bit in
 // which the keys differ at all (one min/max pass), which finds the k-th largest
 // key T and how many keys equal to T still belong to the pick; then an ordered
-// compaction: each wave owns a contiguous range of i, counts, and after one scan
-// over the wave totals writes its picks in place -- no atomics decide an order.
-template <int NT, typename KeyFn, typename EmitFn>
+// compaction: each wave counts its range, one scan over the wave totals, and
+// every wave writes its picks in place with ballot ranks -- no atomics decide
+// an order.
+template <int NT, int KPT, typename KeyFn, typename EmitFn>
 __device__ int block_select_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t *s_hist)
 {
     constexpr int NW = NT / 64;
     const int tid = threadIdx.x;
-    uint32_t *s_aux = s_hist + 2048;   // [0] lo, [1] hi, [2] bin, [3] remaining ; scan scratch after that
-    uint32_t *s_scan = s_aux + 4;
+    const int wv = tid >> 6, ln = lane_id();
+    uint32_t *s_aux = s_hist + 2048;   // [0] lo, [1] hi, [2] bin, [3] remaining
+    uint32_t *s_scan = s_aux + 4;      // NW + 1 words of scan scratch, then 2*NW wave counts
     if (k >= n) {
         for (int i = tid; i < n; i += NT) emit(i, i);
         return n;
     }
+    const int per = ((n + NW - 1) / NW + 63) & ~63;
+    const int beg = wv * per;
+    const int end = min(n, beg + per);
+    uint32_t kreg[KPT > 0 ? KPT : 1];
+    if constexpr (KPT > 0) {
+#pragma unroll
+        for (int it = 0; it < KPT; ++it) {
+            int i = beg + it * 64 + ln;
+            kreg[it] = (i < end) ? key(i) : 0u;
+        }
+    }
+    // f(i, valid, key) for every slot of this thread, wave-uniform trip count
+    auto for_slots = [&](auto f) __attribute__((always_inline)) {
+        if constexpr (KPT > 0) {
+#pragma unroll
+            for (int it = 0; it < KPT; ++it) {
+                if (beg + it * 64 >= end) break;
+                int i = beg + it * 64 + ln;
+                f(i, i < end, kreg[it]);
+            }
+        } else {
+            for (int base = beg; base < end; base += 64) {
+                int i = base + ln;
+                bool valid = i < end;
+                f(i, valid, valid ? key(i) : 0u);
+            }
+        }
+    };
     // pass 0: range of the keys
     uint32_t lo = 0xffffffffu, hi = 0u;
-    for (int i = tid; i < n; i += NT) {
-        uint32_t kk = key(i);
-        lo = min(lo, kk);
-        hi = max(hi, kk);
-    }
+    for_slots([&](int, bool valid, uint32_t kk) {
+        if (valid) {
+            lo = min(lo, kk);
+            hi = max(hi, kk);
+        }
+    });
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) {
         lo = min(lo, (uint32_t)__shfl_xor(lo, o));
@@ -220,21 +256,17 @@ __device__ int block_select_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t 
     __syncthreads();
     if (tid == 0) { s_aux[0] = 0xffffffffu; s_aux[1] = 0u; }
     __syncthreads();
-    if (lane_id() == 0) { atomicMin(&s_aux[0], lo); atomicMax(&s_aux[1], hi); }
+    if (ln == 0) { atomicMin(&s_aux[0], lo); atomicMax(&s_aux[1], hi); }
     __syncthreads();
     lo = s_aux[0];
     hi = s_aux[1];
-    uint32_t prefix = 0, pmask = 0;
+    uint32_t prefix = hi, pmask = 0xffffffffu;
     uint32_t remaining = (uint32_t)k;
     int bit = 0;   // number of still undecided low bits
     if (lo != hi) {
-        int top = 31 - __clz((int)(lo ^ hi));
-        bit = top + 1;
+        bit = 32 - __clz((int)(lo ^ hi));
         pmask = (bit >= 32) ? 0u : ~((1u << bit) - 1u);
         prefix = hi & pmask;
-    } else {
-        prefix = hi;
-        pmask = 0xffffffffu;
     }
     while (bit > 0) {
         const int w = bit < 11 ? bit : 11;
@@ -242,12 +274,11 @@ __device__ int block_select_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t 
         const uint32_t dmask = (1u << w) - 1u;
         const int nbins = 1 << w;
         __syncthreads();
-        for (int i = tid; i < 2048; i += NT) s_hist[i] = 0;
+        for (int i = tid; i < nbins; i += NT) s_hist[i] = 0;
         __syncthreads();
-        for (int i = tid; i < n; i += NT) {
-            uint32_t kk = key(i);
-            if ((kk & pmask) == prefix) atomicAdd(&s_hist[(kk >> shift) & dmask], 1u);
-        }
+        for_slots([&](int, bool valid, uint32_t kk) {
+            if (valid && (kk & pmask) == prefix) atomicAdd(&s_hist[(kk >> shift) & dmask], 1u);
+        });
         __syncthreads();
         // walk the bins from the top: thread t owns the BPT bins below nbins - BPT*t
         constexpr int BPT = 2048 / NT;
@@ -278,41 +309,33 @@ __device__ int block_select_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t 
     }
     const uint32_t T = prefix;
     const uint32_t need_eq = remaining;
-    // ordered compaction; wave wv owns [wv*per, min(n, (wv+1)*per))
-    const int wv = tid >> 6, ln = lane_id();
-    const int per = ((n + NW - 1) / NW + 63) & ~63;
-    const int beg = wv * per;
-    const int end = min(n, beg + per);
+    // ordered compaction
     uint32_t cgt = 0, ceq = 0;
-    for (int i = beg + ln; i < end; i += 64) {
-        uint32_t kk = key(i);
-        cgt += (kk > T);
-        ceq += (kk == T);
-    }
+    for_slots([&](int, bool valid, uint32_t kk) {
+        cgt += (valid && kk > T);
+        ceq += (valid && kk == T);
+    });
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) {
         cgt += __shfl_xor(cgt, o);
         ceq += __shfl_xor(ceq, o);
     }
-    // exclusive scan over waves of (gt, eq) counts, done by every thread redundantly from shared memory
+    uint32_t *s_cnt = s_scan + NW + 1;
     __syncthreads();
-    if (ln == 0) { s_hist[2 * wv] = cgt; s_hist[2 * wv + 1] = ceq; }
+    if (ln == 0) { s_cnt[2 * wv] = cgt; s_cnt[2 * wv + 1] = ceq; }
     __syncthreads();
     uint32_t run_gt = 0, run_eq = 0;
-    for (int q = 0; q < wv; ++q) { run_gt += s_hist[2 * q]; run_eq += s_hist[2 * q + 1]; }
-    for (int base = beg; base < end; base += 64) {
-        int i = base + ln;
-        bool in = i < end;
-        uint32_t kk = in ? key(i) : 0u;
-        bool gt = in && kk > T, eq = in && kk == T;
+    for (int q = 0; q < wv; ++q) { run_gt += s_cnt[2 * q]; run_eq += s_cnt[2 * q + 1]; }
+    const uint64_t below = (1ull << ln) - 1ull;
+    for_slots([&](int i, bool valid, uint32_t kk) {
+        bool gt = valid && kk > T, eq = valid && kk == T;
         uint64_t mg = __ballot(gt), me = __ballot(eq);
-        uint64_t below = (1ull << ln) - 1ull;
         uint32_t gt_before = run_gt + (uint32_t)__popcll(mg & below);
         uint32_t eq_before = run_eq + (uint32_t)__popcll(me & below);
         if (gt || (eq && eq_before < need_eq)) emit((int)(gt_before + min(eq_before, need_eq)), i);
         run_gt += (uint32_t)__popcll(mg);
         run_eq += (uint32_t)__popcll(me);
-    }
+    });
     return k;
 }
 

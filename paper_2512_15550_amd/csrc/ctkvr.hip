@@ -59,9 +59,9 @@ struct ctkvr_index {
     // decode workspace
     float *cos = nullptr;
     int32_t *probe = nullptr, *cand = nullptr, *ncand = nullptr, *sel = nullptr, *nsel = nullptr;
+    uint32_t *crow = nullptr, *srow = nullptr, *done = nullptr;
     float *z = nullptr, *zsel = nullptr, *po = nullptr, *pm = nullptr, *pl = nullptr;
     uint32_t *m_key = nullptr;
-    unsigned long long *S = nullptr;
     size_t recall_lds = 0;
     // per-kernel timing
     std::vector<hipEvent_t> events;
@@ -125,6 +125,7 @@ int check_params(const ctkvr_params *p, const int32_t *ctx_lens)
         if (s < 1 || s > (1 << 20)) return fail(s < 1 ? CTKVR_EINVAL : CTKVR_EUNSUPPORTED, "ctx_lens[%d] = %d outside 1..2^20", b, s);
         int C = p->n_centroids ? p->n_centroids : s / p->centroid_div;
         if (C < 1 || C > s) return fail(CTKVR_EINVAL, "sequence %d: %d centroids for %d tokens", b, C, s);
+        if (C > 8192) return fail(CTKVR_EUNSUPPORTED, "sequence %d: %d centroids > 8192", b, C);
         if (p->n_probe > C) return fail(CTKVR_EINVAL, "sequence %d: n_probe %d > centroids %d", b, p->n_probe, C);
         if (p->list_len > s) return fail(CTKVR_EINVAL, "sequence %d: list_len %d > ctx_len %d", b, p->list_len, s);
     }
@@ -170,7 +171,9 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
     A(&ix->ncand, U * 4);
     A(&ix->z, U * ix->l_stride * ix->G * 4);
     A(&ix->m_key, U * ix->G * 4);
-    A(&ix->S, U * ix->G * 8);
+    A(&ix->crow, U * ix->l_stride * 4);
+    A(&ix->srow, U * p->top_k * 4);
+    A(&ix->done, U * 4);
     A(&ix->sel, U * p->top_k * 4);
     A(&ix->zsel, U * p->top_k * ix->G * 4);
     A(&ix->nsel, U * 4);
@@ -181,13 +184,16 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
         delete ix;
         return rc;
     }
-    ix->recall_lds = (size_t)(2080 + p->n_probe + (ix->s_max + 31) / 32) * 4;
+    ix->recall_lds = (size_t)(kSelLds + p->n_probe + (ix->s_max + 31) / 32) * 4;
     if (ix->recall_lds > 160 * 1024) {
         delete ix;
         return fail(CTKVR_EUNSUPPORTED, "context too long for the in-LDS candidate bitmap");
     }
-    hipError_t e = hipFuncSetAttribute((const void *)recall_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)ix->recall_lds);
+    hipError_t e = hipSuccess;
+    for (const void *fn : {(const void *)recall_kernel<1>, (const void *)recall_kernel<2>, (const void *)recall_kernel<4>,
+                           (const void *)recall_kernel<8>})
+        if (e == hipSuccess) e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ix->recall_lds);
+    if (e == hipSuccess) e = hipMemset(ix->done, 0, U * 4);
     if (e == hipSuccess) e = hipMemcpy(ix->d_ctx_lens, ix->ctx_lens.data(), (size_t)B * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(ix->d_n_cent, ix->n_cent.data(), (size_t)B * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(ix->lists, 0, U * ix->c_max * p->list_len * 4);
@@ -222,8 +228,8 @@ template <typename T> int launch_inv_norms(ctkvr_index *ix, hipStream_t st)
 }
 
 // Algorithm 1 lines 2-4 in the decode path's own arithmetic: for chunks of
-// (sequence, KV head, centroid) units, score all keys, sum the denominators,
-// select the top-rho.
+// (sequence, KV head, centroid) units, score all keys, then per unit sum the
+// denominators and select the top-rho.
 template <typename T, int G>
 int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block_table, int max_pages, hipStream_t st)
 {
@@ -233,51 +239,39 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
     chunk = std::min(chunk, 32768);
     float *z = nullptr;
     uint32_t *m_key = nullptr;
-    unsigned long long *S = nullptr;
     HIP_TRY(hipMalloc((void **)&z, (size_t)chunk * per_unit));
     hipError_t e1 = hipMalloc((void **)&m_key, (size_t)chunk * G * 4);
-    hipError_t e2 = hipMalloc((void **)&S, (size_t)chunk * G * 8);
     int rc = CTKVR_OK;
-    if (e1 != hipSuccess || e2 != hipSuccess) rc = fail(CTKVR_ENOMEM, "build scratch allocation failed");
+    if (e1 != hipSuccess) rc = fail(CTKVR_ENOMEM, "build scratch allocation failed");
     for (int u0 = 0; rc == CTKVR_OK && u0 < total_units; u0 += chunk) {
         const int nu = std::min(chunk, total_units - u0);
         Units u = decode_units(ix);
         u.build = 1;
         u.unit0 = u0;
-        fill_u32_kernel<<<dim3((unsigned)((nu * G * 3 + 255) / 256)), 256, 0, st>>>(m_key, 0u, (size_t)nu * G);
-        fill_u32_kernel<<<dim3((unsigned)((nu * G * 2 + 255) / 256)), 256, 0, st>>>((uint32_t *)S, 0u, (size_t)nu * G * 2);
+        fill_u32_kernel<<<dim3((unsigned)((nu * G + 255) / 256)), 256, 0, st>>>(m_key, 0u, (size_t)nu * G);
         ScoreArgs sa{};
         sa.u = u;
         sa.q = ix->centroids;
         sa.qrows = ix->c_max;
         sa.k = Paged{k_pages, block_table, max_pages, ix->page_shift};
         sa.ctx_lens = ix->d_ctx_lens;
-        sa.cand = nullptr;
+        sa.crow = nullptr;
         sa.ncand = nullptr;
         sa.l_stride = ix->s_max;
         sa.z = z;
         sa.m_key = m_key;
         sa.scale = ix->scale;
-        score_kernel<T, G><<<dim3((ix->s_max + 255) / 256, nu), 256, 0, st>>>(sa);
-        DenomArgs da{};
-        da.u = u;
-        da.ctx_lens = ix->d_ctx_lens;
-        da.ncand = nullptr;
-        da.l_stride = ix->s_max;
-        da.z = z;
-        da.m_key = m_key;
-        da.S = S;
-        denom_kernel<G><<<dim3((ix->s_max + 1023) / 1024, nu), 256, 0, st>>>(da);
+        score_kernel<T, G, 16><<<dim3((ix->s_max + 255) / 256, nu), 256, 0, st>>>(sa);
         SelectArgs se{};
         se.u = u;
         se.ctx_lens = ix->d_ctx_lens;
         se.ncand = nullptr;
         se.cand = nullptr;
+        se.crow = nullptr;
         se.l_stride = ix->s_max;
         se.top_k = ix->p.list_len;
         se.z = z;
         se.m_key = m_key;
-        se.S = S;
         se.sel = ix->lists;
         rerank_select_kernel<G><<<dim3(nu), 1024, 0, st>>>(se);
         hipError_t e = hipGetLastError();
@@ -287,7 +281,6 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
     if (rc == CTKVR_OK && es != hipSuccess) rc = fail(CTKVR_EHIP, "build: %s", hipGetErrorString(es));
     (void)hipFree(z);
     (void)hipFree(m_key);
-    (void)hipFree(S);
     return rc;
 }
 
@@ -316,12 +309,11 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     ca.n_cent = ix->d_n_cent;
     ca.cos = ix->cos;
     ca.m_key = ix->m_key;
-    ca.S = ix->S;
     ca.g = p.n_kv_heads;
     ca.h = p.n_q_heads;
     ca.c_max = ix->c_max;
     ix->mark(0, st);
-    centroid_cos_kernel<T, G><<<dim3((ix->c_max + 63) / 64, U), 256, 0, st>>>(ca);
+    centroid_cos_kernel<T, G><<<dim3((ix->c_max + 15) / 16, U), 256, 0, st>>>(ca);
     ix->mark(1, st);
 
     RecallArgs ra{};
@@ -329,8 +321,12 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     ra.lists = ix->lists;
     ra.n_cent = ix->d_n_cent;
     ra.ctx_lens = ix->d_ctx_lens;
+    ra.block_table = bt;
+    ra.max_pages = max_pages;
+    ra.page_shift = ix->page_shift;
     ra.probe = ix->probe;
     ra.cand = ix->cand;
+    ra.crow = ix->crow;
     ra.ncand = ix->ncand;
     ra.out_probe = out_probe;
     ra.out_ncand = out_ncand;
@@ -339,7 +335,14 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     ra.rho = p.list_len;
     ra.n_probe = p.n_probe;
     ra.l_stride = ix->l_stride;
-    recall_kernel<<<dim3(U), 1024, ix->recall_lds, st>>>(ra);
+    if (ix->c_max <= 1024)
+        recall_kernel<1><<<dim3(U), 1024, ix->recall_lds, st>>>(ra);
+    else if (ix->c_max <= 2048)
+        recall_kernel<2><<<dim3(U), 1024, ix->recall_lds, st>>>(ra);
+    else if (ix->c_max <= 4096)
+        recall_kernel<4><<<dim3(U), 1024, ix->recall_lds, st>>>(ra);
+    else
+        recall_kernel<8><<<dim3(U), 1024, ix->recall_lds, st>>>(ra);
     ix->mark(2, st);
 
     Units u = decode_units(ix);
@@ -349,61 +352,50 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     sa.qrows = 1;
     sa.k = Paged{k_pages, bt, max_pages, ix->page_shift};
     sa.ctx_lens = ix->d_ctx_lens;
-    sa.cand = ix->cand;
+    sa.crow = ix->crow;
     sa.ncand = ix->ncand;
     sa.l_stride = ix->l_stride;
     sa.z = ix->z;
     sa.m_key = ix->m_key;
     sa.scale = ix->scale;
-    score_kernel<T, G><<<dim3((ix->l_stride + 255) / 256, U), 256, 0, st>>>(sa);
+    score_kernel<T, G, 4><<<dim3((ix->l_stride + 63) / 64, U), 256, 0, st>>>(sa);
     ix->mark(3, st);
-
-    DenomArgs da{};
-    da.u = u;
-    da.ctx_lens = ix->d_ctx_lens;
-    da.ncand = ix->ncand;
-    da.l_stride = ix->l_stride;
-    da.z = ix->z;
-    da.m_key = ix->m_key;
-    da.S = ix->S;
-    denom_kernel<G><<<dim3((ix->l_stride + 1023) / 1024, U), 256, 0, st>>>(da);
-    ix->mark(4, st);
 
     SelectArgs se{};
     se.u = u;
     se.ctx_lens = ix->d_ctx_lens;
     se.ncand = ix->ncand;
     se.cand = ix->cand;
+    se.crow = ix->crow;
     se.l_stride = ix->l_stride;
     se.top_k = p.top_k;
     se.z = ix->z;
     se.m_key = ix->m_key;
-    se.S = ix->S;
     se.sel = ix->sel;
+    se.srow = ix->srow;
     se.zsel = ix->zsel;
     se.nsel = ix->nsel;
     se.out_sel = out_sel;
     rerank_select_kernel<G><<<dim3(U), 1024, 0, st>>>(se);
-    ix->mark(5, st);
+    ix->mark(4, st);
 
     AttnArgs aa{};
-    aa.v = Paged{v_pages, bt, max_pages, ix->page_shift};
+    aa.v_pages = v_pages;
     aa.g = p.n_kv_heads;
     aa.h = p.n_q_heads;
     aa.top_k = p.top_k;
     aa.nsplit = ix->nsplit;
-    aa.sel = ix->sel;
+    aa.srow = ix->srow;
     aa.nsel = ix->nsel;
     aa.zsel = ix->zsel;
     aa.po = ix->po;
     aa.pm = ix->pm;
     aa.pl = ix->pl;
+    aa.done = ix->done;
     aa.out = out;
     aa.out_lse = out_lse;
     sparse_attn_kernel<T, G><<<dim3(ix->nsplit, U), 256, 0, st>>>(aa);
-    ix->mark(6, st);
-    attn_merge_kernel<G><<<dim3(p.batch * p.n_q_heads), 128, 0, st>>>(aa);
-    ix->mark(7, st);
+    ix->mark(5, st);
     if (ix->prof_step < ix->prof_max) ix->prof_step++;
     HIP_TRY(hipGetLastError());
     return CTKVR_OK;

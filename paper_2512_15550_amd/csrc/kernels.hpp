@@ -1,8 +1,17 @@
-// gfx950 kernels of the CTkvr path.  Decode (Algorithm 2): centroid_cos ->
-// recall (probe select + list gather/dedup) -> score -> denom -> rerank_select ->
-// sparse_attn -> attn_merge.  The exact index build (Algorithm 1 lines 2-4) runs
-// score -> denom -> rerank_select with "the recalled set" = all s keys and the
-// centroid in the role of the query, which is literally the same formula.
+// gfx950 kernels of the CTkvr path.
+//
+// Decode step (Algorithm 2 lines 1-9), five launches:
+//   centroid_cos  lines 1-2   cosine to every centroid, max over the GQA group
+//   recall        lines 3-4   top-C' centroids; union of their lists as an
+//                             ascending id list plus each id's physical KV row
+//   score         line 5a     z = (q . k) * scale for the G heads over 64-id tiles
+//   rerank_select lines 5b-6  softmax denominators, max over the group of
+//                             log-softmax, top-rho' ids
+//   sparse_attn   lines 7-9   softmax(z_sel) . V_sel in 64-key splits; the last
+//                             split of a (sequence, KV head) merges them
+// The exact index build (Algorithm 1 lines 2-4) runs score -> rerank_select with
+// "the recalled set" = all s keys and the centroid in the role of the query,
+// which is literally the same formula.
 #pragma once
 #include "arith.hpp"
 
@@ -39,10 +48,43 @@ struct Paged {
     int max_pages, page_shift;
 };
 
-__device__ __forceinline__ uint32_t row_of(const Paged &pg, int g, int b, int kv, int t)
+// physical row (in units of 128 elements) of token t of sequence b, KV head kv
+__device__ __forceinline__ uint32_t row_of(const int32_t *block_table, int max_pages, int page_shift, int g, int b,
+                                           int kv, int t)
 {
-    int page = pg.block_table[(size_t)b * pg.max_pages + (t >> pg.page_shift)];
-    return (uint32_t)((page * g + kv) << pg.page_shift) + (uint32_t)(t & ((1 << pg.page_shift) - 1));
+    int page = block_table[(size_t)b * max_pages + (t >> page_shift)];
+    return (uint32_t)((page * g + kv) << page_shift) + (uint32_t)(t & ((1 << page_shift) - 1));
+}
+
+constexpr int kSelLds = 2048 + 64;   // words block_select_topk needs
+
+// the G scores of candidate i (rows of G floats, 4G-byte aligned)
+template <int G> __device__ __forceinline__ void load_z(const float *zb, int i, float (&v)[G])
+{
+    if constexpr (G == 1) {
+        v[0] = zb[i];
+    } else if constexpr (G == 2) {
+        float2 t = reinterpret_cast<const float2 *>(zb)[i];
+        v[0] = t.x; v[1] = t.y;
+    } else {
+#pragma unroll
+        for (int c = 0; c < G / 4; ++c) {
+            float4 t = reinterpret_cast<const float4 *>(zb)[(size_t)i * (G / 4) + c];
+            v[4 * c] = t.x; v[4 * c + 1] = t.y; v[4 * c + 2] = t.z; v[4 * c + 3] = t.w;
+        }
+    }
+}
+template <int G> __device__ __forceinline__ void store_z(float *zb, int i, const float (&v)[G])
+{
+    if constexpr (G == 1) {
+        zb[i] = v[0];
+    } else if constexpr (G == 2) {
+        reinterpret_cast<float2 *>(zb)[i] = make_float2(v[0], v[1]);
+    } else {
+#pragma unroll
+        for (int c = 0; c < G / 4; ++c)
+            reinterpret_cast<float4 *>(zb)[(size_t)i * (G / 4) + c] = make_float4(v[4 * c], v[4 * c + 1], v[4 * c + 2], v[4 * c + 3]);
+    }
 }
 
 // ------------------------------------------------------------------------------
@@ -55,7 +97,7 @@ __global__ void fill_u32_kernel(uint32_t *p, uint32_t v, size_t n)
 }
 
 // Algorithm 1 line 1: centroid j of sequence b, head hd = prompt query at position s_b - C_b + j.
-// q_prefill rows [row0_b + off_b + j][h][128] -> centroids [b][h][c_max][128]
+// q_prefill rows [first_row_b + j][h][128] -> centroids [b][h][c_max][128]
 template <typename T>
 __global__ void copy_centroids_kernel(const T *q_prefill, const int32_t *first_row /*[batch]*/, const int32_t *n_cent,
                                       int h, int c_max, T *centroids)
@@ -81,7 +123,8 @@ template <typename T> __global__ __launch_bounds__(256) void inv_norm_kernel(con
 
 // ------------------------------------------------------------------------------
 // Algorithm 2 lines 1-2: Cos_kv[b][kv][j] = max over the group of cos(q_h, c_{h,j})
-// grid (ceil(c_max/64), batch*g), 256 threads; also clears the step's accumulators.
+// grid (ceil(c_max/16), batch*g), 256 threads: one centroid per 16-lane group, its
+// G head rows loaded together.  Block x == 0 also clears the step's accumulators.
 // ------------------------------------------------------------------------------
 struct CosArgs {
     const void *q;            // [batch][h][128]
@@ -90,7 +133,6 @@ struct CosArgs {
     const int32_t *n_cent;
     float *cos;               // [batch*g][c_max]
     uint32_t *m_key;          // [batch*g][G]  cleared here
-    unsigned long long *S;    // [batch*g][G]  cleared here
     int g, h, c_max;
 };
 
@@ -100,83 +142,100 @@ template <typename T, int G> __global__ __launch_bounds__(256) void centroid_cos
     const int b = ul / a.g, kv = ul - b * a.g;
     const int C = a.n_cent[b];
     const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4;
-    if (blockIdx.x == 0 && tid < G) {
-        a.m_key[ul * G + tid] = 0u;
-        a.S[ul * G + tid] = 0ull;
-    }
-    const int tile0 = blockIdx.x * 64;
+    if (blockIdx.x == 0 && tid < G) a.m_key[ul * G + tid] = 0u;
+    const int tile0 = blockIdx.x * 16;
     if (tile0 >= C) return;
+    const int j = tile0 + grp;
+    const int jj = j < C ? j : C - 1;
     const T *qb = (const T *)a.q + ((size_t)b * a.h + kv * G) * kD;
-    float q[G][8], inv_q[G];
+    const T *cb = (const T *)a.centroids;
+    Chunk<T> cq[G], cc[G];
+    float inc[G];
 #pragma unroll
     for (int hh = 0; hh < G; ++hh) {
-        unpack(load_chunk(qb + (size_t)hh * kD, lane16), q[hh]);
-        inv_q[hh] = inv_norm_from_sq(group16_sum(lane_partial(q[hh], q[hh])));
+        size_t row = ((size_t)b * a.h + kv * G + hh) * a.c_max + jj;
+        cc[hh] = load_chunk(cb + row * kD, lane16);
+        cq[hh] = load_chunk(qb + (size_t)hh * kD, lane16);
+        inc[hh] = a.inv_norm_c[row];
     }
-    const T *cb = (const T *)a.centroids;
+    float best = -__builtin_huge_valf();
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        int j = tile0 + r * 16 + grp;
-        int jj = j < C ? j : C - 1;
-        float best = -__builtin_huge_valf();
-#pragma unroll
-        for (int hh = 0; hh < G; ++hh) {
-            size_t row = ((size_t)b * a.h + kv * G + hh) * a.c_max + jj;
-            float cx[8];
-            unpack(load_chunk(cb + row * kD, lane16), cx);
-            float dot = group16_sum(lane_partial(q[hh], cx));
-            float cs = (dot * a.inv_norm_c[row]) * inv_q[hh];
-            best = fmaxf(best, cs);
-        }
-        if (j < C && lane16 == 0) a.cos[(size_t)ul * a.c_max + j] = best;
+    for (int hh = 0; hh < G; ++hh) {
+        float q[8], cx[8];
+        unpack(cq[hh], q);
+        unpack(cc[hh], cx);
+        float inv_q = inv_norm_from_sq(group16_sum(lane_partial(q, q)));
+        float dot = group16_sum(lane_partial(q, cx));
+        float cs = (dot * inc[hh]) * inv_q;
+        best = fmaxf(best, cs);
     }
+    if (j < C && lane16 == 0) a.cos[(size_t)ul * a.c_max + j] = best;
 }
 
 // ------------------------------------------------------------------------------
 // Algorithm 2 lines 3-4: top-C' centroids, then the deduplicated union of their
-// lists as an ascending id list.  One block of 1024 threads per (sequence, KV head);
-// dynamic shared memory: select scratch (2048 + 32 words) + probe ids (n_probe) +
-// bitmap (ceil(s_max/32) words).
+// lists as an ascending id list, and the physical KV row of every id.  One block
+// of 1024 threads per (sequence, KV head); dynamic shared memory: select scratch
+// (kSelLds words) + probe ids (n_probe) + bitmap (ceil(s_max/32) words).
+// KPT: centroid keys per thread (C <= 1024*KPT).
 // ------------------------------------------------------------------------------
 struct RecallArgs {
     const float *cos;         // [batch*g][c_max]
     const int32_t *lists;     // [batch*g][c_max][rho]
     const int32_t *n_cent, *ctx_lens;
+    const int32_t *block_table;
+    int max_pages, page_shift;
     int32_t *probe;           // [batch*g][n_probe]
     int32_t *cand;            // [batch*g][l_stride]
+    uint32_t *crow;           // [batch*g][l_stride] physical row of cand[i]
     int32_t *ncand;           // [batch*g]
     int32_t *out_probe, *out_ncand;   // optional copies for the caller
     int g, c_max, rho, n_probe, l_stride;
 };
 
-__global__ __launch_bounds__(1024) void recall_kernel(RecallArgs a)
+template <int KPT> __global__ __launch_bounds__(1024) void recall_kernel(RecallArgs a)
 {
     extern __shared__ uint32_t smem[];
-    uint32_t *s_sel = smem;                      // 2048 + 32
-    int32_t *s_probe = (int32_t *)(smem + 2080);
-    uint32_t *s_bits = smem + 2080 + a.n_probe;
+    uint32_t *s_sel = smem;
+    int32_t *s_probe = (int32_t *)(smem + kSelLds);
+    uint32_t *s_bits = smem + kSelLds + a.n_probe;
     const int ul = blockIdx.x, tid = threadIdx.x;
-    const int b = ul / a.g;
+    const int b = ul / a.g, kv = ul - b * a.g;
     const int C = a.n_cent[b], s = a.ctx_lens[b];
     const float *cosv = a.cos + (size_t)ul * a.c_max;
-    // line 3
-    block_select_topk<1024>([&](int j) { return ordered_key(cosv[j]); }, C, a.n_probe,
-                            [&](int pos, int j) {
-                                s_probe[pos] = j;
-                                a.probe[(size_t)ul * a.n_probe + pos] = j;
-                                if (a.out_probe) a.out_probe[(size_t)ul * a.n_probe + pos] = j;
-                            },
-                            s_sel);
     const int W = (s + 31) >> 5;
     for (int w = tid; w < W; w += 1024) s_bits[w] = 0u;
+    // line 3
+    block_select_topk<1024, KPT>([&](int j) { return ordered_key(cosv[j]); }, C, a.n_probe,
+                                 [&](int pos, int j) {
+                                     s_probe[pos] = j;
+                                     a.probe[(size_t)ul * a.n_probe + pos] = j;
+                                     if (a.out_probe) a.out_probe[(size_t)ul * a.n_probe + pos] = j;
+                                 },
+                                 s_sel);
     __syncthreads();
     // line 4: mark every key id of the probed lists
     const int32_t *lb = a.lists + (size_t)ul * a.c_max * a.rho;
-    const int total = a.n_probe * a.rho;
-    for (int idx = tid; idx < total; idx += 1024) {
-        int p = idx / a.rho, r = idx - p * a.rho;
-        int t = lb[(size_t)s_probe[p] * a.rho + r];
-        atomicOr(&s_bits[t >> 5], 1u << (t & 31));
+    if ((a.rho & 3) == 0) {
+        const int rho4 = a.rho >> 2;
+        const int total4 = a.n_probe * rho4;
+#pragma unroll 4
+        for (int idx = tid; idx < total4; idx += 1024) {
+            int p = idx / rho4, r = idx - p * rho4;
+            int4 t = *reinterpret_cast<const int4 *>(lb + (size_t)s_probe[p] * a.rho + 4 * r);
+            atomicOr(&s_bits[t.x >> 5], 1u << (t.x & 31));
+            atomicOr(&s_bits[t.y >> 5], 1u << (t.y & 31));
+            atomicOr(&s_bits[t.z >> 5], 1u << (t.z & 31));
+            atomicOr(&s_bits[t.w >> 5], 1u << (t.w & 31));
+        }
+    } else {
+        const int total = a.n_probe * a.rho;
+#pragma unroll 4
+        for (int idx = tid; idx < total; idx += 1024) {
+            int p = idx / a.rho, r = idx - p * a.rho;
+            int t = lb[(size_t)s_probe[p] * a.rho + r];
+            atomicOr(&s_bits[t >> 5], 1u << (t & 31));
+        }
     }
     __syncthreads();
     // ordered expansion of the bitmap: thread t owns words [t*per, (t+1)*per)
@@ -204,12 +263,18 @@ __global__ __launch_bounds__(1024) void recall_kernel(RecallArgs a)
         a.ncand[ul] = (int32_t)tot;
         if (a.out_ncand) a.out_ncand[ul] = (int32_t)tot;
     }
+    __syncthreads();   // the ids written above are read back by other threads of this block
+    uint32_t *rows = a.crow + (size_t)ul * a.l_stride;
+#pragma unroll 4
+    for (int i = tid; i < (int)tot; i += 1024)
+        rows[i] = row_of(a.block_table, a.max_pages, a.page_shift, a.g, b, kv, out[i]);
 }
 
 // ------------------------------------------------------------------------------
 // Algorithm 2 line 5 / Algorithm 1 line 2, first half: z[h][i] = (q_h . k_i) * scale
-// for the G heads of the group over a tile of 256 ids, plus the running maximum
-// per head.  grid (ceil(l_stride/256), units), 256 threads.
+// for the G heads of the group over a tile of 16*R ids (R rows per 16-lane group,
+// all R loads issued before the first use), plus the running maximum per head.
+// grid (ceil(l_stride/(16*R)), units), 256 threads.
 // ------------------------------------------------------------------------------
 struct ScoreArgs {
     Units u;
@@ -217,29 +282,30 @@ struct ScoreArgs {
     int qrows;
     Paged k;
     const int32_t *ctx_lens;
-    const int32_t *cand;      // [units][l_stride] or nullptr = all ids 0..s-1
-    const int32_t *ncand;     // [units] (with cand)
+    const uint32_t *crow;     // [units][l_stride] physical rows of the recalled ids, or nullptr = all ids 0..s-1
+    const int32_t *ncand;     // [units] (with crow)
     int l_stride;
     float *z;                 // [units][l_stride][G]
     uint32_t *m_key;          // [units][G] ordered-key running max (atomicMax)
     float scale;
 };
 
-template <typename T, int G> __global__ __launch_bounds__(256) void score_kernel(ScoreArgs a)
+template <typename T, int G, int R> __global__ __launch_bounds__(256) void score_kernel(ScoreArgs a)
 {
+    constexpr int TILE = 16 * R;
     int b, kv, j;
     const int ul = blockIdx.y;
     if (!decode_unit(a.u, ul, b, kv, j)) return;
-    const int L = a.cand ? a.ncand[ul] : a.ctx_lens[b];
-    const int tile0 = blockIdx.x * 256;
+    const int L = a.crow ? a.ncand[ul] : a.ctx_lens[b];
+    const int tile0 = blockIdx.x * TILE;
     if (tile0 >= L) return;
-    __shared__ uint32_t s_row[256];
+    __shared__ uint32_t s_row[TILE];
     __shared__ uint32_t s_max[G];
     const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4;
-    {
+    if (tid < TILE) {
         int i = min(tile0 + tid, L - 1);
-        int t = a.cand ? a.cand[(size_t)ul * a.l_stride + i] : i;
-        s_row[tid] = row_of(a.k, a.u.g, b, kv, t);
+        s_row[tid] = a.crow ? a.crow[(size_t)ul * a.l_stride + i]
+                            : row_of(a.k.block_table, a.k.max_pages, a.k.page_shift, a.u.g, b, kv, i);
     }
     if (tid < G) s_max[tid] = 0u;
     float q[G][8];
@@ -248,19 +314,21 @@ template <typename T, int G> __global__ __launch_bounds__(256) void score_kernel
     for (int hh = 0; hh < G; ++hh) unpack(load_chunk(qb + (size_t)hh * a.qrows * kD, lane16), q[hh]);
     __syncthreads();
     const T *K = (const T *)a.k.pages;
+    Chunk<T> ck[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) ck[r] = load_chunk(K + (size_t)s_row[r * 16 + grp] * kD, lane16);
     float mx[G];
 #pragma unroll
     for (int hh = 0; hh < G; ++hh) mx[hh] = -__builtin_huge_valf();
     float *zb = a.z + (size_t)ul * a.l_stride * G;
-#pragma unroll 4
-    for (int r = 0; r < 16; ++r) {
-        const int row = r * 16 + grp;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
         float kx[8];
-        unpack(load_chunk(K + (size_t)s_row[row] * kD, lane16), kx);
+        unpack(ck[r], kx);
         float zz[G];
 #pragma unroll
         for (int hh = 0; hh < G; ++hh) zz[hh] = group16_sum(lane_partial(q[hh], kx)) * a.scale;
-        const int i = tile0 + row;
+        const int i = tile0 + r * 16 + grp;
         if (i < L) {
             float mine = zz[0];
 #pragma unroll
@@ -283,115 +351,53 @@ template <typename T, int G> __global__ __launch_bounds__(256) void score_kernel
 }
 
 // ------------------------------------------------------------------------------
-// softmax denominators: S[h] += sum_i floor(exp(z[h][i] - m[h]) * 2^40)
-// grid (ceil(l_stride/1024), units), 256 threads.
-// ------------------------------------------------------------------------------
-struct DenomArgs {
-    Units u;
-    const int32_t *ctx_lens, *ncand;   // ncand == nullptr => L = ctx_len
-    int l_stride;
-    const float *z;
-    const uint32_t *m_key;
-    unsigned long long *S;
-};
-
-template <int G> __global__ __launch_bounds__(256) void denom_kernel(DenomArgs a)
-{
-    int b, kv, j;
-    const int ul = blockIdx.y;
-    if (!decode_unit(a.u, ul, b, kv, j)) return;
-    const int L = a.ncand ? a.ncand[ul] : a.ctx_lens[b];
-    const int tile0 = blockIdx.x * 1024;
-    if (tile0 >= L) return;
-    const int tid = threadIdx.x;
-    __shared__ unsigned long long s_acc[4][G];
-    float m[G];
-    unsigned long long acc[G];
-#pragma unroll
-    for (int hh = 0; hh < G; ++hh) {
-        m[hh] = ordered_value(a.m_key[ul * G + hh]);
-        acc[hh] = 0ull;
-    }
-    const float *zb = a.z + (size_t)ul * a.l_stride * G;
-    const int end = min(L, tile0 + 1024);
-    for (int i = tile0 + tid; i < end; i += 256) {
-#pragma unroll
-        for (int hh = 0; hh < G; ++hh) acc[hh] += to_fixed40(exp_series(zb[(size_t)i * G + hh] - m[hh]));
-    }
-#pragma unroll
-    for (int hh = 0; hh < G; ++hh) {
-        unsigned long long v = acc[hh];
-#pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
-        if (lane_id() == 0) s_acc[tid >> 6][hh] = v;
-    }
-    __syncthreads();
-    if (tid < G) atomicAdd(&a.S[ul * G + tid], s_acc[0][tid] + s_acc[1][tid] + s_acc[2][tid] + s_acc[3][tid]);
-}
-
-// ------------------------------------------------------------------------------
-// Algorithm 2 lines 5-6 / Algorithm 1 lines 3-4: key_i = max_h log softmax_h(i),
-// top-k ids, ascending.  One block of 1024 threads per unit.
-//   decode: sel[unit][pos] = cand[i], zsel[unit][pos][G] = z[i][G], nsel[unit]
+// Algorithm 2 lines 5-6 / Algorithm 1 lines 3-4.  One block of 1024 threads per
+// unit: S[h] = sum_i floor(exp(z[h][i] - m[h]) * 2^40) (integer, order-free),
+// key_i = max_h ((z[h][i] - m[h]) - log S[h]), top-k ids ascending.
+//   decode: sel[unit][pos] = cand[i], srow[unit][pos] = crow[i],
+//           zsel[unit][pos][G] = z[i][G], nsel[unit]
 //   build : lists[(b*g+kv)*c_max + j][pos] = i
 // ------------------------------------------------------------------------------
 struct SelectArgs {
     Units u;
     const int32_t *ctx_lens, *ncand, *cand;
+    const uint32_t *crow;
     int l_stride, top_k;
     const float *z;
     const uint32_t *m_key;
-    const unsigned long long *S;
     int32_t *sel;       // decode [units][top_k] ; build: lists base
+    uint32_t *srow;     // decode [units][top_k]
     float *zsel;        // decode [units][top_k][G]
     int32_t *nsel;      // decode [units]
     int32_t *out_sel;   // optional copy for the caller
 };
 
-template <int G> __global__ __launch_bounds__(1024) void rerank_select_kernel(SelectArgs a)
+template <int G, int KPT, typename KeyFn>
+__device__ __forceinline__ void select_emit(const SelectArgs &a, int ul, int L, KeyFn key, const float *zb, uint32_t *s_sel)
 {
-    __shared__ uint32_t s_sel[2048 + 32];
-    __shared__ float s_m[G], s_ls[G];
-    int b, kv, j;
-    const int ul = blockIdx.x, tid = threadIdx.x;
-    if (!decode_unit(a.u, ul, b, kv, j)) return;
-    const int L = a.cand ? a.ncand[ul] : a.ctx_lens[b];
-    if (tid < G) {
-        s_m[tid] = ordered_value(a.m_key[ul * G + tid]);
-        s_ls[tid] = (float)log_fixed40(a.S[ul * G + tid]);
-    }
-    __syncthreads();
-    float m[G], ls[G];
-#pragma unroll
-    for (int hh = 0; hh < G; ++hh) {
-        m[hh] = s_m[hh];
-        ls[hh] = s_ls[hh];
-    }
-    const float *zb = a.z + (size_t)ul * a.l_stride * G;
-    auto key = [&](int i) {
-        float best = -__builtin_huge_valf();
-#pragma unroll
-        for (int hh = 0; hh < G; ++hh) best = fmaxf(best, (zb[(size_t)i * G + hh] - m[hh]) - ls[hh]);
-        return ordered_key(best);
-    };
+    const int tid = threadIdx.x;
     if (a.u.build) {
         int32_t *dst = a.sel + (size_t)(a.u.unit0 + ul) * a.top_k;
-        block_select_topk<1024>(key, L, a.top_k, [&](int pos, int i) { dst[pos] = i; }, s_sel);
+        block_select_topk<1024, KPT>(key, L, a.top_k, [&](int pos, int i) { dst[pos] = i; }, s_sel);
         return;
     }
     const int32_t *cb = a.cand + (size_t)ul * a.l_stride;
+    const uint32_t *rb = a.crow + (size_t)ul * a.l_stride;
     int32_t *dst = a.sel + (size_t)ul * a.top_k;
+    uint32_t *dstr = a.srow + (size_t)ul * a.top_k;
     int32_t *dst2 = a.out_sel ? a.out_sel + (size_t)ul * a.top_k : nullptr;
     float *zd = a.zsel + (size_t)ul * a.top_k * G;
-    int n = block_select_topk<1024>(key, L, a.top_k,
-                                    [&](int pos, int i) {
-                                        int t = cb[i];
-                                        dst[pos] = t;
-                                        if (dst2) dst2[pos] = t;
-#pragma unroll
-                                        for (int hh = 0; hh < G; ++hh) zd[(size_t)pos * G + hh] = zb[(size_t)i * G + hh];
-                                    },
-                                    s_sel);
+    int n = block_select_topk<1024, KPT>(key, L, a.top_k,
+                                         [&](int pos, int i) {
+                                             int t = cb[i];
+                                             dst[pos] = t;
+                                             dstr[pos] = rb[i];
+                                             if (dst2) dst2[pos] = t;
+                                             float zv[G];
+                                             load_z<G>(zb, i, zv);
+                                             store_z<G>(zd, pos, zv);
+                                         },
+                                         s_sel);
     for (int pos = n + tid; pos < a.top_k; pos += 1024) {
         dst[pos] = -1;
         if (dst2) dst2[pos] = -1;
@@ -399,18 +405,76 @@ template <int G> __global__ __launch_bounds__(1024) void rerank_select_kernel(Se
     if (tid == 0) a.nsel[ul] = n;
 }
 
+template <int G> __global__ __launch_bounds__(1024) void rerank_select_kernel(SelectArgs a)
+{
+    __shared__ uint32_t s_sel[kSelLds];
+    __shared__ unsigned long long s_S[G];
+    __shared__ float s_ls[G];
+    int b, kv, j;
+    const int ul = blockIdx.x, tid = threadIdx.x;
+    if (!decode_unit(a.u, ul, b, kv, j)) return;
+    const int L = a.cand ? a.ncand[ul] : a.ctx_lens[b];
+    float m[G], ls[G];
+    unsigned long long acc[G];
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+        m[hh] = ordered_value(a.m_key[ul * G + hh]);
+        acc[hh] = 0ull;
+    }
+    if (tid < G) s_S[tid] = 0ull;
+    __syncthreads();
+    const float *zb = a.z + (size_t)ul * a.l_stride * G;
+#pragma unroll 4
+    for (int i = tid; i < L; i += 1024) {
+        float zv[G];
+        load_z<G>(zb, i, zv);
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh) acc[hh] += to_fixed40(exp_series(zv[hh] - m[hh]));
+    }
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+        unsigned long long v = acc[hh];
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+        if (lane_id() == 0) atomicAdd(&s_S[hh], v);
+    }
+    __syncthreads();
+    if (tid < G) s_ls[tid] = (float)log_fixed40(s_S[tid]);
+    __syncthreads();
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) ls[hh] = s_ls[hh];
+    auto key = [&](int i) {
+        float zv[G];
+        load_z<G>(zb, i, zv);
+        float best = -__builtin_huge_valf();
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh) best = fmaxf(best, (zv[hh] - m[hh]) - ls[hh]);
+        return ordered_key(best);
+    };
+    if (L <= 1024 * 8)
+        select_emit<G, 8>(a, ul, L, key, zb, s_sel);
+    else if (L <= 1024 * 32)
+        select_emit<G, 32>(a, ul, L, key, zb, s_sel);
+    else
+        select_emit<G, 0>(a, ul, L, key, zb, s_sel);
+}
+
 // ------------------------------------------------------------------------------
 // Algorithm 2 lines 7-9: softmax(z_sel) . V_sel, split over chunks of 64 selected
-// keys; grid (nsplit, batch*g), 256 threads.  Partials are merged by attn_merge.
+// keys; grid (nsplit, batch*g), 256 threads.  Every split leaves an un-normalised
+// partial (o, max, sum); the split that finishes last for its (sequence, KV head)
+// merges them in split order and writes out / out_lse.
 // ------------------------------------------------------------------------------
 struct AttnArgs {
-    Paged v;
+    const void *v_pages;
     int g, h, top_k, nsplit;
-    const int32_t *sel, *nsel;
+    const uint32_t *srow;
+    const int32_t *nsel;
     const float *zsel;
     float *po;   // [batch*h][nsplit][128] un-normalised partial outputs
     float *pm;   // [batch*h][nsplit] partial maxima
     float *pl;   // [batch*h][nsplit] partial sums
+    uint32_t *done;   // [batch*g] splits finished, returns to 0
     float *out;  // [batch*h][128]
     float *out_lse;
 };
@@ -421,21 +485,33 @@ template <typename T, int G> __global__ __launch_bounds__(256) void sparse_attn_
     const int b = ul / a.g, kv = ul - b * a.g;
     const int nsel = a.nsel[ul];
     const int t0 = split * 64;
+    const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4, wv = tid >> 6, ln = tid & 63;
+    if (nsel == 0) {   // nothing recalled: defined output, no partials
+        if (split == 0)
+            for (int x = tid; x < G * kD; x += 256) {
+                a.out[((size_t)b * a.h + kv * G) * kD + x] = 0.0f;
+                if (a.out_lse && x < G) a.out_lse[(size_t)b * a.h + kv * G + x] = -__builtin_huge_valf();
+            }
+        return;
+    }
     if (t0 >= nsel) return;
     __shared__ float s_p[64][G];
     __shared__ uint32_t s_row[64];
     __shared__ float s_o[4][G][kD];
-    const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4, wv = tid >> 6, ln = tid & 63;
+    __shared__ uint32_t s_last;
     if (tid < 64) {
         int tok = t0 + tid;
         bool ok = tok < nsel;
-        int t = a.sel[(size_t)ul * a.top_k + (ok ? tok : t0)];
-        s_row[tid] = row_of(a.v, a.g, b, kv, t);
+        s_row[tid] = a.srow[(size_t)ul * a.top_k + (ok ? tok : t0)];
 #pragma unroll
         for (int hh = 0; hh < G; ++hh)
             s_p[tid][hh] = ok ? a.zsel[((size_t)ul * a.top_k + tok) * G + hh] : -__builtin_huge_valf();
     }
     __syncthreads();
+    const T *V = (const T *)a.v_pages;
+    Chunk<T> cv[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) cv[r] = load_chunk(V + (size_t)s_row[r * 16 + grp] * kD, lane16);
     if (wv == 0) {
 #pragma unroll
         for (int hh = 0; hh < G; ++hh) {
@@ -461,12 +537,11 @@ template <typename T, int G> __global__ __launch_bounds__(256) void sparse_attn_
     for (int hh = 0; hh < G; ++hh)
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[hh][e] = 0.0f;
-    const T *V = (const T *)a.v.pages;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int row = r * 16 + grp;
         float vx[8];
-        unpack(load_chunk(V + (size_t)s_row[row] * kD, lane16), vx);
+        unpack(cv[r], vx);
 #pragma unroll
         for (int hh = 0; hh < G; ++hh) {
             float p = s_p[row][hh];
@@ -495,34 +570,37 @@ template <typename T, int G> __global__ __launch_bounds__(256) void sparse_attn_
         float v = (s_o[0][hh][e] + s_o[1][hh][e]) + (s_o[2][hh][e] + s_o[3][hh][e]);
         a.po[(((size_t)b * a.h + kv * G + hh) * a.nsplit + split) * kD + e] = v;
     }
-}
-
-// grid (batch*h), 128 threads
-template <int G> __global__ __launch_bounds__(128) void attn_merge_kernel(AttnArgs a)
-{
-    const int head = blockIdx.x;
-    const int b = head / a.h, hq = head - b * a.h;
-    const int ul = b * a.g + hq / G;
-    const int nsel = a.nsel[ul];
+    // ---- last split of this (sequence, KV head) merges ---------------------------
     const int ns = (nsel + 63) >> 6;
-    const int e = threadIdx.x;
-    if (ns == 0) {
-        a.out[(size_t)head * kD + e] = 0.0f;
-        if (a.out_lse && e == 0) a.out_lse[head] = -__builtin_huge_valf();
-        return;
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t prev = atomicAdd(&a.done[ul], 1u);
+        s_last = (prev == (uint32_t)(ns - 1));
+        if (s_last) a.done[ul] = 0u;   // every split has arrived: ready for the next step
     }
-    const float *pm = a.pm + (size_t)head * a.nsplit;
-    const float *pl = a.pl + (size_t)head * a.nsplit;
-    float M = pm[0];
-    for (int s = 1; s < ns; ++s) M = fmaxf(M, pm[s]);
-    float l = 0.0f, o = 0.0f;
-    for (int s = 0; s < ns; ++s) {
-        float w = __expf(pm[s] - M);
-        l = __fmaf_rn(pl[s], w, l);
-        o = __fmaf_rn(a.po[((size_t)head * a.nsplit + s) * kD + e], w, o);
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    for (int x = tid; x < G * kD; x += 256) {
+        int hh = x / kD, e = x - hh * kD;
+        size_t head = (size_t)b * a.h + kv * G + hh;
+        const float *pm = a.pm + head * a.nsplit;
+        const float *pl = a.pl + head * a.nsplit;
+        const float *po = a.po + head * a.nsplit * kD + e;
+        float M = -__builtin_huge_valf();
+#pragma unroll 8
+        for (int s = 0; s < ns; ++s) M = fmaxf(M, pm[s]);
+        float l = 0.0f, o = 0.0f;
+#pragma unroll 8
+        for (int s = 0; s < ns; ++s) {
+            float w = __expf(pm[s] - M);
+            l = __fmaf_rn(pl[s], w, l);
+            o = __fmaf_rn(po[(size_t)s * kD], w, o);
+        }
+        a.out[head * kD + e] = o / l;
+        if (a.out_lse && e == 0) a.out_lse[head] = M + __logf(l);
     }
-    a.out[(size_t)head * kD + e] = o / l;
-    if (a.out_lse && e == 0) a.out_lse[head] = M + __logf(l);
 }
 
 }  // namespace ctkvr
