@@ -165,9 +165,10 @@ int ctkvr_index_last_candidates(const ctkvr_index *idx, int32_t *dst_host);
 /* ---- per-kernel timing (measurement aid) ----------------------------------- */
 /* The decode step runs CTKVR_N_STAGES kernels in this order:
  * 0 centroid cosine, 1 probe select + list gather/dedup, 2 key scoring over the
- * recalled ids, 3 softmax denominators + rerank select, 4 sparse attention with
- * the merge of its splits. */
-#define CTKVR_N_STAGES 5
+ * recalled ids, 3 softmax denominators, 4 rerank select, 5 sparse attention.
+ * While timing is enabled a seventh, empty kernel follows (stage 6): its figure is
+ * what a pair of events costs around a kernel that does nothing. */
+#define CTKVR_N_STAGES 7
 /* After this call every decode step on `idx` records a HIP event before its first
  * kernel and after each kernel, for up to max_steps steps (0 disables and frees
  * the events).  Recording adds work to the stream: use it for the breakdown, not

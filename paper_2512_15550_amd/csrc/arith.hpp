@@ -14,6 +14,18 @@
 
 namespace ctkvr {
 
+// Development aid (compiled in only with -DCTKVR_TRACE): block (0,0), thread 0 stamps
+// the 100 MHz wall clock into g_trace[slot].
+#ifdef CTKVR_TRACE
+__device__ long long g_trace[128];
+#define CTKVR_STAMP(slot)                                                        \
+    do {                                                                         \
+        if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) g_trace[slot] = wall_clock64(); \
+    } while (0)
+#else
+#define CTKVR_STAMP(slot) do { } while (0)
+#endif
+
 constexpr int kD = 128;          // head dimension
 constexpr int kFixShift = 40;    // softmax denominators are summed in 2^-40 fixed point
 
@@ -240,6 +252,7 @@ __device__ int block_select_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t 
             }
         }
     };
+    CTKVR_STAMP(32);
     // pass 0: range of the keys
     uint32_t lo = 0xffffffffu, hi = 0u;
     for_slots([&](int, bool valid, uint32_t kk) {
@@ -268,7 +281,11 @@ __device__ int block_select_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t 
         pmask = (bit >= 32) ? 0u : ~((1u << bit) - 1u);
         prefix = hi & pmask;
     }
+    CTKVR_STAMP(33);
+    int pass_ = 0;
     while (bit > 0) {
+        CTKVR_STAMP(34 + pass_);
+        ++pass_;
         const int w = bit < 11 ? bit : 11;
         const int shift = bit - w;
         const uint32_t dmask = (1u << w) - 1u;
@@ -309,6 +326,7 @@ __device__ int block_select_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t 
     }
     const uint32_t T = prefix;
     const uint32_t need_eq = remaining;
+    CTKVR_STAMP(38);
     // ordered compaction
     uint32_t cgt = 0, ceq = 0;
     for_slots([&](int, bool valid, uint32_t kk) {
@@ -326,6 +344,7 @@ __device__ int block_select_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t 
     __syncthreads();
     uint32_t run_gt = 0, run_eq = 0;
     for (int q = 0; q < wv; ++q) { run_gt += s_cnt[2 * q]; run_eq += s_cnt[2 * q + 1]; }
+    CTKVR_STAMP(39);
     const uint64_t below = (1ull << ln) - 1ull;
     for_slots([&](int i, bool valid, uint32_t kk) {
         bool gt = valid && kk > T, eq = valid && kk == T;
@@ -336,6 +355,7 @@ __device__ int block_select_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t 
         run_gt += (uint32_t)__popcll(mg);
         run_eq += (uint32_t)__popcll(me);
     });
+    CTKVR_STAMP(40);
     return k;
 }
 

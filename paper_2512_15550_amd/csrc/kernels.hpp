@@ -1,14 +1,14 @@
 // gfx950 kernels of the CTkvr path.
 //
-// Decode step (Algorithm 2 lines 1-9), five launches:
+// Decode step (Algorithm 2 lines 1-9), six launches:
 //   centroid_cos  lines 1-2   cosine to every centroid, max over the GQA group
 //   recall        lines 3-4   top-C' centroids; union of their lists as an
 //                             ascending id list plus each id's physical KV row
-//   score         line 5a     z = (q . k) * scale for the G heads over 64-id tiles
-//   rerank_select lines 5b-6  softmax denominators, max over the group of
-//                             log-softmax, top-rho' ids
-//   sparse_attn   lines 7-9   softmax(z_sel) . V_sel in 64-key splits; the last
-//                             split of a (sequence, KV head) merges them
+//   score         line 5a     z = (q . k) * scale for the G heads, running max
+//   denom         line 5b     softmax denominators, integer fixed point
+//   rerank_select lines 5c-6  max over the group of log-softmax, top-rho' ids
+//   sparse_attn   lines 7-9   softmax(z_sel) . V_sel, one block per slice of the
+//                             head dimension (no cross-block reduction)
 // The exact index build (Algorithm 1 lines 2-4) runs score -> rerank_select with
 // "the recalled set" = all s keys and the centroid in the role of the query,
 // which is literally the same formula.
@@ -133,6 +133,7 @@ struct CosArgs {
     const int32_t *n_cent;
     float *cos;               // [batch*g][c_max]
     uint32_t *m_key;          // [batch*g][G]  cleared here
+    unsigned long long *S;    // [batch*g][G]  cleared here
     int g, h, c_max;
 };
 
@@ -142,7 +143,11 @@ template <typename T, int G> __global__ __launch_bounds__(256) void centroid_cos
     const int b = ul / a.g, kv = ul - b * a.g;
     const int C = a.n_cent[b];
     const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4;
-    if (blockIdx.x == 0 && tid < G) a.m_key[ul * G + tid] = 0u;
+    if (blockIdx.x == 0 && tid < G) {
+        a.m_key[ul * G + tid] = 0u;
+        a.S[ul * G + tid] = 0ull;
+    }
+    CTKVR_STAMP(0);
     const int tile0 = blockIdx.x * 16;
     if (tile0 >= C) return;
     const int j = tile0 + grp;
@@ -170,13 +175,15 @@ template <typename T, int G> __global__ __launch_bounds__(256) void centroid_cos
         best = fmaxf(best, cs);
     }
     if (j < C && lane16 == 0) a.cos[(size_t)ul * a.c_max + j] = best;
+    CTKVR_STAMP(1);
 }
 
 // ------------------------------------------------------------------------------
 // Algorithm 2 lines 3-4: top-C' centroids, then the deduplicated union of their
 // lists as an ascending id list, and the physical KV row of every id.  One block
 // of 1024 threads per (sequence, KV head); dynamic shared memory: select scratch
-// (kSelLds words) + probe ids (n_probe) + bitmap (ceil(s_max/32) words).
+// (kSelLds words) + probe ids (n_probe) + bitmap (ceil(s_max/32) words) + the
+// sequence's block-table row when it fits (bt_lds words, else 0).
 // KPT: centroid keys per thread (C <= 1024*KPT).
 // ------------------------------------------------------------------------------
 struct RecallArgs {
@@ -191,6 +198,8 @@ struct RecallArgs {
     int32_t *ncand;           // [batch*g]
     int32_t *out_probe, *out_ncand;   // optional copies for the caller
     int g, c_max, rho, n_probe, l_stride;
+    int bitmap_words;         // words reserved for the bitmap
+    int bt_lds;               // block-table entries staged in shared memory (0: read from global)
 };
 
 template <int KPT> __global__ __launch_bounds__(1024) void recall_kernel(RecallArgs a)
@@ -199,12 +208,17 @@ template <int KPT> __global__ __launch_bounds__(1024) void recall_kernel(RecallA
     uint32_t *s_sel = smem;
     int32_t *s_probe = (int32_t *)(smem + kSelLds);
     uint32_t *s_bits = smem + kSelLds + a.n_probe;
+    int32_t *s_bt = (int32_t *)(s_bits + a.bitmap_words);
     const int ul = blockIdx.x, tid = threadIdx.x;
     const int b = ul / a.g, kv = ul - b * a.g;
     const int C = a.n_cent[b], s = a.ctx_lens[b];
     const float *cosv = a.cos + (size_t)ul * a.c_max;
     const int W = (s + 31) >> 5;
+    const int npages = (s + (1 << a.page_shift) - 1) >> a.page_shift;
+    CTKVR_STAMP(8);
     for (int w = tid; w < W; w += 1024) s_bits[w] = 0u;
+    if (a.bt_lds)
+        for (int pg = tid; pg < npages; pg += 1024) s_bt[pg] = a.block_table[(size_t)b * a.max_pages + pg];
     // line 3
     block_select_topk<1024, KPT>([&](int j) { return ordered_key(cosv[j]); }, C, a.n_probe,
                                  [&](int pos, int j) {
@@ -214,12 +228,13 @@ template <int KPT> __global__ __launch_bounds__(1024) void recall_kernel(RecallA
                                  },
                                  s_sel);
     __syncthreads();
+    CTKVR_STAMP(9);
     // line 4: mark every key id of the probed lists
     const int32_t *lb = a.lists + (size_t)ul * a.c_max * a.rho;
     if ((a.rho & 3) == 0) {
         const int rho4 = a.rho >> 2;
         const int total4 = a.n_probe * rho4;
-#pragma unroll 4
+#pragma unroll 8
         for (int idx = tid; idx < total4; idx += 1024) {
             int p = idx / rho4, r = idx - p * rho4;
             int4 t = *reinterpret_cast<const int4 *>(lb + (size_t)s_probe[p] * a.rho + 4 * r);
@@ -230,7 +245,7 @@ template <int KPT> __global__ __launch_bounds__(1024) void recall_kernel(RecallA
         }
     } else {
         const int total = a.n_probe * a.rho;
-#pragma unroll 4
+#pragma unroll 8
         for (int idx = tid; idx < total; idx += 1024) {
             int p = idx / a.rho, r = idx - p * a.rho;
             int t = lb[(size_t)s_probe[p] * a.rho + r];
@@ -238,6 +253,7 @@ template <int KPT> __global__ __launch_bounds__(1024) void recall_kernel(RecallA
         }
     }
     __syncthreads();
+    CTKVR_STAMP(10);
     // ordered expansion of the bitmap: thread t owns words [t*per, (t+1)*per)
     const int per = (W + 1023) >> 10;
     uint32_t cnt = 0;
@@ -248,6 +264,8 @@ template <int KPT> __global__ __launch_bounds__(1024) void recall_kernel(RecallA
     uint32_t tot;
     uint32_t at = block_excl_scan<1024>(cnt, s_sel, &tot);
     int32_t *out = a.cand + (size_t)ul * a.l_stride;
+    uint32_t *rows = a.crow + (size_t)ul * a.l_stride;
+    const int pmask = (1 << a.page_shift) - 1;
     for (int q = 0; q < per; ++q) {
         int w = tid * per + q;
         if (w < W) {
@@ -255,7 +273,10 @@ template <int KPT> __global__ __launch_bounds__(1024) void recall_kernel(RecallA
             while (m) {
                 int bit = __ffs((int)m) - 1;
                 m &= m - 1;
-                out[at++] = (w << 5) + bit;
+                int t = (w << 5) + bit;
+                out[at] = t;
+                if (a.bt_lds) rows[at] = (uint32_t)((s_bt[t >> a.page_shift] * a.g + kv) << a.page_shift) + (uint32_t)(t & pmask);
+                ++at;
             }
         }
     }
@@ -263,18 +284,21 @@ template <int KPT> __global__ __launch_bounds__(1024) void recall_kernel(RecallA
         a.ncand[ul] = (int32_t)tot;
         if (a.out_ncand) a.out_ncand[ul] = (int32_t)tot;
     }
-    __syncthreads();   // the ids written above are read back by other threads of this block
-    uint32_t *rows = a.crow + (size_t)ul * a.l_stride;
+    CTKVR_STAMP(11);
+    if (!a.bt_lds) {
+        __syncthreads();   // the ids written above are read back by other threads of this block
 #pragma unroll 4
-    for (int i = tid; i < (int)tot; i += 1024)
-        rows[i] = row_of(a.block_table, a.max_pages, a.page_shift, a.g, b, kv, out[i]);
+        for (int i = tid; i < (int)tot; i += 1024)
+            rows[i] = row_of(a.block_table, a.max_pages, a.page_shift, a.g, b, kv, out[i]);
+    }
+    CTKVR_STAMP(12);
 }
 
 // ------------------------------------------------------------------------------
 // Algorithm 2 line 5 / Algorithm 1 line 2, first half: z[h][i] = (q_h . k_i) * scale
-// for the G heads of the group over a tile of 16*R ids (R rows per 16-lane group,
-// all R loads issued before the first use), plus the running maximum per head.
-// grid (ceil(l_stride/(16*R)), units), 256 threads.
+// for the G heads of the group, plus the running maximum per head.  A block walks
+// tiles of 16*R ids (R rows per 16-lane group, all R loads issued before the first
+// use) with stride gridDim.x.  grid (nbx, units), 256 threads.
 // ------------------------------------------------------------------------------
 struct ScoreArgs {
     Units u;
@@ -297,46 +321,50 @@ template <typename T, int G, int R> __global__ __launch_bounds__(256) void score
     const int ul = blockIdx.y;
     if (!decode_unit(a.u, ul, b, kv, j)) return;
     const int L = a.crow ? a.ncand[ul] : a.ctx_lens[b];
-    const int tile0 = blockIdx.x * TILE;
-    if (tile0 >= L) return;
+    if ((int)blockIdx.x * TILE >= L) return;
     __shared__ uint32_t s_row[TILE];
     __shared__ uint32_t s_max[G];
     const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4;
-    if (tid < TILE) {
-        int i = min(tile0 + tid, L - 1);
-        s_row[tid] = a.crow ? a.crow[(size_t)ul * a.l_stride + i]
-                            : row_of(a.k.block_table, a.k.max_pages, a.k.page_shift, a.u.g, b, kv, i);
-    }
+    CTKVR_STAMP(20);
     if (tid < G) s_max[tid] = 0u;
     float q[G][8];
     const T *qb = (const T *)a.q + (((size_t)b * a.u.h + kv * G) * a.qrows + j) * kD;
 #pragma unroll
     for (int hh = 0; hh < G; ++hh) unpack(load_chunk(qb + (size_t)hh * a.qrows * kD, lane16), q[hh]);
-    __syncthreads();
     const T *K = (const T *)a.k.pages;
-    Chunk<T> ck[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) ck[r] = load_chunk(K + (size_t)s_row[r * 16 + grp] * kD, lane16);
+    float *zb = a.z + (size_t)ul * a.l_stride * G;
     float mx[G];
 #pragma unroll
     for (int hh = 0; hh < G; ++hh) mx[hh] = -__builtin_huge_valf();
-    float *zb = a.z + (size_t)ul * a.l_stride * G;
+    for (int tile0 = blockIdx.x * TILE; tile0 < L; tile0 += gridDim.x * TILE) {
+        __syncthreads();   // previous tile's rows are consumed
+        if (tid < TILE) {
+            int i = min(tile0 + tid, L - 1);
+            s_row[tid] = a.crow ? a.crow[(size_t)ul * a.l_stride + i]
+                                : row_of(a.k.block_table, a.k.max_pages, a.k.page_shift, a.u.g, b, kv, i);
+        }
+        __syncthreads();
+        CTKVR_STAMP(21);
+        Chunk<T> ck[R];
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        float kx[8];
-        unpack(ck[r], kx);
-        float zz[G];
+        for (int r = 0; r < R; ++r) ck[r] = load_chunk(K + (size_t)s_row[r * 16 + grp] * kD, lane16);
 #pragma unroll
-        for (int hh = 0; hh < G; ++hh) zz[hh] = group16_sum(lane_partial(q[hh], kx)) * a.scale;
-        const int i = tile0 + r * 16 + grp;
-        if (i < L) {
-            float mine = zz[0];
+        for (int r = 0; r < R; ++r) {
+            float kx[8];
+            unpack(ck[r], kx);
+            float zz[G];
 #pragma unroll
-            for (int hh = 0; hh < G; ++hh) {
-                mx[hh] = fmaxf(mx[hh], zz[hh]);
-                if (lane16 == hh) mine = zz[hh];
+            for (int hh = 0; hh < G; ++hh) zz[hh] = group16_sum(lane_partial(q[hh], kx)) * a.scale;
+            const int i = tile0 + r * 16 + grp;
+            if (i < L) {
+                float mine = zz[0];
+#pragma unroll
+                for (int hh = 0; hh < G; ++hh) {
+                    mx[hh] = fmaxf(mx[hh], zz[hh]);
+                    if (lane16 == hh) mine = zz[hh];
+                }
+                if (lane16 < G) zb[(size_t)i * G + lane16] = mine;
             }
-            if (lane16 < G) zb[(size_t)i * G + lane16] = mine;
         }
     }
 #pragma unroll
@@ -348,15 +376,70 @@ template <typename T, int G, int R> __global__ __launch_bounds__(256) void score
     }
     __syncthreads();
     if (tid < G) atomicMax(&a.m_key[ul * G + tid], s_max[tid]);
+    CTKVR_STAMP(22);
+}
+
+// ------------------------------------------------------------------------------
+// softmax denominators: S[h] += sum_i floor(exp(z[h][i] - m[h]) * 2^40), integer
+// adds, hence the same value in any order.  grid (nbx, units), 256 threads, each
+// block walks chunks of 1024 ids with stride gridDim.x.
+// ------------------------------------------------------------------------------
+struct DenomArgs {
+    Units u;
+    const int32_t *ctx_lens, *ncand;   // ncand == nullptr => L = ctx_len
+    int l_stride;
+    const float *z;
+    const uint32_t *m_key;
+    unsigned long long *S;
+};
+
+template <int G> __global__ __launch_bounds__(256) void denom_kernel(DenomArgs a)
+{
+    int b, kv, j;
+    const int ul = blockIdx.y;
+    if (!decode_unit(a.u, ul, b, kv, j)) return;
+    const int L = a.ncand ? a.ncand[ul] : a.ctx_lens[b];
+    if ((int)blockIdx.x * 1024 >= L) return;
+    const int tid = threadIdx.x;
+    __shared__ unsigned long long s_acc[4][G];
+    float m[G];
+    unsigned long long acc[G];
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+        m[hh] = ordered_value(a.m_key[ul * G + hh]);
+        acc[hh] = 0ull;
+    }
+    const float *zb = a.z + (size_t)ul * a.l_stride * G;
+    for (int c0 = blockIdx.x * 1024; c0 < L; c0 += gridDim.x * 1024) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            int i = c0 + q * 256 + tid;
+            if (i < L) {
+                float zv[G];
+                load_z<G>(zb, i, zv);
+#pragma unroll
+                for (int hh = 0; hh < G; ++hh) acc[hh] += to_fixed40(exp_series(zv[hh] - m[hh]));
+            }
+        }
+    }
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+        unsigned long long v = acc[hh];
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+        if (lane_id() == 0) s_acc[tid >> 6][hh] = v;
+    }
+    __syncthreads();
+    if (tid < G) atomicAdd(&a.S[ul * G + tid], s_acc[0][tid] + s_acc[1][tid] + s_acc[2][tid] + s_acc[3][tid]);
 }
 
 // ------------------------------------------------------------------------------
 // Algorithm 2 lines 5-6 / Algorithm 1 lines 3-4.  One block of 1024 threads per
-// unit: S[h] = sum_i floor(exp(z[h][i] - m[h]) * 2^40) (integer, order-free),
-// key_i = max_h ((z[h][i] - m[h]) - log S[h]), top-k ids ascending.
+// unit: key_i = max_h ((z[h][i] - m[h]) - log S[h]), top-k ids ascending.
 //   decode: sel[unit][pos] = cand[i], srow[unit][pos] = crow[i],
 //           zsel[unit][pos][G] = z[i][G], nsel[unit]
 //   build : lists[(b*g+kv)*c_max + j][pos] = i
+// Dynamic shared memory: top_k words (positions of the picked ids, decode only).
 // ------------------------------------------------------------------------------
 struct SelectArgs {
     Units u;
@@ -365,6 +448,7 @@ struct SelectArgs {
     int l_stride, top_k;
     const float *z;
     const uint32_t *m_key;
+    const unsigned long long *S;
     int32_t *sel;       // decode [units][top_k] ; build: lists base
     uint32_t *srow;     // decode [units][top_k]
     float *zsel;        // decode [units][top_k][G]
@@ -373,7 +457,8 @@ struct SelectArgs {
 };
 
 template <int G, int KPT, typename KeyFn>
-__device__ __forceinline__ void select_emit(const SelectArgs &a, int ul, int L, KeyFn key, const float *zb, uint32_t *s_sel)
+__device__ __forceinline__ void select_emit(const SelectArgs &a, int ul, int L, KeyFn key, const float *zb, uint32_t *s_sel,
+                                            int32_t *s_idx)
 {
     const int tid = threadIdx.x;
     if (a.u.build) {
@@ -381,68 +466,54 @@ __device__ __forceinline__ void select_emit(const SelectArgs &a, int ul, int L, 
         block_select_topk<1024, KPT>(key, L, a.top_k, [&](int pos, int i) { dst[pos] = i; }, s_sel);
         return;
     }
+    int n = block_select_topk<1024, KPT>(key, L, a.top_k, [&](int pos, int i) { s_idx[pos] = i; }, s_sel);
+    __syncthreads();
     const int32_t *cb = a.cand + (size_t)ul * a.l_stride;
     const uint32_t *rb = a.crow + (size_t)ul * a.l_stride;
     int32_t *dst = a.sel + (size_t)ul * a.top_k;
     uint32_t *dstr = a.srow + (size_t)ul * a.top_k;
     int32_t *dst2 = a.out_sel ? a.out_sel + (size_t)ul * a.top_k : nullptr;
     float *zd = a.zsel + (size_t)ul * a.top_k * G;
-    int n = block_select_topk<1024, KPT>(key, L, a.top_k,
-                                         [&](int pos, int i) {
-                                             int t = cb[i];
-                                             dst[pos] = t;
-                                             dstr[pos] = rb[i];
-                                             if (dst2) dst2[pos] = t;
-                                             float zv[G];
-                                             load_z<G>(zb, i, zv);
-                                             store_z<G>(zd, pos, zv);
-                                         },
-                                         s_sel);
-    for (int pos = n + tid; pos < a.top_k; pos += 1024) {
-        dst[pos] = -1;
-        if (dst2) dst2[pos] = -1;
+#pragma unroll 2
+    for (int pos = tid; pos < a.top_k; pos += 1024) {
+        if (pos < n) {
+            int i = s_idx[pos];
+            int t = cb[i];
+            uint32_t r = rb[i];
+            float zv[G];
+            load_z<G>(zb, i, zv);
+            dst[pos] = t;
+            dstr[pos] = r;
+            if (dst2) dst2[pos] = t;
+            store_z<G>(zd, pos, zv);
+        } else {
+            dst[pos] = -1;
+            if (dst2) dst2[pos] = -1;
+        }
     }
     if (tid == 0) a.nsel[ul] = n;
 }
 
 template <int G> __global__ __launch_bounds__(1024) void rerank_select_kernel(SelectArgs a)
 {
-    __shared__ uint32_t s_sel[kSelLds];
-    __shared__ unsigned long long s_S[G];
+    extern __shared__ uint32_t smem[];
+    uint32_t *s_sel = smem;                         // kSelLds
+    int32_t *s_idx = (int32_t *)(smem + kSelLds);   // top_k (decode)
     __shared__ float s_ls[G];
     int b, kv, j;
     const int ul = blockIdx.x, tid = threadIdx.x;
     if (!decode_unit(a.u, ul, b, kv, j)) return;
     const int L = a.cand ? a.ncand[ul] : a.ctx_lens[b];
+    CTKVR_STAMP(28);
     float m[G], ls[G];
-    unsigned long long acc[G];
 #pragma unroll
-    for (int hh = 0; hh < G; ++hh) {
-        m[hh] = ordered_value(a.m_key[ul * G + hh]);
-        acc[hh] = 0ull;
-    }
-    if (tid < G) s_S[tid] = 0ull;
+    for (int hh = 0; hh < G; ++hh) m[hh] = ordered_value(a.m_key[ul * G + hh]);
+    if (tid < G) s_ls[tid] = (float)log_fixed40(a.S[ul * G + tid]);
     __syncthreads();
-    const float *zb = a.z + (size_t)ul * a.l_stride * G;
-#pragma unroll 4
-    for (int i = tid; i < L; i += 1024) {
-        float zv[G];
-        load_z<G>(zb, i, zv);
-#pragma unroll
-        for (int hh = 0; hh < G; ++hh) acc[hh] += to_fixed40(exp_series(zv[hh] - m[hh]));
-    }
-#pragma unroll
-    for (int hh = 0; hh < G; ++hh) {
-        unsigned long long v = acc[hh];
-#pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
-        if (lane_id() == 0) atomicAdd(&s_S[hh], v);
-    }
-    __syncthreads();
-    if (tid < G) s_ls[tid] = (float)log_fixed40(s_S[tid]);
-    __syncthreads();
+    CTKVR_STAMP(30);
 #pragma unroll
     for (int hh = 0; hh < G; ++hh) ls[hh] = s_ls[hh];
+    const float *zb = a.z + (size_t)ul * a.l_stride * G;
     auto key = [&](int i) {
         float zv[G];
         load_z<G>(zb, i, zv);
@@ -452,155 +523,170 @@ template <int G> __global__ __launch_bounds__(1024) void rerank_select_kernel(Se
         return ordered_key(best);
     };
     if (L <= 1024 * 8)
-        select_emit<G, 8>(a, ul, L, key, zb, s_sel);
+        select_emit<G, 8>(a, ul, L, key, zb, s_sel, s_idx);
     else if (L <= 1024 * 32)
-        select_emit<G, 32>(a, ul, L, key, zb, s_sel);
+        select_emit<G, 32>(a, ul, L, key, zb, s_sel, s_idx);
     else
-        select_emit<G, 0>(a, ul, L, key, zb, s_sel);
+        select_emit<G, 0>(a, ul, L, key, zb, s_sel, s_idx);
+    CTKVR_STAMP(31);
 }
 
 // ------------------------------------------------------------------------------
-// Algorithm 2 lines 7-9: softmax(z_sel) . V_sel, split over chunks of 64 selected
-// keys; grid (nsplit, batch*g), 256 threads.  Every split leaves an un-normalised
-// partial (o, max, sum); the split that finishes last for its (sequence, KV head)
-// merges them in split order and writes out / out_lse.
+// Algorithm 2 lines 7-9: o_h = softmax(z_sel[h]) . V_sel.  grid (4, batch*g), 1024
+// threads: block x owns head dimensions 32x .. 32x+31 of all G heads of its
+// (sequence, KV head), so no partial result crosses a block.  Four lanes share a
+// row (8 dimensions each), 256 rows per pass.  Dynamic shared memory:
+// top_k*G floats (softmax weights) .
 // ------------------------------------------------------------------------------
 struct AttnArgs {
     const void *v_pages;
-    int g, h, top_k, nsplit;
+    int g, h, top_k;
     const uint32_t *srow;
     const int32_t *nsel;
     const float *zsel;
-    float *po;   // [batch*h][nsplit][128] un-normalised partial outputs
-    float *pm;   // [batch*h][nsplit] partial maxima
-    float *pl;   // [batch*h][nsplit] partial sums
-    uint32_t *done;   // [batch*g] splits finished, returns to 0
     float *out;  // [batch*h][128]
     float *out_lse;
 };
 
-template <typename T, int G> __global__ __launch_bounds__(256) void sparse_attn_kernel(AttnArgs a)
+template <typename T, int G> __global__ __launch_bounds__(1024) void sparse_attn_kernel(AttnArgs a)
 {
-    const int ul = blockIdx.y, split = blockIdx.x;
+    extern __shared__ float s_p[];                // [top_k][G]
+    __shared__ float s_red[16][G];
+    __shared__ float s_m[G], s_l[G];
+    __shared__ float s_o[16][G][32];
+    const int ul = blockIdx.y, slice = blockIdx.x;
     const int b = ul / a.g, kv = ul - b * a.g;
     const int nsel = a.nsel[ul];
-    const int t0 = split * 64;
-    const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4, wv = tid >> 6, ln = tid & 63;
-    if (nsel == 0) {   // nothing recalled: defined output, no partials
-        if (split == 0)
-            for (int x = tid; x < G * kD; x += 256) {
-                a.out[((size_t)b * a.h + kv * G) * kD + x] = 0.0f;
-                if (a.out_lse && x < G) a.out_lse[(size_t)b * a.h + kv * G + x] = -__builtin_huge_valf();
-            }
+    const int tid = threadIdx.x, wv = tid >> 6, ln = tid & 63;
+    const int quad = tid & 3, rin = tid >> 2;     // 4 lanes per row, 256 rows per pass
+    CTKVR_STAMP(44);
+    if (nsel == 0) {   // nothing recalled: defined output
+        if (tid < G * 32) {
+            int hh = tid >> 5, e = tid & 31;
+            a.out[((size_t)b * a.h + kv * G + hh) * kD + slice * 32 + e] = 0.0f;
+        }
+        if (slice == 0 && a.out_lse && tid < G) a.out_lse[(size_t)b * a.h + kv * G + tid] = -__builtin_huge_valf();
         return;
     }
-    if (t0 >= nsel) return;
-    __shared__ float s_p[64][G];
-    __shared__ uint32_t s_row[64];
-    __shared__ float s_o[4][G][kD];
-    __shared__ uint32_t s_last;
-    if (tid < 64) {
-        int tok = t0 + tid;
-        bool ok = tok < nsel;
-        s_row[tid] = a.srow[(size_t)ul * a.top_k + (ok ? tok : t0)];
+    const T *V = (const T *)a.v_pages + slice * 32 + quad * 8;
+    const uint32_t *rb = a.srow + (size_t)ul * a.top_k;
+    const float *zb = a.zsel + (size_t)ul * a.top_k * G;
+    // softmax statistics over the selected keys, per head
+    float mx[G];
 #pragma unroll
-        for (int hh = 0; hh < G; ++hh)
-            s_p[tid][hh] = ok ? a.zsel[((size_t)ul * a.top_k + tok) * G + hh] : -__builtin_huge_valf();
-    }
-    __syncthreads();
-    const T *V = (const T *)a.v_pages;
-    Chunk<T> cv[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) cv[r] = load_chunk(V + (size_t)s_row[r * 16 + grp] * kD, lane16);
-    if (wv == 0) {
+    for (int hh = 0; hh < G; ++hh) mx[hh] = -__builtin_huge_valf();
+    for (int t = tid; t < nsel; t += 1024) {
+        float zv[G];
+        load_z<G>(zb, t, zv);
 #pragma unroll
         for (int hh = 0; hh < G; ++hh) {
-            float v = s_p[ln][hh];
-            float m = v;
-#pragma unroll
-            for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-            float p = __expf(v - m);
-            float l = p;
-#pragma unroll
-            for (int o = 32; o >= 1; o >>= 1) l += __shfl_xor(l, o);
-            s_p[ln][hh] = p;
-            if (ln == 0) {
-                size_t pi = ((size_t)b * a.h + kv * G + hh) * a.nsplit + split;
-                a.pm[pi] = m;
-                a.pl[pi] = l;
-            }
+            s_p[t * G + hh] = zv[hh];
+            mx[hh] = fmaxf(mx[hh], zv[hh]);
         }
     }
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+        float v = mx[hh];
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+        if (ln == 0) s_red[wv][hh] = v;
+    }
     __syncthreads();
+    if (tid < G) {
+        float v = s_red[0][tid];
+#pragma unroll
+        for (int w = 1; w < 16; ++w) v = fmaxf(v, s_red[w][tid]);
+        s_m[tid] = v;
+    }
+    __syncthreads();
+    float sm[G];
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+        mx[hh] = s_m[hh];
+        sm[hh] = 0.0f;
+    }
+    for (int t = tid; t < nsel; t += 1024) {
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh) {
+            float p = __expf(s_p[t * G + hh] - mx[hh]);
+            s_p[t * G + hh] = p;
+            sm[hh] += p;
+        }
+    }
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+        float v = sm[hh];
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+        if (ln == 0) s_red[wv][hh] = v;
+    }
+    __syncthreads();
+    if (tid < G) {
+        float v = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) v += s_red[w][tid];
+        s_l[tid] = v;
+    }
+    __syncthreads();
+    CTKVR_STAMP(45);
+    // weighted sum of the value rows
     float acc[G][8];
 #pragma unroll
     for (int hh = 0; hh < G; ++hh)
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[hh][e] = 0.0f;
+    for (int r0 = 0; r0 < nsel; r0 += 1024) {
+        Chunk<T> cv[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int row = r * 16 + grp;
-        float vx[8];
-        unpack(cv[r], vx);
+        for (int u = 0; u < 4; ++u) {
+            int t = r0 + u * 256 + rin;
+            uint32_t row = rb[t < nsel ? t : nsel - 1];
+            cv[u] = load_chunk(V + (size_t)row * kD, 0);
+        }
 #pragma unroll
-        for (int hh = 0; hh < G; ++hh) {
-            float p = s_p[row][hh];
+        for (int u = 0; u < 4; ++u) {
+            int t = r0 + u * 256 + rin;
+            if (t < nsel) {
+                float vx[8];
+                unpack(cv[u], vx);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[hh][e] = __fmaf_rn(p, vx[e], acc[hh][e]);
+                for (int hh = 0; hh < G; ++hh) {
+                    float p = s_p[t * G + hh];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[hh][e] = __fmaf_rn(p, vx[e], acc[hh][e]);
+                }
+            }
         }
     }
+    // sum over the 16 rows of a wave (lanes with equal quad), then over the 16 waves in order
 #pragma unroll
     for (int hh = 0; hh < G; ++hh)
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             float v = acc[hh][e];
+            v += __shfl_xor(v, 4);
+            v += __shfl_xor(v, 8);
             v += __shfl_xor(v, 16);
             v += __shfl_xor(v, 32);
             acc[hh][e] = v;
         }
-    if (ln < 16) {
+    if (ln < 4) {
 #pragma unroll
         for (int hh = 0; hh < G; ++hh)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) s_o[wv][hh][8 * lane16 + e] = acc[hh][e];
+            for (int e = 0; e < 8; ++e) s_o[wv][hh][quad * 8 + e] = acc[hh][e];
     }
     __syncthreads();
-    for (int x = tid; x < G * kD; x += 256) {
-        int hh = x / kD, e = x - hh * kD;
-        float v = (s_o[0][hh][e] + s_o[1][hh][e]) + (s_o[2][hh][e] + s_o[3][hh][e]);
-        a.po[(((size_t)b * a.h + kv * G + hh) * a.nsplit + split) * kD + e] = v;
+    CTKVR_STAMP(46);
+    if (tid < G * 32) {
+        int hh = tid >> 5, e = tid & 31;
+        float v = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) v += s_o[w][hh][e];
+        a.out[((size_t)b * a.h + kv * G + hh) * kD + slice * 32 + e] = v / s_l[hh];
     }
-    // ---- last split of this (sequence, KV head) merges ---------------------------
-    const int ns = (nsel + 63) >> 6;
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        uint32_t prev = atomicAdd(&a.done[ul], 1u);
-        s_last = (prev == (uint32_t)(ns - 1));
-        if (s_last) a.done[ul] = 0u;   // every split has arrived: ready for the next step
-    }
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    for (int x = tid; x < G * kD; x += 256) {
-        int hh = x / kD, e = x - hh * kD;
-        size_t head = (size_t)b * a.h + kv * G + hh;
-        const float *pm = a.pm + head * a.nsplit;
-        const float *pl = a.pl + head * a.nsplit;
-        const float *po = a.po + head * a.nsplit * kD + e;
-        float M = -__builtin_huge_valf();
-#pragma unroll 8
-        for (int s = 0; s < ns; ++s) M = fmaxf(M, pm[s]);
-        float l = 0.0f, o = 0.0f;
-#pragma unroll 8
-        for (int s = 0; s < ns; ++s) {
-            float w = __expf(pm[s] - M);
-            l = __fmaf_rn(pl[s], w, l);
-            o = __fmaf_rn(po[(size_t)s * kD], w, o);
-        }
-        a.out[head * kD + e] = o / l;
-        if (a.out_lse && e == 0) a.out_lse[head] = M + __logf(l);
-    }
+    if (slice == 0 && a.out_lse && tid < G) a.out_lse[(size_t)b * a.h + kv * G + tid] = s_m[tid] + __logf(s_l[tid]);
+    CTKVR_STAMP(47);
 }
 
 }  // namespace ctkvr
