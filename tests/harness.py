@@ -126,3 +126,63 @@ def run_decode_parity(bt: Batch, oi: OracleIndex, idx, db: DeviceBatch, steps: O
             worst_lse = max(worst_lse, el)
             alphas.append(float(np.mean(r.ncand)) / (wl.n_probe * wl.list_len))
     return {"max_rel_err": worst, "max_lse_err": worst_lse, "alpha": float(np.mean(alphas))}
+
+
+def run_sampled_parity(bt: Batch, idx, db: DeviceBatch, steps: List[int], n_list_samples: int = 32, seed: int = 0,
+                       say=print) -> dict:
+    """Full-size parity where the oracle cannot afford the whole index: the GPU
+    builds its own index; the oracle (a) rebuilds a random sample of its lists
+    and (b) for the given decode steps rebuilds exactly the lists the step
+    probes, then runs Algorithm 2 on them.  Every integer must be bit-equal
+    (probed centroids, the probed lists themselves, L, selected ids), outputs
+    within REL_TOL."""
+    import torch
+    import paper_2512_15550_amd as ck
+    wl = bt.wl
+    B, h, g, d = wl.batch, wl.h, wl.g, wl.d
+    gl = ck.ctkvr_index_lists(idx)                     # [B][g][C_max][rho]
+    Qc = [oracle.centroids_last_c(sq.q_tail, wl.centroids_of(sq.s)) for sq in bt.seqs]
+    rng = np.random.Generator(np.random.Philox(seed))
+    n_checked = 0
+    for b, sq in enumerate(bt.seqs):
+        Cb = wl.centroids_of(sq.s)
+        n = max(1, n_list_samples // B)
+        pairs = np.stack([rng.integers(0, g, n), rng.integers(0, Cb, n)], axis=1).astype(np.int32)
+        built = oracle.build_lists(sq.K, Qc[b], wl.list_len, pairs=pairs)
+        for (kv, j), row in zip(pairs, built):
+            assert np.array_equal(gl[b, kv, j], row), f"list (seq {b}, kv {kv}, centroid {j}) differs from the oracle"
+        n_checked += n
+    say(f"  {n_checked} sampled lists bit-equal")
+    out = torch.empty((B, h, d), dtype=torch.float32, device="cuda")
+    lse = torch.empty((B, h), dtype=torch.float32, device="cuda")
+    sel = torch.empty((B, g, wl.top_k), dtype=torch.int32, device="cuda")
+    ncand = torch.empty((B, g), dtype=torch.int32, device="cuda")
+    probe = torch.empty((B, g, wl.n_probe), dtype=torch.int32, device="cuda")
+    worst, alphas = 0.0, []
+    for st in steps:
+        q = np.stack([sq.q_decode[st] for sq in bt.seqs])
+        ck.ctkvr_decode_step(idx, to_dev(q, wl), db.k_pages, db.v_pages, db.block_table, out, lse, sel, ncand, probe)
+        torch.cuda.synchronize()
+        g_out, g_lse = out.cpu().numpy(), lse.cpu().numpy()
+        g_sel, g_ncand, g_probe = sel.cpu().numpy(), ncand.cpu().numpy(), probe.cpu().numpy()
+        for b, sq in enumerate(bt.seqs):
+            tag = f"step {st} seq {b}"
+            Cb = wl.centroids_of(sq.s)
+            _, pr = oracle.recall(q[b], Qc[b], g, wl.n_probe)
+            assert np.array_equal(g_probe[b], pr), f"{tag}: probed centroids differ"
+            pairs = np.array([[kv, j] for kv in range(g) for j in pr[kv]], np.int32)
+            built = oracle.build_lists(sq.K, Qc[b], wl.list_len, pairs=pairs)
+            lst = np.zeros((g, Cb, wl.list_len), np.int32)
+            for (kv, j), row in zip(pairs, built):
+                assert np.array_equal(gl[b, kv, j], row), f"{tag}: probed list (kv {kv}, centroid {j}) differs"
+                lst[kv, j] = row
+            cand, nc, _, o_sel, o_out, o_lse = oracle.rerank_attend(q[b], sq.K, sq.V, lst, pr, wl.top_k)
+            assert np.array_equal(g_ncand[b], nc), f"{tag}: L differs {g_ncand[b]} vs {nc}"
+            assert np.array_equal(g_sel[b], o_sel), f"{tag}: selected ids differ ({int(np.sum(g_sel[b] != o_sel))} slots)"
+            e = rel_err(g_out[b], o_out)
+            assert e <= REL_TOL, f"{tag}: output relative error {e:.3e}"
+            worst = max(worst, e)
+            assert float(np.max(np.abs(g_lse[b] - o_lse) / np.maximum(1.0, np.abs(o_lse)))) <= 1e-4, f"{tag}: lse"
+            alphas.append(float(np.mean(nc)) / (wl.n_probe * wl.list_len))
+        say(f"  step {st}: all {B} sequences bit-equal, worst rel err so far {worst:.2e}")
+    return {"max_rel_err": worst, "alpha": float(np.mean(alphas)), "lists_checked": n_checked}

@@ -157,3 +157,26 @@ def test_bad_max_pages_is_an_error_not_a_fault(ck):
     with pytest.raises(ck.CtkvrError):
         ck.ctkvr_index_load(H.params_of(wl), db.ctx_lens, cen, bad)
     ck.ctkvr_free(idx)
+
+
+def _full_size(ck, name, steps, n_decode):
+    wl = workload(name)
+    _say(f"[{name}] generating inputs")
+    bt = gen_batch(wl, n_decode=n_decode)
+    db = H.device_batch(bt)
+    _say(f"[{name}] GPU index build")
+    idx = ck.ctkvr_build_index(H.params_of(wl), db.q_prefill, db.cu_seqlens, True, db.k_pages, db.block_table,
+                               db.ctx_lens)
+    _say(f"[{name}] sampled parity against the oracle")
+    st = H.run_sampled_parity(bt, idx, db, steps, say=_say)
+    _say(f"[{name}] ok {st}")
+    ck.ctkvr_free(idx)
+
+
+def test_cfg3_128k_batch4_sampled(ck):
+    """Full size, launch configuration of the benchmark: sampled lists and two decode steps."""
+    _full_size(ck, "cfg3", steps=[0, 5], n_decode=6)
+
+
+def test_cfg4_ragged_batch16_sampled(ck):
+    _full_size(ck, "cfg4", steps=[0, 3], n_decode=4)
