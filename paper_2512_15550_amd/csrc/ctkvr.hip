@@ -11,6 +11,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <type_traits>
 #include <vector>
 
 #include "kernels.hpp"
@@ -264,10 +265,16 @@ template <typename T> int launch_inv_norms(ctkvr_index *ix, hipStream_t st)
 template <typename T, int G>
 int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block_table, int max_pages, hipStream_t st)
 {
+    const bool mfma = ix->p.build_algo == CTKVR_BUILD_MFMA;
     const int total_units = ix->units * ix->c_max;
     const size_t per_unit = (size_t)ix->s_max * G * 4;
     int chunk = (int)std::min<size_t>(total_units, std::max<size_t>(1, ((size_t)2 << 30) / per_unit));
     chunk = std::min(chunk, 32768);
+    if (mfma) {   // whole (sequence, KV head) groups per chunk, up to 8 GiB of scores
+        int nbk = (int)std::max<size_t>(1, ((size_t)8 << 30) / (per_unit * ix->c_max));
+        nbk = std::min(nbk, std::max(1, 32768 / ix->c_max));
+        chunk = std::min(ix->units, nbk) * ix->c_max;
+    }
     float *z = nullptr;
     uint32_t *m_key = nullptr;
     unsigned long long *S = nullptr;
@@ -295,7 +302,33 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
         sa.z = z;
         sa.m_key = m_key;
         sa.scale = ix->scale;
-        score_kernel<T, G, 16><<<dim3((ix->s_max + 255) / 256, nu), 256, 0, st>>>(sa);
+        if constexpr (std::is_same<T, bf16_t>::value) {
+            if (mfma) {
+                constexpr int CT = 32 * (8 / G);
+                MfmaScoreArgs ma{};
+                ma.g = ix->p.n_kv_heads;
+                ma.G = G;
+                ma.h = ix->p.n_q_heads;
+                ma.c_max = ix->c_max;
+                ma.bk0 = u0 / ix->c_max;
+                ma.tiles_per_bk = (ix->c_max + CT - 1) / CT;
+                const int tiles = (nu / ix->c_max) * ma.tiles_per_bk;
+                ma.t_splits = std::max(1, std::min((ix->s_max + 1023) / 1024, (4 * ix->num_cu + tiles - 1) / tiles));
+                ma.n_cent = ix->d_n_cent;
+                ma.ctx_lens = ix->d_ctx_lens;
+                ma.centroids = (const bf16_t *)ix->centroids;
+                ma.k = sa.k;
+                ma.l_stride = ix->s_max;
+                ma.z = z;
+                ma.m_key = m_key;
+                ma.scale = ix->scale;
+                mfma_score_kernel<G><<<dim3(ma.t_splits, tiles), 256, 0, st>>>(ma);
+            } else {
+                score_kernel<T, G, 16><<<dim3((ix->s_max + 255) / 256, nu), 256, 0, st>>>(sa);
+            }
+        } else {
+            score_kernel<T, G, 16><<<dim3((ix->s_max + 255) / 256, nu), 256, 0, st>>>(sa);
+        }
         DenomArgs da{};
         da.u = u;
         da.ctx_lens = ix->d_ctx_lens;
@@ -497,7 +530,8 @@ int ctkvr_build_index(const ctkvr_params *p, const void *q_prefill, const int32_
     TRY(check_params(p, ctx_lens));
     if (!q_prefill || !cu_seqlens || !k_pages || !block_table) return fail(CTKVR_EINVAL, "a required pointer is NULL");
     if (p->centroid_mode == CTKVR_CENTROID_KMEANS) return fail(CTKVR_EUNSUPPORTED, "k-means centroid mode is not built yet");
-    if (p->build_algo == CTKVR_BUILD_MFMA) return fail(CTKVR_EUNSUPPORTED, "MFMA list build is not built yet");
+    if (p->build_algo == CTKVR_BUILD_MFMA && p->dtype != CTKVR_BF16)
+        return fail(CTKVR_EUNSUPPORTED, "the matrix-core list build needs bf16 data");
     (void)init_pos;
     std::vector<int32_t> first_row(p->batch);
     for (int b = 0; b < p->batch; ++b) {

@@ -380,6 +380,121 @@ template <typename T, int G, int R> __global__ __launch_bounds__(256) void score
 }
 
 // ------------------------------------------------------------------------------
+// Algorithm 1 line 2 on the matrix cores (bf16 only): the same z = (c_{h,j} . k_t) *
+// scale as score_kernel in build mode, but the 128-term dot is a chain of eight
+// v_mfma_f32_32x32x16_bf16.  A block owns 8/G sub-tiles of 32 centroids of one
+// (sequence, KV head) for all G heads (8 wave work items, two per wave, their A
+// fragments resident in registers) and walks a range of keys 32 at a time: B
+// fragments are 16-byte pieces of the paged key rows, the 32x32 results go through
+// shared memory so that z leaves as G contiguous floats per (centroid, key), the
+// layout denom and rerank_select read.  grid (t_splits, tiles), 256 threads.
+// Only the accumulation order inside the MFMA differs from the fixed arithmetic;
+// on inputs whose dot products are exact in fp32 the two builds agree bit for bit.
+// ------------------------------------------------------------------------------
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+
+struct MfmaScoreArgs {
+    int g, G, h, c_max;
+    int bk0;                   // first (sequence, KV head) pair of this chunk
+    int tiles_per_bk;          // ceil(c_max / (32 * 8/G))
+    int t_splits;
+    const int32_t *n_cent, *ctx_lens;
+    const bf16_t *centroids;   // [batch][h][c_max][128]
+    Paged k;
+    int l_stride;              // s_max
+    float *z;                  // [chunk units][l_stride][G]
+    uint32_t *m_key;           // [chunk units][G]
+    float scale;
+};
+
+template <int G> __global__ __launch_bounds__(256) void mfma_score_kernel(MfmaScoreArgs a)
+{
+    constexpr int MT = 8 / G;        // 32-centroid sub-tiles per block
+    constexpr int CT = 32 * MT;      // centroids per block
+    __shared__ float s_z[CT * 32 * G];
+    __shared__ uint32_t s_row[32];
+    const int tid = threadIdx.x, wv = tid >> 6, ln = tid & 63;
+    const int col = ln & 31, half = ln >> 5;
+    const int bkl = blockIdx.y / a.tiles_per_bk, jt = blockIdx.y - bkl * a.tiles_per_bk;
+    const int bk = a.bk0 + bkl;
+    const int b = bk / a.g, kv = bk - b * a.g;
+    const int C = a.n_cent[b], s = a.ctx_lens[b];
+    const int j0 = jt * CT;
+    if (j0 >= C) return;
+    const int tper = (((s + a.t_splits - 1) / a.t_splits) + 31) & ~31;
+    const int tbeg = blockIdx.x * tper;
+    const int tend = min(s, tbeg + tper);
+    if (tbeg >= s) return;
+    int hh[2], mt[2];
+    bf16x8_t afrag[2][8];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        int it = wv * 2 + q;
+        hh[q] = it / MT;
+        mt[q] = it - hh[q] * MT;
+        int j = min(j0 + mt[q] * 32 + col, C - 1);
+        const bf16_t *row = a.centroids + (((size_t)b * a.h + kv * G + hh[q]) * a.c_max + j) * kD;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) afrag[q][ks] = *reinterpret_cast<const bf16x8_t *>(row + ks * 16 + 8 * half);
+    }
+    float mx[2][16];
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx[q][r] = -__builtin_huge_valf();
+    const bf16_t *K = (const bf16_t *)a.k.pages;
+    float *zb = a.z + (size_t)bkl * a.c_max * a.l_stride * G;
+    for (int t0 = tbeg; t0 < tend; t0 += 32) {
+        __syncthreads();
+        if (tid < 32) s_row[tid] = row_of(a.k.block_table, a.k.max_pages, a.k.page_shift, a.g, b, kv, min(t0 + tid, s - 1));
+        __syncthreads();
+        bf16x8_t bfrag[8];
+        const bf16_t *krow = K + (size_t)s_row[col] * kD + 8 * half;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) bfrag[ks] = *reinterpret_cast<const bf16x8_t *>(krow + ks * 16);
+        const bool tok = (t0 + col) < tend;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            f32x16_t acc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[q][ks], bfrag[ks], acc, 0, 0, 0);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                int i = 8 * (r >> 2) + 4 * half + (r & 3);   // row of the 32x32 tile held in acc[r]
+                int jj = mt[q] * 32 + i;
+                float v = acc[r] * a.scale;
+                if (tok && (j0 + jj) < C) mx[q][r] = fmaxf(mx[q][r], v);
+                s_z[(jj * 32 + col) * G + hh[q]] = v;
+            }
+        }
+        __syncthreads();
+        for (int p = tid; p < CT * 32; p += 256) {
+            int n = p & 31, jj = p >> 5;
+            if ((j0 + jj) < C && (t0 + n) < tend) {
+                float zv[G];
+#pragma unroll
+                for (int c = 0; c < G; ++c) zv[c] = s_z[p * G + c];
+                store_z<G>(zb + (size_t)(j0 + jj) * a.l_stride * G, t0 + n, zv);
+            }
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float v = mx[q][r];
+#pragma unroll
+            for (int o = 16; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+            int i = 8 * (r >> 2) + 4 * half + (r & 3);
+            int jj = mt[q] * 32 + i;
+            if (col == 0 && (j0 + jj) < C) atomicMax(&a.m_key[((size_t)bkl * a.c_max + j0 + jj) * G + hh[q]], ordered_key(v));
+        }
+}
+
+// ------------------------------------------------------------------------------
 // softmax denominators: S[h] += sum_i floor(exp(z[h][i] - m[h]) * 2^40), integer
 // adds, hence the same value in any order.  grid (nbx, units), 256 threads, each
 // block walks chunks of 1024 ids with stride gridDim.x.

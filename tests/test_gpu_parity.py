@@ -180,3 +180,78 @@ def test_cfg3_128k_batch4_sampled(ck):
 
 def test_cfg4_ragged_batch16_sampled(ck):
     _full_size(ck, "cfg4", steps=[0, 3], n_decode=4)
+
+
+# --------------------------------------------------------------------------- #
+# matrix-core list build (Algorithm 1 lines 2-4 with the dot products on MFMA)
+# --------------------------------------------------------------------------- #
+KEY_BAND = 5e-4   # absolute, in log-probability: MFMA accumulation order is the only difference
+
+
+def _check_lists_within_band(gpu_lists, sq, Qc, wl, pairs=None):
+    """GPU lists may differ from the oracle's only in ids whose (oracle) key lies within KEY_BAND of the rho-th."""
+    ref, keys = oracle.build_lists(sq.K, Qc, wl.list_len, pairs=pairs, return_keys=True)
+    g, C = wl.g, Qc.shape[1]
+    if pairs is None:
+        pairs = np.array([[kv, j] for kv in range(g) for j in range(C)], np.int32)
+        ref = ref.reshape(-1, wl.list_len)
+    n_diff = 0
+    for (kv, j), r, key in zip(pairs, ref, keys):
+        got = gpu_lists[kv, j]
+        assert np.all(np.diff(got) > 0) and got[0] >= 0 and got[-1] < sq.s
+        if np.array_equal(got, r):
+            continue
+        kth = np.sort(key)[::-1][wl.list_len - 1]
+        odd = np.setxor1d(got, r)
+        assert np.all(np.abs(key[odd] - kth) <= KEY_BAND), f"list (kv {kv}, centroid {j}) differs outside the tie band"
+        n_diff += len(odd) // 2
+    return n_diff
+
+
+def test_mfma_build_is_bit_exact_on_lattice_inputs(ck):
+    wl = small_workload("lattice_mfma", "bf16", 8, 2, (2500,), (510,), 70, 0, 4, 120, 60, 2)
+    sq = gen_lattice_sequence(510, 2500, 8, 2, 128, 70, 2)
+    bt = Batch(wl=wl, seqs=[sq], paged=paginate([sq], wl.page_size, 6))
+    oi = H.oracle_index(bt)
+    db = H.device_batch(bt)
+    idx = ck.ctkvr_build_index(H.params_of(wl, build_algo=ck.BUILD_MFMA), db.q_prefill, db.cu_seqlens, True, db.k_pages,
+                               db.block_table, db.ctx_lens)
+    assert np.array_equal(ck.ctkvr_index_lists(idx)[0], oi.lists[0])
+    H.run_decode_parity(bt, oi, idx, db)
+    ck.ctkvr_free(idx)
+
+
+@pytest.mark.parametrize("case", [SMALL[0], SMALL[1], SMALL[3], SMALL[4], SMALL[7]],
+                         ids=[SMALL[i][0] for i in (0, 1, 3, 4, 7)])
+def test_mfma_build_matches_oracle_up_to_ties(ck, case):
+    name, dtype, h, g, lens, C, div, n_probe, rho, top_k = case
+    wl = small_workload(name, dtype, h, g, lens, tuple(range(600, 600 + len(lens))), C, div, n_probe, rho, top_k, 1)
+    bt = gen_batch(wl)
+    db = H.device_batch(bt)
+    idx = ck.ctkvr_build_index(H.params_of(wl, build_algo=ck.BUILD_MFMA), db.q_prefill, db.cu_seqlens, True, db.k_pages,
+                               db.block_table, db.ctx_lens)
+    lists = ck.ctkvr_index_lists(idx)
+    n_diff = 0
+    for b, sq in enumerate(bt.seqs):
+        Cb = wl.centroids_of(sq.s)
+        n_diff += _check_lists_within_band(lists[b, :, :Cb], sq, oracle.centroids_last_c(sq.q_tail, Cb), wl)
+    _say(f"[mfma {name}] ids that differ inside the tie band: {n_diff}")
+    ck.ctkvr_free(idx)
+
+
+def test_mfma_build_cfg2_and_128k_sampled(ck):
+    for name, n_pairs in (("cfg2", 96), ("cfg5", 48)):
+        wl = workload(name)
+        _say(f"[mfma {name}] generating")
+        bt = gen_batch(wl, n_decode=1)
+        db = H.device_batch(bt)
+        idx = ck.ctkvr_build_index(H.params_of(wl, build_algo=ck.BUILD_MFMA), db.q_prefill, db.cu_seqlens, True,
+                                   db.k_pages, db.block_table, db.ctx_lens)
+        lists = ck.ctkvr_index_lists(idx)
+        sq = bt.seqs[0]
+        C = wl.centroids_of(sq.s)
+        rng = np.random.Generator(np.random.Philox(77))
+        pairs = np.stack([rng.integers(0, wl.g, n_pairs), rng.integers(0, C, n_pairs)], axis=1).astype(np.int32)
+        n_diff = _check_lists_within_band(lists[0], sq, oracle.centroids_last_c(sq.q_tail, C), wl, pairs=pairs)
+        _say(f"[mfma {name}] {n_pairs} sampled lists agree; ids inside the tie band: {n_diff}")
+        ck.ctkvr_free(idx)
