@@ -36,6 +36,41 @@ def step_bytes(wl, C, L_sum_per_seq, e):
             + (L_sum_per_seq + g * wl.top_k) * 4 + g * wl.top_k * d * e + 2 * h * d * 4)
 
 
+def bench_build(args, wl):
+    """Index build only (Algorithm 1 lines 1-4): a "step" is one complete build."""
+    import torch
+    import paper_2512_15550_amd as ck
+    from ctkvr_inputs import gen_batch
+    from tests import harness as H
+    K = args.steps if args.steps is not None else 3
+    W = min(args.warmup, 1)
+    bt = gen_batch(wl, n_decode=1)
+    db = H.device_batch(bt)
+    res = {}
+    for name, algo in (("mfma", ck.BUILD_MFMA), ("exact", ck.BUILD_EXACT)):
+        p = H.params_of(wl, build_algo=algo)
+        for _ in range(W):
+            ck.ctkvr_free(ck.ctkvr_build_index(p, db.q_prefill, db.cu_seqlens, True, db.k_pages, db.block_table, db.ctx_lens))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K):
+            ck.ctkvr_free(ck.ctkvr_build_index(p, db.q_prefill, db.cu_seqlens, True, db.k_pages, db.block_table, db.ctx_lens))
+        torch.cuda.synchronize()
+        res[name] = (time.perf_counter() - t0) / K * 1e3
+    flops = sum(2.0 * wl.h * wl.centroids_of(s) * s * wl.d for s in wl.ctx_lens)
+    tf = flops / (res["mfma"] * 1e-3) / 1e12
+    rec = {"metric": "index build ms (centroid table + top-rho inverted lists)", "value": res["mfma"], "unit": "ms",
+           "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": res["mfma"], "higher_is_better": False, "scaling": "weak",
+           "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": wl.name, "ctx_lens": wl.ctx_lens, "q_heads": wl.h, "kv_heads": wl.g,
+                      "centroids": wl.n_centroids, "list_len": wl.list_len, "build_algo": "mfma"},
+           "exact_build_ms": res["exact"], "score_gemm_flops": flops,
+           "roofline": {"kernel": "whole build (score GEMM + denominators + selection)", "bound": "mfma", "achieved": tf,
+                        "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None},
+           "cpu_baseline": None}
+    print(json.dumps(rec))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -57,6 +92,8 @@ def main():
     ck.load_library()
     torch.cuda.set_device(0)
     wl = workload(args.workload)
+    if wl.n_decode == 0:
+        return bench_build(args, wl)
     K = args.steps if args.steps is not None else max(1, wl.n_decode)
     W = args.warmup
     n_q = max(1, min(wl.n_decode, K))

@@ -61,6 +61,8 @@ def lib() -> ctypes.CDLL:
         L.ctkvr_oracle_rerank_attend.restype = None
         L.ctkvr_oracle_rerank_attend.argtypes = [fp, fp, fp, ip, ip, ci, ci, ci, ci, ci, ci, ci, ctypes.c_float,
                                                  ip, ip, fp, ip, dp, dp]
+        L.ctkvr_oracle_kmeans.restype = None
+        L.ctkvr_oracle_kmeans.argtypes = [fp, ci, ci, fp, ci, ci, ci, ip, dp]
         L.ctkvr_oracle_num_threads.restype = ci
         L.ctkvr_oracle_set_threads.argtypes = [ci]
         _lib = L
@@ -202,6 +204,33 @@ def decode_step(q, K, V, Qc, lists, n_probe, top_k, scale=None) -> DecodeResult:
     cand, ncand, rkey, sel, out, lse = rerank_attend(q, K, V, lists, probe, top_k, scale)
     return DecodeResult(cos_kv, probe, [cand[i, :ncand[i]].copy() for i in range(g)], ncand,
                         [rkey[i, :ncand[i]].copy() for i in range(g)], sel, out, lse)
+
+
+# ---- k-means centroid mode -------------------------------------------------- #
+def group_points(q_full: np.ndarray, g: int) -> np.ndarray:
+    """[s][h][d] prompt queries -> [g][s][G*d]: a point is the concatenation of the G
+    query-head vectors of a KV group at one position."""
+    s, h, d = q_full.shape
+    G = h // g
+    return np.ascontiguousarray(q_full.reshape(s, g, G * d).transpose(1, 0, 2), np.float32)
+
+
+def kmeans_centroids(q_full: np.ndarray, g: int, init_pos: np.ndarray, iters: int, dtype: str = "bf16"):
+    """Lloyd iterations from the centres at prompt positions init_pos [g][C].
+    Returns (Qc [h][C][d], assign [g][s], inertia [g][iters+1])."""
+    s, h, d = q_full.shape
+    G = h // g
+    C = init_pos.shape[1]
+    X = group_points(q_full, g)
+    Qc = np.empty((h, C, d), np.float32)
+    assign = np.empty((g, s), np.int32)
+    inertia = np.empty((g, iters + 1), np.float64)
+    for kv in range(g):
+        cent = np.ascontiguousarray(X[kv][init_pos[kv]], np.float32)
+        lib().ctkvr_oracle_kmeans(_f(X[kv]), s, G * d, _f(cent), C, iters, int(dtype == "bf16"), _i(assign[kv]),
+                                  _d(inertia[kv]))
+        Qc[kv * G:(kv + 1) * G] = cent.reshape(C, G, d).transpose(1, 0, 2)
+    return Qc, assign, inertia
 
 
 def num_threads() -> int:

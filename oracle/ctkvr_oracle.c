@@ -361,3 +361,89 @@ void ctkvr_oracle_set_threads(int n)
     (void)n;
 #endif
 }
+
+/* ========================================================================= */
+/* k-means centroid mode (replaces Algorithm 1 line 1 only; not in the paper: */
+/* the benchmark's index-build configuration asks for Lloyd iterations over   */
+/* the post-RoPE prompt queries).  Reading, per sequence and KV head:          */
+/*   - a point is one prompt position: the concatenation of the G query-head  */
+/*     vectors of the group at that position (G*128 numbers);                  */
+/*   - squared-Euclidean Lloyd: assign every point to its nearest centre      */
+/*     (ties to the lowest centre id), replace every non-empty centre by the  */
+/*     mean of its points; an empty centre keeps its place;                    */
+/*   - sums are taken in 2^-20 fixed point (llrint(v * 2^20), exact for bf16   */
+/*     values of magnitude >= 2^-13), so they do not depend on the order;      */
+/*     mean = (double)sum * 2^-20 / count, rounded to fp32 and then, for bf16  */
+/*     data, to bf16 (nearest even): the next assignment reads bf16 centres.   */
+/* Distances here are fp64; a GPU that scores in fp32 on the matrix cores may  */
+/* assign a point differently when two centres tie within rounding, after     */
+/* which the two runs drift apart: PARITY UNPINNED bit-wise beyond such ties.  */
+/* Pins (tests/test_oracle_kmeans.py): one centre = the mean; as many centres  */
+/* as distinct points = zero inertia; inertia never increases; scipy's         */
+/* kmeans2 step from the same start.                                            */
+/* ========================================================================= */
+static float round_bf16(float x)
+{
+    union { float f; uint32_t u; } v;
+    v.f = x;
+    uint32_t lsb = (v.u >> 16) & 1u;
+    v.u += 0x7fffu + lsb;
+    v.u &= 0xffff0000u;
+    return v.f;
+}
+
+/* X [n][dim] points, cent [C][dim] centres (in/out), assign_out [n], inertia_out [iters+1]:
+ * inertia_out[i] = sum of squared distances to the nearest centre BEFORE update i
+ * (so entry iters is measured on the final centres). */
+void ctkvr_oracle_kmeans(const float *X, int n, int dim, float *cent, int C, int iters, int is_bf16,
+                         int32_t *assign_out, double *inertia_out)
+{
+    int64_t *sum = (int64_t *)malloc(sizeof(int64_t) * (size_t)C * dim);
+    int32_t *cnt = (int32_t *)malloc(sizeof(int32_t) * (size_t)C);
+    double *hn = (double *)malloc(sizeof(double) * (size_t)C);
+    for (int it = 0; it <= iters; ++it) {
+        for (int c = 0; c < C; ++c) {
+            double a = 0.0;
+            for (int e = 0; e < dim; ++e) a += (double)cent[(size_t)c * dim + e] * (double)cent[(size_t)c * dim + e];
+            hn[c] = 0.5 * a;
+        }
+        double inertia = 0.0;
+#pragma omp parallel for reduction(+ : inertia) schedule(static)
+        for (int t = 0; t < n; ++t) {
+            const float *x = X + (size_t)t * dim;
+            double xx = 0.0;
+            for (int e = 0; e < dim; ++e) xx += (double)x[e] * (double)x[e];
+            double best = -INFINITY;
+            int bi = 0;
+            for (int c = 0; c < C; ++c) {
+                const float *m = cent + (size_t)c * dim;
+                double dot = 0.0;
+                for (int e = 0; e < dim; ++e) dot += (double)x[e] * (double)m[e];
+                double sc = dot - hn[c];          /* |x-m|^2 = |x|^2 - 2 (x.m - |m|^2/2) */
+                if (sc > best) { best = sc; bi = c; }
+            }
+            assign_out[t] = bi;
+            double d2 = xx - 2.0 * best;
+            inertia += d2 > 0.0 ? d2 : 0.0;
+        }
+        inertia_out[it] = inertia;
+        if (it == iters) break;
+        memset(sum, 0, sizeof(int64_t) * (size_t)C * dim);
+        memset(cnt, 0, sizeof(int32_t) * (size_t)C);
+        for (int t = 0; t < n; ++t) {
+            int c = assign_out[t];
+            cnt[c] += 1;
+            for (int e = 0; e < dim; ++e) sum[(size_t)c * dim + e] += (int64_t)llrint((double)X[(size_t)t * dim + e] * 1048576.0);
+        }
+        for (int c = 0; c < C; ++c) {
+            if (cnt[c] == 0) continue;
+            for (int e = 0; e < dim; ++e) {
+                float m = (float)((double)sum[(size_t)c * dim + e] * (1.0 / 1048576.0) / (double)cnt[c]);
+                cent[(size_t)c * dim + e] = is_bf16 ? round_bf16(m) : m;
+            }
+        }
+    }
+    free(sum);
+    free(cnt);
+    free(hn);
+}
