@@ -15,6 +15,7 @@
 #include <vector>
 
 #include "kernels.hpp"
+#include "kmeans.hpp"
 
 using namespace ctkvr;
 
@@ -509,6 +510,65 @@ int decode_dispatch(ctkvr_index *ix, const void *q, const void *k, const void *v
     }
 }
 
+// Lloyd iterations on the centroid table (k-means centroid mode)
+template <int G> int run_kmeans_g(ctkvr_index *ix, KmeansArgs ka, hipStream_t st)
+{
+    const int U = ix->units;
+    hipError_t e = hipFuncSetAttribute((const void *)kmeans_assign_kernel<G>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       ix->c_max * 4);
+    if (e != hipSuccess) return fail(CTKVR_EHIP, "k-means set-up: %s", hipGetErrorString(e));
+    kmeans_init_kernel<<<dim3(ix->c_max, ix->p.n_q_heads, ix->p.batch), 128, 0, st>>>(ka, G);
+    for (int it = 0; it < ix->p.kmeans_iters; ++it) {
+        kmeans_halfnorm_kernel<G><<<dim3((ix->c_max + 15) / 16, U), 256, 0, st>>>(ka);
+        kmeans_assign_kernel<G><<<dim3((ix->s_max + 127) / 128, U), 256, ix->c_max * 4, st>>>(ka);
+        kmeans_accumulate_kernel<G><<<dim3((ix->s_max + 15) / 16, U), 256, 0, st>>>(ka);
+        kmeans_update_kernel<G><<<dim3(ix->c_max, U), 128, 0, st>>>(ka);
+    }
+    HIP_TRY(hipGetLastError());
+    return CTKVR_OK;
+}
+
+int run_kmeans(ctkvr_index *ix, const bf16_t *q_prefill, const int32_t *d_first, const int32_t *init_pos, hipStream_t st)
+{
+    const size_t U = ix->units;
+    KmeansArgs ka{};
+    ka.g = ix->p.n_kv_heads;
+    ka.h = ix->p.n_q_heads;
+    ka.c_max = ix->c_max;
+    ka.s_max = ix->s_max;
+    ka.n_cent = ix->d_n_cent;
+    ka.ctx_lens = ix->d_ctx_lens;
+    ka.first_row = d_first;
+    ka.q = q_prefill;
+    ka.centroids = (bf16_t *)ix->centroids;
+    ka.init_pos = init_pos;
+    void *bufs[4] = {nullptr, nullptr, nullptr, nullptr};
+    const size_t sz[4] = {U * ix->c_max * 4, U * ix->s_max * 4, U * ix->c_max * ix->G * 128 * 8, U * ix->c_max * 4};
+    int rc = CTKVR_OK;
+    for (int i = 0; i < 4 && rc == CTKVR_OK; ++i) {
+        hipError_t e = hipMalloc(&bufs[i], sz[i]);
+        if (e == hipSuccess && i >= 2) e = hipMemsetAsync(bufs[i], 0, sz[i], st);
+        if (e != hipSuccess) rc = fail(CTKVR_ENOMEM, "k-means scratch: %s", hipGetErrorString(e));
+    }
+    if (rc == CTKVR_OK) {
+        ka.half_norm = (float *)bufs[0];
+        ka.assign = (int32_t *)bufs[1];
+        ka.sums = (unsigned long long *)bufs[2];
+        ka.counts = (uint32_t *)bufs[3];
+        switch (ix->G) {
+            case 1: rc = run_kmeans_g<1>(ix, ka, st); break;
+            case 2: rc = run_kmeans_g<2>(ix, ka, st); break;
+            case 4: rc = run_kmeans_g<4>(ix, ka, st); break;
+            default: rc = run_kmeans_g<8>(ix, ka, st); break;
+        }
+    }
+    hipError_t es = hipStreamSynchronize(st);
+    if (rc == CTKVR_OK && es != hipSuccess) rc = fail(CTKVR_EHIP, "k-means: %s", hipGetErrorString(es));
+    for (void *b : bufs)
+        if (b) (void)hipFree(b);
+    return rc;
+}
+
 int min_pages_needed(const ctkvr_index *ix)
 {
     return (ix->s_max + ix->p.page_size - 1) / ix->p.page_size;
@@ -529,10 +589,15 @@ int ctkvr_build_index(const ctkvr_params *p, const void *q_prefill, const int32_
     *out_index = nullptr;
     TRY(check_params(p, ctx_lens));
     if (!q_prefill || !cu_seqlens || !k_pages || !block_table) return fail(CTKVR_EINVAL, "a required pointer is NULL");
-    if (p->centroid_mode == CTKVR_CENTROID_KMEANS) return fail(CTKVR_EUNSUPPORTED, "k-means centroid mode is not built yet");
+    const bool kmeans = p->centroid_mode == CTKVR_CENTROID_KMEANS;
+    if (kmeans) {
+        if (p->dtype != CTKVR_BF16) return fail(CTKVR_EUNSUPPORTED, "the k-means centroid mode needs bf16 data");
+        if (q_is_tail) return fail(CTKVR_EINVAL, "the k-means centroid mode needs all prompt queries (q_is_tail = 0)");
+        if (!init_pos) return fail(CTKVR_EINVAL, "the k-means centroid mode needs init_pos");
+        if (p->kmeans_iters < 0 || p->kmeans_iters > 1000) return fail(CTKVR_EINVAL, "kmeans_iters %d outside 0..1000", p->kmeans_iters);
+    }
     if (p->build_algo == CTKVR_BUILD_MFMA && p->dtype != CTKVR_BF16)
         return fail(CTKVR_EUNSUPPORTED, "the matrix-core list build needs bf16 data");
-    (void)init_pos;
     std::vector<int32_t> first_row(p->batch);
     for (int b = 0; b < p->batch; ++b) {
         int s = ctx_lens[b];
@@ -542,7 +607,7 @@ int ctkvr_build_index(const ctkvr_params *p, const void *q_prefill, const int32_
         if (rows != need)
             return fail(CTKVR_EINVAL, "sequence %d: cu_seqlens gives %d query rows, expected %d", b, rows, need);
         if (max_pages * p->page_size < s) return fail(CTKVR_EINVAL, "max_pages %d too small for ctx_len %d", max_pages, s);
-        first_row[b] = cu_seqlens[b] + rows - C;
+        first_row[b] = kmeans ? cu_seqlens[b] : cu_seqlens[b] + rows - C;
     }
     ctkvr_index *ix = nullptr;
     TRY(create_index(p, ctx_lens, &ix));
@@ -554,7 +619,11 @@ int ctkvr_build_index(const ctkvr_params *p, const void *q_prefill, const int32_
     if (e != hipSuccess) rc = fail(CTKVR_EHIP, "build set-up: %s", hipGetErrorString(e));
     if (rc == CTKVR_OK) {
         dim3 grid(ix->c_max, p->n_q_heads, p->batch);
-        if (p->dtype == CTKVR_BF16) {
+        if (kmeans) {
+            rc = run_kmeans(ix, (const bf16_t *)q_prefill, d_first, init_pos, st);
+            if (rc == CTKVR_OK) rc = launch_inv_norms<bf16_t>(ix, st);
+            if (rc == CTKVR_OK) rc = build_lists_dispatch<bf16_t>(ix, k_pages, block_table, max_pages, st);
+        } else if (p->dtype == CTKVR_BF16) {
             copy_centroids_kernel<bf16_t><<<grid, 128, 0, st>>>((const bf16_t *)q_prefill, d_first, ix->d_n_cent,
                                                                  p->n_q_heads, ix->c_max, (bf16_t *)ix->centroids);
             rc = launch_inv_norms<bf16_t>(ix, st);

@@ -1,0 +1,174 @@
+// k-means centroid mode of the index build (replaces Algorithm 1 line 1 only; the
+// paper itself takes the last C prompt queries).  Per (sequence, KV head) the s
+// prompt positions are clustered; a point is the concatenation of the G query-head
+// vectors of the group at one position (G*128 numbers, contiguous in q_prefill).
+// Lloyd iteration = half-norms -> assignment on the matrix cores -> fixed-point
+// accumulation -> update.  The centres live in the index's centroid table
+// [b][h][c_max][128] all along: head hh of centre c is one 128-element row.
+#pragma once
+#include "kernels.hpp"
+
+namespace ctkvr {
+
+struct KmeansArgs {
+    int g, h, c_max, s_max;
+    const int32_t *n_cent, *ctx_lens;
+    const int32_t *first_row;      // [batch] row of position 0 of each sequence in q_prefill
+    const bf16_t *q;               // [rows][h][128]
+    bf16_t *centroids;             // [batch][h][c_max][128]
+    const int32_t *init_pos;       // [batch][g][c_max]
+    float *half_norm;              // [batch*g][c_max]
+    int32_t *assign;               // [batch*g][s_max]
+    unsigned long long *sums;      // [batch*g][c_max][G*128]  2^-20 fixed point, two's complement
+    uint32_t *counts;              // [batch*g][c_max]
+};
+
+// centres start as the prompt queries at init_pos; grid (c_max, h, batch), 128 threads
+__global__ void kmeans_init_kernel(KmeansArgs a, int G)
+{
+    const int j = blockIdx.x, hd = blockIdx.y, b = blockIdx.z;
+    if (j >= a.n_cent[b]) return;
+    const int kv = hd / G;
+    int pos = a.init_pos[((size_t)b * a.g + kv) * a.c_max + j];
+    pos = max(0, min(pos, a.ctx_lens[b] - 1));
+    const bf16_t *src = a.q + ((size_t)(a.first_row[b] + pos) * a.h + hd) * kD;
+    a.centroids[(((size_t)b * a.h + hd) * a.c_max + j) * kD + threadIdx.x] = src[threadIdx.x];
+}
+
+// half_norm[c] = |mu_c|^2 / 2 (heads summed in order); grid (ceil(c_max/16), batch*g), 256 threads
+template <int G> __global__ __launch_bounds__(256) void kmeans_halfnorm_kernel(KmeansArgs a)
+{
+    const int ul = blockIdx.y, b = ul / a.g, kv = ul - b * a.g;
+    const int C = a.n_cent[b];
+    const int lane16 = threadIdx.x & 15, grp = threadIdx.x >> 4;
+    const int c = blockIdx.x * 16 + grp;
+    if (blockIdx.x * 16 >= C) return;
+    const int cc = c < C ? c : C - 1;
+    float n2 = 0.0f;
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+        float x[8];
+        unpack(load_chunk(a.centroids + (((size_t)b * a.h + kv * G + hh) * a.c_max + cc) * kD, lane16), x);
+        n2 = n2 + group16_sum(lane_partial(x, x));
+    }
+    if (c < C && lane16 == 0) a.half_norm[(size_t)ul * a.c_max + c] = 0.5f * n2;
+}
+
+// assignment: argmax_c (x . mu_c - |mu_c|^2/2), ties to the lowest c.  A = 32 centres x 16 dims,
+// B = 16 dims x 32 points per v_mfma_f32_32x32x16_bf16; a wave owns 32 points, keeps their
+// fragments in registers (G <= 4) and walks the centres 128 at a time.
+// grid (ceil(s_max/128), batch*g), 256 threads; dynamic shared memory: c_max floats.
+template <int G> __global__ __launch_bounds__(256) void kmeans_assign_kernel(KmeansArgs a)
+{
+    extern __shared__ float s_hn[];
+    constexpr int KS = 8 * G;                 // k-steps of 16 dims
+    constexpr bool REG_B = (G <= 4);
+    const int ul = blockIdx.y, b = ul / a.g, kv = ul - b * a.g;
+    const int C = a.n_cent[b], s = a.ctx_lens[b];
+    if ((int)blockIdx.x * 128 >= s) return;
+    const int tid = threadIdx.x, wv = tid >> 6, ln = tid & 63, col = ln & 31, half = ln >> 5;
+    for (int c = tid; c < C; c += 256) s_hn[c] = a.half_norm[(size_t)ul * a.c_max + c];
+    __syncthreads();
+    const int p0 = blockIdx.x * 128 + wv * 32;
+    if (p0 >= s) return;
+    const int t = min(p0 + col, s - 1);
+    const bf16_t *xrow = a.q + ((size_t)(a.first_row[b] + t) * a.h + kv * G) * kD + 8 * half;
+    bf16x8_t bfrag[REG_B ? KS : 1];
+    if constexpr (REG_B) {
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) bfrag[kk] = *reinterpret_cast<const bf16x8_t *>(xrow + kk * 16);
+    }
+    float best = -__builtin_huge_valf();
+    int bi = 0;
+    for (int c0 = 0; c0 < C; c0 += 128) {
+        f32x16_t acc[4];
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[ct][r] = 0.0f;
+        const bf16_t *arow[4];
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) {
+            int c = min(c0 + ct * 32 + col, C - 1);
+            arow[ct] = a.centroids + (((size_t)b * a.h + kv * G) * a.c_max + c) * kD + 8 * half;
+        }
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) {
+            bf16x8_t bf;
+            if constexpr (REG_B) bf = bfrag[kk];
+            else bf = *reinterpret_cast<const bf16x8_t *>(xrow + kk * 16);
+            const size_t aoff = (size_t)(kk >> 3) * a.c_max * kD + (kk & 7) * 16;   // head kk/8, dims 16*(kk%8)..
+#pragma unroll
+            for (int ct = 0; ct < 4; ++ct) {
+                bf16x8_t af = *reinterpret_cast<const bf16x8_t *>(arow[ct] + aoff);
+                acc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bf, acc[ct], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                int c = c0 + ct * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                if (c < C) {
+                    float sc = acc[ct][r] - s_hn[c];
+                    if (sc > best) { best = sc; bi = c; }
+                }
+            }
+    }
+    float ob = __shfl_xor(best, 32);
+    int oi = __shfl_xor(bi, 32);
+    if (ob > best || (ob == best && oi < bi)) bi = oi;
+    if (half == 0 && (p0 + col) < s) a.assign[(size_t)ul * a.s_max + p0 + col] = bi;
+}
+
+// sums[c] += llrint(x * 2^20) over the points assigned to c, counts[c] += 1
+// grid (ceil(s_max/16), batch*g), 256 threads: one point per 16-lane group
+template <int G> __global__ __launch_bounds__(256) void kmeans_accumulate_kernel(KmeansArgs a)
+{
+    const int ul = blockIdx.y, b = ul / a.g, kv = ul - b * a.g;
+    const int s = a.ctx_lens[b];
+    const int lane16 = threadIdx.x & 15, grp = threadIdx.x >> 4;
+    const int t = blockIdx.x * 16 + grp;
+    if (t >= s) return;
+    const int c = a.assign[(size_t)ul * a.s_max + t];
+    const bf16_t *xrow = a.q + ((size_t)(a.first_row[b] + t) * a.h + kv * G) * kD;
+    unsigned long long *dst = a.sums + ((size_t)ul * a.c_max + c) * (G * kD);
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+        float x[8];
+        unpack(load_chunk(xrow + hh * kD, lane16), x);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            long long f = __float2ll_rn(x[e] * 1048576.0f);
+            if (f != 0) atomicAdd(&dst[hh * kD + 8 * lane16 + e], (unsigned long long)f);
+        }
+    }
+    if (lane16 == 0) atomicAdd(&a.counts[(size_t)ul * a.c_max + c], 1u);
+}
+
+// mu_c = sum / count (fp64 divide, rounded to fp32, then to bf16 nearest-even); an empty
+// centre keeps its place.  Clears sums and counts.  grid (c_max, batch*g), 128 threads
+template <int G> __global__ __launch_bounds__(128) void kmeans_update_kernel(KmeansArgs a)
+{
+    const int ul = blockIdx.y, b = ul / a.g, kv = ul - b * a.g;
+    const int c = blockIdx.x;
+    if (c >= a.n_cent[b]) return;
+    const uint32_t n = a.counts[(size_t)ul * a.c_max + c];
+    unsigned long long *src = a.sums + ((size_t)ul * a.c_max + c) * (G * kD);
+    const int e = threadIdx.x;
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+        long long sfix = (long long)src[hh * kD + e];
+        src[hh * kD + e] = 0ull;
+        if (n) {
+            float m = (float)((double)sfix * (1.0 / 1048576.0) / (double)n);
+            uint32_t u = __float_as_uint(m);
+            u += 0x7fffu + ((u >> 16) & 1u);
+            a.centroids[(((size_t)b * a.h + kv * G + hh) * a.c_max + c) * kD + e] = (bf16_t)(u >> 16);
+        }
+    }
+    __syncthreads();
+    if (e == 0) a.counts[(size_t)ul * a.c_max + c] = 0u;
+}
+
+}  // namespace ctkvr

@@ -186,3 +186,12 @@ def run_sampled_parity(bt: Batch, idx, db: DeviceBatch, steps: List[int], n_list
             alphas.append(float(np.mean(nc)) / (wl.n_probe * wl.list_len))
         say(f"  step {st}: all {B} sequences bit-equal, worst rel err so far {worst:.2e}")
     return {"max_rel_err": worst, "alpha": float(np.mean(alphas)), "lists_checked": n_checked}
+
+
+def device_full_queries(bt: Batch):
+    """All prompt queries of every sequence (needs gen_batch(..., full_walk=True)) as one
+    device tensor [sum s_i][h][d] plus the HOST cu_seqlens the k-means centroid mode takes."""
+    wl = bt.wl
+    cu = np.zeros(len(bt.seqs) + 1, np.int32)
+    cu[1:] = np.cumsum([sq.s for sq in bt.seqs])
+    return to_dev(np.concatenate([sq.q_full for sq in bt.seqs], axis=0), wl), cu

@@ -1,0 +1,146 @@
+"""k-means centroid mode on the GPU (matrix-core assignment, fixed-point sums)
+against the oracle's Lloyd iterations from the same seeded start positions.
+Bit-exact where the arithmetic is exact (lattice inputs, first update); beyond
+that a tie in the assignment may resolve differently and the runs drift:
+compared through inertia and through the argmin property of the final centres."""
+import numpy as np
+import pytest
+
+import oracle
+from ctkvr_inputs import Batch, bf16_bits_to_f32, gen_batch, paginate, small_workload, Sequence
+from ctkvr_inputs.kmeans_init import kmeanspp_for_sequence
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ck():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2512_15550_amd as ck
+    ck.load_library()
+    return ck
+
+
+def _gpu_kmeans(ck, bt, init_pos, iters, algo=None):
+    import torch
+    wl = bt.wl
+    db = H.device_batch(bt)
+    qf, cu = H.device_full_queries(bt)
+    p = H.params_of(wl, centroid_mode=ck.KMEANS, kmeans_iters=iters)
+    if algo is not None:
+        p.build_algo = algo
+    ip = torch.from_numpy(np.ascontiguousarray(init_pos, np.int32)).cuda()
+    idx = ck.ctkvr_build_index(p, qf, cu, False, db.k_pages, db.block_table, db.ctx_lens, init_pos=ip)
+    cen = bf16_bits_to_f32(ck.ctkvr_index_centroids(idx))     # [B][h][C][d]
+    return idx, db, cen
+
+
+def _inertia_of(q_full, g, Qc):
+    """Inertia of given centres [h][C][d], measured by the oracle's assignment step (no update)."""
+    s, h, d = q_full.shape
+    G = h // g
+    X = oracle.group_points(q_full, g)
+    out = []
+    for kv in range(g):
+        cent = np.ascontiguousarray(Qc[kv * G:(kv + 1) * G].transpose(1, 0, 2).reshape(Qc.shape[1], G * d), np.float32)
+        a = np.empty(s, np.int32)
+        ine = np.empty(1, np.float64)
+        oracle.lib().ctkvr_oracle_kmeans(oracle._f(X[kv]), s, G * d, oracle._f(cent), Qc.shape[1], 0, 1, oracle._i(a),
+                                         oracle._d(ine))
+        out.append(ine[0])
+    return np.array(out)
+
+
+def _lattice_batch(seed, s, h, g, C, rho, n_probe, top_k):
+    r = np.random.Generator(np.random.Philox(seed))
+    lat = lambda shape: (r.integers(-8, 9, size=shape) / 8.0).astype(np.float32)
+    sq = Sequence(seed=seed, dtype="bf16", s=s, K=lat((g, s, 128)), V=lat((g, s, 128)), q_tail=None,
+                  q_decode=lat((2, h, 128)), q_full=lat((s, h, 128)))
+    sq.q_tail = sq.q_full[s - C:]
+    wl = small_workload("km_lattice", "bf16", h, g, (s,), (seed,), C, 0, n_probe, rho, top_k, 2)
+    return Batch(wl=wl, seqs=[sq], paged=paginate([sq], wl.page_size, seed))
+
+
+@pytest.mark.parametrize("h,g", [(8, 2), (2, 2), (8, 1)])
+def test_first_update_on_lattice_inputs_is_bit_exact_and_decodes_like_the_oracle(ck, h, g):
+    s, C = 1500, 40
+    bt = _lattice_batch(700 + h + g, s, h, g, C, 64, 4, 48)
+    sq = bt.seqs[0]
+    init = kmeanspp_for_sequence(sq.q_full, g, C, seed=5)
+    Qc, _, _ = oracle.kmeans_centroids(sq.q_full, g, init, iters=1)
+    idx, db, cen = _gpu_kmeans(ck, bt, init[None], 1)
+    assert np.array_equal(cen[0], Qc), "centres after the first update differ"
+    lists = oracle.build_lists(sq.K, Qc, bt.wl.list_len)
+    assert np.array_equal(ck.ctkvr_index_lists(idx)[0], lists)
+    H.run_decode_parity(bt, H.OracleIndex([Qc], [lists]), idx, db)
+    ck.ctkvr_free(idx)
+
+
+def test_zero_iterations_is_the_start_positions(ck):
+    wl = small_workload("km0", "bf16", 8, 2, (900,), (710,), 24, 0, 4, 64, 32, 1)
+    bt = gen_batch(wl, full_walk=True)
+    sq = bt.seqs[0]
+    init = kmeanspp_for_sequence(sq.q_full, 2, 24, seed=1)
+    idx, _, cen = _gpu_kmeans(ck, bt, init[None], 0)
+    G = 4
+    for kv in range(2):
+        for hh in range(G):
+            assert np.array_equal(cen[0, kv * G + hh], sq.q_full[init[kv], kv * G + hh])
+    ck.ctkvr_free(idx)
+
+
+def test_gaussian_inputs_inertia_tracks_the_oracle_and_never_increases(ck):
+    wl = small_workload("km_gauss", "bf16", 8, 2, (3000, 1700), (720, 721), 0, 50, 4, 96, 64, 1)
+    bt = gen_batch(wl, full_walk=True)
+    c_max = max(wl.centroids_of(s) for s in wl.ctx_lens)
+    inits = [kmeanspp_for_sequence(sq.q_full, 2, wl.centroids_of(sq.s), seed=3 + b) for b, sq in enumerate(bt.seqs)]
+    init_pad = np.zeros((2, 2, c_max), np.int32)
+    for b, ip in enumerate(inits):
+        init_pad[b, :, :ip.shape[1]] = ip
+    prev = None
+    for iters in (0, 1, 2, 5):
+        idx, _, cen = _gpu_kmeans(ck, bt, init_pad, iters)
+        ck.ctkvr_free(idx)
+        cur = []
+        for b, sq in enumerate(bt.seqs):
+            Cb = wl.centroids_of(sq.s)
+            gi = _inertia_of(sq.q_full, 2, cen[b, :, :Cb])
+            _, _, oi = oracle.kmeans_centroids(sq.q_full, 2, inits[b], iters=iters)
+            assert np.all(np.abs(gi - oi[:, -1]) <= 1e-3 * oi[:, -1]), (iters, b, gi, oi[:, -1])
+            cur.append(gi)
+        cur = np.concatenate(cur)
+        if prev is not None:
+            assert np.all(cur <= prev * (1 + 1e-3))
+        prev = cur
+
+
+def test_one_centre_is_the_mean_and_s_centres_give_zero_inertia(ck):
+    wl = small_workload("km_one", "bf16", 4, 2, (64,), (730,), 1, 0, 1, 16, 8, 1)
+    bt = gen_batch(wl, full_walk=True)
+    sq = bt.seqs[0]
+    idx, _, cen = _gpu_kmeans(ck, bt, np.zeros((1, 2, 1), np.int32), 1)
+    Qc, _, _ = oracle.kmeans_centroids(sq.q_full, 2, np.zeros((2, 1), np.int32), iters=1)
+    assert np.array_equal(cen[0], Qc)          # one cluster: no assignment to disagree on
+    ck.ctkvr_free(idx)
+    wl2 = small_workload("km_all", "bf16", 4, 2, (64,), (731,), 64, 0, 4, 16, 8, 1)
+    bt2 = gen_batch(wl2, full_walk=True)
+    init = np.tile(np.arange(64, dtype=np.int32), (1, 2, 1))
+    idx, _, cen = _gpu_kmeans(ck, bt2, init, 2)
+    assert np.all(_inertia_of(bt2.seqs[0].q_full, 2, cen[0]) == 0.0)
+    ck.ctkvr_free(idx)
+
+
+def test_kmeans_argument_errors(ck):
+    import torch
+    wl = small_workload("km_err", "bf16", 4, 2, (200,), (740,), 8, 0, 2, 16, 8, 1)
+    bt = gen_batch(wl, full_walk=True)
+    db = H.device_batch(bt)
+    qf, cu = H.device_full_queries(bt)
+    p = H.params_of(wl, centroid_mode=ck.KMEANS, kmeans_iters=1)
+    with pytest.raises(ck.CtkvrError):       # needs init_pos
+        ck.ctkvr_build_index(p, qf, cu, False, db.k_pages, db.block_table, db.ctx_lens)
+    ip = torch.zeros((1, 2, 8), dtype=torch.int32, device="cuda")
+    with pytest.raises(ck.CtkvrError):       # needs all prompt queries
+        ck.ctkvr_build_index(p, db.q_prefill, db.cu_seqlens, True, db.k_pages, db.block_table, db.ctx_lens, init_pos=ip)
