@@ -44,9 +44,30 @@ def bench_build(args, wl):
     from tests import harness as H
     K = args.steps if args.steps is not None else 3
     W = min(args.warmup, 1)
-    bt = gen_batch(wl, n_decode=1)
+    bt = gen_batch(wl, n_decode=1, full_walk=bool(args.kmeans))
     db = H.device_batch(bt)
     res = {}
+    if args.kmeans:   # k-means centroid mode: 10 Lloyd iterations from k-means++ positions (drawn on the host, untimed)
+        from ctkvr_inputs.kmeans_init import kmeanspp_for_sequence
+        t0 = time.time()
+        init = np.stack([kmeanspp_for_sequence(sq.q_full, wl.g, wl.centroids_of(sq.s), seed=sq.seed) for sq in bt.seqs])
+        t_pp = time.time() - t0
+        qf, cu = H.device_full_queries(bt)
+        ip = torch.from_numpy(np.ascontiguousarray(init, np.int32)).cuda()
+        for iters in (0, 10):
+            p = H.params_of(wl, build_algo=ck.BUILD_MFMA, centroid_mode=ck.KMEANS, kmeans_iters=iters)
+            ck.ctkvr_free(ck.ctkvr_build_index(p, qf, cu, False, db.k_pages, db.block_table, db.ctx_lens, init_pos=ip))
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(K):
+                ck.ctkvr_free(ck.ctkvr_build_index(p, qf, cu, False, db.k_pages, db.block_table, db.ctx_lens, init_pos=ip))
+            torch.cuda.synchronize()
+            res[f"kmeans{iters}"] = (time.perf_counter() - t0) / K * 1e3
+        lloyd_ms = res["kmeans10"] - res["kmeans0"]
+        lloyd_flops = sum(10 * 2.0 * s * wl.centroids_of(s) * wl.h * wl.d for s in wl.ctx_lens)
+        res["kmeans"] = {"build_ms_with_10_lloyd_iterations": res["kmeans10"], "lloyd_ms": lloyd_ms,
+                         "assignment_gemm_flops": lloyd_flops, "lloyd_TFLOPs": lloyd_flops / (lloyd_ms * 1e-3) / 1e12,
+                         "kmeanspp_host_s": t_pp}
     for name, algo in (("mfma", ck.BUILD_MFMA), ("exact", ck.BUILD_EXACT)):
         p = H.params_of(wl, build_algo=algo)
         for _ in range(W):
@@ -64,7 +85,7 @@ def bench_build(args, wl):
            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "config": {"workload": wl.name, "ctx_lens": wl.ctx_lens, "q_heads": wl.h, "kv_heads": wl.g,
                       "centroids": wl.n_centroids, "list_len": wl.list_len, "build_algo": "mfma"},
-           "exact_build_ms": res["exact"], "score_gemm_flops": flops,
+           "exact_build_ms": res["exact"], "score_gemm_flops": flops, "kmeans": res.get("kmeans"),
            "roofline": {"kernel": "whole build (score GEMM + denominators + selection)", "bound": "mfma", "achieved": tf,
                         "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None},
            "cpu_baseline": None}
@@ -78,6 +99,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"])
+    ap.add_argument("--kmeans", action="store_true", help="cfg5 only: also time the k-means centroid mode")
     ap.add_argument("--cpu-steps", type=int, default=None, help="decode steps of the CPU oracle sample (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:

@@ -22,8 +22,15 @@ __device__ long long g_trace[128];
     do {                                                                         \
         if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) g_trace[slot] = wall_clock64(); \
     } while (0)
+__device__ long long g_blk[8][1024];
+#define CTKVR_STAMP_BLK(slot)                                                    \
+    do {                                                                         \
+        int bi_ = blockIdx.x + blockIdx.y * gridDim.x;                           \
+        if (threadIdx.x == 0 && bi_ < 1024) g_blk[slot][bi_] = wall_clock64();   \
+    } while (0)
 #else
 #define CTKVR_STAMP(slot) do { } while (0)
+#define CTKVR_STAMP_BLK(slot) do { } while (0)
 #endif
 
 constexpr int kD = 128;          // head dimension
@@ -220,6 +227,7 @@ __device__ int block_select_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t 
     const int wv = tid >> 6, ln = lane_id();
     uint32_t *s_aux = s_hist + 2048;   // [0] lo, [1] hi, [2] bin, [3] remaining
     uint32_t *s_scan = s_aux + 4;      // NW + 1 words of scan scratch, then 2*NW wave counts
+    uint32_t *s_x = s_hist + 2048 + 56;   // [0] population of the deciding bin, [1] gather cursor
     if (k >= n) {
         for (int i = tid; i < n; i += NT) emit(i, i);
         return n;
@@ -245,10 +253,20 @@ __device__ int block_select_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t 
                 f(i, i < end, kreg[it]);
             }
         } else {
-            for (int base = beg; base < end; base += 64) {
-                int i = base + ln;
-                bool valid = i < end;
-                f(i, valid, valid ? key(i) : 0u);
+            constexpr int CH = 16;   // keys fetched together, so that their loads overlap
+            for (int base = beg; base < end; base += 64 * CH) {
+                uint32_t kk[CH];
+#pragma unroll
+                for (int c = 0; c < CH; ++c) {
+                    int i = base + c * 64 + ln;
+                    kk[c] = (i < end) ? key(i) : 0u;
+                }
+#pragma unroll
+                for (int c = 0; c < CH; ++c) {
+                    if (base + c * 64 >= end) break;
+                    int i = base + c * 64 + ln;
+                    f(i, i < end, kk[c]);
+                }
             }
         }
     };
@@ -315,6 +333,8 @@ __device__ int block_select_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t 
             if (bq >= 0 && before < remaining && remaining <= before + c[q]) {
                 s_aux[2] = (uint32_t)bq;
                 s_aux[3] = remaining - before;
+                s_x[0] = c[q];
+                s_x[1] = 0u;
             }
             before += c[q];
         }
@@ -323,6 +343,40 @@ __device__ int block_select_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t 
         pmask |= dmask << shift;
         remaining = s_aux[3];
         bit = shift;
+        const uint32_t nb = s_x[0];
+        if (bit > 0 && nb <= 128u) {   // ranking is quadratic in nb: only when it is cheaper than another digit
+            // Few keys share the deciding digit: gather them and rank them against each other
+            // instead of walking the remaining digits.  The key of rank `remaining` among them is
+            // the threshold T; the picks among the keys equal to T are the lowest ids, as always.
+            uint32_t *l_key = s_hist, *l_idx = s_hist + 1024;
+            __syncthreads();   // the histogram has been read by everyone
+            for_slots([&](int i, bool valid, uint32_t kk) {
+                if (valid && (kk & pmask) == prefix) {
+                    uint32_t at = atomicAdd(&s_x[1], 1u);
+                    l_key[at] = kk;
+                    l_idx[at] = (uint32_t)i;
+                }
+            });
+            __syncthreads();
+            for (uint32_t j = tid; j < nb; j += NT) {
+                const uint32_t mk = l_key[j], mi = l_idx[j];
+                uint32_t rank = 0, gt = 0;
+                for (uint32_t e = 0; e < nb; ++e) {
+                    const uint32_t ke = l_key[e], ie = l_idx[e];
+                    gt += (ke > mk);
+                    rank += (ke > mk) || (ke == mk && ie < mi);
+                }
+                if (rank == remaining - 1u) {
+                    s_aux[2] = mk;
+                    s_aux[3] = remaining - gt;
+                }
+            }
+            __syncthreads();
+            prefix = s_aux[2];
+            pmask = 0xffffffffu;
+            remaining = s_aux[3];
+            bit = 0;
+        }
     }
     const uint32_t T = prefix;
     const uint32_t need_eq = remaining;
@@ -357,6 +411,116 @@ __device__ int block_select_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t 
     });
     CTKVR_STAMP(40);
     return k;
+}
+
+}  // namespace ctkvr
+
+namespace ctkvr {
+
+// Sum of one value per lane over the wave, returned as a wave-uniform value: DPP butterfly inside
+// each 16-lane row (full-rate, no LDS), then four scalar lane reads.
+__device__ __forceinline__ uint32_t wave_sum_uniform(uint32_t v)
+{
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, false);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, false);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, false);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, false);
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 0) + (uint32_t)__builtin_amdgcn_readlane((int)v, 16) +
+           (uint32_t)__builtin_amdgcn_readlane((int)v, 32) + (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+}
+
+// ---- small-n top-k selection by bisection ----------------------------------------------
+// Same contract as block_select_topk for n <= NT*KPT keys held in registers (slot it of
+// thread t is id it*NT + t).  The k-th largest key is found two bits at a time from the top: 16
+// rounds of "how many keys are >= candidate" for three candidates, DPP reductions per wave and
+// one block barrier per round; then the picks are written in ascending id order with ballot
+// ranks.  s_tmp: 6*(NT/64) + 2*KPT*(NT/64) words.  Every thread of the block takes part.
+template <int NT, int KPT, typename KeyFn, typename EmitFn>
+__device__ __forceinline__ void block_bisect_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t *s_tmp)
+{
+    constexpr int NW = NT / 64;
+    const int tid = threadIdx.x, wv = tid >> 6, ln = lane_id();
+    if (k >= n) {
+        for (int i = tid; i < n; i += NT) emit(i, i);
+        return;
+    }
+    // slots beyond n hold key 0: below every candidate (candidates are >= 1) and below every real key
+    uint32_t kreg[KPT];
+#pragma unroll
+    for (int it = 0; it < KPT; ++it) {
+        int i = it * NT + tid;
+        kreg[it] = (i < n) ? key(i) : 0u;
+    }
+    CTKVR_STAMP(13);
+    // two bits per round: the counts for the three candidates T|01, T|10, T|11 (times 2^b) are
+    // monotone, so the largest candidate still reaching k keys fixes both bits
+    uint32_t T = 0;
+    for (int b = 30; b >= 0; b -= 2) {
+        const uint32_t c1 = T | (1u << b), c2 = T | (2u << b), c3 = T | (3u << b);
+        uint32_t n1 = 0, n2 = 0, n3 = 0;
+#pragma unroll
+        for (int it = 0; it < KPT; ++it) {
+            n1 += (kreg[it] >= c1);
+            n2 += (kreg[it] >= c2);
+            n3 += (kreg[it] >= c3);
+        }
+        n1 = wave_sum_uniform(n1);
+        n2 = wave_sum_uniform(n2);
+        n3 = wave_sum_uniform(n3);
+        uint32_t *buf = s_tmp + ((b >> 1) & 1) * 3 * NW;
+        if (ln == 0) {
+            buf[wv] = n1;
+            buf[NW + wv] = n2;
+            buf[2 * NW + wv] = n3;
+        }
+        __syncthreads();
+        uint32_t t1 = 0, t2 = 0, t3 = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            t1 += buf[w];
+            t2 += buf[NW + w];
+            t3 += buf[2 * NW + w];
+        }
+        if (t3 >= (uint32_t)k) T = c3;
+        else if (t2 >= (uint32_t)k) T = c2;
+        else if (t1 >= (uint32_t)k) T = c1;
+    }
+    CTKVR_STAMP(14);
+    // T is now the k-th largest key; keys above it are all picked, ties by lowest id.
+    // Ordered compaction: ids ascend with (slot, wave, lane).
+    uint32_t *s_gt = s_tmp + 6 * NW, *s_eq = s_gt + KPT * NW;
+    const uint64_t below = (1ull << ln) - 1ull;
+#pragma unroll
+    for (int it = 0; it < KPT; ++it) {
+        const bool valid = (it * NT + tid) < n;
+        const uint64_t mg = __ballot(valid && kreg[it] > T), me = __ballot(valid && kreg[it] == T);
+        if (ln == 0) {
+            s_gt[it * NW + wv] = (uint32_t)__popcll(mg);
+            s_eq[it * NW + wv] = (uint32_t)__popcll(me);
+        }
+    }
+    __syncthreads();
+    uint32_t tot_gt = 0;
+    for (int q = 0; q < KPT * NW; ++q) tot_gt += s_gt[q];
+    const uint32_t need_eq = (uint32_t)k - tot_gt;
+    uint32_t run_gt = 0, run_eq = 0;
+#pragma unroll
+    for (int it = 0; it < KPT; ++it) {
+        // counts of everything before (it, wv)
+        uint32_t pg = run_gt, pe = run_eq;
+        for (int w = 0; w < NW; ++w) {
+            if (w < wv) { pg += s_gt[it * NW + w]; pe += s_eq[it * NW + w]; }
+            run_gt += s_gt[it * NW + w];
+            run_eq += s_eq[it * NW + w];
+        }
+        const int i = it * NT + tid;
+        const bool valid = i < n;
+        const bool g = valid && kreg[it] > T, e = valid && kreg[it] == T;
+        const uint64_t mg = __ballot(g), me = __ballot(e);
+        const uint32_t gb = pg + (uint32_t)__popcll(mg & below);
+        const uint32_t eb = pe + (uint32_t)__popcll(me & below);
+        if (g || (e && eb < need_eq)) emit((int)(gb + min(eb, need_eq)), i);
+    }
 }
 
 }  // namespace ctkvr

@@ -61,12 +61,12 @@ struct ctkvr_index {
     // decode workspace
     float *cos = nullptr;
     int32_t *probe = nullptr, *cand = nullptr, *ncand = nullptr, *sel = nullptr, *nsel = nullptr;
-    uint32_t *crow = nullptr, *srow = nullptr;
+    uint32_t *crow = nullptr, *srow = nullptr, *kbuf = nullptr, *gbits = nullptr;
     unsigned long long *S = nullptr;
     float *z = nullptr, *zsel = nullptr;
     uint32_t *m_key = nullptr;
     size_t recall_lds = 0, select_lds = 0, attn_lds = 0;
-    int bitmap_words = 0, bt_lds = 0, num_cu = 256;
+    int bitmap_words = 0, recall_split = 1, num_cu = 256;
     // per-kernel timing
     std::vector<hipEvent_t> events;
     int prof_max = 0, prof_step = 0;
@@ -176,6 +176,8 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
     A(&ix->z, U * ix->l_stride * ix->G * 4);
     A(&ix->m_key, U * ix->G * 4);
     A(&ix->crow, U * ix->l_stride * 4);
+    A(&ix->gbits, U * (size_t)((ix->s_max + 31) / 32) * 4);
+    A(&ix->kbuf, ix->l_stride > 32768 ? U * ix->l_stride * 4 : 16);
     A(&ix->srow, U * p->top_k * 4);
     A(&ix->S, U * ix->G * 8);
     A(&ix->sel, U * p->top_k * 4);
@@ -185,14 +187,22 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
         delete ix;
         return rc;
     }
-    // shared-memory plan of the one-block-per-unit kernels
+    // shared-memory plan
     ix->bitmap_words = (ix->s_max + 31) / 32;
-    const int bt_entries = (ix->s_max + p->page_size - 1) / p->page_size;
-    size_t base_words = (size_t)kSelLds + p->n_probe + ix->bitmap_words;
-    ix->bt_lds = ((base_words + bt_entries) * 4 <= 150 * 1024) ? bt_entries : 0;
-    ix->recall_lds = (base_words + ix->bt_lds) * 4;
+    ix->recall_lds = ((size_t)kSelLds + p->n_probe + ix->bitmap_words) * 4;
     ix->select_lds = ((size_t)kSelLds + std::max(p->top_k, 1)) * 4;
     ix->attn_lds = (size_t)p->top_k * ix->G * 4;
+    {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+            ix->num_cu = cus;
+    }
+    // The selection runs as one 1024-thread block per (sequence, KV head) and is latency-critical:
+    // while there are no more such blocks than CUs, ask for over half a CU's shared memory so that
+    // two never share a CU.  The recall is spread over recall_split blocks per unit.
+    if ((int)U <= ix->num_cu) ix->select_lds = std::max<size_t>(ix->select_lds, 84 * 1024);
+    ix->recall_split = std::max(1, std::min(8, ix->num_cu / (int)U));
     if (ix->recall_lds > 150 * 1024 || ix->select_lds > 150 * 1024 || ix->attn_lds > 128 * 1024) {
         delete ix;
         return fail(CTKVR_EUNSUPPORTED, "context, top_k or n_probe too large for the shared-memory plan");
@@ -201,10 +211,10 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
     auto want = [&](const void *fn, size_t bytes) {
         if (e == hipSuccess) e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
     };
-    want((const void *)recall_kernel<1>, ix->recall_lds);
-    want((const void *)recall_kernel<2>, ix->recall_lds);
-    want((const void *)recall_kernel<4>, ix->recall_lds);
-    want((const void *)recall_kernel<8>, ix->recall_lds);
+    want((const void *)recall_gather_kernel<2>, ix->recall_lds);
+    want((const void *)recall_gather_kernel<8>, ix->recall_lds);
+    want((const void *)recall_gather_kernel<32>, ix->recall_lds);
+    want((const void *)recall_expand_kernel, 64 * 1024);
     const size_t sel_b = std::max(ix->select_lds, ((size_t)kSelLds + 1) * 4);
     want((const void *)rerank_select_kernel<1>, sel_b);
     want((const void *)rerank_select_kernel<2>, sel_b);
@@ -227,6 +237,8 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
             ix->num_cu = cus;
     }
+    if (e == hipSuccess) e = hipMemset(ix->gbits, 0, U * (size_t)ix->bitmap_words * 4);
+    if (e == hipSuccess) e = hipMemset(ix->srow, 0, U * p->top_k * 4);   // always valid rows (see sparse_attn_kernel)
     if (e == hipSuccess) e = hipMemcpy(ix->d_ctx_lens, ix->ctx_lens.data(), (size_t)B * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(ix->d_n_cent, ix->n_cent.data(), (size_t)B * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(ix->lists, 0, U * ix->c_max * p->list_len * 4);
@@ -282,8 +294,10 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
     HIP_TRY(hipMalloc((void **)&z, (size_t)chunk * per_unit));
     hipError_t e1 = hipMalloc((void **)&m_key, (size_t)chunk * G * 4);
     hipError_t e2 = hipMalloc((void **)&S, (size_t)chunk * G * 8);
+    uint32_t *kbuf = nullptr;
+    hipError_t e3 = hipMalloc((void **)&kbuf, ix->s_max > 32768 ? (size_t)chunk * ix->s_max * 4 : 16);
     int rc = CTKVR_OK;
-    if (e1 != hipSuccess || e2 != hipSuccess) rc = fail(CTKVR_ENOMEM, "build scratch allocation failed");
+    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess) rc = fail(CTKVR_ENOMEM, "build scratch allocation failed");
     for (int u0 = 0; rc == CTKVR_OK && u0 < total_units; u0 += chunk) {
         const int nu = std::min(chunk, total_units - u0);
         Units u = decode_units(ix);
@@ -350,6 +364,7 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
         se.z = z;
         se.m_key = m_key;
         se.S = S;
+        se.kbuf = kbuf;
         se.sel = ix->lists;
         rerank_select_kernel<G><<<dim3(nu), 1024, (kSelLds + 1) * 4, st>>>(se);
         hipError_t e = hipGetLastError();
@@ -360,6 +375,7 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
     (void)hipFree(z);
     (void)hipFree(m_key);
     (void)hipFree(S);
+    (void)hipFree(kbuf);
     return rc;
 }
 
@@ -396,36 +412,43 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     centroid_cos_kernel<T, G><<<dim3((ix->c_max + 15) / 16, U), 256, 0, st>>>(ca);
     ix->mark(1, st);
 
-    RecallArgs ra{};
-    ra.cos = ix->cos;
-    ra.lists = ix->lists;
-    ra.n_cent = ix->d_n_cent;
-    ra.ctx_lens = ix->d_ctx_lens;
-    ra.block_table = bt;
-    ra.max_pages = max_pages;
-    ra.page_shift = ix->page_shift;
-    ra.probe = ix->probe;
-    ra.cand = ix->cand;
-    ra.crow = ix->crow;
-    ra.ncand = ix->ncand;
-    ra.out_probe = out_probe;
-    ra.out_ncand = out_ncand;
-    ra.g = p.n_kv_heads;
-    ra.c_max = ix->c_max;
-    ra.rho = p.list_len;
-    ra.n_probe = p.n_probe;
-    ra.l_stride = ix->l_stride;
-    ra.bitmap_words = ix->bitmap_words;
-    ra.bt_lds = ix->bt_lds;
-    if (ix->c_max <= 1024)
-        recall_kernel<1><<<dim3(U), 1024, ix->recall_lds, st>>>(ra);
+    GatherArgs ga{};
+    ga.cos = ix->cos;
+    ga.lists = ix->lists;
+    ga.n_cent = ix->d_n_cent;
+    ga.ctx_lens = ix->d_ctx_lens;
+    ga.probe = ix->probe;
+    ga.out_probe = out_probe;
+    ga.gbits = ix->gbits;
+    ga.g = p.n_kv_heads;
+    ga.c_max = ix->c_max;
+    ga.rho = p.list_len;
+    ga.n_probe = p.n_probe;
+    ga.bitmap_words = ix->bitmap_words;
+    const dim3 rgrid(ix->recall_split, U);
+    if (ix->c_max <= 512)
+        recall_gather_kernel<2><<<rgrid, 256, ix->recall_lds, st>>>(ga);
     else if (ix->c_max <= 2048)
-        recall_kernel<2><<<dim3(U), 1024, ix->recall_lds, st>>>(ra);
-    else if (ix->c_max <= 4096)
-        recall_kernel<4><<<dim3(U), 1024, ix->recall_lds, st>>>(ra);
+        recall_gather_kernel<8><<<rgrid, 256, ix->recall_lds, st>>>(ga);
     else
-        recall_kernel<8><<<dim3(U), 1024, ix->recall_lds, st>>>(ra);
+        recall_gather_kernel<32><<<rgrid, 256, ix->recall_lds, st>>>(ga);
     ix->mark(2, st);
+
+    ExpandArgs ea{};
+    ea.gbits = ix->gbits;
+    ea.ctx_lens = ix->d_ctx_lens;
+    ea.block_table = bt;
+    ea.max_pages = max_pages;
+    ea.page_shift = ix->page_shift;
+    ea.cand = ix->cand;
+    ea.crow = ix->crow;
+    ea.ncand = ix->ncand;
+    ea.out_ncand = out_ncand;
+    ea.g = p.n_kv_heads;
+    ea.l_stride = ix->l_stride;
+    ea.bitmap_words = ix->bitmap_words;
+    recall_expand_kernel<<<rgrid, 1024, 64 * 1024, st>>>(ea);
+    ix->mark(3, st);
 
     Units u = decode_units(ix);
     ScoreArgs sa{};
@@ -442,9 +465,9 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     sa.scale = ix->scale;
     // enough blocks to fill the chip a few times over, each walking its share of 128-id tiles
     const int tiles = (ix->l_stride + 127) / 128;
-    const int nbx = std::max(1, std::min(tiles, (8 * ix->num_cu + U - 1) / U));
+    const int nbx = std::max(1, std::min(tiles, (4 * ix->num_cu + U - 1) / U));
     score_kernel<T, G, 8><<<dim3(nbx, U), 256, 0, st>>>(sa);
-    ix->mark(3, st);
+    ix->mark(4, st);
 
     DenomArgs da{};
     da.u = u;
@@ -454,9 +477,11 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     da.z = ix->z;
     da.m_key = ix->m_key;
     da.S = ix->S;
+    da.gbits = ix->gbits;
+    da.bitmap_words = ix->bitmap_words;
     const int chunks = (ix->l_stride + 1023) / 1024;
     denom_kernel<G><<<dim3(std::max(1, std::min(chunks, (4 * ix->num_cu + U - 1) / U)), U), 256, 0, st>>>(da);
-    ix->mark(4, st);
+    ix->mark(5, st);
 
     SelectArgs se{};
     se.u = u;
@@ -469,13 +494,14 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     se.z = ix->z;
     se.m_key = ix->m_key;
     se.S = ix->S;
+    se.kbuf = ix->kbuf;
     se.sel = ix->sel;
     se.srow = ix->srow;
     se.zsel = ix->zsel;
     se.nsel = ix->nsel;
     se.out_sel = out_sel;
     rerank_select_kernel<G><<<dim3(U), 1024, ix->select_lds, st>>>(se);
-    ix->mark(5, st);
+    ix->mark(6, st);
 
     AttnArgs aa{};
     aa.v_pages = v_pages;
@@ -488,10 +514,10 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     aa.out = out;
     aa.out_lse = out_lse;
     sparse_attn_kernel<T, G><<<dim3(4, U), 1024, ix->attn_lds, st>>>(aa);
-    ix->mark(6, st);
+    ix->mark(7, st);
     if (ix->prof_step < ix->prof_max) {   // a null kernel between two events: what the bracketing itself costs
         fill_u32_kernel<<<dim3(1), 64, 0, st>>>((uint32_t *)ix->nsel, 0u, 0);
-        ix->mark(7, st);
+        ix->mark(8, st);
     }
     if (ix->prof_step < ix->prof_max) ix->prof_step++;
     HIP_TRY(hipGetLastError());
@@ -793,6 +819,12 @@ int ctkvr_debug_trace_read(long long *dst_host)
 {
     HIP_TRY(hipDeviceSynchronize());
     HIP_TRY(hipMemcpyFromSymbol(dst_host, HIP_SYMBOL(ctkvr::g_trace), sizeof(long long) * 128));
+    return CTKVR_OK;
+}
+int ctkvr_debug_blk_read(long long *dst_host)
+{
+    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipMemcpyFromSymbol(dst_host, HIP_SYMBOL(ctkvr::g_blk), sizeof(long long) * 8 * 1024));
     return CTKVR_OK;
 }
 #endif

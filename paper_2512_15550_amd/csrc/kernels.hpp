@@ -1,9 +1,10 @@
 // gfx950 kernels of the CTkvr path.
 //
-// Decode step (Algorithm 2 lines 1-9), six launches:
+// Decode step (Algorithm 2 lines 1-9), seven launches:
 //   centroid_cos  lines 1-2   cosine to every centroid, max over the GQA group
-//   recall        lines 3-4   top-C' centroids; union of their lists as an
-//                             ascending id list plus each id's physical KV row
+//   recall_gather lines 3-4a  top-C' centroids; their lists OR-ed into a bitmap
+//   recall_expand line  4b    the bitmap as an ascending id list plus each id's
+//                             physical KV row
 //   score         line 5a     z = (q . k) * scale for the G heads, running max
 //   denom         line 5b     softmax denominators, integer fixed point
 //   rerank_select lines 5c-6  max over the group of log-softmax, top-rho' ids
@@ -179,119 +180,175 @@ template <typename T, int G> __global__ __launch_bounds__(256) void centroid_cos
 }
 
 // ------------------------------------------------------------------------------
-// Algorithm 2 lines 3-4: top-C' centroids, then the deduplicated union of their
-// lists as an ascending id list, and the physical KV row of every id.  One block
-// of 1024 threads per (sequence, KV head); dynamic shared memory: select scratch
-// (kSelLds words) + probe ids (n_probe) + bitmap (ceil(s_max/32) words) + the
-// sequence's block-table row when it fits (bt_lds words, else 0).
-// KPT: centroid keys per thread (C <= 1024*KPT).
+// Algorithm 2 lines 3-4 in two launches, each (sequence, KV head) spread over
+// several blocks so that no single CU has to pull all the probed lists.
+//
+// recall_gather: every block of a unit finds the same top-C' centroids (keys in
+// registers, C <= 256*KPT, bisection on the key), takes every gridDim.x-th probed list, ORs its ids into a bitmap in shared memory and then
+// ORs the non-empty words into the unit's bitmap in global memory (integer ORs: any
+// order gives the same bitmap).  grid (nsplit, batch*g), 256 threads; dynamic shared
+// memory: kSelLds + n_probe + bitmap words.
 // ------------------------------------------------------------------------------
-struct RecallArgs {
+struct GatherArgs {
     const float *cos;         // [batch*g][c_max]
     const int32_t *lists;     // [batch*g][c_max][rho]
     const int32_t *n_cent, *ctx_lens;
-    const int32_t *block_table;
-    int max_pages, page_shift;
     int32_t *probe;           // [batch*g][n_probe]
-    int32_t *cand;            // [batch*g][l_stride]
-    uint32_t *crow;           // [batch*g][l_stride] physical row of cand[i]
-    int32_t *ncand;           // [batch*g]
-    int32_t *out_probe, *out_ncand;   // optional copies for the caller
-    int g, c_max, rho, n_probe, l_stride;
-    int bitmap_words;         // words reserved for the bitmap
-    int bt_lds;               // block-table entries staged in shared memory (0: read from global)
+    int32_t *out_probe;       // optional copy for the caller
+    uint32_t *gbits;          // [batch*g][bitmap_words], all zero between steps
+    int g, c_max, rho, n_probe, bitmap_words;
 };
 
-template <int KPT> __global__ __launch_bounds__(1024) void recall_kernel(RecallArgs a)
+template <int KPT> __global__ __launch_bounds__(256) void recall_gather_kernel(GatherArgs a)
 {
     extern __shared__ uint32_t smem[];
     uint32_t *s_sel = smem;
     int32_t *s_probe = (int32_t *)(smem + kSelLds);
     uint32_t *s_bits = smem + kSelLds + a.n_probe;
-    int32_t *s_bt = (int32_t *)(s_bits + a.bitmap_words);
-    const int ul = blockIdx.x, tid = threadIdx.x;
-    const int b = ul / a.g, kv = ul - b * a.g;
+    const int ul = blockIdx.y, tid = threadIdx.x, wv = tid >> 6, ln = tid & 63;
+    const int b = ul / a.g;
     const int C = a.n_cent[b], s = a.ctx_lens[b];
     const float *cosv = a.cos + (size_t)ul * a.c_max;
     const int W = (s + 31) >> 5;
-    const int npages = (s + (1 << a.page_shift) - 1) >> a.page_shift;
     CTKVR_STAMP(8);
-    for (int w = tid; w < W; w += 1024) s_bits[w] = 0u;
-    if (a.bt_lds)
-        for (int pg = tid; pg < npages; pg += 1024) s_bt[pg] = a.block_table[(size_t)b * a.max_pages + pg];
+    CTKVR_STAMP_BLK(0);
+    for (int w = tid; w < W; w += 256) s_bits[w] = 0u;
+    auto keep = [&](int pos, int j) {
+        s_probe[pos] = j;
+        if (blockIdx.x == 0) {
+            a.probe[(size_t)ul * a.n_probe + pos] = j;
+            if (a.out_probe) a.out_probe[(size_t)ul * a.n_probe + pos] = j;
+        }
+    };
     // line 3
-    block_select_topk<1024, KPT>([&](int j) { return ordered_key(cosv[j]); }, C, a.n_probe,
-                                 [&](int pos, int j) {
-                                     s_probe[pos] = j;
-                                     a.probe[(size_t)ul * a.n_probe + pos] = j;
-                                     if (a.out_probe) a.out_probe[(size_t)ul * a.n_probe + pos] = j;
-                                 },
-                                 s_sel);
+    block_bisect_topk<256, KPT>([&](int j) { return ordered_key(cosv[j]); }, C, a.n_probe, keep, s_sel);
     __syncthreads();
     CTKVR_STAMP(9);
-    // line 4: mark every key id of the probed lists
+    // line 4: this block's share of the probed lists, one list per wave at a time
     const int32_t *lb = a.lists + (size_t)ul * a.c_max * a.rho;
-    if ((a.rho & 3) == 0) {
-        const int rho4 = a.rho >> 2;
-        const int total4 = a.n_probe * rho4;
+    for (int p = blockIdx.x + gridDim.x * wv; p < a.n_probe; p += gridDim.x * 4) {
+        if ((a.rho & 3) == 0) {
+            const int4 *src = reinterpret_cast<const int4 *>(lb + (size_t)s_probe[p] * a.rho);
+            const int rho4 = a.rho >> 2;
 #pragma unroll 8
-        for (int idx = tid; idx < total4; idx += 1024) {
-            int p = idx / rho4, r = idx - p * rho4;
-            int4 t = *reinterpret_cast<const int4 *>(lb + (size_t)s_probe[p] * a.rho + 4 * r);
-            atomicOr(&s_bits[t.x >> 5], 1u << (t.x & 31));
-            atomicOr(&s_bits[t.y >> 5], 1u << (t.y & 31));
-            atomicOr(&s_bits[t.z >> 5], 1u << (t.z & 31));
-            atomicOr(&s_bits[t.w >> 5], 1u << (t.w & 31));
-        }
-    } else {
-        const int total = a.n_probe * a.rho;
+            for (int r = ln; r < rho4; r += 64) {
+                int4 t = src[r];
+                atomicOr(&s_bits[t.x >> 5], 1u << (t.x & 31));
+                atomicOr(&s_bits[t.y >> 5], 1u << (t.y & 31));
+                atomicOr(&s_bits[t.z >> 5], 1u << (t.z & 31));
+                atomicOr(&s_bits[t.w >> 5], 1u << (t.w & 31));
+            }
+        } else {
+            const int32_t *src = lb + (size_t)s_probe[p] * a.rho;
 #pragma unroll 8
-        for (int idx = tid; idx < total; idx += 1024) {
-            int p = idx / a.rho, r = idx - p * a.rho;
-            int t = lb[(size_t)s_probe[p] * a.rho + r];
-            atomicOr(&s_bits[t >> 5], 1u << (t & 31));
+            for (int r = ln; r < a.rho; r += 64) {
+                int t = src[r];
+                atomicOr(&s_bits[t >> 5], 1u << (t & 31));
+            }
         }
     }
     __syncthreads();
     CTKVR_STAMP(10);
-    // ordered expansion of the bitmap: thread t owns words [t*per, (t+1)*per)
-    const int per = (W + 1023) >> 10;
-    uint32_t cnt = 0;
-    for (int q = 0; q < per; ++q) {
-        int w = tid * per + q;
-        if (w < W) cnt += __popc(s_bits[w]);
+    uint32_t *gb = a.gbits + (size_t)ul * a.bitmap_words;
+    for (int w = tid; w < W; w += 256) {
+        uint32_t v = s_bits[w];
+        if (v) atomicOr(&gb[w], v);
     }
-    uint32_t tot;
-    uint32_t at = block_excl_scan<1024>(cnt, s_sel, &tot);
+    CTKVR_STAMP_BLK(1);
+}
+
+// ------------------------------------------------------------------------------
+// recall_expand: the unit's bitmap -> ascending id list + physical KV rows.  Block x
+// of a unit owns a contiguous slice of 32-word chunks; it counts the bits before its
+// slice (the bitmap is a few KB), then every wave scatters the set bits of a chunk
+// into its shared-memory staging area (at most 1024 ids) and copies that out with
+// consecutive lanes writing consecutive ids.  The bitmap is cleared later in the step
+// (by denom), once nobody reads it any more.  grid (nsplit, batch*g), 1024 threads;
+// dynamic shared memory: 16 x 1024 words of staging.
+// ------------------------------------------------------------------------------
+struct ExpandArgs {
+    const uint32_t *gbits;
+    const int32_t *ctx_lens;
+    const int32_t *block_table;
+    int max_pages, page_shift;
+    int32_t *cand;            // [batch*g][l_stride]
+    uint32_t *crow;           // [batch*g][l_stride] physical row of cand[i]
+    int32_t *ncand;           // [batch*g]
+    int32_t *out_ncand;       // optional copy for the caller
+    int g, l_stride, bitmap_words;
+};
+
+__global__ __launch_bounds__(1024) void recall_expand_kernel(ExpandArgs a)
+{
+    extern __shared__ uint32_t s_stage_all[];   // 16 x 1024 words
+    __shared__ uint32_t s_ctot[1024];
+    __shared__ uint32_t s_tmp[64];
+    const int ul = blockIdx.y, tid = threadIdx.x, wv = tid >> 6, ln = tid & 63;
+    const int b = ul / a.g, kv = ul - b * a.g;
+    const int s = a.ctx_lens[b];
+    const int W = (s + 31) >> 5;
+    const int chunks = (W + 31) >> 5;
+    const int cps = (chunks + gridDim.x - 1) / gridDim.x;   // chunks per slice (<= 1024 because W <= 32768)
+    const int c_beg = blockIdx.x * cps;
+    if (c_beg >= chunks) return;
+    const int c_end = min(chunks, c_beg + cps);
+    const uint32_t *gb = a.gbits + (size_t)ul * a.bitmap_words;
+    CTKVR_STAMP(11);
+    CTKVR_STAMP_BLK(6);
+    // ids before this slice
+    uint32_t before = 0;
+#pragma unroll 4
+    for (int w = tid; w < c_beg * 32; w += 1024) before += __popc(gb[w]);
+    // totals of this slice's chunks
+    for (int c = c_beg + wv; c < c_end; c += 16) {
+        int w = c * 32 + ln;
+        uint32_t cnt = (ln < 32 && w < W) ? __popc(gb[w]) : 0u;
+#pragma unroll
+        for (int o = 16; o >= 1; o >>= 1) cnt += __shfl_xor(cnt, o);
+        if (ln == 0) s_ctot[c - c_beg] = cnt;
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) before += __shfl_xor(before, o);
+    if (ln == 0) s_tmp[32 + wv] = before;
+    __syncthreads();
+    uint32_t base0 = 0;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) base0 += s_tmp[32 + q];
+    uint32_t own;
+    uint32_t ex = block_excl_scan<1024>(tid < (c_end - c_beg) ? s_ctot[tid] : 0u, s_tmp, &own);
+    if (tid < (c_end - c_beg)) s_ctot[tid] = base0 + ex;
+    __syncthreads();
     int32_t *out = a.cand + (size_t)ul * a.l_stride;
     uint32_t *rows = a.crow + (size_t)ul * a.l_stride;
-    const int pmask = (1 << a.page_shift) - 1;
-    for (int q = 0; q < per; ++q) {
-        int w = tid * per + q;
-        if (w < W) {
-            uint32_t m = s_bits[w];
-            while (m) {
+    for (int c = c_beg + wv; c < c_end; c += 16) {
+        int w = c * 32 + ln;
+        uint32_t m = (ln < 32 && w < W) ? gb[w] : 0u;
+        uint32_t cnt = __popc(m);
+        uint32_t incl = wave_incl_scan(cnt);
+        uint32_t pos = incl - cnt;
+        const uint32_t total = __shfl(incl, 63);
+        while (__ballot(m != 0u)) {
+            if (m) {
                 int bit = __ffs((int)m) - 1;
                 m &= m - 1;
-                int t = (w << 5) + bit;
-                out[at] = t;
-                if (a.bt_lds) rows[at] = (uint32_t)((s_bt[t >> a.page_shift] * a.g + kv) << a.page_shift) + (uint32_t)(t & pmask);
-                ++at;
+                s_stage_all[wv * 1024 + pos++] = (uint32_t)((w << 5) + bit);
             }
         }
+        __threadfence_block();   // the wave's own staging writes, before other lanes read them
+        const uint32_t cb = s_ctot[c - c_beg];
+        for (uint32_t k = ln; k < total; k += 64) {
+            int t = (int)s_stage_all[wv * 1024 + k];
+            out[cb + k] = t;
+            rows[cb + k] = row_of(a.block_table, a.max_pages, a.page_shift, a.g, b, kv, t);
+        }
+        __threadfence_block();
     }
-    if (tid == 0) {
-        a.ncand[ul] = (int32_t)tot;
-        if (a.out_ncand) a.out_ncand[ul] = (int32_t)tot;
-    }
-    CTKVR_STAMP(11);
-    if (!a.bt_lds) {
-        __syncthreads();   // the ids written above are read back by other threads of this block
-#pragma unroll 4
-        for (int i = tid; i < (int)tot; i += 1024)
-            rows[i] = row_of(a.block_table, a.max_pages, a.page_shift, a.g, b, kv, out[i]);
+    if (c_end == chunks && tid == 0) {
+        a.ncand[ul] = (int32_t)(base0 + own);
+        if (a.out_ncand) a.out_ncand[ul] = (int32_t)(base0 + own);
     }
     CTKVR_STAMP(12);
+    CTKVR_STAMP_BLK(7);
 }
 
 // ------------------------------------------------------------------------------
@@ -506,6 +563,8 @@ struct DenomArgs {
     const float *z;
     const uint32_t *m_key;
     unsigned long long *S;
+    uint32_t *gbits;          // decode only: the recall bitmap, cleared here for the next step
+    int bitmap_words;
 };
 
 template <int G> __global__ __launch_bounds__(256) void denom_kernel(DenomArgs a)
@@ -513,6 +572,10 @@ template <int G> __global__ __launch_bounds__(256) void denom_kernel(DenomArgs a
     int b, kv, j;
     const int ul = blockIdx.y;
     if (!decode_unit(a.u, ul, b, kv, j)) return;
+    if (a.gbits) {
+        const int W = (a.ctx_lens[b] + 31) >> 5;
+        for (int w = blockIdx.x * 256 + threadIdx.x; w < W; w += gridDim.x * 256) a.gbits[(size_t)ul * a.bitmap_words + w] = 0u;
+    }
     const int L = a.ncand ? a.ncand[ul] : a.ctx_lens[b];
     if ((int)blockIdx.x * 1024 >= L) return;
     const int tid = threadIdx.x;
@@ -564,6 +627,7 @@ struct SelectArgs {
     const float *z;
     const uint32_t *m_key;
     const unsigned long long *S;
+    uint32_t *kbuf;     // [units][l_stride] key scratch, used when a unit has more than 32768 keys
     int32_t *sel;       // decode [units][top_k] ; build: lists base
     uint32_t *srow;     // decode [units][top_k]
     float *zsel;        // decode [units][top_k][G]
@@ -620,6 +684,7 @@ template <int G> __global__ __launch_bounds__(1024) void rerank_select_kernel(Se
     if (!decode_unit(a.u, ul, b, kv, j)) return;
     const int L = a.cand ? a.ncand[ul] : a.ctx_lens[b];
     CTKVR_STAMP(28);
+    CTKVR_STAMP_BLK(2);
     float m[G], ls[G];
 #pragma unroll
     for (int hh = 0; hh < G; ++hh) m[hh] = ordered_value(a.m_key[ul * G + hh]);
@@ -641,16 +706,23 @@ template <int G> __global__ __launch_bounds__(1024) void rerank_select_kernel(Se
         select_emit<G, 8>(a, ul, L, key, zb, s_sel, s_idx);
     else if (L <= 1024 * 32)
         select_emit<G, 32>(a, ul, L, key, zb, s_sel, s_idx);
-    else
-        select_emit<G, 0>(a, ul, L, key, zb, s_sel, s_idx);
+    else {
+        // too many keys for registers: compute each key once into global scratch, then select on that
+        uint32_t *kb = a.kbuf + (size_t)ul * a.l_stride;
+#pragma unroll 8
+        for (int i = tid; i < L; i += 1024) kb[i] = key(i);
+        __syncthreads();
+        select_emit<G, 0>(a, ul, L, [&](int i) { return kb[i]; }, zb, s_sel, s_idx);
+    }
     CTKVR_STAMP(31);
+    CTKVR_STAMP_BLK(3);
 }
 
 // ------------------------------------------------------------------------------
 // Algorithm 2 lines 7-9: o_h = softmax(z_sel[h]) . V_sel.  grid (4, batch*g), 1024
 // threads: block x owns head dimensions 32x .. 32x+31 of all G heads of its
 // (sequence, KV head), so no partial result crosses a block.  Four lanes share a
-// row (8 dimensions each), 256 rows per pass.  Dynamic shared memory:
+// row (8 dimensions each; lane l, l+16, l+32, l+48 of a wave), 256 rows per pass.  Dynamic shared memory:
 // top_k*G floats (softmax weights) .
 // ------------------------------------------------------------------------------
 struct AttnArgs {
@@ -665,16 +737,28 @@ struct AttnArgs {
 
 template <typename T, int G> __global__ __launch_bounds__(1024) void sparse_attn_kernel(AttnArgs a)
 {
-    extern __shared__ float s_p[];                // [top_k][G]
+    extern __shared__ __align__(16) float s_p[];   // [top_k][G]
     __shared__ float s_red[16][G];
     __shared__ float s_m[G], s_l[G];
     __shared__ float s_o[16][G][32];
     const int ul = blockIdx.y, slice = blockIdx.x;
     const int b = ul / a.g, kv = ul - b * a.g;
-    const int nsel = a.nsel[ul];
     const int tid = threadIdx.x, wv = tid >> 6, ln = tid & 63;
-    const int quad = tid & 3, rin = tid >> 2;     // 4 lanes per row, 256 rows per pass
+    const int quad = ln >> 4, rin = wv * 16 + (ln & 15);   // 4 lanes (one per 16-lane row of the wave) share a key row
     CTKVR_STAMP(44);
+    CTKVR_STAMP_BLK(4);
+    const T *V = (const T *)a.v_pages + slice * 32 + quad * 8;
+    const uint32_t *rb = a.srow + (size_t)ul * a.top_k;
+    const float *zb = a.zsel + (size_t)ul * a.top_k * G;
+    // The first 1024 value rows are requested before anything else: srow always holds valid rows
+    // (beyond nsel they are stale ones whose products get weight 0), so nothing here waits for nsel.
+    Chunk<T> cv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        uint32_t row = rb[min(u * 256 + rin, a.top_k - 1)];
+        cv[u] = load_chunk(V + (size_t)row * kD, 0);
+    }
+    const int nsel = a.nsel[ul];
     if (nsel == 0) {   // nothing recalled: defined output
         if (tid < G * 32) {
             int hh = tid >> 5, e = tid & 31;
@@ -683,9 +767,6 @@ template <typename T, int G> __global__ __launch_bounds__(1024) void sparse_attn
         if (slice == 0 && a.out_lse && tid < G) a.out_lse[(size_t)b * a.h + kv * G + tid] = -__builtin_huge_valf();
         return;
     }
-    const T *V = (const T *)a.v_pages + slice * 32 + quad * 8;
-    const uint32_t *rb = a.srow + (size_t)ul * a.top_k;
-    const float *zb = a.zsel + (size_t)ul * a.top_k * G;
     // softmax statistics over the selected keys, per head
     float mx[G];
 #pragma unroll
@@ -751,12 +832,12 @@ template <typename T, int G> __global__ __launch_bounds__(1024) void sparse_attn
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[hh][e] = 0.0f;
     for (int r0 = 0; r0 < nsel; r0 += 1024) {
-        Chunk<T> cv[4];
+        if (r0 > 0) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            int t = r0 + u * 256 + rin;
-            uint32_t row = rb[t < nsel ? t : nsel - 1];
-            cv[u] = load_chunk(V + (size_t)row * kD, 0);
+            for (int u = 0; u < 4; ++u) {
+                uint32_t row = rb[min(r0 + u * 256 + rin, a.top_k - 1)];
+                cv[u] = load_chunk(V + (size_t)row * kD, 0);
+            }
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -764,28 +845,21 @@ template <typename T, int G> __global__ __launch_bounds__(1024) void sparse_attn
             if (t < nsel) {
                 float vx[8];
                 unpack(cv[u], vx);
+                float pv[G];
+                load_z<G>(s_p, t, pv);
 #pragma unroll
-                for (int hh = 0; hh < G; ++hh) {
-                    float p = s_p[t * G + hh];
+                for (int hh = 0; hh < G; ++hh)
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[hh][e] = __fmaf_rn(p, vx[e], acc[hh][e]);
-                }
+                    for (int e = 0; e < 8; ++e) acc[hh][e] = __fmaf_rn(pv[hh], vx[e], acc[hh][e]);
             }
         }
     }
-    // sum over the 16 rows of a wave (lanes with equal quad), then over the 16 waves in order
+    // sum over the 16 rows of a wave (a DPP butterfly inside each 16-lane row), then over the 16 waves in order
 #pragma unroll
     for (int hh = 0; hh < G; ++hh)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            float v = acc[hh][e];
-            v += __shfl_xor(v, 4);
-            v += __shfl_xor(v, 8);
-            v += __shfl_xor(v, 16);
-            v += __shfl_xor(v, 32);
-            acc[hh][e] = v;
-        }
-    if (ln < 4) {
+        for (int e = 0; e < 8; ++e) acc[hh][e] = group16_sum(acc[hh][e]);
+    if ((ln & 15) == 0) {
 #pragma unroll
         for (int hh = 0; hh < G; ++hh)
 #pragma unroll
@@ -802,6 +876,7 @@ template <typename T, int G> __global__ __launch_bounds__(1024) void sparse_attn
     }
     if (slice == 0 && a.out_lse && tid < G) a.out_lse[(size_t)b * a.h + kv * G + tid] = s_m[tid] + __logf(s_l[tid]);
     CTKVR_STAMP(47);
+    CTKVR_STAMP_BLK(5);
 }
 
 }  // namespace ctkvr
