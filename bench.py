@@ -99,6 +99,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"])
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run a plain device copy of known size instead (scale for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--kmeans", action="store_true", help="cfg5 only: also time the k-means centroid mode")
     ap.add_argument("--cpu-steps", type=int, default=None, help="decode steps of the CPU oracle sample (0 = skip)")
     args = ap.parse_args()
@@ -107,6 +109,20 @@ def main():
         sys.exit(2)
 
     import torch
+    if args.calibrate_copy:
+        # 1 GiB read + 1 GiB written per launch of torch's copy kernel, 8 launches (the first is a warm-up)
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(8):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 8
+        print(json.dumps({"calibrate_copy": True, "bytes_read_per_launch": src.numel() * 4,
+                          "bytes_written_per_launch": src.numel() * 4, "launches": 8,
+                          "GBps_read_plus_write": 2 * src.numel() * 4 / dt / 1e9}))
+        return
     import paper_2512_15550_amd as ck
     from ctkvr_inputs import gen_batch, workload
     from tests import harness as H   # device upload helpers only

@@ -457,16 +457,14 @@ __device__ __forceinline__ void block_bisect_topk(KeyFn key, int n, int k, EmitF
     uint32_t T = 0;
     for (int b = 30; b >= 0; b -= 2) {
         const uint32_t c1 = T | (1u << b), c2 = T | (2u << b), c3 = T | (3u << b);
+        // a compare leaves a 64-bit lane mask; its population count is the wave's count, all scalar
         uint32_t n1 = 0, n2 = 0, n3 = 0;
 #pragma unroll
         for (int it = 0; it < KPT; ++it) {
-            n1 += (kreg[it] >= c1);
-            n2 += (kreg[it] >= c2);
-            n3 += (kreg[it] >= c3);
+            n1 += (uint32_t)__popcll(__ballot(kreg[it] >= c1));
+            n2 += (uint32_t)__popcll(__ballot(kreg[it] >= c2));
+            n3 += (uint32_t)__popcll(__ballot(kreg[it] >= c3));
         }
-        n1 = wave_sum_uniform(n1);
-        n2 = wave_sum_uniform(n2);
-        n3 = wave_sum_uniform(n3);
         uint32_t *buf = s_tmp + ((b >> 1) & 1) * 3 * NW;
         if (ln == 0) {
             buf[wv] = n1;

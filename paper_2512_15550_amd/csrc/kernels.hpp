@@ -390,9 +390,9 @@ template <typename T, int G, int R> __global__ __launch_bounds__(256) void score
     for (int hh = 0; hh < G; ++hh) unpack(load_chunk(qb + (size_t)hh * a.qrows * kD, lane16), q[hh]);
     const T *K = (const T *)a.k.pages;
     float *zb = a.z + (size_t)ul * a.l_stride * G;
-    float mx[G];
-#pragma unroll
-    for (int hh = 0; hh < G; ++hh) mx[hh] = -__builtin_huge_valf();
+    // lane l of a 16-lane group keeps head (l mod G): its score, and that head's running maximum
+    float mxl = -__builtin_huge_valf();
+    const int myh = lane16 & (G - 1);
     for (int tile0 = blockIdx.x * TILE; tile0 < L; tile0 += gridDim.x * TILE) {
         __syncthreads();   // previous tile's rows are consumed
         if (tid < TILE) {
@@ -409,27 +409,25 @@ template <typename T, int G, int R> __global__ __launch_bounds__(256) void score
         for (int r = 0; r < R; ++r) {
             float kx[8];
             unpack(ck[r], kx);
-            float zz[G];
+            float mine = 0.0f;
 #pragma unroll
-            for (int hh = 0; hh < G; ++hh) zz[hh] = group16_sum(lane_partial(q[hh], kx)) * a.scale;
+            for (int hh = 0; hh < G; ++hh) {
+                float tot = group16_sum(lane_partial(q[hh], kx));
+                if (hh == 0 || myh == hh) mine = tot;
+            }
+            mine = mine * a.scale;
             const int i = tile0 + r * 16 + grp;
             if (i < L) {
-                float mine = zz[0];
-#pragma unroll
-                for (int hh = 0; hh < G; ++hh) {
-                    mx[hh] = fmaxf(mx[hh], zz[hh]);
-                    if (lane16 == hh) mine = zz[hh];
-                }
+                mxl = __builtin_amdgcn_fmed3f(mxl, mine, __builtin_huge_valf());   // max of two non-NaN values
                 if (lane16 < G) zb[(size_t)i * G + lane16] = mine;
             }
         }
     }
-#pragma unroll
-    for (int hh = 0; hh < G; ++hh) {
-        float v = mx[hh];
-        v = fmaxf(v, __shfl_xor(v, 16));
-        v = fmaxf(v, __shfl_xor(v, 32));
-        if (lane_id() == 0) atomicMax(&s_max[hh], ordered_key(v));
+    {
+        float v = mxl;
+        v = __builtin_amdgcn_fmed3f(v, __shfl_xor(v, 16), __builtin_huge_valf());
+        v = __builtin_amdgcn_fmed3f(v, __shfl_xor(v, 32), __builtin_huge_valf());
+        if (lane_id() < G) atomicMax(&s_max[lane_id()], ordered_key(v));
     }
     __syncthreads();
     if (tid < G) atomicMax(&a.m_key[ul * G + tid], s_max[tid]);
