@@ -464,16 +464,9 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     sa.m_key = ix->m_key;
     sa.scale = ix->scale;
     // enough blocks to fill the chip a few times over, each walking its share of 128-id tiles
-    static const int bpc = getenv("CTKVR_SCORE_BPC") ? atoi(getenv("CTKVR_SCORE_BPC")) : 4;
-    static const int rr = getenv("CTKVR_SCORE_R") ? atoi(getenv("CTKVR_SCORE_R")) : 8;
-    const int tiles = (ix->l_stride + 16 * rr - 1) / (16 * rr);
-    const int nbx = std::max(1, std::min(tiles, (bpc * ix->num_cu + U - 1) / U));
-    if (rr == 4)
-        score_kernel<T, G, 4><<<dim3(nbx, U), 256, 0, st>>>(sa);
-    else if (rr == 16)
-        score_kernel<T, G, 16><<<dim3(nbx, U), 256, 0, st>>>(sa);
-    else
-        score_kernel<T, G, 8><<<dim3(nbx, U), 256, 0, st>>>(sa);
+    const int tiles = (ix->l_stride + 127) / 128;
+    const int nbx = std::max(1, std::min(tiles, (8 * ix->num_cu + U - 1) / U));
+    score_kernel<T, G, 8><<<dim3(nbx, U), 256, 0, st>>>(sa);
     ix->mark(4, st);
 
     DenomArgs da{};
@@ -520,7 +513,7 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     aa.zsel = ix->zsel;
     aa.out = out;
     aa.out_lse = out_lse;
-    sparse_attn_kernel<T, G><<<dim3(4, U), 1024, ix->attn_lds, st>>>(aa);
+    sparse_attn_kernel<T, G><<<dim3(4 * U), 1024, ix->attn_lds, st>>>(aa);
     ix->mark(7, st);
     if (ix->prof_step < ix->prof_max) {   // a null kernel between two events: what the bracketing itself costs
         fill_u32_kernel<<<dim3(1), 64, 0, st>>>((uint32_t *)ix->nsel, 0u, 0);

@@ -717,7 +717,7 @@ template <int G> __global__ __launch_bounds__(1024) void rerank_select_kernel(Se
 }
 
 // ------------------------------------------------------------------------------
-// Algorithm 2 lines 7-9: o_h = softmax(z_sel[h]) . V_sel.  grid (4, batch*g), 1024
+// Algorithm 2 lines 7-9: o_h = softmax(z_sel[h]) . V_sel.  grid 4*batch*g, 1024
 // threads: block x owns head dimensions 32x .. 32x+31 of all G heads of its
 // (sequence, KV head), so no partial result crosses a block.  Four lanes share a
 // row (8 dimensions each; lane l, l+16, l+32, l+48 of a wave), 256 rows per pass.  Dynamic shared memory:
@@ -739,7 +739,20 @@ template <typename T, int G> __global__ __launch_bounds__(1024) void sparse_attn
     __shared__ float s_red[16][G];
     __shared__ float s_m[G], s_l[G];
     __shared__ float s_o[16][G][32];
-    const int ul = blockIdx.y, slice = blockIdx.x;
+    // Workgroups go to the 8 XCDs round-robin by linear id.  The four slices of a unit read the same
+    // 128-byte lines, so they are given ids that are congruent modulo 8: one XCD, one L2.
+    int ul, slice;
+    {
+        const int lin = blockIdx.x, nu = gridDim.x >> 2;
+        if ((nu & 7) == 0) {
+            const int xcd = lin & 7, k = lin >> 3;
+            ul = (k >> 2) * 8 + xcd;
+            slice = k & 3;
+        } else {
+            ul = lin >> 2;
+            slice = lin & 3;
+        }
+    }
     const int b = ul / a.g, kv = ul - b * a.g;
     const int tid = threadIdx.x, wv = tid >> 6, ln = tid & 63;
     const int quad = ln >> 4, rin = wv * 16 + (ln & 15);   // 4 lanes (one per 16-lane row of the wave) share a key row
