@@ -165,10 +165,12 @@ int ctkvr_index_last_candidates(const ctkvr_index *idx, int32_t *dst_host);
 /* ---- per-kernel timing (measurement aid) ----------------------------------- */
 /* The decode step runs these kernels in order: 0 centroid cosine, 1 probe select +
  * list gather into a bitmap, 2 bitmap expansion into the recalled id list, 3 key
- * scoring over the recalled ids, 4 softmax denominators, 5 rerank select, 6 sparse
- * attention.  While timing is enabled an eighth, empty kernel follows (stage 7):
- * its figure is what a pair of events costs around a kernel that does nothing. */
-#define CTKVR_N_STAGES 8
+ * scoring over the recalled ids, 4 softmax denominators, 5 ranking keys + their
+ * histogram, 6 chip-wide pass over the ranking keys (bitmap + deciding bucket's list),
+ * 7 rerank select, 8 sparse attention.  While timing is enabled a tenth, empty kernel
+ * follows (stage 9): its figure is what a pair of events costs around a kernel that
+ * does nothing. */
+#define CTKVR_N_STAGES 10
 /* After this call every decode step on `idx` records a HIP event before its first
  * kernel and after each kernel, for up to max_steps steps (0 disables and frees
  * the events).  Recording adds work to the stream: use it for the breakdown, not

@@ -73,8 +73,9 @@ _lib = None
 EXPORTS = ["ctkvr_build_index", "ctkvr_index_load", "ctkvr_decode_step", "ctkvr_free", "ctkvr_last_error",
            "ctkvr_index_info", "ctkvr_index_lists", "ctkvr_index_centroids", "ctkvr_index_last_candidates",
            "ctkvr_profile_enable", "ctkvr_profile_collect"]
-N_STAGES = 8
-STAGE_NAMES = ["centroid_cos", "recall_gather", "recall_expand", "score", "denom", "rerank_select", "sparse_attn", "null"]
+N_STAGES = 10
+STAGE_NAMES = ["centroid_cos", "recall_gather", "recall_expand", "score", "denom", "keyhist", "classify",
+               "rerank_select", "sparse_attn", "null"]
 
 
 def library_path() -> str:

@@ -203,31 +203,149 @@ template <int NT> __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v
 }
 
 // ---- block-wide top-k selection ---------------------------------------------------
-// Among keys key(i), i in [0, n), pick the k largest, ties towards the lowest i,
-// and call emit(pos, i) with pos = rank of i among the picked in ascending i.
-// One block of NT threads; s_hist needs 2048 + 64 words.  Returns min(n, k) to
-// every thread.
+// Shared-memory words the selection routines need at `s_hist`: 2048 histogram bins, then
+// [0] lo, [1] hi, [2] bin, [3] remaining, scan scratch, wave counts, and two words at +56.
+//
+// block_kth_largest: T = the k-th largest of the keys that `for_slots` enumerates (as
+// f(id, valid, key), the same sequence in every call, ids distinct), and need_eq = how many of
+// the keys equal to T belong to the k largest.  MSB-first radix select on 11-bit digits,
+// starting at the highest bit in which the keys differ at all (one min/max pass); when at most
+// 128 keys share the deciding digit they are gathered and ranked against each other instead of
+// walking the remaining digits.  Every thread of the block takes part; 1 <= k <= number of keys.
+template <int NT, typename SlotsFn>
+__device__ __forceinline__ void block_kth_largest(SlotsFn for_slots, uint32_t k, uint32_t *s_hist, uint32_t &T,
+                                                  uint32_t &need_eq)
+{
+    const int tid = threadIdx.x;
+    const int ln = lane_id();
+    uint32_t *s_aux = s_hist + 2048;
+    uint32_t *s_scan = s_aux + 4;
+    uint32_t *s_x = s_hist + 2048 + 56;   // [0] population of the deciding bin, [1] gather cursor
+    // pass 0: range of the keys
+    uint32_t lo = 0xffffffffu, hi = 0u;
+    for_slots([&](int, bool valid, uint32_t kk) {
+        if (valid) {
+            lo = min(lo, kk);
+            hi = max(hi, kk);
+        }
+    });
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        lo = min(lo, (uint32_t)__shfl_xor(lo, o));
+        hi = max(hi, (uint32_t)__shfl_xor(hi, o));
+    }
+    __syncthreads();
+    if (tid == 0) { s_aux[0] = 0xffffffffu; s_aux[1] = 0u; }
+    __syncthreads();
+    if (ln == 0) { atomicMin(&s_aux[0], lo); atomicMax(&s_aux[1], hi); }
+    __syncthreads();
+    lo = s_aux[0];
+    hi = s_aux[1];
+    uint32_t prefix = hi, pmask = 0xffffffffu;
+    uint32_t remaining = k;
+    int bit = 0;   // number of still undecided low bits
+    if (lo != hi) {
+        bit = 32 - __clz((int)(lo ^ hi));
+        pmask = (bit >= 32) ? 0u : ~((1u << bit) - 1u);
+        prefix = hi & pmask;
+    }
+    while (bit > 0) {
+        const int w = bit < 11 ? bit : 11;
+        const int shift = bit - w;
+        const uint32_t dmask = (1u << w) - 1u;
+        const int nbins = 1 << w;
+        __syncthreads();
+        for (int i = tid; i < nbins; i += NT) s_hist[i] = 0;
+        __syncthreads();
+        for_slots([&](int, bool valid, uint32_t kk) {
+            if (valid && (kk & pmask) == prefix) atomicAdd(&s_hist[(kk >> shift) & dmask], 1u);
+        });
+        __syncthreads();
+        // walk the bins from the top: thread t owns the BPT bins below nbins - BPT*t
+        constexpr int BPT = 2048 / NT;
+        uint32_t c[BPT];
+        uint32_t mine = 0;
+#pragma unroll
+        for (int q = 0; q < BPT; ++q) {
+            int bq = nbins - 1 - (BPT * tid + q);
+            c[q] = (bq >= 0) ? s_hist[bq] : 0u;
+            mine += c[q];
+        }
+        uint32_t tot;
+        uint32_t before = block_excl_scan<NT>(mine, s_scan, &tot);
+#pragma unroll
+        for (int q = 0; q < BPT; ++q) {
+            int bq = nbins - 1 - (BPT * tid + q);
+            if (bq >= 0 && before < remaining && remaining <= before + c[q]) {
+                s_aux[2] = (uint32_t)bq;
+                s_aux[3] = remaining - before;
+                s_x[0] = c[q];
+                s_x[1] = 0u;
+            }
+            before += c[q];
+        }
+        __syncthreads();
+        prefix |= s_aux[2] << shift;
+        pmask |= dmask << shift;
+        remaining = s_aux[3];
+        bit = shift;
+        const uint32_t nb = s_x[0];
+        if (bit > 0 && nb <= 128u) {   // ranking is quadratic in nb: only when it is cheaper than another digit
+            // The key of rank `remaining` among the gathered ones is T.  Ids only make the ranks
+            // distinct here: which of the keys equal to T are picked is decided by the caller.
+            uint32_t *l_key = s_hist, *l_idx = s_hist + 1024;
+            __syncthreads();   // the histogram has been read by everyone
+            for_slots([&](int i, bool valid, uint32_t kk) {
+                if (valid && (kk & pmask) == prefix) {
+                    uint32_t at = atomicAdd(&s_x[1], 1u);
+                    l_key[at] = kk;
+                    l_idx[at] = (uint32_t)i;
+                }
+            });
+            __syncthreads();
+            for (uint32_t j = tid; j < nb; j += NT) {
+                const uint32_t mk = l_key[j], mi = l_idx[j];
+                uint32_t rank = 0, gt = 0;
+                for (uint32_t e = 0; e < nb; ++e) {
+                    const uint32_t ke = l_key[e], ie = l_idx[e];
+                    gt += (ke > mk);
+                    rank += (ke > mk) || (ke == mk && ie < mi);
+                }
+                if (rank == remaining - 1u) {
+                    s_aux[2] = mk;
+                    s_aux[3] = remaining - gt;
+                }
+            }
+            __syncthreads();
+            prefix = s_aux[2];
+            pmask = 0xffffffffu;
+            remaining = s_aux[3];
+            bit = 0;
+        }
+    }
+    T = prefix;
+    need_eq = remaining;
+}
+
+// block_select_topk: among keys key(i), i in [0, n), pick the k largest, ties towards the
+// lowest i, and call emit(pos, i) with pos = rank of i among the picked in ascending i.
+// One block of NT threads; s_hist needs 2048 + 64 words.  Returns min(n, k) to every thread.
 //
 // Layout: wave w owns the contiguous ids [w*per, (w+1)*per), lane-strided inside,
 // per = a multiple of 64 covering n/NW.  With KPT > 0 each thread keeps its keys
 // in KPT registers (needs n <= NT*KPT) and key() is called once per id; with
 // KPT == 0 key() is called again in every pass.
 //
-// Method: MSB-first radix select on 11-bit digits, starting at the highest bit in
-// which the keys differ at all (one min/max pass), which finds the k-th largest
-// key T and how many keys equal to T still belong to the pick; then an ordered
-// compaction: each wave counts its range, one scan over the wave totals, and
-// every wave writes its picks in place with ballot ranks -- no atomics decide
-// an order.
+// After block_kth_largest the picks are compacted in order: each wave counts its range, one scan
+// over the wave totals, and every wave writes its picks in place with ballot ranks -- no atomics
+// decide an order.
 template <int NT, int KPT, typename KeyFn, typename EmitFn>
 __device__ int block_select_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t *s_hist)
 {
     constexpr int NW = NT / 64;
     const int tid = threadIdx.x;
     const int wv = tid >> 6, ln = lane_id();
-    uint32_t *s_aux = s_hist + 2048;   // [0] lo, [1] hi, [2] bin, [3] remaining
-    uint32_t *s_scan = s_aux + 4;      // NW + 1 words of scan scratch, then 2*NW wave counts
-    uint32_t *s_x = s_hist + 2048 + 56;   // [0] population of the deciding bin, [1] gather cursor
+    uint32_t *s_scan = s_hist + 2048 + 4;
     if (k >= n) {
         for (int i = tid; i < n; i += NT) emit(i, i);
         return n;
@@ -270,117 +388,8 @@ __device__ int block_select_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t 
             }
         }
     };
-    CTKVR_STAMP(32);
-    // pass 0: range of the keys
-    uint32_t lo = 0xffffffffu, hi = 0u;
-    for_slots([&](int, bool valid, uint32_t kk) {
-        if (valid) {
-            lo = min(lo, kk);
-            hi = max(hi, kk);
-        }
-    });
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-        lo = min(lo, (uint32_t)__shfl_xor(lo, o));
-        hi = max(hi, (uint32_t)__shfl_xor(hi, o));
-    }
-    __syncthreads();
-    if (tid == 0) { s_aux[0] = 0xffffffffu; s_aux[1] = 0u; }
-    __syncthreads();
-    if (ln == 0) { atomicMin(&s_aux[0], lo); atomicMax(&s_aux[1], hi); }
-    __syncthreads();
-    lo = s_aux[0];
-    hi = s_aux[1];
-    uint32_t prefix = hi, pmask = 0xffffffffu;
-    uint32_t remaining = (uint32_t)k;
-    int bit = 0;   // number of still undecided low bits
-    if (lo != hi) {
-        bit = 32 - __clz((int)(lo ^ hi));
-        pmask = (bit >= 32) ? 0u : ~((1u << bit) - 1u);
-        prefix = hi & pmask;
-    }
-    CTKVR_STAMP(33);
-    int pass_ = 0;
-    while (bit > 0) {
-        CTKVR_STAMP(34 + pass_);
-        ++pass_;
-        const int w = bit < 11 ? bit : 11;
-        const int shift = bit - w;
-        const uint32_t dmask = (1u << w) - 1u;
-        const int nbins = 1 << w;
-        __syncthreads();
-        for (int i = tid; i < nbins; i += NT) s_hist[i] = 0;
-        __syncthreads();
-        for_slots([&](int, bool valid, uint32_t kk) {
-            if (valid && (kk & pmask) == prefix) atomicAdd(&s_hist[(kk >> shift) & dmask], 1u);
-        });
-        __syncthreads();
-        // walk the bins from the top: thread t owns the BPT bins below nbins - BPT*t
-        constexpr int BPT = 2048 / NT;
-        uint32_t c[BPT];
-        uint32_t mine = 0;
-#pragma unroll
-        for (int q = 0; q < BPT; ++q) {
-            int bq = nbins - 1 - (BPT * tid + q);
-            c[q] = (bq >= 0) ? s_hist[bq] : 0u;
-            mine += c[q];
-        }
-        uint32_t tot;
-        uint32_t before = block_excl_scan<NT>(mine, s_scan, &tot);
-#pragma unroll
-        for (int q = 0; q < BPT; ++q) {
-            int bq = nbins - 1 - (BPT * tid + q);
-            if (bq >= 0 && before < remaining && remaining <= before + c[q]) {
-                s_aux[2] = (uint32_t)bq;
-                s_aux[3] = remaining - before;
-                s_x[0] = c[q];
-                s_x[1] = 0u;
-            }
-            before += c[q];
-        }
-        __syncthreads();
-        prefix |= s_aux[2] << shift;
-        pmask |= dmask << shift;
-        remaining = s_aux[3];
-        bit = shift;
-        const uint32_t nb = s_x[0];
-        if (bit > 0 && nb <= 128u) {   // ranking is quadratic in nb: only when it is cheaper than another digit
-            // Few keys share the deciding digit: gather them and rank them against each other
-            // instead of walking the remaining digits.  The key of rank `remaining` among them is
-            // the threshold T; the picks among the keys equal to T are the lowest ids, as always.
-            uint32_t *l_key = s_hist, *l_idx = s_hist + 1024;
-            __syncthreads();   // the histogram has been read by everyone
-            for_slots([&](int i, bool valid, uint32_t kk) {
-                if (valid && (kk & pmask) == prefix) {
-                    uint32_t at = atomicAdd(&s_x[1], 1u);
-                    l_key[at] = kk;
-                    l_idx[at] = (uint32_t)i;
-                }
-            });
-            __syncthreads();
-            for (uint32_t j = tid; j < nb; j += NT) {
-                const uint32_t mk = l_key[j], mi = l_idx[j];
-                uint32_t rank = 0, gt = 0;
-                for (uint32_t e = 0; e < nb; ++e) {
-                    const uint32_t ke = l_key[e], ie = l_idx[e];
-                    gt += (ke > mk);
-                    rank += (ke > mk) || (ke == mk && ie < mi);
-                }
-                if (rank == remaining - 1u) {
-                    s_aux[2] = mk;
-                    s_aux[3] = remaining - gt;
-                }
-            }
-            __syncthreads();
-            prefix = s_aux[2];
-            pmask = 0xffffffffu;
-            remaining = s_aux[3];
-            bit = 0;
-        }
-    }
-    const uint32_t T = prefix;
-    const uint32_t need_eq = remaining;
-    CTKVR_STAMP(38);
+    uint32_t T, need_eq;
+    block_kth_largest<NT>(for_slots, (uint32_t)k, s_hist, T, need_eq);
     // ordered compaction
     uint32_t cgt = 0, ceq = 0;
     for_slots([&](int, bool valid, uint32_t kk) {
@@ -398,7 +407,6 @@ __device__ int block_select_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t 
     __syncthreads();
     uint32_t run_gt = 0, run_eq = 0;
     for (int q = 0; q < wv; ++q) { run_gt += s_cnt[2 * q]; run_eq += s_cnt[2 * q + 1]; }
-    CTKVR_STAMP(39);
     const uint64_t below = (1ull << ln) - 1ull;
     for_slots([&](int i, bool valid, uint32_t kk) {
         bool gt = valid && kk > T, eq = valid && kk == T;
@@ -409,7 +417,223 @@ __device__ int block_select_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t 
         run_gt += (uint32_t)__popcll(mg);
         run_eq += (uint32_t)__popcll(me);
     });
-    CTKVR_STAMP(40);
+    return k;
+}
+
+// ---- top-k selection helped by a histogram of the keys ---------------------------------
+constexpr int kBuckets = 2048;
+constexpr int kListCap = 2048;
+
+// bucket 0 holds the largest keys: buckets are 1/32 wide in the log domain down to -64,
+// everything below shares the last one.  Monotone in the key.
+__device__ __forceinline__ uint32_t key_bucket(uint32_t kk)
+{
+    float t = fminf(-ordered_value(kk) * 32.0f, (float)(kBuckets - 1));
+    return (uint32_t)fmaxf(t, 0.0f);
+}
+
+// Second half of the histogram-helped selection, on data already in shared memory: s_gt = bitmap
+// of the ids above the deciding bucket, s_eq = zeroed bitmap, l_ent[0..nb) = the (key, id) pairs
+// of the deciding bucket, of which the `rem` largest keys are still wanted (ties: lowest ids).
+// n ids in all (both bitmaps have 2*ceil(n/64) words).  Starts with the data as written by other
+// threads: the caller places a barrier before the call.
+template <int NT, typename EmitFn>
+__device__ __forceinline__ void block_resolve_emit(uint32_t nb, uint32_t rem, int n, uint32_t *s_hist, uint32_t *s_gt,
+                                                   uint32_t *s_eq, const uint2 *l_ent, EmitFn emit)
+{
+    const int tid = threadIdx.x;
+    uint32_t *s_scan = s_hist + 2048 + 4;
+    const int nw64 = (n + 63) >> 6;
+    // T among the nb listed keys (rem-th largest)
+    uint32_t T, need_eq;
+    {
+        auto for_list = [&](auto f) __attribute__((always_inline)) {
+#pragma unroll
+            for (int q = 0; q < kListCap / NT; ++q) {
+                const uint32_t e = (uint32_t)(q * NT + tid);
+                const bool valid = e < nb;
+                f((int)e, valid, valid ? l_ent[e].x : 0u);
+            }
+        };
+        block_kth_largest<NT>(for_list, rem, s_hist, T, need_eq);
+    }
+    __syncthreads();
+    CTKVR_STAMP(35);
+    for (uint32_t e = tid; e < nb; e += NT) {
+        const uint2 en = l_ent[e];
+        if (en.x > T) atomicOr(&s_gt[en.y >> 5], 1u << (en.y & 31u));
+        if (en.x == T) atomicOr(&s_eq[en.y >> 5], 1u << (en.y & 31u));
+    }
+    __syncthreads();
+    CTKVR_STAMP(36);
+    // thread t owns the words [t*wpt, (t+1)*wpt) of both bitmaps: count, scan, emit in order
+    const int nw32 = 2 * nw64;
+    const int wpt = (nw32 + NT - 1) / NT;
+    const int w0 = min(nw32, tid * wpt), w1 = min(nw32, w0 + wpt);
+    uint32_t cgt = 0, ceq = 0;
+    for (int w = w0; w < w1; ++w) {
+        cgt += (uint32_t)__popc(s_gt[w]);
+        ceq += (uint32_t)__popc(s_eq[w]);
+    }
+    uint32_t tot;
+    uint32_t gt_before = block_excl_scan<NT>(cgt, s_scan, &tot);
+    __syncthreads();
+    uint32_t eq_before = block_excl_scan<NT>(ceq, s_scan, &tot);
+    uint32_t pos = gt_before + min(eq_before, need_eq);
+    CTKVR_STAMP(38);
+    for (int w = w0; w < w1; ++w) {
+        const uint32_t mg = s_gt[w], me = s_eq[w];
+        uint32_t m = mg | me;
+        while (m) {
+            const int bpos = __ffs((int)m) - 1;
+            const uint32_t one = 1u << bpos;
+            m &= m - 1u;
+            if (mg & one) {
+                emit((int)pos++, w * 32 + bpos);
+            } else {
+                if (eq_before < need_eq) emit((int)pos++, w * 32 + bpos);
+                ++eq_before;
+            }
+        }
+    }
+}
+
+// Same contract as block_select_topk, for keys that are images of log-probabilities (<= 0) and
+// come with a histogram `ghist` (kBuckets counts) over key_bucket(), built beforehand by a
+// chip-wide kernel.  One scan of the histogram names the bucket that holds the k-th key; then ONE
+// pass over the keys writes a bitmap of the ids in higher buckets (ballots, no atomics) and
+// appends the (key, id) pairs of the deciding bucket to a list in shared memory.  The k-th key T
+// is found inside that list (block_kth_largest over at most kListCap entries); list entries above
+// T join the bitmap, entries equal to T go to a second bitmap, and a popcount scan over both
+// emits the picks in ascending id order, the lowest ids among the keys equal to T first.
+//   s_bits : 4 * ceil(n / 64) words (two bitmaps), s_list : 2 * kListCap words.
+// Returns -1 to every thread, with nothing emitted, when the deciding bucket holds more than
+// kListCap keys (many equal keys, or keys below the histogram's range): the caller then takes
+// block_select_topk.
+template <int NT, typename KeyFn, typename EmitFn>
+__device__ int block_select_hist(KeyFn key, int n, int k, EmitFn emit, uint32_t *s_hist, uint32_t *s_bits,
+                                 uint32_t *s_list, const uint32_t *ghist)
+{
+    constexpr int NW = NT / 64;
+    const int tid = threadIdx.x;
+    const int wv = tid >> 6, ln = lane_id();
+    uint32_t *s_aux = s_hist + 2048;
+    uint32_t *s_scan = s_aux + 4;
+    uint32_t *s_x = s_hist + 2048 + 56;
+    if (k >= n) {
+        for (int i = tid; i < n; i += NT) emit(i, i);
+        return n;
+    }
+    // wave w owns the contiguous ids [beg, end), lane-strided inside; the first CH keys of every
+    // thread are requested before the histogram is looked at, so that both latencies overlap
+    const int per = ((n + NW - 1) / NW + 63) & ~63;
+    const int beg = wv * per;
+    const int end = min(n, beg + per);
+    constexpr int CH = 32;
+    uint32_t kk[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        int i = beg + c * 64 + ln;
+        kk[c] = (i < end) ? key(i) : 0u;
+    }
+    CTKVR_STAMP(32);
+    // the bucket of the k-th key, and how many of its keys are still wanted
+    {
+        constexpr int BPB = kBuckets / NT;   // buckets per thread, in descending key order
+        uint32_t c[BPB];
+        uint32_t mine = 0;
+#pragma unroll
+        for (int q = 0; q < BPB; ++q) {
+            c[q] = ghist[BPB * tid + q];
+            mine += c[q];
+        }
+        uint32_t tot;
+        uint32_t before = block_excl_scan<NT>(mine, s_scan, &tot);
+#pragma unroll
+        for (int q = 0; q < BPB; ++q) {
+            if (before < (uint32_t)k && (uint32_t)k <= before + c[q]) {
+                s_aux[2] = (uint32_t)(BPB * tid + q);
+                s_aux[3] = (uint32_t)k - before;
+                s_x[0] = c[q];
+                s_x[1] = 0u;
+            }
+            before += c[q];
+        }
+        __syncthreads();
+    }
+    const uint32_t bkt = s_aux[2], rem = s_aux[3], nb = s_x[0];
+    if (nb > (uint32_t)kListCap) {
+        __syncthreads();
+        return -1;
+    }
+    CTKVR_STAMP(33);
+    const int nw64 = (n + 63) >> 6;
+    uint32_t *s_gt = s_bits, *s_eq = s_bits + 2 * nw64;
+    uint2 *l_ent = reinterpret_cast<uint2 *>(s_list);
+    // the one pass over the keys
+    const uint64_t below = (1ull << ln) - 1ull;
+    for (int base = beg; base < end; base += 64 * CH) {
+        if (base != beg) {
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                int i = base + c * 64 + ln;
+                kk[c] = (i < end) ? key(i) : 0u;
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            const int i0 = base + c * 64;
+            if (i0 < end) {
+                const int i = i0 + ln;
+                const bool valid = i < end;
+                const uint32_t bk = key_bucket(kk[c]);
+                const bool inb = valid && bk == bkt;
+                const uint64_t above = __ballot(valid && bk < bkt);
+                const uint64_t listed = __ballot(inb);
+                if (ln == 0) {
+                    s_gt[2 * (i0 >> 6)] = (uint32_t)above;
+                    s_gt[2 * (i0 >> 6) + 1] = (uint32_t)(above >> 32);
+                }
+                if (ln == 1) {
+                    s_eq[2 * (i0 >> 6)] = 0u;
+                    s_eq[2 * (i0 >> 6) + 1] = 0u;
+                }
+                if (listed) {   // one cursor bump per wave, places by ballot rank
+                    uint32_t at0 = 0;
+                    if (ln == 0) at0 = atomicAdd(&s_x[1], (uint32_t)__popcll(listed));
+                    at0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)at0);
+                    if (inb) l_ent[at0 + (uint32_t)__popcll(listed & below)] = make_uint2(kk[c], (uint32_t)i);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    CTKVR_STAMP(34);
+    block_resolve_emit<NT>(nb, rem, n, s_hist, s_gt, s_eq, l_ent, emit);
+    CTKVR_STAMP(39);
+    return k;
+}
+
+// The same selection when a chip-wide kernel has already made the pass over the keys: gbm = its
+// bitmap of the ids above the deciding bucket (2*ceil(n/64) words), glist[0..nb) = that bucket's
+// (key, id) pairs, both in global memory.  s_bits: 4*ceil(n/64) words, s_list: 2*nb words.
+template <int NT, typename EmitFn>
+__device__ int block_select_classified(int n, int k, uint32_t rem, uint32_t nb, const uint32_t *gbm, const uint2 *glist,
+                                       EmitFn emit, uint32_t *s_hist, uint32_t *s_bits, uint32_t *s_list)
+{
+    const int tid = threadIdx.x;
+    const int nw32 = 2 * ((n + 63) >> 6);
+    uint32_t *s_gt = s_bits, *s_eq = s_bits + nw32;
+    uint2 *l_ent = reinterpret_cast<uint2 *>(s_list);
+    for (uint32_t e = tid; e < nb; e += NT) l_ent[e] = glist[e];
+    for (int w = tid; w < nw32; w += NT) {
+        s_gt[w] = gbm[w];
+        s_eq[w] = 0u;
+    }
+    __syncthreads();
+    CTKVR_STAMP(34);
+    block_resolve_emit<NT>(nb, rem, n, s_hist, s_gt, s_eq, l_ent, emit);
+    CTKVR_STAMP(39);
     return k;
 }
 

@@ -61,11 +61,14 @@ struct ctkvr_index {
     // decode workspace
     float *cos = nullptr;
     int32_t *probe = nullptr, *cand = nullptr, *ncand = nullptr, *sel = nullptr, *nsel = nullptr;
-    uint32_t *crow = nullptr, *srow = nullptr, *kbuf = nullptr, *gbits = nullptr;
+    uint32_t *crow = nullptr, *srow = nullptr, *kbuf = nullptr, *gbits = nullptr, *ghist = nullptr;
+    uint32_t *gbm = nullptr, *gcur = nullptr, *ginfo = nullptr;   // classify_kernel's outputs
+    uint2 *glist = nullptr;
     unsigned long long *S = nullptr;
     float *z = nullptr, *zsel = nullptr;
     uint32_t *m_key = nullptr;
-    size_t recall_lds = 0, select_lds = 0, attn_lds = 0;
+    size_t recall_lds = 0, select_lds = 0, attn_lds = 0, build_select_lds = 0;
+    int sel_bits = 0, build_bits = 0;   // words for the selection's id bitmaps (0: histogram route off)
     int bitmap_words = 0, recall_split = 1, num_cu = 256;
     // per-kernel timing
     std::vector<hipEvent_t> events;
@@ -177,7 +180,12 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
     A(&ix->m_key, U * ix->G * 4);
     A(&ix->crow, U * ix->l_stride * 4);
     A(&ix->gbits, U * (size_t)((ix->s_max + 31) / 32) * 4);
-    A(&ix->kbuf, ix->l_stride > 32768 ? U * ix->l_stride * 4 : 16);
+    A(&ix->kbuf, U * ix->l_stride * 4);
+    A(&ix->ghist, U * (size_t)kBuckets * 4);
+    A(&ix->gbm, U * (size_t)(2 * ((ix->l_stride + 63) / 64)) * 4);
+    A(&ix->glist, U * (size_t)kListCap * 8);
+    A(&ix->gcur, U * 4);
+    A(&ix->ginfo, U * 16);
     A(&ix->srow, U * p->top_k * 4);
     A(&ix->S, U * ix->G * 8);
     A(&ix->sel, U * p->top_k * 4);
@@ -190,7 +198,15 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
     // shared-memory plan
     ix->bitmap_words = (ix->s_max + 31) / 32;
     ix->recall_lds = ((size_t)kSelLds + p->n_probe + ix->bitmap_words) * 4;
-    ix->select_lds = ((size_t)kSelLds + std::max(p->top_k, 1)) * 4;
+    // selection: radix scratch, the deciding bucket's list, two id bitmaps, the picked positions;
+    // where the bitmaps would not fit the histogram route is switched off
+    const size_t sel_fixed = (size_t)kSelLds + 2 * kListCap;
+    ix->sel_bits = 4 * ((ix->l_stride + 63) / 64);
+    if ((sel_fixed + ix->sel_bits + p->top_k) * 4 > 150 * 1024) ix->sel_bits = 0;
+    ix->select_lds = (sel_fixed + ix->sel_bits + std::max(p->top_k, 1)) * 4;
+    ix->build_bits = 4 * ((ix->s_max + 63) / 64);
+    if ((sel_fixed + ix->build_bits + 1) * 4 > 150 * 1024) ix->build_bits = 0;
+    ix->build_select_lds = (sel_fixed + ix->build_bits + 1) * 4;
     ix->attn_lds = (size_t)p->top_k * ix->G * 4;
     {
         int dev = 0, cus = 0;
@@ -215,7 +231,7 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
     want((const void *)recall_gather_kernel<8>, ix->recall_lds);
     want((const void *)recall_gather_kernel<32>, ix->recall_lds);
     want((const void *)recall_expand_kernel, 64 * 1024);
-    const size_t sel_b = std::max(ix->select_lds, ((size_t)kSelLds + 1) * 4);
+    const size_t sel_b = std::max(ix->select_lds, ix->build_select_lds);
     want((const void *)rerank_select_kernel<1>, sel_b);
     want((const void *)rerank_select_kernel<2>, sel_b);
     want((const void *)rerank_select_kernel<4>, sel_b);
@@ -237,6 +253,7 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
             ix->num_cu = cus;
     }
+    if (e == hipSuccess) e = hipMemset(ix->ghist, 0, U * (size_t)kBuckets * 4);
     if (e == hipSuccess) e = hipMemset(ix->gbits, 0, U * (size_t)ix->bitmap_words * 4);
     if (e == hipSuccess) e = hipMemset(ix->srow, 0, U * p->top_k * 4);   // always valid rows (see sparse_attn_kernel)
     if (e == hipSuccess) e = hipMemcpy(ix->d_ctx_lens, ix->ctx_lens.data(), (size_t)B * 4, hipMemcpyHostToDevice);
@@ -282,10 +299,10 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
     const int total_units = ix->units * ix->c_max;
     const size_t per_unit = (size_t)ix->s_max * G * 4;
     int chunk = (int)std::min<size_t>(total_units, std::max<size_t>(1, ((size_t)2 << 30) / per_unit));
-    chunk = std::min(chunk, 32768);
+    chunk = std::min(chunk, 16384);
     if (mfma) {   // whole (sequence, KV head) groups per chunk, up to 8 GiB of scores
         int nbk = (int)std::max<size_t>(1, ((size_t)8 << 30) / (per_unit * ix->c_max));
-        nbk = std::min(nbk, std::max(1, 32768 / ix->c_max));
+        nbk = std::min(nbk, std::max(1, 16384 / ix->c_max));
         chunk = std::min(ix->units, nbk) * ix->c_max;
     }
     float *z = nullptr;
@@ -294,10 +311,12 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
     HIP_TRY(hipMalloc((void **)&z, (size_t)chunk * per_unit));
     hipError_t e1 = hipMalloc((void **)&m_key, (size_t)chunk * G * 4);
     hipError_t e2 = hipMalloc((void **)&S, (size_t)chunk * G * 8);
-    uint32_t *kbuf = nullptr;
-    hipError_t e3 = hipMalloc((void **)&kbuf, ix->s_max > 32768 ? (size_t)chunk * ix->s_max * 4 : 16);
+    uint32_t *kbuf = nullptr, *ghist = nullptr;
+    hipError_t e3 = hipMalloc((void **)&kbuf, (size_t)chunk * ix->s_max * 4);
+    hipError_t e4 = hipMalloc((void **)&ghist, (size_t)chunk * kBuckets * 4);
     int rc = CTKVR_OK;
-    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess) rc = fail(CTKVR_ENOMEM, "build scratch allocation failed");
+    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess || e4 != hipSuccess)
+        rc = fail(CTKVR_ENOMEM, "build scratch allocation failed");
     for (int u0 = 0; rc == CTKVR_OK && u0 < total_units; u0 += chunk) {
         const int nu = std::min(chunk, total_units - u0);
         Units u = decode_units(ix);
@@ -305,6 +324,7 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
         u.unit0 = u0;
         fill_u32_kernel<<<dim3((unsigned)((nu * G + 255) / 256)), 256, 0, st>>>(m_key, 0u, (size_t)nu * G);
         fill_u32_kernel<<<dim3((unsigned)((nu * G * 2 + 255) / 256)), 256, 0, st>>>((uint32_t *)S, 0u, (size_t)nu * G * 2);
+        fill_u32_kernel<<<dim3((unsigned)(((size_t)nu * kBuckets + 255) / 256)), 256, 0, st>>>(ghist, 0u, (size_t)nu * kBuckets);
         ScoreArgs sa{};
         sa.u = u;
         sa.q = ix->centroids;
@@ -353,6 +373,17 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
         da.m_key = m_key;
         da.S = S;
         denom_kernel<G><<<dim3(std::min((ix->s_max + 1023) / 1024, 64), nu), 256, 0, st>>>(da);
+        KeyArgs ka{};
+        ka.u = u;
+        ka.ctx_lens = ix->d_ctx_lens;
+        ka.ncand = nullptr;
+        ka.l_stride = ix->s_max;
+        ka.z = z;
+        ka.m_key = m_key;
+        ka.S = S;
+        ka.kbuf = kbuf;
+        ka.ghist = ghist;
+        keyhist_kernel<G><<<dim3(std::min((ix->s_max + 4095) / 4096, 8), nu), 1024, 0, st>>>(ka);
         SelectArgs se{};
         se.u = u;
         se.ctx_lens = ix->d_ctx_lens;
@@ -363,10 +394,11 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
         se.top_k = ix->p.list_len;
         se.z = z;
         se.m_key = m_key;
-        se.S = S;
         se.kbuf = kbuf;
+        se.ghist = ghist;
+        se.bits_words = ix->build_bits;
         se.sel = ix->lists;
-        rerank_select_kernel<G><<<dim3(nu), 1024, (kSelLds + 1) * 4, st>>>(se);
+        rerank_select_kernel<G><<<dim3(nu), 1024, ix->build_select_lds, st>>>(se);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) rc = fail(CTKVR_EHIP, "build launch: %s", hipGetErrorString(e));
     }
@@ -376,6 +408,7 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
     (void)hipFree(m_key);
     (void)hipFree(S);
     (void)hipFree(kbuf);
+    (void)hipFree(ghist);
     return rc;
 }
 
@@ -462,6 +495,7 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     sa.l_stride = ix->l_stride;
     sa.z = ix->z;
     sa.m_key = ix->m_key;
+    sa.ghist = ix->ghist;
     sa.scale = ix->scale;
     // enough blocks to fill the chip a few times over, each walking its share of 128-id tiles
     const int tiles = (ix->l_stride + 127) / 128;
@@ -483,6 +517,38 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     denom_kernel<G><<<dim3(std::max(1, std::min(chunks, (4 * ix->num_cu + U - 1) / U)), U), 256, 0, st>>>(da);
     ix->mark(5, st);
 
+    KeyArgs ka{};
+    ka.u = u;
+    ka.ctx_lens = ix->d_ctx_lens;
+    ka.ncand = ix->ncand;
+    ka.l_stride = ix->l_stride;
+    ka.z = ix->z;
+    ka.m_key = ix->m_key;
+    ka.S = ix->S;
+    ka.kbuf = ix->kbuf;
+    ka.ghist = ix->ghist;
+    ka.gcur = ix->gcur;
+    keyhist_kernel<G><<<dim3(std::max(1, std::min((ix->l_stride + 4095) / 4096, (2 * ix->num_cu + U - 1) / U)), U), 1024, 0, st>>>(ka);
+    ix->mark(6, st);
+
+    if (ix->sel_bits) {
+        ClassifyArgs ca{};
+        ca.u = u;
+        ca.ctx_lens = ix->d_ctx_lens;
+        ca.ncand = ix->ncand;
+        ca.l_stride = ix->l_stride;
+        ca.top_k = p.top_k;
+        ca.kbuf = ix->kbuf;
+        ca.ghist = ix->ghist;
+        ca.bits_stride = 2 * ((ix->l_stride + 63) / 64);
+        ca.gbm = ix->gbm;
+        ca.glist = ix->glist;
+        ca.gcur = ix->gcur;
+        ca.ginfo = ix->ginfo;
+        classify_kernel<<<dim3(std::max(1, std::min(chunks, (4 * ix->num_cu + U - 1) / U)), U), 256, 0, st>>>(ca);
+    }
+    ix->mark(7, st);
+
     SelectArgs se{};
     se.u = u;
     se.ctx_lens = ix->d_ctx_lens;
@@ -493,15 +559,22 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     se.top_k = p.top_k;
     se.z = ix->z;
     se.m_key = ix->m_key;
-    se.S = ix->S;
     se.kbuf = ix->kbuf;
+    se.ghist = ix->ghist;
+    se.bits_words = ix->sel_bits;
+    if (ix->sel_bits) {
+        se.gbm = ix->gbm;
+        se.glist = ix->glist;
+        se.ginfo = ix->ginfo;
+        se.bits_stride = 2 * ((ix->l_stride + 63) / 64);
+    }
     se.sel = ix->sel;
     se.srow = ix->srow;
     se.zsel = ix->zsel;
     se.nsel = ix->nsel;
     se.out_sel = out_sel;
     rerank_select_kernel<G><<<dim3(U), 1024, ix->select_lds, st>>>(se);
-    ix->mark(6, st);
+    ix->mark(8, st);
 
     AttnArgs aa{};
     aa.v_pages = v_pages;
@@ -514,10 +587,10 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     aa.out = out;
     aa.out_lse = out_lse;
     sparse_attn_kernel<T, G><<<dim3(4 * U), 1024, ix->attn_lds, st>>>(aa);
-    ix->mark(7, st);
+    ix->mark(9, st);
     if (ix->prof_step < ix->prof_max) {   // a null kernel between two events: what the bracketing itself costs
         fill_u32_kernel<<<dim3(1), 64, 0, st>>>((uint32_t *)ix->nsel, 0u, 0);
-        ix->mark(8, st);
+        ix->mark(10, st);
     }
     if (ix->prof_step < ix->prof_max) ix->prof_step++;
     HIP_TRY(hipGetLastError());

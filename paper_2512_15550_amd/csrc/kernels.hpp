@@ -1,16 +1,18 @@
 // gfx950 kernels of the CTkvr path.
 //
-// Decode step (Algorithm 2 lines 1-9), seven launches:
+// Decode step (Algorithm 2 lines 1-9), eight launches:
 //   centroid_cos  lines 1-2   cosine to every centroid, max over the GQA group
 //   recall_gather lines 3-4a  top-C' centroids; their lists OR-ed into a bitmap
 //   recall_expand line  4b    the bitmap as an ascending id list plus each id's
 //                             physical KV row
 //   score         line 5a     z = (q . k) * scale for the G heads, running max
 //   denom         line 5b     softmax denominators, integer fixed point
-//   rerank_select lines 5c-6  max over the group of log-softmax, top-rho' ids
+//   keyhist       line 5c     max over the group of log-softmax as a ranking key,
+//                             and a histogram of the keys
+//   rerank_select line 6      top-rho' ids
 //   sparse_attn   lines 7-9   softmax(z_sel) . V_sel, one block per slice of the
 //                             head dimension (no cross-block reduction)
-// The exact index build (Algorithm 1 lines 2-4) runs score -> rerank_select with
+// The exact index build (Algorithm 1 lines 2-4) runs score -> denom -> keyhist -> rerank_select with
 // "the recalled set" = all s keys and the centroid in the role of the query,
 // which is literally the same formula.
 #pragma once
@@ -368,6 +370,7 @@ struct ScoreArgs {
     int l_stride;
     float *z;                 // [units][l_stride][G]
     uint32_t *m_key;          // [units][G] ordered-key running max (atomicMax)
+    uint32_t *ghist;          // decode only: [units][kBuckets] key histogram, cleared here for keyhist
     float scale;
 };
 
@@ -378,6 +381,8 @@ template <typename T, int G, int R> __global__ __launch_bounds__(256) void score
     const int ul = blockIdx.y;
     if (!decode_unit(a.u, ul, b, kv, j)) return;
     const int L = a.crow ? a.ncand[ul] : a.ctx_lens[b];
+    if (a.ghist)
+        for (int w = blockIdx.x * 256 + threadIdx.x; w < kBuckets; w += gridDim.x * 256) a.ghist[(size_t)ul * kBuckets + w] = 0u;
     if ((int)blockIdx.x * TILE >= L) return;
     __shared__ uint32_t s_row[TILE];
     __shared__ uint32_t s_max[G];
@@ -610,22 +615,198 @@ template <int G> __global__ __launch_bounds__(256) void denom_kernel(DenomArgs a
 }
 
 // ------------------------------------------------------------------------------
-// Algorithm 2 lines 5-6 / Algorithm 1 lines 3-4.  One block of 1024 threads per
-// unit: key_i = max_h ((z[h][i] - m[h]) - log S[h]), top-k ids ascending.
+// ranking keys, chip-wide: key_i = max_h ((z[h][i] - m[h]) - log S[h]) as an ordered
+// uint32 into kbuf, and the unit's histogram of key_bucket() (shared-memory
+// histogram per block, non-empty buckets added to the global one: integer adds).
+// grid (nbx, units), 1024 threads, chunks of 4096 ids with stride gridDim.x.
+// ------------------------------------------------------------------------------
+struct KeyArgs {
+    Units u;
+    const int32_t *ctx_lens, *ncand;   // ncand == nullptr => L = ctx_len
+    int l_stride;
+    const float *z;
+    const uint32_t *m_key;
+    const unsigned long long *S;
+    uint32_t *kbuf;     // [units][l_stride]
+    uint32_t *ghist;    // [units][kBuckets], zero on entry
+    uint32_t *gcur;     // decode only: [units] list cursors of classify_kernel, cleared here
+};
+
+template <int G> __global__ __launch_bounds__(1024) void keyhist_kernel(KeyArgs a)
+{
+    int b, kv, j;
+    const int ul = blockIdx.y;
+    if (!decode_unit(a.u, ul, b, kv, j)) return;
+    const int L = a.ncand ? a.ncand[ul] : a.ctx_lens[b];
+    if (a.gcur && blockIdx.x == 0 && threadIdx.x == 0) a.gcur[ul] = 0u;
+    if ((int)blockIdx.x * 4096 >= L) return;
+    __shared__ uint32_t s_h[kBuckets];
+    __shared__ float s_ls[G];
+    const int tid = threadIdx.x;
+    for (int w = tid; w < kBuckets; w += 1024) s_h[w] = 0u;
+    if (tid < G) s_ls[tid] = (float)log_fixed40(a.S[ul * G + tid]);
+    float m[G], ls[G];
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) m[hh] = ordered_value(a.m_key[ul * G + hh]);
+    __syncthreads();
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) ls[hh] = s_ls[hh];
+    const float *zb = a.z + (size_t)ul * a.l_stride * G;
+    uint32_t *kb = a.kbuf + (size_t)ul * a.l_stride;
+    for (int c0 = blockIdx.x * 4096; c0 < L; c0 += gridDim.x * 4096) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            int i = c0 + q * 1024 + tid;
+            if (i < L) {
+                float zv[G];
+                load_z<G>(zb, i, zv);
+                float best = -__builtin_huge_valf();
+#pragma unroll
+                for (int hh = 0; hh < G; ++hh) best = fmaxf(best, (zv[hh] - m[hh]) - ls[hh]);
+                uint32_t ok = ordered_key(best);
+                kb[i] = ok;
+                atomicAdd(&s_h[key_bucket(ok)], 1u);
+            }
+        }
+    }
+    __syncthreads();
+    uint32_t *gh = a.ghist + (size_t)ul * kBuckets;
+    for (int w = tid; w < kBuckets; w += 1024) {
+        uint32_t v = s_h[w];
+        if (v) atomicAdd(&gh[w], v);
+    }
+}
+
+// ------------------------------------------------------------------------------
+// Algorithm 2 line 6, the pass over the ranking keys, spread over the chip (decode).  Every block
+// scans its unit's key histogram for the bucket that holds the top_k-th key, then walks its share
+// of the ids in groups of 64: ids in higher buckets go into a bitmap (one ballot per group, plain
+// stores), the (key, id) pairs of the deciding bucket are appended to the unit's list (one
+// cursor bump per wave; the order of the list is arbitrary and nothing depends on it).
+// Units with top_k >= L, or with more than kListCap keys in the deciding bucket, are left to the
+// select kernel.  grid (nbx, units), 256 threads; keyhist_kernel has cleared the cursors.
+// ------------------------------------------------------------------------------
+struct ClassifyArgs {
+    Units u;
+    const int32_t *ctx_lens, *ncand;
+    int l_stride, top_k;
+    const uint32_t *kbuf;    // [units][l_stride]
+    const uint32_t *ghist;   // [units][kBuckets]
+    int bits_stride;         // bitmap words per unit
+    uint32_t *gbm;           // [units][bits_stride] ids above the deciding bucket
+    uint2 *glist;            // [units][kListCap] (key, id) of the deciding bucket
+    uint32_t *gcur;          // [units] list cursor, zero on entry
+    uint32_t *ginfo;         // [units][4] deciding bucket, keys wanted from it, its population, unused
+};
+
+__global__ __launch_bounds__(256) void classify_kernel(ClassifyArgs a)
+{
+    int b, kv, j;
+    const int ul = blockIdx.y;
+    if (!decode_unit(a.u, ul, b, kv, j)) return;
+    const int L = a.ncand ? a.ncand[ul] : a.ctx_lens[b];
+    if (a.top_k >= L) return;
+    __shared__ uint32_t s_scan[8];
+    __shared__ uint32_t s_res[3];
+    const int tid = threadIdx.x, ln = lane_id();
+    const int nw64 = (L + 63) >> 6;
+    const int wg = blockIdx.x * 4 + (tid >> 6), nwg = gridDim.x * 4;
+    const uint32_t *kb = a.kbuf + (size_t)ul * a.l_stride;
+    constexpr int UNR = 4;
+    // this wave's first groups of keys are requested before the histogram is looked at
+    uint32_t kk[UNR];
+#pragma unroll
+    for (int q = 0; q < UNR; ++q) {
+        int i = (wg + q * nwg) * 64 + ln;
+        kk[q] = (i < L) ? kb[i] : 0u;
+    }
+    // thread t owns buckets BPT*t .. BPT*t + BPT-1, in descending key order
+    constexpr int BPT = kBuckets / 256;
+    static_assert(BPT % 4 == 0, "bucket counts are read as uint4");
+    uint32_t c[BPT];
+    {
+        const uint4 *gh = reinterpret_cast<const uint4 *>(a.ghist + (size_t)ul * kBuckets) + (BPT / 4) * tid;
+#pragma unroll
+        for (int q = 0; q < BPT / 4; ++q) {
+            uint4 v = gh[q];
+            c[4 * q] = v.x; c[4 * q + 1] = v.y; c[4 * q + 2] = v.z; c[4 * q + 3] = v.w;
+        }
+    }
+    uint32_t mine = 0;
+#pragma unroll
+    for (int q = 0; q < BPT; ++q) mine += c[q];
+    uint32_t tot;
+    uint32_t before = block_excl_scan<256>(mine, s_scan, &tot);
+#pragma unroll
+    for (int q = 0; q < BPT; ++q) {
+        if (before < (uint32_t)a.top_k && (uint32_t)a.top_k <= before + c[q]) {
+            s_res[0] = (uint32_t)(BPT * tid + q);
+            s_res[1] = (uint32_t)a.top_k - before;
+            s_res[2] = c[q];
+        }
+        before += c[q];
+    }
+    __syncthreads();
+    const uint32_t bkt = s_res[0], nb = s_res[2];
+    if (blockIdx.x == 0 && tid == 0)
+        *reinterpret_cast<uint4 *>(a.ginfo + 4 * (size_t)ul) = make_uint4(bkt, s_res[1], nb, 0u);
+    if (nb > (uint32_t)kListCap) return;
+    uint32_t *bm = a.gbm + (size_t)ul * a.bits_stride;
+    uint2 *lst = a.glist + (size_t)ul * kListCap;
+    const uint64_t below = (1ull << ln) - 1ull;
+    for (int g0 = wg; g0 < nw64; g0 += UNR * nwg) {
+        if (g0 != wg) {
+#pragma unroll
+            for (int q = 0; q < UNR; ++q) {
+                int i = (g0 + q * nwg) * 64 + ln;
+                kk[q] = (i < L) ? kb[i] : 0u;
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < UNR; ++q) {
+            const int gq = g0 + q * nwg;
+            if (gq < nw64) {
+                const int i = gq * 64 + ln;
+                const bool valid = i < L;
+                const uint32_t bk = key_bucket(kk[q]);
+                const bool inb = valid && bk == bkt;
+                const uint64_t above = __ballot(valid && bk < bkt);
+                const uint64_t listed = __ballot(inb);
+                if (ln == 0) *reinterpret_cast<uint2 *>(bm + 2 * gq) = make_uint2((uint32_t)above, (uint32_t)(above >> 32));
+                if (listed) {
+                    uint32_t at0 = 0;
+                    if (ln == 0) at0 = atomicAdd(&a.gcur[ul], (uint32_t)__popcll(listed));
+                    at0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)at0);
+                    if (inb) lst[at0 + (uint32_t)__popcll(listed & below)] = make_uint2(kk[q], (uint32_t)i);
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------
+// Algorithm 2 line 6 / Algorithm 1 line 4.  One block of 1024 threads per unit: the
+// top-k ids by ranking key (kbuf), ascending, helped by the key histogram.
 //   decode: sel[unit][pos] = cand[i], srow[unit][pos] = crow[i],
 //           zsel[unit][pos][G] = z[i][G], nsel[unit]
 //   build : lists[(b*g+kv)*c_max + j][pos] = i
-// Dynamic shared memory: top_k words (positions of the picked ids, decode only).
+// Dynamic shared memory: kSelLds + 2*kListCap + bits_words + top_k words (the last: positions of
+// the picked ids, decode only).
 // ------------------------------------------------------------------------------
 struct SelectArgs {
     Units u;
     const int32_t *ctx_lens, *ncand, *cand;
     const uint32_t *crow;
     int l_stride, top_k;
+    int bits_words;          // shared-memory words set aside for the two id bitmaps (0: none)
     const float *z;
     const uint32_t *m_key;
-    const unsigned long long *S;
-    uint32_t *kbuf;     // [units][l_stride] key scratch, used when a unit has more than 32768 keys
+    const uint32_t *kbuf;    // [units][l_stride] ranking keys (keyhist_kernel)
+    const uint32_t *ghist;   // [units][kBuckets] their histogram
+    const uint32_t *gbm;     // decode: classify_kernel's outputs (nullptr: the block makes the pass itself)
+    const uint2 *glist;
+    const uint32_t *ginfo;
+    int bits_stride;
     int32_t *sel;       // decode [units][top_k] ; build: lists base
     uint32_t *srow;     // decode [units][top_k]
     float *zsel;        // decode [units][top_k][G]
@@ -633,18 +814,11 @@ struct SelectArgs {
     int32_t *out_sel;   // optional copy for the caller
 };
 
-template <int G, int KPT, typename KeyFn>
-__device__ __forceinline__ void select_emit(const SelectArgs &a, int ul, int L, KeyFn key, const float *zb, uint32_t *s_sel,
-                                            int32_t *s_idx)
+// writes the decode outputs of one unit from the positions picked into s_idx[0..n)
+template <int G>
+__device__ __forceinline__ void select_gather(const SelectArgs &a, int ul, int n, const float *zb, const int32_t *s_idx)
 {
     const int tid = threadIdx.x;
-    if (a.u.build) {
-        int32_t *dst = a.sel + (size_t)(a.u.unit0 + ul) * a.top_k;
-        block_select_topk<1024, KPT>(key, L, a.top_k, [&](int pos, int i) { dst[pos] = i; }, s_sel);
-        return;
-    }
-    int n = block_select_topk<1024, KPT>(key, L, a.top_k, [&](int pos, int i) { s_idx[pos] = i; }, s_sel);
-    __syncthreads();
     const int32_t *cb = a.cand + (size_t)ul * a.l_stride;
     const uint32_t *rb = a.crow + (size_t)ul * a.l_stride;
     int32_t *dst = a.sel + (size_t)ul * a.top_k;
@@ -671,46 +845,60 @@ __device__ __forceinline__ void select_emit(const SelectArgs &a, int ul, int L, 
     if (tid == 0) a.nsel[ul] = n;
 }
 
+template <int KPT, typename KeyFn, typename EmitFn>
+__device__ __forceinline__ int select_generic(KeyFn key, int L, int k, EmitFn emit, uint32_t *s_sel)
+{
+    return block_select_topk<1024, KPT>(key, L, k, emit, s_sel);
+}
+
 template <int G> __global__ __launch_bounds__(1024) void rerank_select_kernel(SelectArgs a)
 {
-    extern __shared__ uint32_t smem[];
-    uint32_t *s_sel = smem;                         // kSelLds
-    int32_t *s_idx = (int32_t *)(smem + kSelLds);   // top_k (decode)
-    __shared__ float s_ls[G];
+    extern __shared__ __align__(16) uint32_t smem[];
+    uint32_t *s_sel = smem;                          // kSelLds
+    uint32_t *s_list = smem + kSelLds;               // 2 * kListCap
+    uint32_t *s_bits = s_list + 2 * kListCap;        // a.bits_words (two bitmaps over the ids)
+    int32_t *s_idx = (int32_t *)(s_bits + a.bits_words);   // top_k (decode)
     int b, kv, j;
-    const int ul = blockIdx.x, tid = threadIdx.x;
+    const int ul = blockIdx.x;
     if (!decode_unit(a.u, ul, b, kv, j)) return;
     const int L = a.cand ? a.ncand[ul] : a.ctx_lens[b];
     CTKVR_STAMP(28);
     CTKVR_STAMP_BLK(2);
-    float m[G], ls[G];
-#pragma unroll
-    for (int hh = 0; hh < G; ++hh) m[hh] = ordered_value(a.m_key[ul * G + hh]);
-    if (tid < G) s_ls[tid] = (float)log_fixed40(a.S[ul * G + tid]);
-    __syncthreads();
-    CTKVR_STAMP(30);
-#pragma unroll
-    for (int hh = 0; hh < G; ++hh) ls[hh] = s_ls[hh];
     const float *zb = a.z + (size_t)ul * a.l_stride * G;
-    auto key = [&](int i) {
-        float zv[G];
-        load_z<G>(zb, i, zv);
-        float best = -__builtin_huge_valf();
-#pragma unroll
-        for (int hh = 0; hh < G; ++hh) best = fmaxf(best, (zv[hh] - m[hh]) - ls[hh]);
-        return ordered_key(best);
+    const uint32_t *kb = a.kbuf + (size_t)ul * a.l_stride;
+    auto key = [&](int i) { return kb[i]; };
+    int32_t *lst = a.u.build ? a.sel + (size_t)(a.u.unit0 + ul) * a.top_k : nullptr;
+    auto emit = [&](int pos, int i) {
+        if (lst)
+            lst[pos] = i;
+        else
+            s_idx[pos] = i;
     };
-    if (L <= 1024 * 8)
-        select_emit<G, 8>(a, ul, L, key, zb, s_sel, s_idx);
-    else if (L <= 1024 * 32)
-        select_emit<G, 32>(a, ul, L, key, zb, s_sel, s_idx);
-    else {
-        // too many keys for registers: compute each key once into global scratch, then select on that
-        uint32_t *kb = a.kbuf + (size_t)ul * a.l_stride;
-#pragma unroll 8
-        for (int i = tid; i < L; i += 1024) kb[i] = key(i);
+    int n = -1;
+    if (a.top_k >= L) {
+        for (int i = threadIdx.x; i < L; i += 1024) emit(i, i);
+        n = L;
+    } else if (4 * ((L + 63) >> 6) <= a.bits_words) {
+        if (a.ginfo) {
+            const uint4 info = *reinterpret_cast<const uint4 *>(a.ginfo + 4 * (size_t)ul);
+            if (info.z <= (uint32_t)kListCap)
+                n = block_select_classified<1024>(L, a.top_k, info.y, info.z, a.gbm + (size_t)ul * a.bits_stride,
+                                                  a.glist + (size_t)ul * kListCap, emit, s_sel, s_bits, s_list);
+        } else {
+            n = block_select_hist<1024>(key, L, a.top_k, emit, s_sel, s_bits, s_list, a.ghist + (size_t)ul * kBuckets);
+        }
+    }
+    if (n < 0) {   // crowded deciding bucket (or no room for the bitmaps): the histogram-free route
+        if (L <= 1024 * 8)
+            n = select_generic<8>(key, L, a.top_k, emit, s_sel);
+        else if (L <= 1024 * 32)
+            n = select_generic<32>(key, L, a.top_k, emit, s_sel);
+        else
+            n = select_generic<0>(key, L, a.top_k, emit, s_sel);
+    }
+    if (!a.u.build) {
         __syncthreads();
-        select_emit<G, 0>(a, ul, L, [&](int i) { return kb[i]; }, zb, s_sel, s_idx);
+        select_gather<G>(a, ul, n, zb, s_idx);
     }
     CTKVR_STAMP(31);
     CTKVR_STAMP_BLK(3);
