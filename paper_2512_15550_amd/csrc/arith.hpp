@@ -655,10 +655,10 @@ __device__ __forceinline__ uint32_t wave_sum_uniform(uint32_t v)
 
 // ---- small-n top-k selection by bisection ----------------------------------------------
 // Same contract as block_select_topk for n <= NT*KPT keys held in registers (slot it of
-// thread t is id it*NT + t).  The k-th largest key is found two bits at a time from the top: 16
-// rounds of "how many keys are >= candidate" for three candidates, DPP reductions per wave and
-// one block barrier per round; then the picks are written in ascending id order with ballot
-// ranks.  s_tmp: 6*(NT/64) + 2*KPT*(NT/64) words.  Every thread of the block takes part.
+// thread t is id it*NT + t).  The k-th largest key is found two bits at a time from the top: up to
+// 16 rounds of "how many keys are >= candidate" for three candidates (ballot counts per wave, one
+// block barrier per round), stopping early at a candidate that exactly k keys reach; then the
+// picks are written in ascending id order with ballot ranks.  s_tmp: 6*(NT/64) + 2*KPT*(NT/64) words.  Every thread of the block takes part.
 template <int NT, int KPT, typename KeyFn, typename EmitFn>
 __device__ __forceinline__ void block_bisect_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t *s_tmp)
 {
@@ -706,6 +706,14 @@ __device__ __forceinline__ void block_bisect_topk(KeyFn key, int n, int k, EmitF
         if (t3 >= (uint32_t)k) T = c3;
         else if (t2 >= (uint32_t)k) T = c2;
         else if (t1 >= (uint32_t)k) T = c1;
+        // A candidate that exactly k keys reach separates the pick from the rest: the keys >= it
+        // are the answer and the remaining bits need not be resolved.  (Every thread sees the same
+        // totals, so the exit is uniform.)  Never taken while keys tie at the k-th place.
+        const uint32_t hit = (t3 == (uint32_t)k) ? c3 : (t2 == (uint32_t)k) ? c2 : (t1 == (uint32_t)k) ? c1 : 0u;
+        if (hit) {
+            T = hit - 1u;   // "above T" is then "at least hit"; no key equal to T is wanted
+            break;
+        }
     }
     CTKVR_STAMP(14);
     // T is now the k-th largest key; keys above it are all picked, ties by lowest id.

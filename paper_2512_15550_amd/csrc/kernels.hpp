@@ -228,24 +228,44 @@ template <int KPT> __global__ __launch_bounds__(256) void recall_gather_kernel(G
     CTKVR_STAMP(9);
     // line 4: this block's share of the probed lists, one list per wave at a time
     const int32_t *lb = a.lists + (size_t)ul * a.c_max * a.rho;
-    for (int p = blockIdx.x + gridDim.x * wv; p < a.n_probe; p += gridDim.x * 4) {
+    // Two lists per round and wave, all of a round's loads requested before the first id is used.
+    const int pstride = gridDim.x * 4;
+    auto mark = [&](int t) { atomicOr(&s_bits[t >> 5], 1u << (t & 31)); };
+    for (int p = blockIdx.x + gridDim.x * wv; p < a.n_probe; p += 2 * pstride) {
+        const bool two = p + pstride < a.n_probe;
+        const int32_t *l0 = lb + (size_t)s_probe[p] * a.rho;
+        const int32_t *l1 = lb + (size_t)s_probe[two ? p + pstride : p] * a.rho;
         if ((a.rho & 3) == 0) {
-            const int4 *src = reinterpret_cast<const int4 *>(lb + (size_t)s_probe[p] * a.rho);
+            const int4 *s0 = reinterpret_cast<const int4 *>(l0), *s1 = reinterpret_cast<const int4 *>(l1);
             const int rho4 = a.rho >> 2;
-#pragma unroll 8
-            for (int r = ln; r < rho4; r += 64) {
-                int4 t = src[r];
-                atomicOr(&s_bits[t.x >> 5], 1u << (t.x & 31));
-                atomicOr(&s_bits[t.y >> 5], 1u << (t.y & 31));
-                atomicOr(&s_bits[t.z >> 5], 1u << (t.z & 31));
-                atomicOr(&s_bits[t.w >> 5], 1u << (t.w & 31));
+            for (int r0 = 0; r0 < rho4; r0 += 64 * 8) {
+                int4 t0[8], t1[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int r = r0 + u * 64 + ln;
+                    if (r < rho4) t0[u] = s0[r];
+                }
+                if (two) {
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int r = r0 + u * 64 + ln;
+                        if (r < rho4) t1[u] = s1[r];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int r = r0 + u * 64 + ln;
+                    if (r < rho4) {
+                        mark(t0[u].x); mark(t0[u].y); mark(t0[u].z); mark(t0[u].w);
+                        if (two) { mark(t1[u].x); mark(t1[u].y); mark(t1[u].z); mark(t1[u].w); }
+                    }
+                }
             }
         } else {
-            const int32_t *src = lb + (size_t)s_probe[p] * a.rho;
 #pragma unroll 8
             for (int r = ln; r < a.rho; r += 64) {
-                int t = src[r];
-                atomicOr(&s_bits[t >> 5], 1u << (t & 31));
+                mark(l0[r]);
+                if (two) mark(l1[r]);
             }
         }
     }
