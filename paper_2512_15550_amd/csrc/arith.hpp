@@ -446,7 +446,37 @@ __device__ __forceinline__ void block_resolve_emit(uint32_t nb, uint32_t rem, in
     const int nw64 = (n + 63) >> 6;
     // T among the nb listed keys (rem-th largest)
     uint32_t T, need_eq;
-    {
+    static_assert(NT <= 1024, "rank counters live in the two halves of the 2048-word histogram");
+    if (nb <= (uint32_t)NT / 2) {
+        // Few enough to rank every listed key against all the others: the comparisons of one key
+        // are split over NT/cap threads (cap = nb rounded up to a power of two, at least a wave, so
+        // that the lanes of a wave walk the list together) and their counts meet in shared memory.
+        uint32_t *s_aux = s_hist + 2048;
+        uint32_t cap = 64;
+        while (cap < nb) cap <<= 1;
+        const uint32_t parts = (uint32_t)NT / cap, e = (uint32_t)tid & (cap - 1u), part = (uint32_t)tid / cap;
+        for (int w = tid; w < 2048; w += NT) s_hist[w] = 0u;
+        __syncthreads();
+        if (e < nb) {
+            const uint32_t mk = l_ent[e].x;
+            uint32_t rank = 0, gt = 0;
+            for (uint32_t f = part; f < nb; f += parts) {
+                const uint32_t ke = l_ent[f].x;
+                gt += (ke > mk);
+                rank += (ke > mk) || (ke == mk && f < e);
+            }
+            atomicAdd(&s_hist[e], rank);
+            atomicAdd(&s_hist[1024 + e], gt);
+        }
+        __syncthreads();
+        if ((uint32_t)tid < nb && s_hist[tid] == rem - 1u) {
+            s_aux[2] = l_ent[tid].x;
+            s_aux[3] = rem - s_hist[1024 + tid];
+        }
+        __syncthreads();
+        T = s_aux[2];
+        need_eq = s_aux[3];
+    } else {
         auto for_list = [&](auto f) __attribute__((always_inline)) {
 #pragma unroll
             for (int q = 0; q < kListCap / NT; ++q) {
