@@ -228,9 +228,10 @@ def bench_decode(args, wl, steps, cpu_steps):
                                for b, s in enumerate(wl.ctx_lens)) for k in range(K)], dtype=np.float64)
     achieved = float(bytes_step.mean() / (dt / K)) / 1e9
     score_bytes = float(L.sum(axis=(1, 2)).mean()) * (d * e + 4)   # key row + its physical row index
-    # a pair of events around a kernel that does nothing reads stage_us["null"]; such a kernel lasts
-    # NULL_KERNEL_US in a rocprofv3 kernel trace, the rest is the bracketing's own cost
-    NULL_KERNEL_US = 1.0
+    # a pair of events around a kernel that does nothing reads stage_us["null"]; such a kernel, launched
+    # behind another one, lasts NULL_KERNEL_US in a rocprofv3 kernel trace (profiles/decode_*_kernel_trace.md),
+    # the rest is the bracketing's own cost
+    NULL_KERNEL_US = 3.4
     event_overhead = max(0.0, stage_us["null"] - NULL_KERNEL_US)
     score_us = max(stage_us["score"] - event_overhead, 1e-3)
     score_gbps = score_bytes / (score_us * 1e-6) / 1e9

@@ -499,7 +499,8 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     sa.scale = ix->scale;
     // enough blocks to fill the chip a few times over, each walking its share of 128-id tiles
     const int tiles = (ix->l_stride + 127) / 128;
-    const int nbx = std::max(1, std::min(tiles, (8 * ix->num_cu + U - 1) / U));
+    // (at least 32 per unit, so that the long units of a ragged batch do not set the pace)
+    const int nbx = std::max(1, std::min(tiles, std::max(32, (8 * ix->num_cu + U - 1) / U)));
     score_kernel<T, G, 8><<<dim3(nbx, U), 256, 0, st>>>(sa);
     ix->mark(4, st);
 
