@@ -400,13 +400,17 @@ template <typename T, int G, int R> __global__ __launch_bounds__(256) void score
     int b, kv, j;
     const int ul = blockIdx.y;
     if (!decode_unit(a.u, ul, b, kv, j)) return;
+    const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4;
+    // decode: the first tile's row ids are requested together with L, not after it (slots beyond
+    // L hold stale words; they are never used as rows, see the clamp below)
+    uint32_t pre = 0;
+    if (a.crow && tid < TILE) pre = a.crow[(size_t)ul * a.l_stride + min((int)blockIdx.x * TILE + tid, a.l_stride - 1)];
     const int L = a.crow ? a.ncand[ul] : a.ctx_lens[b];
     if (a.ghist)
         for (int w = blockIdx.x * 256 + threadIdx.x; w < kBuckets; w += gridDim.x * 256) a.ghist[(size_t)ul * kBuckets + w] = 0u;
     if ((int)blockIdx.x * TILE >= L) return;
     __shared__ uint32_t s_row[TILE];
     __shared__ uint32_t s_max[G];
-    const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4;
     CTKVR_STAMP(20);
     if (tid < G) s_max[tid] = 0u;
     float q[G][8];
@@ -422,14 +426,17 @@ template <typename T, int G, int R> __global__ __launch_bounds__(256) void score
         __syncthreads();   // previous tile's rows are consumed
         if (tid < TILE) {
             int i = min(tile0 + tid, L - 1);
-            s_row[tid] = a.crow ? a.crow[(size_t)ul * a.l_stride + i]
-                                : row_of(a.k.block_table, a.k.max_pages, a.k.page_shift, a.u.g, b, kv, i);
+            if (a.crow)
+                s_row[tid] = (tile0 == (int)blockIdx.x * TILE) ? pre : a.crow[(size_t)ul * a.l_stride + i];
+            else
+                s_row[tid] = row_of(a.k.block_table, a.k.max_pages, a.k.page_shift, a.u.g, b, kv, i);
         }
         __syncthreads();
+        const int last = L - 1 - tile0;   // slots of the tile beyond it repeat the last valid row
         CTKVR_STAMP(21);
         Chunk<T> ck[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r) ck[r] = load_chunk(K + (size_t)s_row[r * 16 + grp] * kD, lane16);
+        for (int r = 0; r < R; ++r) ck[r] = load_chunk(K + (size_t)s_row[min(r * 16 + grp, last)] * kD, lane16);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             float kx[8];
