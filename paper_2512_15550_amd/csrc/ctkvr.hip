@@ -621,8 +621,9 @@ template <int G> int run_kmeans_g(ctkvr_index *ix, KmeansArgs ka, hipStream_t st
     for (int it = 0; it < ix->p.kmeans_iters; ++it) {
         kmeans_halfnorm_kernel<G><<<dim3((ix->c_max + 15) / 16, U), 256, 0, st>>>(ka);
         kmeans_assign_kernel<G><<<dim3((ix->s_max + 127) / 128, U), 256, ix->c_max * 4, st>>>(ka);
-        kmeans_accumulate_kernel<G><<<dim3((ix->s_max + 15) / 16, U), 256, 0, st>>>(ka);
-        kmeans_update_kernel<G><<<dim3(ix->c_max, U), 128, 0, st>>>(ka);
+        kmeans_offsets_kernel<<<dim3(U), 1024, 0, st>>>(ka);
+        kmeans_scatter_kernel<<<dim3((ix->s_max + 255) / 256, U), 256, 0, st>>>(ka);
+        kmeans_reduce_kernel<G><<<dim3(ix->c_max, U), 128, 0, st>>>(ka);
     }
     HIP_TRY(hipGetLastError());
     return CTKVR_OK;
@@ -642,19 +643,22 @@ int run_kmeans(ctkvr_index *ix, const bf16_t *q_prefill, const int32_t *d_first,
     ka.q = q_prefill;
     ka.centroids = (bf16_t *)ix->centroids;
     ka.init_pos = init_pos;
-    void *bufs[4] = {nullptr, nullptr, nullptr, nullptr};
-    const size_t sz[4] = {U * ix->c_max * 4, U * ix->s_max * 4, U * ix->c_max * ix->G * 128 * 8, U * ix->c_max * 4};
+    void *bufs[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    const size_t sz[6] = {U * ix->c_max * 4, U * ix->s_max * 4, U * ix->c_max * 4,
+                          U * ix->c_max * 4, U * ix->c_max * 4, U * ix->s_max * 4};
     int rc = CTKVR_OK;
-    for (int i = 0; i < 4 && rc == CTKVR_OK; ++i) {
+    for (int i = 0; i < 6 && rc == CTKVR_OK; ++i) {
         hipError_t e = hipMalloc(&bufs[i], sz[i]);
-        if (e == hipSuccess && i >= 2) e = hipMemsetAsync(bufs[i], 0, sz[i], st);
+        if (e == hipSuccess && i == 2) e = hipMemsetAsync(bufs[i], 0, sz[i], st);
         if (e != hipSuccess) rc = fail(CTKVR_ENOMEM, "k-means scratch: %s", hipGetErrorString(e));
     }
     if (rc == CTKVR_OK) {
         ka.half_norm = (float *)bufs[0];
         ka.assign = (int32_t *)bufs[1];
-        ka.sums = (unsigned long long *)bufs[2];
-        ka.counts = (uint32_t *)bufs[3];
+        ka.counts = (uint32_t *)bufs[2];
+        ka.start = (uint32_t *)bufs[3];
+        ka.cursor = (uint32_t *)bufs[4];
+        ka.order = (int32_t *)bufs[5];
         switch (ix->G) {
             case 1: rc = run_kmeans_g<1>(ix, ka, st); break;
             case 2: rc = run_kmeans_g<2>(ix, ka, st); break;

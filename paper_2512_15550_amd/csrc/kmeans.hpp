@@ -2,8 +2,9 @@
 // paper itself takes the last C prompt queries).  Per (sequence, KV head) the s
 // prompt positions are clustered; a point is the concatenation of the G query-head
 // vectors of the group at one position (G*128 numbers, contiguous in q_prefill).
-// Lloyd iteration = half-norms -> assignment on the matrix cores -> fixed-point
-// accumulation -> update.  The centres live in the index's centroid table
+// Lloyd iteration = half-norms -> assignment on the matrix cores (which also counts the
+// members of every centre) -> counting sort of the positions by centre -> one block per
+// centre sums its members in fixed point and writes the new centre.  The centres live in the index's centroid table
 // [b][h][c_max][128] all along: head hh of centre c is one 128-element row.
 #pragma once
 #include "kernels.hpp"
@@ -19,8 +20,10 @@ struct KmeansArgs {
     const int32_t *init_pos;       // [batch][g][c_max]
     float *half_norm;              // [batch*g][c_max]
     int32_t *assign;               // [batch*g][s_max]
-    unsigned long long *sums;      // [batch*g][c_max][G*128]  2^-20 fixed point, two's complement
-    uint32_t *counts;              // [batch*g][c_max]
+    uint32_t *counts;              // [batch*g][c_max] members per centre (zero before the assignment)
+    uint32_t *start;               // [batch*g][c_max] first slot of each centre in `order`
+    uint32_t *cursor;              // [batch*g][c_max] next free slot while scattering
+    int32_t *order;                // [batch*g][s_max] positions grouped by centre
 };
 
 // centres start as the prompt queries at init_pos; grid (c_max, h, batch), 128 threads
@@ -118,53 +121,94 @@ template <int G> __global__ __launch_bounds__(256) void kmeans_assign_kernel(Kme
     float ob = __shfl_xor(best, 32);
     int oi = __shfl_xor(bi, 32);
     if (ob > best || (ob == best && oi < bi)) bi = oi;
-    if (half == 0 && (p0 + col) < s) a.assign[(size_t)ul * a.s_max + p0 + col] = bi;
-}
-
-// sums[c] += llrint(x * 2^20) over the points assigned to c, counts[c] += 1
-// grid (ceil(s_max/16), batch*g), 256 threads: one point per 16-lane group
-template <int G> __global__ __launch_bounds__(256) void kmeans_accumulate_kernel(KmeansArgs a)
-{
-    const int ul = blockIdx.y, b = ul / a.g, kv = ul - b * a.g;
-    const int s = a.ctx_lens[b];
-    const int lane16 = threadIdx.x & 15, grp = threadIdx.x >> 4;
-    const int t = blockIdx.x * 16 + grp;
-    if (t >= s) return;
-    const int c = a.assign[(size_t)ul * a.s_max + t];
-    const bf16_t *xrow = a.q + ((size_t)(a.first_row[b] + t) * a.h + kv * G) * kD;
-    unsigned long long *dst = a.sums + ((size_t)ul * a.c_max + c) * (G * kD);
-#pragma unroll
-    for (int hh = 0; hh < G; ++hh) {
-        float x[8];
-        unpack(load_chunk(xrow + hh * kD, lane16), x);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            long long f = __float2ll_rn(x[e] * 1048576.0f);
-            if (f != 0) atomicAdd(&dst[hh * kD + 8 * lane16 + e], (unsigned long long)f);
-        }
+    if (half == 0 && (p0 + col) < s) {
+        a.assign[(size_t)ul * a.s_max + p0 + col] = bi;
+        atomicAdd(&a.counts[(size_t)ul * a.c_max + bi], 1u);
     }
-    if (lane16 == 0) atomicAdd(&a.counts[(size_t)ul * a.c_max + c], 1u);
 }
 
-// mu_c = sum / count (fp64 divide, rounded to fp32, then to bf16 nearest-even); an empty
-// centre keeps its place.  Clears sums and counts.  grid (c_max, batch*g), 128 threads
-template <int G> __global__ __launch_bounds__(128) void kmeans_update_kernel(KmeansArgs a)
+// start[c] = number of positions assigned to centres below c; cursor[c] = start[c].
+// grid batch*g, 1024 threads (C <= 8192: eight centres per thread)
+__global__ __launch_bounds__(1024) void kmeans_offsets_kernel(KmeansArgs a)
+{
+    __shared__ uint32_t s_tmp[32];
+    const int ul = blockIdx.x, b = ul / a.g;
+    const int C = a.n_cent[b], tid = threadIdx.x;
+    uint32_t c[8], mine = 0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        int j = tid * 8 + q;
+        c[q] = j < C ? a.counts[(size_t)ul * a.c_max + j] : 0u;
+        mine += c[q];
+    }
+    uint32_t tot;
+    uint32_t before = block_excl_scan<1024>(mine, s_tmp, &tot);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        int j = tid * 8 + q;
+        if (j < C) {
+            a.start[(size_t)ul * a.c_max + j] = before;
+            a.cursor[(size_t)ul * a.c_max + j] = before;
+        }
+        before += c[q];
+    }
+}
+
+// order[cursor[assign[t]]++] = t.  The order inside a centre's range is whatever the atomics give:
+// the sums taken over it are integer sums.  grid (ceil(s_max/256), batch*g), 256 threads
+__global__ __launch_bounds__(256) void kmeans_scatter_kernel(KmeansArgs a)
+{
+    const int ul = blockIdx.y, b = ul / a.g;
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t >= a.ctx_lens[b]) return;
+    const int c = a.assign[(size_t)ul * a.s_max + t];
+    const uint32_t pos = atomicAdd(&a.cursor[(size_t)ul * a.c_max + c], 1u);
+    a.order[(size_t)ul * a.s_max + pos] = t;
+}
+
+// One block per centre: sum_c = sum of llrint(x * 2^20) over its members (int64 per element, in
+// registers), mu_c = sum / count (fp64 divide, rounded to fp32, then to bf16 nearest-even); an
+// empty centre keeps its place.  Thread e owns the G consecutive elements e*G .. e*G+G-1 of the
+// G*128-element point.  Clears the count for the next iteration.  grid (c_max, batch*g), 128 threads
+template <int G> __global__ __launch_bounds__(128) void kmeans_reduce_kernel(KmeansArgs a)
 {
     const int ul = blockIdx.y, b = ul / a.g, kv = ul - b * a.g;
     const int c = blockIdx.x;
     if (c >= a.n_cent[b]) return;
     const uint32_t n = a.counts[(size_t)ul * a.c_max + c];
-    unsigned long long *src = a.sums + ((size_t)ul * a.c_max + c) * (G * kD);
+    const uint32_t st = a.start[(size_t)ul * a.c_max + c];
+    const int32_t *ord = a.order + (size_t)ul * a.s_max + st;
     const int e = threadIdx.x;
+    const bf16_t *base = a.q + ((size_t)a.first_row[b] * a.h + kv * G) * kD + e * G;
+    const size_t rstride = (size_t)a.h * kD;
+    long long acc[G];
 #pragma unroll
-    for (int hh = 0; hh < G; ++hh) {
-        long long sfix = (long long)src[hh * kD + e];
-        src[hh * kD + e] = 0ull;
-        if (n) {
-            float m = (float)((double)sfix * (1.0 / 1048576.0) / (double)n);
+    for (int r = 0; r < G; ++r) acc[r] = 0;
+    for (uint32_t m0 = 0; m0 < n; m0 += 8) {
+        int t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = ord[min(m0 + u, n - 1)];
+        bf16_t x[8][G];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int r = 0; r < G; ++r) x[u][r] = base[(size_t)t[u] * rstride + r];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (m0 + u < n) {
+#pragma unroll
+                for (int r = 0; r < G; ++r)
+                    acc[r] += __float2ll_rn(__uint_as_float((uint32_t)x[u][r] << 16) * 1048576.0f);
+            }
+    }
+    if (n) {
+#pragma unroll
+        for (int r = 0; r < G; ++r) {
+            const int ee = e * G + r, hh = ee >> 7, dim = ee & 127;
+            float m = (float)((double)acc[r] * (1.0 / 1048576.0) / (double)n);
             uint32_t u = __float_as_uint(m);
             u += 0x7fffu + ((u >> 16) & 1u);
-            a.centroids[(((size_t)b * a.h + kv * G + hh) * a.c_max + c) * kD + e] = (bf16_t)(u >> 16);
+            a.centroids[(((size_t)b * a.h + kv * G + hh) * a.c_max + c) * kD + dim] = (bf16_t)(u >> 16);
         }
     }
     __syncthreads();
