@@ -206,6 +206,32 @@ def decode_step(q, K, V, Qc, lists, n_probe, top_k, scale=None) -> DecodeResult:
                         [rkey[i, :ncand[i]].copy() for i in range(g)], sel, out, lse)
 
 
+def centroid_update(q, Qc, lists, res: DecodeResult, n_updates: int) -> int:
+    """Algorithm 2 line 12 (dynamic centroid update), in place, after the decode step `res` of
+    query q: the query becomes the centroid of FIFO slot n_updates mod C for every query head,
+    and that slot's list becomes the rho keys with the largest rerank score A'_kv (the same
+    score line 6 ranks by, over the recalled set), ties to the lowest key id, stored ascending.
+    The oldest mapping goes first: slot 0 holds the earliest prompt query.  Should fewer than rho
+    keys have been recalled the last one is repeated (a list always has rho entries).
+    Returns the slot written."""
+    q = np.asarray(q, np.float32)
+    g, C, rho = lists.shape
+    slot = int(n_updates) % C
+    for kv in range(g):
+        key = np.asarray(res.rerank_key[kv], np.float32)
+        cand = np.asarray(res.cand[kv], np.int32)
+        L = len(cand)
+        if L == 0:
+            continue
+        n = min(rho, L)
+        order = np.lexsort((cand, -key.astype(np.float64)))   # score descending, then key id ascending
+        top = np.sort(cand[order[:n]])
+        lists[kv, slot, :n] = top
+        lists[kv, slot, n:] = top[-1]
+    Qc[:, slot, :] = q
+    return slot
+
+
 # ---- k-means centroid mode -------------------------------------------------- #
 def group_points(q_full: np.ndarray, g: int) -> np.ndarray:
     """[s][h][d] prompt queries -> [g][s][G*d]: a point is the concatenation of the G
