@@ -138,6 +138,21 @@ int ctkvr_decode_step(ctkvr_index *idx, const void *q, const void *k_pages, cons
                       const int32_t *block_table, int32_t max_pages, float *out, float *out_lse, int32_t *out_sel,
                       int32_t *out_ncand, int32_t *out_probe, void *hip_stream);
 
+/*
+ * Dynamic centroid update (Algorithm 2 line 12; Section 3.1.2, "Dynamic Centroid Update"),
+ * to be called after ctkvr_decode_step with the same q, on the same stream, before the next
+ * step: for every sequence and KV head the query vectors of the group's heads replace the
+ * centroids of one slot of the index, and that slot's list becomes the rho keys with the
+ * largest rerank score of the step (the quantity line 6 ranks by, over the recalled keys),
+ * ties to the lowest id, ascending.  Slots are taken first in, first out: update number n
+ * (counted from 0 since the build) writes slot n mod C_i, so the earliest prompt query goes
+ * first.  With rho = rho' the list is the step's selection; otherwise the ranking is run
+ * once more with budget rho.  Should fewer than rho keys have been recalled the last one is
+ * repeated.  Asynchronous, allocates nothing, uses the index's workspace like a step.
+ * Errors: EINVAL (null pointer; no decode step since the build or the last update).
+ */
+int ctkvr_centroid_update(ctkvr_index *idx, const void *q, void *hip_stream);
+
 /* Release an index (NULL is allowed).  Synchronises the device first. */
 void ctkvr_free(ctkvr_index *idx);
 

@@ -72,7 +72,7 @@ _lib = None
 
 EXPORTS = ["ctkvr_build_index", "ctkvr_index_load", "ctkvr_decode_step", "ctkvr_free", "ctkvr_last_error",
            "ctkvr_index_info", "ctkvr_index_lists", "ctkvr_index_centroids", "ctkvr_index_last_candidates",
-           "ctkvr_profile_enable", "ctkvr_profile_collect"]
+           "ctkvr_profile_enable", "ctkvr_profile_collect", "ctkvr_centroid_update"]
 N_STAGES = 10
 STAGE_NAMES = ["centroid_cos", "recall_gather", "recall_expand", "score", "denom", "keyhist", "classify",
                "rerank_select", "sparse_attn", "null"]
@@ -100,6 +100,8 @@ def load_library() -> ctypes.CDLL:
     L.ctkvr_index_load.argtypes = [ctypes.POINTER(_CParams), ip, vp, ip, vp, ctypes.POINTER(ctypes.c_void_p)]
     L.ctkvr_decode_step.restype = ctypes.c_int
     L.ctkvr_decode_step.argtypes = [vp, vp, vp, vp, ip, ctypes.c_int32, fp, fp, ip, ip, ip, vp]
+    L.ctkvr_centroid_update.restype = ctypes.c_int
+    L.ctkvr_centroid_update.argtypes = [vp, vp, vp]
     L.ctkvr_free.restype = None
     L.ctkvr_free.argtypes = [vp]
     L.ctkvr_index_info.restype = ctypes.c_int
@@ -207,6 +209,11 @@ def ctkvr_decode_step(idx: Index, q, k_pages, v_pages, block_table, out, out_lse
                              _dev(out_lse, torch.float32), _dev(out_sel, torch.int32), _dev(out_ncand, torch.int32),
                              _dev(out_probe, torch.int32), _stream())
     _check(rc)
+
+
+def ctkvr_centroid_update(idx: Index, q) -> None:
+    td = _torch_dtype(idx.params.dtype)
+    _check(load_library().ctkvr_centroid_update(idx.handle, _dev(q, td), _stream()))
 
 
 def ctkvr_free(idx: Optional[Index]) -> None:

@@ -64,6 +64,10 @@ struct ctkvr_index {
     uint32_t *crow = nullptr, *srow = nullptr, *kbuf = nullptr, *gbits = nullptr, *ghist = nullptr;
     uint32_t *gbm = nullptr, *gcur = nullptr, *ginfo = nullptr;   // classify_kernel's outputs
     uint2 *glist = nullptr;
+    // dynamic centroid update
+    uint32_t *d_dcu_count = nullptr;   // updates so far (device side, so that captured graphs replay correctly)
+    int32_t *dsel = nullptr, *dnsel = nullptr;   // top-rho ids of the second ranking (only when rho != rho')
+    bool have_step = false;
     unsigned long long *S = nullptr;
     float *z = nullptr, *zsel = nullptr;
     uint32_t *m_key = nullptr;
@@ -186,6 +190,11 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
     A(&ix->glist, U * (size_t)kListCap * 8);
     A(&ix->gcur, U * 4);
     A(&ix->ginfo, U * 16);
+    A(&ix->d_dcu_count, 4);
+    if (p->list_len != p->top_k) {
+        A(&ix->dsel, U * (size_t)p->list_len * 4);
+        A(&ix->dnsel, U * 4);
+    }
     A(&ix->srow, U * p->top_k * 4);
     A(&ix->S, U * ix->G * 8);
     A(&ix->sel, U * p->top_k * 4);
@@ -202,8 +211,9 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
     // where the bitmaps would not fit the histogram route is switched off
     const size_t sel_fixed = (size_t)kSelLds + 2 * kListCap;
     ix->sel_bits = 4 * ((ix->l_stride + 63) / 64);
-    if ((sel_fixed + ix->sel_bits + p->top_k) * 4 > 150 * 1024) ix->sel_bits = 0;
-    ix->select_lds = (sel_fixed + ix->sel_bits + std::max(p->top_k, 1)) * 4;
+    const size_t picks = std::max(p->top_k, p->list_len);   // the update ranks once more with budget rho
+    if ((sel_fixed + ix->sel_bits + picks) * 4 > 150 * 1024) ix->sel_bits = 0;
+    ix->select_lds = (sel_fixed + ix->sel_bits + picks) * 4;
     ix->build_bits = 4 * ((ix->s_max + 63) / 64);
     if ((sel_fixed + ix->build_bits + 1) * 4 > 150 * 1024) ix->build_bits = 0;
     ix->build_select_lds = (sel_fixed + ix->build_bits + 1) * 4;
@@ -254,6 +264,7 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
             ix->num_cu = cus;
     }
     if (e == hipSuccess) e = hipMemset(ix->ghist, 0, U * (size_t)kBuckets * 4);
+    if (e == hipSuccess) e = hipMemset(ix->d_dcu_count, 0, 4);
     if (e == hipSuccess) e = hipMemset(ix->gbits, 0, U * (size_t)ix->bitmap_words * 4);
     if (e == hipSuccess) e = hipMemset(ix->srow, 0, U * p->top_k * 4);   // always valid rows (see sparse_attn_kernel)
     if (e == hipSuccess) e = hipMemcpy(ix->d_ctx_lens, ix->ctx_lens.data(), (size_t)B * 4, hipMemcpyHostToDevice);
@@ -595,6 +606,7 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     }
     if (ix->prof_step < ix->prof_max) ix->prof_step++;
     HIP_TRY(hipGetLastError());
+    ix->have_step = true;
     return CTKVR_OK;
 }
 
@@ -671,6 +683,89 @@ int run_kmeans(ctkvr_index *ix, const bf16_t *q_prefill, const int32_t *d_first,
     for (void *b : bufs)
         if (b) (void)hipFree(b);
     return rc;
+}
+
+// Algorithm 2 line 12 after a decode step: the step's ranking keys, their histogram and the
+// recalled ids are still in the workspace.
+template <typename T, int G> int update_launch(ctkvr_index *ix, const void *q, hipStream_t st)
+{
+    const ctkvr_params &p = ix->p;
+    const int U = ix->units;
+    DcuArgs da{};
+    da.g = p.n_kv_heads;
+    da.h = p.n_q_heads;
+    da.G = G;
+    da.c_max = ix->c_max;
+    da.rho = p.list_len;
+    da.n_cent = ix->d_n_cent;
+    da.count = ix->d_dcu_count;
+    da.q = q;
+    da.centroids = ix->centroids;
+    da.inv_norm_c = ix->inv_norm_c;
+    da.lists = ix->lists;
+    if (p.list_len == p.top_k) {   // the list is the selection of line 6
+        da.src = ix->sel;
+        da.nsrc = ix->nsel;
+        da.src_stride = p.top_k;
+    } else {                       // the same ranking once more, with budget rho
+        Units u = decode_units(ix);
+        const int chunks = (ix->l_stride + 1023) / 1024;
+        SelectArgs se{};
+        se.u = u;
+        se.ctx_lens = ix->d_ctx_lens;
+        se.ncand = ix->ncand;
+        se.cand = ix->cand;
+        se.l_stride = ix->l_stride;
+        se.top_k = p.list_len;
+        se.z = ix->z;
+        se.m_key = ix->m_key;
+        se.kbuf = ix->kbuf;
+        se.ghist = ix->ghist;
+        se.bits_words = ix->sel_bits;
+        se.sel = ix->dsel;
+        se.nsel = ix->dnsel;
+        se.ids_only = 1;
+        if (ix->sel_bits) {
+            fill_u32_kernel<<<dim3((U + 255) / 256), 256, 0, st>>>(ix->gcur, 0u, (size_t)U);
+            ClassifyArgs ca{};
+            ca.u = u;
+            ca.ctx_lens = ix->d_ctx_lens;
+            ca.ncand = ix->ncand;
+            ca.l_stride = ix->l_stride;
+            ca.top_k = p.list_len;
+            ca.kbuf = ix->kbuf;
+            ca.ghist = ix->ghist;
+            ca.bits_stride = 2 * ((ix->l_stride + 63) / 64);
+            ca.gbm = ix->gbm;
+            ca.glist = ix->glist;
+            ca.gcur = ix->gcur;
+            ca.ginfo = ix->ginfo;
+            classify_kernel<<<dim3(std::max(1, std::min(chunks, (4 * ix->num_cu + U - 1) / U)), U), 256, 0, st>>>(ca);
+            se.gbm = ix->gbm;
+            se.glist = ix->glist;
+            se.ginfo = ix->ginfo;
+            se.bits_stride = ca.bits_stride;
+        }
+        rerank_select_kernel<G><<<dim3(U), 1024, ix->select_lds, st>>>(se);
+        da.src = ix->dsel;
+        da.nsrc = ix->dnsel;
+        da.src_stride = p.list_len;
+    }
+    dcu_write_kernel<T><<<dim3(U), 256, 0, st>>>(da);
+    dcu_advance_kernel<<<dim3(1), 64, 0, st>>>(ix->d_dcu_count);
+    HIP_TRY(hipGetLastError());
+    ix->have_step = false;
+    return CTKVR_OK;
+}
+
+template <typename T> int update_dispatch(ctkvr_index *ix, const void *q, hipStream_t st)
+{
+    switch (ix->G) {
+        case 1: return update_launch<T, 1>(ix, q, st);
+        case 2: return update_launch<T, 2>(ix, q, st);
+        case 4: return update_launch<T, 4>(ix, q, st);
+        default: return update_launch<T, 8>(ix, q, st);
+    }
 }
 
 int min_pages_needed(const ctkvr_index *ix)
@@ -808,6 +903,16 @@ int ctkvr_decode_step(ctkvr_index *idx, const void *q, const void *k_pages, cons
                                        out_probe, st);
     return decode_dispatch<float>(idx, q, k_pages, v_pages, block_table, max_pages, out, out_lse, out_sel, out_ncand,
                                   out_probe, st);
+}
+
+int ctkvr_centroid_update(ctkvr_index *idx, const void *q, void *hip_stream)
+{
+    if (!idx) return fail(CTKVR_EINVAL, "index is NULL");
+    if (!q) return fail(CTKVR_EINVAL, "q is NULL");
+    if (!idx->have_step) return fail(CTKVR_EINVAL, "no decode step since the index was built or last updated");
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (idx->p.dtype == CTKVR_BF16) return update_dispatch<bf16_t>(idx, q, st);
+    return update_dispatch<float>(idx, q, st);
 }
 
 void ctkvr_free(ctkvr_index *idx)

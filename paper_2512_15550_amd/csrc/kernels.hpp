@@ -839,6 +839,7 @@ struct SelectArgs {
     float *zsel;        // decode [units][top_k][G]
     int32_t *nsel;      // decode [units]
     int32_t *out_sel;   // optional copy for the caller
+    int ids_only;       // decode: write sel and nsel only (the dynamic centroid update's second ranking)
 };
 
 // writes the decode outputs of one unit from the positions picked into s_idx[0..n)
@@ -847,8 +848,13 @@ __device__ __forceinline__ void select_gather(const SelectArgs &a, int ul, int n
 {
     const int tid = threadIdx.x;
     const int32_t *cb = a.cand + (size_t)ul * a.l_stride;
-    const uint32_t *rb = a.crow + (size_t)ul * a.l_stride;
     int32_t *dst = a.sel + (size_t)ul * a.top_k;
+    if (a.ids_only) {
+        for (int pos = tid; pos < a.top_k; pos += 1024) dst[pos] = pos < n ? cb[s_idx[pos]] : -1;
+        if (tid == 0) a.nsel[ul] = n;
+        return;
+    }
+    const uint32_t *rb = a.crow + (size_t)ul * a.l_stride;
     uint32_t *dstr = a.srow + (size_t)ul * a.top_k;
     int32_t *dst2 = a.out_sel ? a.out_sel + (size_t)ul * a.top_k : nullptr;
     float *zd = a.zsel + (size_t)ul * a.top_k * G;
@@ -1103,6 +1109,62 @@ template <typename T, int G> __global__ __launch_bounds__(1024) void sparse_attn
     if (slice == 0 && a.out_lse && tid < G) a.out_lse[(size_t)b * a.h + kv * G + tid] = s_m[tid] + __logf(s_l[tid]);
     CTKVR_STAMP(47);
     CTKVR_STAMP_BLK(5);
+}
+
+// ------------------------------------------------------------------------------
+// Algorithm 2 line 12 (dynamic centroid update): the step's query becomes the centroid of the
+// FIFO slot (updates so far mod C: the oldest mapping goes first) for the G heads of the group,
+// with its inverse norm, and the slot's list becomes src[unit][0..rho): the top-rho ids by rerank
+// score, ascending (should fewer have been recalled, the last one is repeated; none: no update).
+// grid batch*g, 256 threads.  dcu_advance_kernel then counts the update.
+// ------------------------------------------------------------------------------
+struct DcuArgs {
+    int g, h, G, c_max, rho, src_stride;
+    const int32_t *n_cent;
+    const uint32_t *count;    // [1] updates so far
+    const void *q;            // [batch][h][128]
+    const int32_t *src;       // [units][src_stride]
+    const int32_t *nsrc;      // [units]
+    void *centroids;          // [batch][h][c_max][128]
+    float *inv_norm_c;        // [batch][h][c_max]
+    int32_t *lists;           // [units][c_max][rho]
+};
+
+__device__ __forceinline__ void store_chunk(float *row, int lane16, const Chunk<float> &c)
+{
+    float4 *p = reinterpret_cast<float4 *>(row + 8 * lane16);
+    p[0] = c.a;
+    p[1] = c.b;
+}
+__device__ __forceinline__ void store_chunk(bf16_t *row, int lane16, const Chunk<bf16_t> &c)
+{
+    *reinterpret_cast<uint4 *>(row + 8 * lane16) = c.w;
+}
+
+template <typename T> __global__ __launch_bounds__(256) void dcu_write_kernel(DcuArgs a)
+{
+    const int ul = blockIdx.x, b = ul / a.g, kv = ul - b * a.g, tid = threadIdx.x;
+    const int slot = (int)(a.count[0] % (uint32_t)a.n_cent[b]);
+    const int n = min(a.nsrc[ul], a.rho);
+    if (n <= 0) return;
+    const int32_t *src = a.src + (size_t)ul * a.src_stride;
+    int32_t *dst = a.lists + ((size_t)ul * a.c_max + slot) * a.rho;
+    for (int r = tid; r < a.rho; r += 256) dst[r] = src[min(r, n - 1)];
+    if (tid < 16 * a.G) {
+        const int hh = tid >> 4, lane16 = tid & 15;
+        const size_t head = (size_t)b * a.h + kv * a.G + hh;
+        Chunk<T> c = load_chunk((const T *)a.q + head * kD, lane16);
+        store_chunk((T *)a.centroids + (head * a.c_max + slot) * kD, lane16, c);
+        float x[8];
+        unpack(c, x);
+        const float n2 = group16_sum(lane_partial(x, x));
+        if (lane16 == 0) a.inv_norm_c[head * a.c_max + slot] = inv_norm_from_sq(n2);
+    }
+}
+
+__global__ void dcu_advance_kernel(uint32_t *count)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) count[0] += 1u;
 }
 
 }  // namespace ctkvr

@@ -88,9 +88,11 @@ def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
 
 
 def run_decode_parity(bt: Batch, oi: OracleIndex, idx, db: DeviceBatch, steps: Optional[List[int]] = None,
-                      check_candidates: bool = True) -> dict:
+                      check_candidates: bool = True, update: bool = False) -> dict:
     """Run decode steps on the GPU index `idx` and on the oracle with index `oi`;
-    assert bit-equal integers and outputs within REL_TOL.  Returns statistics."""
+    assert bit-equal integers and outputs within REL_TOL.  With update=True both sides
+    apply the dynamic centroid update after every step (`oi` is changed in place).
+    Returns statistics."""
     import torch
     import paper_2512_15550_amd as ck
     wl = bt.wl
@@ -102,9 +104,11 @@ def run_decode_parity(bt: Batch, oi: OracleIndex, idx, db: DeviceBatch, steps: O
     ncand = torch.empty((B, g), dtype=torch.int32, device="cuda")
     probe = torch.empty((B, g, wl.n_probe), dtype=torch.int32, device="cuda")
     worst, worst_lse, alphas = 0.0, 0.0, []
+    n_updates = 0
     for st in steps:
         q = np.stack([sq.q_decode[st] for sq in bt.seqs])
-        ck.ctkvr_decode_step(idx, to_dev(q, wl), db.k_pages, db.v_pages, db.block_table, out, lse, sel, ncand, probe)
+        q_dev = to_dev(q, wl)
+        ck.ctkvr_decode_step(idx, q_dev, db.k_pages, db.v_pages, db.block_table, out, lse, sel, ncand, probe)
         torch.cuda.synchronize()
         g_out, g_lse = out.cpu().numpy(), lse.cpu().numpy()
         g_sel, g_ncand, g_probe = sel.cpu().numpy(), ncand.cpu().numpy(), probe.cpu().numpy()
@@ -125,6 +129,11 @@ def run_decode_parity(bt: Batch, oi: OracleIndex, idx, db: DeviceBatch, steps: O
             assert el <= 1e-4, f"{tag}: lse error {el:.3e}"
             worst_lse = max(worst_lse, el)
             alphas.append(float(np.mean(r.ncand)) / (wl.n_probe * wl.list_len))
+            if update:
+                oracle.centroid_update(q[b], oi.Qc[b], oi.lists[b], r, n_updates)
+        if update:
+            ck.ctkvr_centroid_update(idx, q_dev)
+            n_updates += 1
     return {"max_rel_err": worst, "max_lse_err": worst_lse, "alpha": float(np.mean(alphas))}
 
 
@@ -161,7 +170,8 @@ def run_sampled_parity(bt: Batch, idx, db: DeviceBatch, steps: List[int], n_list
     worst, alphas = 0.0, []
     for st in steps:
         q = np.stack([sq.q_decode[st] for sq in bt.seqs])
-        ck.ctkvr_decode_step(idx, to_dev(q, wl), db.k_pages, db.v_pages, db.block_table, out, lse, sel, ncand, probe)
+        q_dev = to_dev(q, wl)
+        ck.ctkvr_decode_step(idx, q_dev, db.k_pages, db.v_pages, db.block_table, out, lse, sel, ncand, probe)
         torch.cuda.synchronize()
         g_out, g_lse = out.cpu().numpy(), lse.cpu().numpy()
         g_sel, g_ncand, g_probe = sel.cpu().numpy(), ncand.cpu().numpy(), probe.cpu().numpy()
