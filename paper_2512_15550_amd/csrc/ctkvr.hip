@@ -72,6 +72,7 @@ struct ctkvr_index {
     float *z = nullptr, *zsel = nullptr;
     uint32_t *m_key = nullptr;
     size_t recall_lds = 0, select_lds = 0, attn_lds = 0, build_select_lds = 0;
+    size_t fused_lds = 0;   // non-zero: selection and attention run as one launch (select_attn_kernel)
     int sel_bits = 0, build_bits = 0;   // words for the selection's id bitmaps (0: histogram route off)
     int bitmap_words = 0, recall_split = 1, num_cu = 256;
     // per-kernel timing
@@ -229,6 +230,11 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
     // two never share a CU.  The recall is spread over recall_split blocks per unit.
     if ((int)U <= ix->num_cu) ix->select_lds = std::max<size_t>(ix->select_lds, 84 * 1024);
     ix->recall_split = std::max(1, std::min(8, ix->num_cu / (int)U));
+    // Few enough units for every (unit, slice) block to have a CU of its own: one launch for lines 6-9.
+    {
+        const size_t fw = ((size_t)kSelLds + 2 * kListCap + ix->sel_bits + p->top_k + (size_t)p->top_k * ix->G) * 4;
+        if (4 * (int)U <= ix->num_cu && fw <= 150 * 1024) ix->fused_lds = fw;
+    }
     if (ix->recall_lds > 150 * 1024 || ix->select_lds > 150 * 1024 || ix->attn_lds > 128 * 1024) {
         delete ix;
         return fail(CTKVR_EUNSUPPORTED, "context, top_k or n_probe too large for the shared-memory plan");
@@ -246,6 +252,19 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
     want((const void *)rerank_select_kernel<2>, sel_b);
     want((const void *)rerank_select_kernel<4>, sel_b);
     want((const void *)rerank_select_kernel<8>, sel_b);
+    if (ix->fused_lds) {
+        if (p->dtype == CTKVR_BF16) {
+            want((const void *)select_attn_kernel<bf16_t, 1>, ix->fused_lds);
+            want((const void *)select_attn_kernel<bf16_t, 2>, ix->fused_lds);
+            want((const void *)select_attn_kernel<bf16_t, 4>, ix->fused_lds);
+            want((const void *)select_attn_kernel<bf16_t, 8>, ix->fused_lds);
+        } else {
+            want((const void *)select_attn_kernel<float, 1>, ix->fused_lds);
+            want((const void *)select_attn_kernel<float, 2>, ix->fused_lds);
+            want((const void *)select_attn_kernel<float, 4>, ix->fused_lds);
+            want((const void *)select_attn_kernel<float, 8>, ix->fused_lds);
+        }
+    }
     if (p->dtype == CTKVR_BF16) {
         want((const void *)sparse_attn_kernel<bf16_t, 1>, ix->attn_lds);
         want((const void *)sparse_attn_kernel<bf16_t, 2>, ix->attn_lds);
@@ -585,9 +604,6 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     se.zsel = ix->zsel;
     se.nsel = ix->nsel;
     se.out_sel = out_sel;
-    rerank_select_kernel<G><<<dim3(U), 1024, ix->select_lds, st>>>(se);
-    ix->mark(8, st);
-
     AttnArgs aa{};
     aa.v_pages = v_pages;
     aa.g = p.n_kv_heads;
@@ -598,7 +614,14 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     aa.zsel = ix->zsel;
     aa.out = out;
     aa.out_lse = out_lse;
-    sparse_attn_kernel<T, G><<<dim3(4 * U), 1024, ix->attn_lds, st>>>(aa);
+    if (ix->fused_lds) {
+        ix->mark(8, st);   // no separate selection launch: its stage reads as the cost of an event pair
+        select_attn_kernel<T, G><<<dim3(4 * U), 1024, ix->fused_lds, st>>>(se, aa);
+    } else {
+        rerank_select_kernel<G><<<dim3(U), 1024, ix->select_lds, st>>>(se);
+        ix->mark(8, st);
+        sparse_attn_kernel<T, G><<<dim3(4 * U), 1024, ix->attn_lds, st>>>(aa);
+    }
     ix->mark(9, st);
     if (ix->prof_step < ix->prof_max) {   // a null kernel between two events: what the bracketing itself costs
         fill_u32_kernel<<<dim3(1), 64, 0, st>>>((uint32_t *)ix->nsel, 0u, 0);

@@ -884,20 +884,19 @@ __device__ __forceinline__ int select_generic(KeyFn key, int L, int k, EmitFn em
     return block_select_topk<1024, KPT>(key, L, k, emit, s_sel);
 }
 
-template <int G> __global__ __launch_bounds__(1024) void rerank_select_kernel(SelectArgs a)
+// Shared-memory words of the selection: radix scratch, the deciding bucket's list, the two id
+// bitmaps, then the positions of the picks (decode).
+__device__ __forceinline__ int select_smem_words(int bits_words, int top_k) { return kSelLds + 2 * kListCap + bits_words + top_k; }
+
+// The selection of one unit: positions (decode: into s_idx, ascending; build: ids straight into
+// the list) of the top_k ranking keys among L.  Returns their number.  Every thread of the
+// 1024-thread block takes part.
+template <int G> __device__ __forceinline__ int select_unit(const SelectArgs &a, int ul, int L, uint32_t *smem)
 {
-    extern __shared__ __align__(16) uint32_t smem[];
     uint32_t *s_sel = smem;                          // kSelLds
     uint32_t *s_list = smem + kSelLds;               // 2 * kListCap
     uint32_t *s_bits = s_list + 2 * kListCap;        // a.bits_words (two bitmaps over the ids)
     int32_t *s_idx = (int32_t *)(s_bits + a.bits_words);   // top_k (decode)
-    int b, kv, j;
-    const int ul = blockIdx.x;
-    if (!decode_unit(a.u, ul, b, kv, j)) return;
-    const int L = a.cand ? a.ncand[ul] : a.ctx_lens[b];
-    CTKVR_STAMP(28);
-    CTKVR_STAMP_BLK(2);
-    const float *zb = a.z + (size_t)ul * a.l_stride * G;
     const uint32_t *kb = a.kbuf + (size_t)ul * a.l_stride;
     auto key = [&](int i) { return kb[i]; };
     int32_t *lst = a.u.build ? a.sel + (size_t)(a.u.unit0 + ul) * a.top_k : nullptr;
@@ -929,9 +928,23 @@ template <int G> __global__ __launch_bounds__(1024) void rerank_select_kernel(Se
         else
             n = select_generic<0>(key, L, a.top_k, emit, s_sel);
     }
+    return n;
+}
+
+template <int G> __global__ __launch_bounds__(1024) void rerank_select_kernel(SelectArgs a)
+{
+    extern __shared__ __align__(16) uint32_t smem[];
+    int b, kv, j;
+    const int ul = blockIdx.x;
+    if (!decode_unit(a.u, ul, b, kv, j)) return;
+    const int L = a.cand ? a.ncand[ul] : a.ctx_lens[b];
+    CTKVR_STAMP(28);
+    CTKVR_STAMP_BLK(2);
+    const int n = select_unit<G>(a, ul, L, smem);
     if (!a.u.build) {
         __syncthreads();
-        select_gather<G>(a, ul, n, zb, s_idx);
+        select_gather<G>(a, ul, n, a.z + (size_t)ul * a.l_stride * G,
+                         (const int32_t *)(smem + kSelLds + 2 * kListCap + a.bits_words));
     }
     CTKVR_STAMP(31);
     CTKVR_STAMP_BLK(3);
@@ -954,43 +967,45 @@ struct AttnArgs {
     float *out_lse;
 };
 
-template <typename T, int G> __global__ __launch_bounds__(1024) void sparse_attn_kernel(AttnArgs a)
+// Block id -> (unit, slice).  Workgroups go to the 8 XCDs round-robin by linear id; the four slices
+// of a unit read the same 128-byte lines, so they get ids that are congruent modulo 8: one XCD, one L2.
+__device__ __forceinline__ void attn_block_of(int &ul, int &slice)
 {
-    extern __shared__ __align__(16) float s_p[];   // [top_k][G]
+    const int lin = blockIdx.x, nu = gridDim.x >> 2;
+    if ((nu & 7) == 0) {
+        const int xcd = lin & 7, k = lin >> 3;
+        ul = (k >> 2) * 8 + xcd;
+        slice = k & 3;
+    } else {
+        ul = lin >> 2;
+        slice = lin & 3;
+    }
+}
+
+// The attention of one (unit, slice).  row_of(t) = physical row of the t-th selected key (valid for
+// every t < top_k), z_of(t, zv) = its G logits, nsel_of() = how many keys were selected; nsel_of is
+// asked only after the first value rows have been requested.  s_p: top_k*G floats of shared memory.
+template <typename T, int G, typename RowFn, typename ZFn, typename NFn>
+__device__ __forceinline__ void attend_unit(const AttnArgs &a, int ul, int slice, float *s_p, RowFn row_of, ZFn z_of, NFn nsel_of)
+{
     __shared__ float s_red[16][G];
     __shared__ float s_m[G], s_l[G];
     __shared__ float s_o[16][G][32];
-    // Workgroups go to the 8 XCDs round-robin by linear id.  The four slices of a unit read the same
-    // 128-byte lines, so they are given ids that are congruent modulo 8: one XCD, one L2.
-    int ul, slice;
-    {
-        const int lin = blockIdx.x, nu = gridDim.x >> 2;
-        if ((nu & 7) == 0) {
-            const int xcd = lin & 7, k = lin >> 3;
-            ul = (k >> 2) * 8 + xcd;
-            slice = k & 3;
-        } else {
-            ul = lin >> 2;
-            slice = lin & 3;
-        }
-    }
     const int b = ul / a.g, kv = ul - b * a.g;
     const int tid = threadIdx.x, wv = tid >> 6, ln = tid & 63;
     const int quad = ln >> 4, rin = wv * 16 + (ln & 15);   // 4 lanes (one per 16-lane row of the wave) share a key row
     CTKVR_STAMP(44);
     CTKVR_STAMP_BLK(4);
     const T *V = (const T *)a.v_pages + slice * 32 + quad * 8;
-    const uint32_t *rb = a.srow + (size_t)ul * a.top_k;
-    const float *zb = a.zsel + (size_t)ul * a.top_k * G;
-    // The first 1024 value rows are requested before anything else: srow always holds valid rows
-    // (beyond nsel they are stale ones whose products get weight 0), so nothing here waits for nsel.
+    // The first 1024 value rows are requested before anything else (rows beyond nsel are valid
+    // stale ones whose products get weight 0).
     Chunk<T> cv[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-        uint32_t row = rb[min(u * 256 + rin, a.top_k - 1)];
+        uint32_t row = row_of(min(u * 256 + rin, a.top_k - 1));
         cv[u] = load_chunk(V + (size_t)row * kD, 0);
     }
-    const int nsel = a.nsel[ul];
+    const int nsel = nsel_of();
     if (nsel == 0) {   // nothing recalled: defined output
         if (tid < G * 32) {
             int hh = tid >> 5, e = tid & 31;
@@ -1005,7 +1020,7 @@ template <typename T, int G> __global__ __launch_bounds__(1024) void sparse_attn
     for (int hh = 0; hh < G; ++hh) mx[hh] = -__builtin_huge_valf();
     for (int t = tid; t < nsel; t += 1024) {
         float zv[G];
-        load_z<G>(zb, t, zv);
+        z_of(t, zv);
 #pragma unroll
         for (int hh = 0; hh < G; ++hh) {
             s_p[t * G + hh] = zv[hh];
@@ -1067,7 +1082,7 @@ template <typename T, int G> __global__ __launch_bounds__(1024) void sparse_attn
         if (r0 > 0) {
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                uint32_t row = rb[min(r0 + u * 256 + rin, a.top_k - 1)];
+                uint32_t row = row_of(min(r0 + u * 256 + rin, a.top_k - 1));
                 cv[u] = load_chunk(V + (size_t)row * kD, 0);
             }
         }
@@ -1109,6 +1124,55 @@ template <typename T, int G> __global__ __launch_bounds__(1024) void sparse_attn
     if (slice == 0 && a.out_lse && tid < G) a.out_lse[(size_t)b * a.h + kv * G + tid] = s_m[tid] + __logf(s_l[tid]);
     CTKVR_STAMP(47);
     CTKVR_STAMP_BLK(5);
+}
+
+template <typename T, int G> __global__ __launch_bounds__(1024) void sparse_attn_kernel(AttnArgs a)
+{
+    extern __shared__ __align__(16) float s_p[];   // [top_k][G]
+    int ul, slice;
+    attn_block_of(ul, slice);
+    const uint32_t *rb = a.srow + (size_t)ul * a.top_k;
+    const float *zb = a.zsel + (size_t)ul * a.top_k * G;
+    attend_unit<T, G>(a, ul, slice, s_p, [&](int t) { return rb[t]; }, [&](int t, float(&zv)[G]) { load_z<G>(zb, t, zv); },
+                      [&]() { return a.nsel[ul]; });
+}
+
+// ------------------------------------------------------------------------------
+// Algorithm 2 lines 6-9 in one launch, for batches small enough that every block has a CU of its
+// own: each of the four slice blocks of a unit makes the unit's selection itself (the same work
+// four times over, on four CUs, instead of a second launch and a round trip of the picks through
+// global memory) and then attends over the picks straight from the recalled ids' rows and logits.
+// Slice 0 also writes the selected ids and their number.  grid 4*batch*g, 1024 threads; dynamic
+// shared memory: the selection's words, then top_k*G floats.
+// ------------------------------------------------------------------------------
+template <typename T, int G> __global__ __launch_bounds__(1024) void select_attn_kernel(SelectArgs sa, AttnArgs a)
+{
+    extern __shared__ __align__(16) uint32_t smem[];
+    int ul, slice;
+    attn_block_of(ul, slice);
+    const int L = sa.ncand[ul];
+    CTKVR_STAMP(28);
+    const int n = select_unit<G>(sa, ul, L, smem);
+    __syncthreads();
+    const int32_t *s_idx = (const int32_t *)(smem + kSelLds + 2 * kListCap + sa.bits_words);
+    float *s_p = reinterpret_cast<float *>(smem + select_smem_words(sa.bits_words, sa.top_k));
+    const int32_t *cb = sa.cand + (size_t)ul * sa.l_stride;
+    const uint32_t *rb = sa.crow + (size_t)ul * sa.l_stride;
+    const float *zb = sa.z + (size_t)ul * sa.l_stride * G;
+    CTKVR_STAMP(31);
+    if (slice == 0) {
+        int32_t *dst = sa.sel + (size_t)ul * sa.top_k;
+        int32_t *dst2 = sa.out_sel ? sa.out_sel + (size_t)ul * sa.top_k : nullptr;
+        for (int pos = threadIdx.x; pos < sa.top_k; pos += 1024) {
+            const int t = pos < n ? cb[s_idx[pos]] : -1;
+            dst[pos] = t;
+            if (dst2) dst2[pos] = t;
+        }
+        if (threadIdx.x == 0) sa.nsel[ul] = n;
+    }
+    // positions beyond n repeat the last pick (or candidate 0 when nothing was recalled: never loaded then)
+    attend_unit<T, G>(a, ul, slice, s_p, [&](int t) { return n > 0 ? rb[s_idx[min(t, n - 1)]] : 0u; },
+                      [&](int t, float(&zv)[G]) { load_z<G>(zb, s_idx[t], zv); }, [&]() { return n; });
 }
 
 // ------------------------------------------------------------------------------
