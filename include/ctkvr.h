@@ -178,14 +178,14 @@ int ctkvr_index_centroids(const ctkvr_index *idx, void *dst_host);
 int ctkvr_index_last_candidates(const ctkvr_index *idx, int32_t *dst_host);
 
 /* ---- per-kernel timing (measurement aid) ----------------------------------- */
-/* The decode step runs these kernels in order: 0 centroid cosine, 1 probe select +
- * list gather into a bitmap, 2 bitmap expansion into the recalled id list, 3 key
- * scoring over the recalled ids, 4 softmax denominators, 5 ranking keys + their
- * histogram, 6 chip-wide pass over the ranking keys (bitmap + deciding bucket's list),
- * 7 rerank select, 8 sparse attention.  While timing is enabled a tenth, empty kernel
- * follows (stage 9): its figure is what a pair of events costs around a kernel that
- * does nothing. */
-#define CTKVR_N_STAGES 10
+/* The decode step runs these kernels in order: 0 centroid cosine, 1 probe select + list
+ * gather into a bitmap, 2 bitmap expansion into the recalled id list fused with key scoring,
+ * 3 softmax denominators, 4 ranking keys + their histogram, 5 chip-wide pass over the
+ * ranking keys (bitmap + deciding bucket's list), 6 rerank select, 7 sparse attention.  For
+ * small batches 6 and 7 are one launch, timed as stage 7 (stage 6 then reads as the cost of
+ * an event pair).  While timing is enabled a ninth, empty kernel follows (stage 8): its
+ * figure is what a pair of events costs around a kernel that does nothing. */
+#define CTKVR_N_STAGES 9
 /* After this call every decode step on `idx` records a HIP event before its first
  * kernel and after each kernel, for up to max_steps steps (0 disables and frees
  * the events).  Recording adds work to the stream: use it for the breakdown, not

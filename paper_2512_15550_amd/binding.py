@@ -73,8 +73,8 @@ _lib = None
 EXPORTS = ["ctkvr_build_index", "ctkvr_index_load", "ctkvr_decode_step", "ctkvr_free", "ctkvr_last_error",
            "ctkvr_index_info", "ctkvr_index_lists", "ctkvr_index_centroids", "ctkvr_index_last_candidates",
            "ctkvr_profile_enable", "ctkvr_profile_collect", "ctkvr_centroid_update"]
-N_STAGES = 10
-STAGE_NAMES = ["centroid_cos", "recall_gather", "recall_expand", "score", "denom", "keyhist", "classify",
+N_STAGES = 9
+STAGE_NAMES = ["centroid_cos", "recall_gather", "score", "denom", "keyhist", "classify",
                "rerank_select", "sparse_attn", "null"]
 
 

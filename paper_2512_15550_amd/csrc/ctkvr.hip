@@ -246,7 +246,6 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
     want((const void *)recall_gather_kernel<2>, ix->recall_lds);
     want((const void *)recall_gather_kernel<8>, ix->recall_lds);
     want((const void *)recall_gather_kernel<32>, ix->recall_lds);
-    want((const void *)recall_expand_kernel, 64 * 1024);
     const size_t sel_b = std::max(ix->select_lds, ix->build_select_lds);
     want((const void *)rerank_select_kernel<1>, sel_b);
     want((const void *)rerank_select_kernel<2>, sel_b);
@@ -497,42 +496,32 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
         recall_gather_kernel<32><<<rgrid, 256, ix->recall_lds, st>>>(ga);
     ix->mark(2, st);
 
-    ExpandArgs ea{};
-    ea.gbits = ix->gbits;
-    ea.ctx_lens = ix->d_ctx_lens;
-    ea.block_table = bt;
-    ea.max_pages = max_pages;
-    ea.page_shift = ix->page_shift;
-    ea.cand = ix->cand;
-    ea.crow = ix->crow;
-    ea.ncand = ix->ncand;
-    ea.out_ncand = out_ncand;
-    ea.g = p.n_kv_heads;
-    ea.l_stride = ix->l_stride;
-    ea.bitmap_words = ix->bitmap_words;
-    recall_expand_kernel<<<rgrid, 1024, 64 * 1024, st>>>(ea);
-    ix->mark(3, st);
-
+    // lines 4-5: bitmap -> recalled ids, their rows and their scores in one launch
     Units u = decode_units(ix);
-    ScoreArgs sa{};
+    RecallScoreArgs sa{};
     sa.u = u;
     sa.q = q;
-    sa.qrows = 1;
     sa.k = Paged{k_pages, bt, max_pages, ix->page_shift};
     sa.ctx_lens = ix->d_ctx_lens;
+    sa.gbits = ix->gbits;
+    sa.bitmap_words = ix->bitmap_words;
+    sa.l_stride = ix->l_stride;
+    sa.cand = ix->cand;
     sa.crow = ix->crow;
     sa.ncand = ix->ncand;
-    sa.l_stride = ix->l_stride;
+    sa.out_ncand = out_ncand;
     sa.z = ix->z;
     sa.m_key = ix->m_key;
     sa.ghist = ix->ghist;
     sa.scale = ix->scale;
-    // enough blocks to fill the chip a few times over, each walking its share of 128-id tiles
-    const int tiles = (ix->l_stride + 127) / 128;
-    // (at least 32 per unit, so that the long units of a ragged batch do not set the pace)
-    const int nbx = std::max(1, std::min(tiles, std::max(32, (8 * ix->num_cu + U - 1) / U)));
-    score_kernel<T, G, 8><<<dim3(nbx, U), 256, 0, st>>>(sa);
-    ix->mark(4, st);
+    {   // enough blocks to fill the chip a few times over (at least 32 per unit, so that the long
+        // units of a ragged batch do not set the pace), each owning 8..64 words of the bitmap
+        const int target = std::max(32, (8 * ix->num_cu + U - 1) / U);
+        const int wpb = std::max(8, std::min(kRecallWpb, (ix->bitmap_words + target - 1) / target));
+        const int nbx = (ix->bitmap_words + wpb - 1) / wpb;
+        recall_score_kernel<T, G><<<dim3(nbx, U), 256, 0, st>>>(sa);
+    }
+    ix->mark(3, st);
 
     DenomArgs da{};
     da.u = u;
@@ -546,7 +535,7 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     da.bitmap_words = ix->bitmap_words;
     const int chunks = (ix->l_stride + 1023) / 1024;
     denom_kernel<G><<<dim3(std::max(1, std::min(chunks, (4 * ix->num_cu + U - 1) / U)), U), 256, 0, st>>>(da);
-    ix->mark(5, st);
+    ix->mark(4, st);
 
     KeyArgs ka{};
     ka.u = u;
@@ -560,7 +549,7 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     ka.ghist = ix->ghist;
     ka.gcur = ix->gcur;
     keyhist_kernel<G><<<dim3(std::max(1, std::min((ix->l_stride + 4095) / 4096, (2 * ix->num_cu + U - 1) / U)), U), 1024, 0, st>>>(ka);
-    ix->mark(6, st);
+    ix->mark(5, st);
 
     if (ix->sel_bits) {
         ClassifyArgs ca{};
@@ -578,7 +567,7 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
         ca.ginfo = ix->ginfo;
         classify_kernel<<<dim3(std::max(1, std::min(chunks, (4 * ix->num_cu + U - 1) / U)), U), 256, 0, st>>>(ca);
     }
-    ix->mark(7, st);
+    ix->mark(6, st);
 
     SelectArgs se{};
     se.u = u;
@@ -615,17 +604,17 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     aa.out = out;
     aa.out_lse = out_lse;
     if (ix->fused_lds) {
-        ix->mark(8, st);   // no separate selection launch: its stage reads as the cost of an event pair
+        ix->mark(7, st);   // no separate selection launch: its stage reads as the cost of an event pair
         select_attn_kernel<T, G><<<dim3(4 * U), 1024, ix->fused_lds, st>>>(se, aa);
     } else {
         rerank_select_kernel<G><<<dim3(U), 1024, ix->select_lds, st>>>(se);
-        ix->mark(8, st);
+        ix->mark(7, st);
         sparse_attn_kernel<T, G><<<dim3(4 * U), 1024, ix->attn_lds, st>>>(aa);
     }
-    ix->mark(9, st);
+    ix->mark(8, st);
     if (ix->prof_step < ix->prof_max) {   // a null kernel between two events: what the bracketing itself costs
         fill_u32_kernel<<<dim3(1), 64, 0, st>>>((uint32_t *)ix->nsel, 0u, 0);
-        ix->mark(10, st);
+        ix->mark(9, st);
     }
     if (ix->prof_step < ix->prof_max) ix->prof_step++;
     HIP_TRY(hipGetLastError());

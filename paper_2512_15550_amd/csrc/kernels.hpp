@@ -1,17 +1,19 @@
 // gfx950 kernels of the CTkvr path.
 //
-// Decode step (Algorithm 2 lines 1-9), eight launches:
+// Decode step (Algorithm 2 lines 1-9), seven or eight launches:
 //   centroid_cos  lines 1-2   cosine to every centroid, max over the GQA group
 //   recall_gather lines 3-4a  top-C' centroids; their lists OR-ed into a bitmap
-//   recall_expand line  4b    the bitmap as an ascending id list plus each id's
-//                             physical KV row
-//   score         line 5a     z = (q . k) * scale for the G heads, running max
+//   recall_score  lines 4b-5a the bitmap as an ascending id list plus each id's physical
+//                             KV row; z = (q . k) * scale for the G heads, running max
 //   denom         line 5b     softmax denominators, integer fixed point
 //   keyhist       line 5c     max over the group of log-softmax as a ranking key,
 //                             and a histogram of the keys
-//   rerank_select line 6      top-rho' ids
+//   classify      line 6a     chip-wide pass over the keys: sure picks as a bitmap, the
+//                             deciding bucket as a list
+//   rerank_select line 6b     top-rho' ids
 //   sparse_attn   lines 7-9   softmax(z_sel) . V_sel, one block per slice of the
 //                             head dimension (no cross-block reduction)
+//   (select_attn = the last two in one launch, for small batches)
 // The exact index build (Algorithm 1 lines 2-4) runs score -> denom -> keyhist -> rerank_select with
 // "the recalled set" = all s keys and the centroid in the role of the query,
 // which is literally the same formula.
@@ -182,8 +184,9 @@ template <typename T, int G> __global__ __launch_bounds__(256) void centroid_cos
 }
 
 // ------------------------------------------------------------------------------
-// Algorithm 2 lines 3-4 in two launches, each (sequence, KV head) spread over
-// several blocks so that no single CU has to pull all the probed lists.
+// Algorithm 2 lines 3-4, first part, each (sequence, KV head) spread over several
+// blocks so that no single CU has to pull all the probed lists (the bitmap becomes the
+// ascending id list in recall_score_kernel).
 //
 // recall_gather: every block of a unit finds the same top-C' centroids (keys in
 // registers, C <= 256*KPT, bisection on the key), takes every gridDim.x-th probed list, ORs its ids into a bitmap in shared memory and then
@@ -280,100 +283,6 @@ template <int KPT> __global__ __launch_bounds__(256) void recall_gather_kernel(G
 }
 
 // ------------------------------------------------------------------------------
-// recall_expand: the unit's bitmap -> ascending id list + physical KV rows.  Block x
-// of a unit owns a contiguous slice of 32-word chunks; it counts the bits before its
-// slice (the bitmap is a few KB), then every wave scatters the set bits of a chunk
-// into its shared-memory staging area (at most 1024 ids) and copies that out with
-// consecutive lanes writing consecutive ids.  The bitmap is cleared later in the step
-// (by denom), once nobody reads it any more.  grid (nsplit, batch*g), 1024 threads;
-// dynamic shared memory: 16 x 1024 words of staging.
-// ------------------------------------------------------------------------------
-struct ExpandArgs {
-    const uint32_t *gbits;
-    const int32_t *ctx_lens;
-    const int32_t *block_table;
-    int max_pages, page_shift;
-    int32_t *cand;            // [batch*g][l_stride]
-    uint32_t *crow;           // [batch*g][l_stride] physical row of cand[i]
-    int32_t *ncand;           // [batch*g]
-    int32_t *out_ncand;       // optional copy for the caller
-    int g, l_stride, bitmap_words;
-};
-
-__global__ __launch_bounds__(1024) void recall_expand_kernel(ExpandArgs a)
-{
-    extern __shared__ uint32_t s_stage_all[];   // 16 x 1024 words
-    __shared__ uint32_t s_ctot[1024];
-    __shared__ uint32_t s_tmp[64];
-    const int ul = blockIdx.y, tid = threadIdx.x, wv = tid >> 6, ln = tid & 63;
-    const int b = ul / a.g, kv = ul - b * a.g;
-    const int s = a.ctx_lens[b];
-    const int W = (s + 31) >> 5;
-    const int chunks = (W + 31) >> 5;
-    const int cps = (chunks + gridDim.x - 1) / gridDim.x;   // chunks per slice (<= 1024 because W <= 32768)
-    const int c_beg = blockIdx.x * cps;
-    if (c_beg >= chunks) return;
-    const int c_end = min(chunks, c_beg + cps);
-    const uint32_t *gb = a.gbits + (size_t)ul * a.bitmap_words;
-    CTKVR_STAMP(11);
-    CTKVR_STAMP_BLK(6);
-    // ids before this slice
-    uint32_t before = 0;
-#pragma unroll 4
-    for (int w = tid; w < c_beg * 32; w += 1024) before += __popc(gb[w]);
-    // totals of this slice's chunks
-    for (int c = c_beg + wv; c < c_end; c += 16) {
-        int w = c * 32 + ln;
-        uint32_t cnt = (ln < 32 && w < W) ? __popc(gb[w]) : 0u;
-#pragma unroll
-        for (int o = 16; o >= 1; o >>= 1) cnt += __shfl_xor(cnt, o);
-        if (ln == 0) s_ctot[c - c_beg] = cnt;
-    }
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) before += __shfl_xor(before, o);
-    if (ln == 0) s_tmp[32 + wv] = before;
-    __syncthreads();
-    uint32_t base0 = 0;
-#pragma unroll
-    for (int q = 0; q < 16; ++q) base0 += s_tmp[32 + q];
-    uint32_t own;
-    uint32_t ex = block_excl_scan<1024>(tid < (c_end - c_beg) ? s_ctot[tid] : 0u, s_tmp, &own);
-    if (tid < (c_end - c_beg)) s_ctot[tid] = base0 + ex;
-    __syncthreads();
-    int32_t *out = a.cand + (size_t)ul * a.l_stride;
-    uint32_t *rows = a.crow + (size_t)ul * a.l_stride;
-    for (int c = c_beg + wv; c < c_end; c += 16) {
-        int w = c * 32 + ln;
-        uint32_t m = (ln < 32 && w < W) ? gb[w] : 0u;
-        uint32_t cnt = __popc(m);
-        uint32_t incl = wave_incl_scan(cnt);
-        uint32_t pos = incl - cnt;
-        const uint32_t total = __shfl(incl, 63);
-        while (__ballot(m != 0u)) {
-            if (m) {
-                int bit = __ffs((int)m) - 1;
-                m &= m - 1;
-                s_stage_all[wv * 1024 + pos++] = (uint32_t)((w << 5) + bit);
-            }
-        }
-        __threadfence_block();   // the wave's own staging writes, before other lanes read them
-        const uint32_t cb = s_ctot[c - c_beg];
-        for (uint32_t k = ln; k < total; k += 64) {
-            int t = (int)s_stage_all[wv * 1024 + k];
-            out[cb + k] = t;
-            rows[cb + k] = row_of(a.block_table, a.max_pages, a.page_shift, a.g, b, kv, t);
-        }
-        __threadfence_block();
-    }
-    if (c_end == chunks && tid == 0) {
-        a.ncand[ul] = (int32_t)(base0 + own);
-        if (a.out_ncand) a.out_ncand[ul] = (int32_t)(base0 + own);
-    }
-    CTKVR_STAMP(12);
-    CTKVR_STAMP_BLK(7);
-}
-
-// ------------------------------------------------------------------------------
 // Algorithm 2 line 5 / Algorithm 1 line 2, first half: z[h][i] = (q_h . k_i) * scale
 // for the G heads of the group, plus the running maximum per head.  A block walks
 // tiles of 16*R ids (R rows per 16-lane group, all R loads issued before the first
@@ -464,6 +373,147 @@ template <typename T, int G, int R> __global__ __launch_bounds__(256) void score
     __syncthreads();
     if (tid < G) atomicMax(&a.m_key[ul * G + tid], s_max[tid]);
     CTKVR_STAMP(22);
+}
+
+// ------------------------------------------------------------------------------
+// Algorithm 2 lines 4-5 in one launch (decode): block x of a unit owns words
+// [x*wpb, (x+1)*wpb) of the unit's recall bitmap.  It counts the ids before its range (the
+// bitmap is a few KB), turns its own words into ascending ids in shared memory (one word per
+// thread, positions by a block scan), writes them and their physical rows to their ranks of
+// the recalled list (consecutive lanes, consecutive ranks), and scores them like score_kernel:
+// z[rank][G], running maximum per head.  The block owning the last word also writes L.
+// grid (nbx, units), 256 threads, with nbx >= W_max / kRecallWpb; a unit with W words gives
+// ceil(W / nbx) of them to each block.
+// ------------------------------------------------------------------------------
+constexpr int kRecallWpb = 64;   // at most 2048 ids per block
+
+struct RecallScoreArgs {
+    Units u;
+    const void *q;            // [batch][h][128]
+    Paged k;
+    const int32_t *ctx_lens;
+    const uint32_t *gbits;    // [units][bitmap_words]
+    int bitmap_words, l_stride;
+    int32_t *cand;            // [units][l_stride] recalled ids, ascending
+    uint32_t *crow;           // [units][l_stride] their physical rows
+    int32_t *ncand;           // [units] L
+    int32_t *out_ncand;       // optional copy for the caller
+    float *z;                 // [units][l_stride][G]
+    uint32_t *m_key;          // [units][G] ordered-key running max (atomicMax)
+    uint32_t *ghist;          // [units][kBuckets] key histogram, cleared here for keyhist
+    float scale;
+};
+
+template <typename T, int G> __global__ __launch_bounds__(256) void recall_score_kernel(RecallScoreArgs a)
+{
+    constexpr int R = 8, TILE = 16 * R;
+    __shared__ uint32_t s_ids[kRecallWpb * 32];   // ids of this block's range, then their rows
+    __shared__ int32_t s_page[256];               // block-table entries of the range's pages
+    __shared__ uint32_t s_tmp[8], s_bef[4];
+    __shared__ uint32_t s_max[G];
+    const int ul = blockIdx.y, b = ul / a.u.g, kv = ul - b * a.u.g;
+    const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4, ln = lane_id();
+    CTKVR_STAMP_BLK(6);
+    const int s_len = a.ctx_lens[b];
+    const int W = (s_len + 31) >> 5;
+    // the unit's own words split evenly over the blocks of its row (a short sequence of a ragged
+    // batch still uses all of them)
+    const int wpb = min(kRecallWpb, (W + (int)gridDim.x - 1) / (int)gridDim.x);
+    const int w_beg = blockIdx.x * wpb;
+    for (int w = blockIdx.x * 256 + tid; w < kBuckets; w += gridDim.x * 256) a.ghist[(size_t)ul * kBuckets + w] = 0u;
+    if (w_beg >= W) return;
+    const int w_end = min(W, w_beg + wpb);
+    const uint32_t *gb = a.gbits + (size_t)ul * a.bitmap_words;
+    // Requested together: this thread's byte of the range (four threads per word), the block-table
+    // entries of the pages the range covers, the queries, and the words before the range.
+    const uint32_t myword = ((tid >> 2) < w_end - w_beg) ? gb[w_beg + (tid >> 2)] : 0u;
+    const int page0 = (w_beg << 5) >> a.k.page_shift;
+    const int npages = ((min(w_end << 5, s_len) - 1) >> a.k.page_shift) - page0 + 1;   // ids stop at s_len - 1
+    const bool lds_pages = npages <= 256;
+    if (lds_pages && tid < npages) s_page[tid] = a.k.block_table[(size_t)b * a.k.max_pages + page0 + tid];
+    float q[G][8];
+    const T *qb = (const T *)a.q + ((size_t)b * a.u.h + kv * G) * kD;
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) unpack(load_chunk(qb + (size_t)hh * kD, lane16), q[hh]);
+    uint32_t before = 0;
+#pragma unroll 4
+    for (int w = tid; w < w_beg; w += 256) before += (uint32_t)__popc(gb[w]);
+    before = wave_sum_uniform(before);
+    if (tid < G) s_max[tid] = 0u;
+    if (ln == 0) s_bef[tid >> 6] = before;
+    const uint32_t mine = (myword >> ((tid & 3) << 3)) & 0xffu;
+    uint32_t n_blk;
+    uint32_t pos = block_excl_scan<256>((uint32_t)__popc(mine), s_tmp, &n_blk);   // barriers inside
+    const uint32_t base = s_bef[0] + s_bef[1] + s_bef[2] + s_bef[3];
+    if (w_end == W && tid == 0) {
+        a.ncand[ul] = (int32_t)(base + n_blk);
+        if (a.out_ncand) a.out_ncand[ul] = (int32_t)(base + n_blk);
+    }
+    CTKVR_STAMP_BLK(7);
+    if (n_blk == 0) return;
+    {
+        uint32_t m = mine;
+        const uint32_t id0 = ((uint32_t)(w_beg + (tid >> 2)) << 5) + ((uint32_t)(tid & 3) << 3);
+        while (m) {
+            const int bit = __ffs((int)m) - 1;
+            m &= m - 1u;
+            s_ids[pos++] = id0 + (uint32_t)bit;
+        }
+    }
+    __syncthreads();
+    int32_t *cd = a.cand + (size_t)ul * a.l_stride + base;
+    uint32_t *rw = a.crow + (size_t)ul * a.l_stride + base;
+    const int pmask = (1 << a.k.page_shift) - 1;
+    for (uint32_t i = tid; i < n_blk; i += 256) {
+        const int t = (int)s_ids[i];
+        uint32_t row;
+        if (lds_pages)
+            row = (uint32_t)((s_page[(t >> a.k.page_shift) - page0] * a.u.g + kv) << a.k.page_shift) + (uint32_t)(t & pmask);
+        else
+            row = row_of(a.k.block_table, a.k.max_pages, a.k.page_shift, a.u.g, b, kv, t);
+        cd[i] = t;
+        rw[i] = row;
+        s_ids[i] = row;   // each slot is read and rewritten by the same thread
+    }
+    __syncthreads();
+    CTKVR_STAMP_BLK(2);
+    const T *K = (const T *)a.k.pages;
+    float *zb = a.z + ((size_t)ul * a.l_stride + base) * G;
+    // lane l of a 16-lane group keeps head (l mod G): its score, and that head's running maximum
+    float mxl = -__builtin_huge_valf();
+    const int myh = lane16 & (G - 1);
+    const int last = (int)n_blk - 1;
+    for (int t0 = 0; t0 < (int)n_blk; t0 += TILE) {
+        Chunk<T> ck[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) ck[r] = load_chunk(K + (size_t)s_ids[min(t0 + r * 16 + grp, last)] * kD, lane16);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            float kx[8];
+            unpack(ck[r], kx);
+            float mine_z = 0.0f;
+#pragma unroll
+            for (int hh = 0; hh < G; ++hh) {
+                float tot = group16_sum(lane_partial(q[hh], kx));
+                if (hh == 0 || myh == hh) mine_z = tot;
+            }
+            mine_z = mine_z * a.scale;
+            const int i = t0 + r * 16 + grp;
+            if (i <= last) {
+                mxl = __builtin_amdgcn_fmed3f(mxl, mine_z, __builtin_huge_valf());   // max of two non-NaN values
+                if (lane16 < G) zb[(size_t)i * G + lane16] = mine_z;
+            }
+        }
+    }
+    {
+        float v = mxl;
+        v = __builtin_amdgcn_fmed3f(v, __shfl_xor(v, 16), __builtin_huge_valf());
+        v = __builtin_amdgcn_fmed3f(v, __shfl_xor(v, 32), __builtin_huge_valf());
+        if (lane_id() < G) atomicMax(&s_max[lane_id()], ordered_key(v));
+    }
+    __syncthreads();
+    if (tid < G) atomicMax(&a.m_key[ul * G + tid], s_max[tid]);
+    CTKVR_STAMP_BLK(3);
 }
 
 // ------------------------------------------------------------------------------
