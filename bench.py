@@ -300,7 +300,7 @@ def bench_decode(args, wl, steps, cpu_steps):
         "algorithmic_bytes_per_step": float(bytes_step.mean()),
         "L_recall_mean": float(L.mean()), "alpha": float(L.mean()) / (wl.n_probe * wl.list_len),
         "index_build_ms": build_ms, "stage_us": stage_us,
-        "roofline": {"kernel": "score_kernel", "bound": "hbm", "achieved": score_gbps, "peak": HBM_PEAK_GBPS,
+        "roofline": {"kernel": "recall_score_kernel", "bound": "hbm", "achieved": score_gbps, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": score_gbps / HBM_PEAK_GBPS, "traffic": traffic,
                      "bytes_per_launch": score_bytes, "avg_us": score_us, "avg_us_between_events": stage_us["score"],
                      "event_overhead_us": event_overhead},
