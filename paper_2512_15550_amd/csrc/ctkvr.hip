@@ -644,7 +644,7 @@ template <int G> int run_kmeans_g(ctkvr_index *ix, KmeansArgs ka, hipStream_t st
     kmeans_init_kernel<<<dim3(ix->c_max, ix->p.n_q_heads, ix->p.batch), 128, 0, st>>>(ka, G);
     for (int it = 0; it < ix->p.kmeans_iters; ++it) {
         kmeans_halfnorm_kernel<G><<<dim3((ix->c_max + 15) / 16, U), 256, 0, st>>>(ka);
-        kmeans_assign_kernel<G><<<dim3((ix->s_max + 127) / 128, U), 256, ix->c_max * 4, st>>>(ka);
+        kmeans_assign_kernel<G><<<dim3((ix->s_max + 255) / 256, U), 512, ix->c_max * 4, st>>>(ka);
         kmeans_offsets_kernel<<<dim3(U), 1024, 0, st>>>(ka);
         kmeans_scatter_kernel<<<dim3((ix->s_max + 255) / 256, U), 256, 0, st>>>(ka);
         kmeans_reduce_kernel<G><<<dim3(ix->c_max, U), 128, 0, st>>>(ka);

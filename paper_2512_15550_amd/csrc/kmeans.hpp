@@ -58,15 +58,14 @@ template <int G> __global__ __launch_bounds__(256) void kmeans_halfnorm_kernel(K
 }
 
 // assignment: argmax_c (x . mu_c - |mu_c|^2/2), ties to the lowest c.  A = 32 centres x 16 dims,
-// B = 16 dims x 32 points per v_mfma_f32_32x32x16_bf16.  A block owns 128 points, a wave 32 of
+// B = 16 dims x 32 points per v_mfma_f32_32x32x16_bf16.  A block owns 256 points, a wave 32 of
 // them with their B fragments resident in registers (G <= 4); the centres are walked 128 at a
 // time, and each 128-centre x 64-dim piece of the centre table goes through shared memory once
-// for the four waves (double-buffered: the next piece is in flight while the current one
-// feeds the matrix cores; rows padded to 144 bytes so that the 16-byte fragment reads of a
+// for the eight waves (double-buffered, requested two pieces ahead; rows padded to 144 bytes so that the 16-byte fragment reads of a
 // wave spread over the banks).  With G = 8 the fragments do not fit the registers and are
 // re-read from memory.  Counts the members of every centre as it goes.
-// grid (ceil(s_max/128), batch*g), 256 threads; dynamic shared memory: c_max floats.
-template <int G> __global__ __launch_bounds__(256) void kmeans_assign_kernel(KmeansArgs a)
+// grid (ceil(s_max/256), batch*g), 512 threads; dynamic shared memory: c_max floats.
+template <int G> __global__ __launch_bounds__(512) void kmeans_assign_kernel(KmeansArgs a)
 {
     extern __shared__ float s_hn[];
     constexpr int KS = 8 * G;                 // k-steps of 16 dims
@@ -75,10 +74,10 @@ template <int G> __global__ __launch_bounds__(256) void kmeans_assign_kernel(Kme
     __shared__ __align__(16) unsigned char s_a[2][128 * ROWB];
     const int ul = blockIdx.y, b = ul / a.g, kv = ul - b * a.g;
     const int C = a.n_cent[b], s = a.ctx_lens[b];
-    if ((int)blockIdx.x * 128 >= s) return;
+    if ((int)blockIdx.x * 256 >= s) return;
     const int tid = threadIdx.x, wv = tid >> 6, ln = tid & 63, col = ln & 31, half = ln >> 5;
-    for (int c = tid; c < C; c += 256) s_hn[c] = a.half_norm[(size_t)ul * a.c_max + c];
-    const int p0 = blockIdx.x * 128 + wv * 32;
+    for (int c = tid; c < C; c += 512) s_hn[c] = a.half_norm[(size_t)ul * a.c_max + c];
+    const int p0 = blockIdx.x * 256 + wv * 32;
     const int t = min(p0 + col, s - 1);
     const bf16_t *xrow = a.q + ((size_t)(a.first_row[b] + t) * a.h + kv * G) * kD + 8 * half;
     bf16x8_t bfrag[REG_B ? KS : 1];
@@ -86,32 +85,32 @@ template <int G> __global__ __launch_bounds__(256) void kmeans_assign_kernel(Kme
 #pragma unroll
         for (int kk = 0; kk < KS; ++kk) bfrag[kk] = *reinterpret_cast<const bf16x8_t *>(xrow + kk * 16);
     }
-    // staging: thread t moves half a row (64 bytes) of piece (c0, kc): centre c0 + t/2, head kc/2,
-    // dims 64*(kc%2) + 32*(t%2) ..
+    // staging: thread t moves a quarter row (32 bytes) of piece (c0, kc): centre c0 + t/4, head kc/2,
+    // dims 64*(kc%2) + 16*(t%4) ..
     constexpr int NKC = 2 * G;                // 64-dim pieces per 128-centre tile
-    const int srow = tid >> 1, shalf = tid & 1;
+    static_assert(NKC % 2 == 0, "piece parity must carry over from one centre tile to the next");
+    const int srow = tid >> 2, sq = tid & 3;
     const bf16_t *cbase = a.centroids + ((size_t)b * a.h + kv * G) * a.c_max * kD;
-    auto piece_src = [&](int c0, int kc) {
+    // two pieces ahead in registers: piece i+2 is requested while piece i feeds the matrix cores
+    // and piece i+1 waits to be written to the other buffer
+    uint4 stage[2][2];
+    auto fetch = [&](int set, int c0, int kc) {
         const int c = min(c0 + srow, C - 1);
-        return reinterpret_cast<const uint4 *>(cbase + ((size_t)(kc >> 1) * a.c_max + c) * kD + (kc & 1) * 64 + shalf * 32);
+        const uint4 *src = reinterpret_cast<const uint4 *>(cbase + ((size_t)(kc >> 1) * a.c_max + c) * kD + (kc & 1) * 64 + sq * 16);
+        stage[set][0] = src[0];
+        stage[set][1] = src[1];
     };
-    uint4 stage[4];
-    auto fetch = [&](int c0, int kc) {
-        const uint4 *src = piece_src(c0, kc);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) stage[q] = src[q];
-    };
-    auto put = [&](int buf) {
-        uint4 *dst = reinterpret_cast<uint4 *>(&s_a[buf][srow * ROWB + shalf * 64]);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) dst[q] = stage[q];
+    auto put = [&](int set, int buf) {
+        uint4 *dst = reinterpret_cast<uint4 *>(&s_a[buf][srow * ROWB + sq * 32]);
+        dst[0] = stage[set][0];
+        dst[1] = stage[set][1];
     };
     float best = -__builtin_huge_valf();
     int bi = 0;
-    fetch(0, 0);
-    put(0);
+    fetch(0, 0, 0);
+    fetch(1, 0, 1);
+    put(0, 0);
     __syncthreads();
-    int buf = 0;
     for (int c0 = 0; c0 < C; c0 += 128) {
         f32x16_t acc[4];
 #pragma unroll
@@ -120,9 +119,11 @@ template <int G> __global__ __launch_bounds__(256) void kmeans_assign_kernel(Kme
             for (int r = 0; r < 16; ++r) acc[ct][r] = 0.0f;
 #pragma unroll
         for (int kc = 0; kc < NKC; ++kc) {
-            // the next piece travels while this one is used
-            const bool more = (kc + 1 < NKC) || (c0 + 128 < C);
-            if (more) fetch(kc + 1 < NKC ? c0 : c0 + 128, kc + 1 < NKC ? kc + 1 : 0);
+            const int buf = kc & 1;
+            {   // piece i + 2
+                const int c2 = kc + 2 < NKC ? c0 : c0 + 128, k2 = kc + 2 < NKC ? kc + 2 : kc + 2 - NKC;
+                if (c2 < C) fetch(kc & 1, c2, k2);
+            }
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
                 bf16x8_t bf;
@@ -134,9 +135,8 @@ template <int G> __global__ __launch_bounds__(256) void kmeans_assign_kernel(Kme
                     acc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bf, acc[ct], 0, 0, 0);
                 }
             }
-            if (more) put(buf ^ 1);
+            if (kc + 1 < NKC || c0 + 128 < C) put((kc + 1) & 1, buf ^ 1);   // piece i + 1
             __syncthreads();
-            buf ^= 1;
         }
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct)
