@@ -53,7 +53,7 @@ def lib() -> ctypes.CDLL:
         L.ctkvr_oracle_log_fixed.restype = ctypes.c_double
         L.ctkvr_oracle_log_fixed.argtypes = [ctypes.c_uint64]
         L.ctkvr_oracle_build_lists.restype = None
-        L.ctkvr_oracle_build_lists.argtypes = [fp, fp, ci, ci, ci, ci, ci, ctypes.c_float, ip, ci, ip, fp]
+        L.ctkvr_oracle_build_lists.argtypes = [fp, fp, ci, ci, ci, ci, ci, ctypes.c_float, ip, ci, ci, ci, ip, fp]
         L.ctkvr_oracle_inv_norms.restype = None
         L.ctkvr_oracle_inv_norms.argtypes = [fp, ci, fp]
         L.ctkvr_oracle_recall.restype = None
@@ -124,15 +124,16 @@ def centroids_last_c(q_tail: np.ndarray, C: int) -> np.ndarray:
 
 
 def build_lists(K: np.ndarray, Qc: np.ndarray, rho: int, scale: Optional[float] = None,
-                pairs: Optional[np.ndarray] = None, return_keys: bool = False):
+                pairs: Optional[np.ndarray] = None, return_keys: bool = False, n_init: int = 0, n_local: int = 0):
     """Algorithm 1 lines 2-4.  K [g][s][d], Qc [h][C][d] -> lists int32.
     With ``pairs`` ([n][2] of (kv head, centroid)) only those lists are built,
-    returned as [n][rho]; otherwise [g][C][rho]."""
+    returned as [n][rho]; otherwise [g][C][rho].  The first n_init and last n_local keys
+    (the resident window of lines 5-6) are scored but never listed."""
     K = np.ascontiguousarray(K, np.float32)
     Qc = np.ascontiguousarray(Qc, np.float32)
     g, s, d = K.shape
     h, C, _ = Qc.shape
-    assert d == 128 and h % g == 0 and 1 <= rho <= s
+    assert d == 128 and h % g == 0 and n_init >= 0 and n_local >= 0 and 1 <= rho <= s - n_init - n_local
     scale = default_scale(d) if scale is None else np.float32(scale)
     if pairs is not None:
         pairs = np.ascontiguousarray(pairs, np.int32).reshape(-1, 2)
@@ -144,7 +145,7 @@ def build_lists(K: np.ndarray, Qc: np.ndarray, rho: int, scale: Optional[float] 
     lists = np.empty(shape, np.int32)
     keys = np.empty((n, s), np.float32) if return_keys else None
     lib().ctkvr_oracle_build_lists(_f(K), _f(Qc), h, g, s, C, rho, ctypes.c_float(scale), _i(pairs), n,
-                                   _i(lists), _f(keys) if keys is not None else None)
+                                   int(n_init), int(n_local), _i(lists), _f(keys) if keys is not None else None)
     return (lists, keys) if return_keys else lists
 
 
@@ -204,6 +205,52 @@ def decode_step(q, K, V, Qc, lists, n_probe, top_k, scale=None) -> DecodeResult:
     cand, ncand, rkey, sel, out, lse = rerank_attend(q, K, V, lists, probe, top_k, scale)
     return DecodeResult(cos_kv, probe, [cand[i, :ncand[i]].copy() for i in range(g)], ncand,
                         [rkey[i, :ncand[i]].copy() for i in range(g)], sel, out, lse)
+
+
+def window_attention(q, K, V, n_init: int, s_index: int, n_local: int, scale=None):
+    """Attention of every query head over the resident window (Algorithm 2 line 10): the first
+    n_init keys and the keys from s_index - n_local to the end of K (the local window grows with
+    the tokens decoded since the index was built).  fp64.  Returns (out [h][d], lse [h]);
+    an empty window gives zeros and -inf."""
+    q = np.asarray(q, np.float64)
+    g, s_cur, d = K.shape
+    h = q.shape[0]
+    G = h // g
+    scale = float(default_scale(d) if scale is None else scale)
+    rows = np.concatenate([np.arange(0, n_init), np.arange(s_index - n_local, s_cur)])
+    out = np.zeros((h, d), np.float64)
+    lse = np.full(h, -np.inf, np.float64)
+    if len(rows) == 0:
+        return out, lse
+    for head in range(h):
+        kv = head // G
+        z = (np.asarray(K[kv, rows], np.float64) @ q[head]) * scale
+        m = z.max()
+        e = np.exp(z - m)
+        out[head] = (e / e.sum()) @ np.asarray(V[kv, rows], np.float64)
+        lse[head] = m + np.log(e.sum())
+    return out, lse
+
+
+def merge_attention(out_a, lse_a, out_b, lse_b):
+    """Algorithm 2 line 11: two attention outputs over disjoint key sets combined into the
+    attention over their union, through their log-sum-exps."""
+    m = np.maximum(lse_a, lse_b)
+    m = np.where(np.isfinite(m), m, 0.0)
+    wa, wb = np.exp(lse_a - m), np.exp(lse_b - m)
+    den = wa + wb
+    out = (out_a * wa[:, None] + out_b * wb[:, None]) / den[:, None]
+    return out, m + np.log(den)
+
+
+def decode_step_window(q, K, V, Qc, lists, n_probe, top_k, s_index: int, n_init: int, n_local: int, scale=None) -> DecodeResult:
+    """Algorithm 2 lines 1-11 with a resident window: retrieval and sparse attention over the
+    s_index keys the index was built on (its lists hold no window keys), attention over the
+    window -- K and V may have grown beyond s_index by the decoded tokens -- and the merge."""
+    r = decode_step(q, K[:, :s_index], V[:, :s_index], Qc, lists, n_probe, top_k, scale)
+    out_w, lse_w = window_attention(q, K, V, n_init, s_index, n_local, scale)
+    r.out, r.lse = merge_attention(r.out, r.lse, out_w, lse_w)
+    return r
 
 
 def centroid_update(q, Qc, lists, res: DecodeResult, n_updates: int) -> int:

@@ -210,9 +210,13 @@ static void group_log_softmax_max(const float *q, int G, const float *Kg, const 
 /* K [g][s][D]; Qc [h][C][D] (line 1: the centroids, already sliced by the    */
 /* caller); pairs = n_pairs x (kv head, centroid) to build, or NULL for all   */
 /* g*C in order; lists_out [n_pairs][rho] ascending key ids.                  */
+/* n_init, n_local (lines 5-6): the first n_init and the last n_local keys    */
+/* stay resident with the attention and are left out of the lists; the scores */
+/* (line 2) are still a softmax over all s keys.                              */
 /* ------------------------------------------------------------------------- */
 void ctkvr_oracle_build_lists(const float *K, const float *Qc, int h, int g, int s, int C, int rho, float scale,
-                              const int32_t *pairs, int n_pairs, int32_t *lists_out, float *keys_out /* [n_pairs][s] or NULL */)
+                              const int32_t *pairs, int n_pairs, int n_init, int n_local, int32_t *lists_out,
+                              float *keys_out /* [n_pairs][s] or NULL */)
 {
     int G = h / g;
     if (!pairs) n_pairs = g * C;
@@ -226,8 +230,11 @@ void ctkvr_oracle_build_lists(const float *K, const float *Qc, int h, int g, int
             memcpy(q + (size_t)hh * D, Qc + ((size_t)(kv * G + hh) * C + j) * D, sizeof(float) * D);
         /* lines 2-3: A_kv[kv, j, :] */
         group_log_softmax_max(q, G, K + (size_t)kv * s * D, NULL, s, scale, key, NULL);
-        /* line 4: top-rho */
-        top_n_ids(key, NULL, s, rho, lists_out + (size_t)p * rho);
+        /* line 4: top-rho, among the keys that leave the resident window */
+        int32_t *lst = lists_out + (size_t)p * rho;
+        top_n_ids(key + n_init, NULL, s - n_init - n_local, rho, lst);
+        for (int r = 0; r < rho; ++r)
+            lst[r] += n_init;
         if (keys_out)
             memcpy(keys_out + (size_t)p * s, key, sizeof(float) * (size_t)s);
         free(q);
