@@ -108,6 +108,7 @@ def main():
     ap.add_argument("--cpu-steps", type=int, default=None, help="decode steps of the CPU oracle sample (0 = skip)")
     ap.add_argument("--dcu", action="store_true",
                     help="every timed step is followed by the dynamic centroid update (Algorithm 2 line 12)")
+    ap.add_argument("--window", default="", help="N_INIT,N_LOCAL: build and decode with a resident window (Algorithm 2 lines 10-11)")
     ap.add_argument("--skip-128k", action="store_true", help="cfg2 only: do not append the 128K workload's figures")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -167,8 +168,9 @@ def bench_decode(args, wl, steps, cpu_steps):
 
     torch.cuda.synchronize()
     t0 = time.time()
-    idx = ck.ctkvr_build_index(H.params_of(wl), db.q_prefill, db.cu_seqlens, True, db.k_pages, db.block_table,
-                               db.ctx_lens)
+    n_init, n_local = (int(x) for x in args.window.split(",")) if args.window else (0, 0)
+    idx = ck.ctkvr_build_index(H.params_of(wl, n_init=n_init, n_local=n_local), db.q_prefill, db.cu_seqlens, True,
+                               db.k_pages, db.block_table, db.ctx_lens)
     torch.cuda.synchronize()
     build_ms = (time.time() - t0) * 1e3
 
@@ -297,7 +299,8 @@ def bench_decode(args, wl, steps, cpu_steps):
         "config": {"workload": wl.name, "storage_dtype": wl.dtype, "batch": B, "q_heads": h, "kv_heads": g,
                    "ctx_lens": wl.ctx_lens if B <= 4 else [min(wl.ctx_lens), max(wl.ctx_lens)],
                    "centroids": wl.n_centroids or f"ctx/{wl.centroid_div}", "n_probe": wl.n_probe,
-                   "list_len": wl.list_len, "top_k": wl.top_k, "launch": mode, "centroid_update": bool(args.dcu)},
+                   "list_len": wl.list_len, "top_k": wl.top_k, "launch": mode, "centroid_update": bool(args.dcu),
+                   "window": [n_init, n_local]},
         "tokens_per_s": B / (dt / K), "tokens_per_s_32_layers": B / (dt / K) / 32,
         "achieved_GBps": achieved, "hbm_frac": achieved / HBM_PEAK_GBPS,
         "algorithmic_bytes_per_step": float(bytes_step.mean()),

@@ -76,7 +76,8 @@ typedef struct {
     int32_t centroid_mode;   /* ctkvr_centroid_mode */
     int32_t kmeans_iters;    /* Lloyd iterations when centroid_mode == KMEANS */
     int32_t build_algo;      /* ctkvr_build_algo */
-    int32_t reserved;
+    int32_t n_init;          /* L_init: the first n_init keys stay with the attention (Algorithm 1 lines 5-6) */
+    int32_t n_local;         /* L_local: so do the last n_local keys of the prompt; neither enters a list */
 } ctkvr_params;
 
 /*
@@ -93,10 +94,11 @@ typedef struct {
  *               queries seed the centres (e.g. from k-means++ run by the caller).
  * For every sequence, KV head and centroid j the list holds the rho keys with the
  * largest max over the group's query heads of softmax_t(c_{h,j} . k_t * sm_scale)
- * taken over all s keys (lines 2-4), ascending.
+ * taken over all s keys (lines 2-4), ascending; with n_init, n_local > 0 the rho keys are
+ * chosen among keys n_init .. s - n_local - 1 only (the scores are unchanged).
  * On success *out_index owns device memory until ctkvr_free.  The call
  * synchronises the stream before returning.
- * Errors: EINVAL for null/inconsistent arguments (C_i < n_probe, rho > s_i, ...);
+ * Errors: EINVAL for null/inconsistent arguments (C_i < n_probe, rho > s_i - n_init - n_local, ...);
  * EUNSUPPORTED for head_dim != 128, G not in {1,2,4,8}, MFMA build with f32 data.
  */
 int ctkvr_build_index(const ctkvr_params *p, const void *q_prefill, const int32_t *cu_seqlens, int32_t q_is_tail,
@@ -137,6 +139,25 @@ int ctkvr_index_load(const ctkvr_params *p, const int32_t *ctx_lens, const void 
 int ctkvr_decode_step(ctkvr_index *idx, const void *q, const void *k_pages, const void *v_pages,
                       const int32_t *block_table, int32_t max_pages, float *out, float *out_lse, int32_t *out_sel,
                       int32_t *out_ncand, int32_t *out_probe, void *hip_stream);
+
+/*
+ * The decode step with the resident window (Algorithm 2 lines 1-11; Section 3.2): as
+ * ctkvr_decode_step, and in addition every query head attends over the first n_init keys and
+ * over the keys from ctx_len_i - n_local to cur_lens[i] - 1, and the two attention outputs are
+ * merged through their log-sum-exps (line 11), which equals attention over the union.
+ *   cur_lens   DEVICE int32 [batch] or NULL: tokens of each sequence now in the KV cache,
+ *              cur_lens[i] >= ctx_len_i.  The tokens decoded since the index was built belong
+ *              to the local window; the caller appends their keys and values to the paged cache.
+ *              NULL means cur_lens[i] = ctx_len_i.  Values are clamped to
+ *              [ctx_len_i, max_pages * page_size].
+ * The lists of an index built with n_init, n_local > 0 hold no window key, so nothing is
+ * counted twice.  out_lse is the log-sum-exp over selected and window keys together.
+ * ctkvr_decode_step on such an index is this call with cur_lens = NULL.
+ * Errors: as ctkvr_decode_step.
+ */
+int ctkvr_decode_step_window(ctkvr_index *idx, const void *q, const void *k_pages, const void *v_pages,
+                             const int32_t *block_table, int32_t max_pages, const int32_t *cur_lens, float *out,
+                             float *out_lse, int32_t *out_sel, int32_t *out_ncand, int32_t *out_probe, void *hip_stream);
 
 /*
  * Dynamic centroid update (Algorithm 2 line 12; Section 3.1.2, "Dynamic Centroid Update"),

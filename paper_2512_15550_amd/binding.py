@@ -34,7 +34,7 @@ class _CParams(ctypes.Structure):
                 ("n_centroids", ctypes.c_int32), ("centroid_div", ctypes.c_int32), ("list_len", ctypes.c_int32),
                 ("n_probe", ctypes.c_int32), ("top_k", ctypes.c_int32), ("sm_scale", ctypes.c_float),
                 ("centroid_mode", ctypes.c_int32), ("kmeans_iters", ctypes.c_int32), ("build_algo", ctypes.c_int32),
-                ("reserved", ctypes.c_int32)]
+                ("n_init", ctypes.c_int32), ("n_local", ctypes.c_int32)]
 
 
 class _CInfo(ctypes.Structure):
@@ -61,18 +61,21 @@ class Params:
     centroid_mode: int = LAST_C
     kmeans_iters: int = 0
     build_algo: int = BUILD_EXACT
+    n_init: int = 0
+    n_local: int = 0
 
     def c(self) -> _CParams:
         return _CParams(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.page_size, self.dtype,
                         self.n_centroids, self.centroid_div, self.list_len, self.n_probe, self.top_k,
-                        float(self.sm_scale), self.centroid_mode, self.kmeans_iters, self.build_algo, 0)
+                        float(self.sm_scale), self.centroid_mode, self.kmeans_iters, self.build_algo, self.n_init,
+                        self.n_local)
 
 
 _lib = None
 
 EXPORTS = ["ctkvr_build_index", "ctkvr_index_load", "ctkvr_decode_step", "ctkvr_free", "ctkvr_last_error",
            "ctkvr_index_info", "ctkvr_index_lists", "ctkvr_index_centroids", "ctkvr_index_last_candidates",
-           "ctkvr_profile_enable", "ctkvr_profile_collect", "ctkvr_centroid_update"]
+           "ctkvr_profile_enable", "ctkvr_profile_collect", "ctkvr_centroid_update", "ctkvr_decode_step_window"]
 N_STAGES = 9
 STAGE_NAMES = ["centroid_cos", "recall_gather", "score", "denom", "keyhist", "classify",
                "rerank_select", "sparse_attn", "null"]
@@ -100,6 +103,8 @@ def load_library() -> ctypes.CDLL:
     L.ctkvr_index_load.argtypes = [ctypes.POINTER(_CParams), ip, vp, ip, vp, ctypes.POINTER(ctypes.c_void_p)]
     L.ctkvr_decode_step.restype = ctypes.c_int
     L.ctkvr_decode_step.argtypes = [vp, vp, vp, vp, ip, ctypes.c_int32, fp, fp, ip, ip, ip, vp]
+    L.ctkvr_decode_step_window.restype = ctypes.c_int
+    L.ctkvr_decode_step_window.argtypes = [vp, vp, vp, vp, ip, ctypes.c_int32, ip, fp, fp, ip, ip, ip, vp]
     L.ctkvr_centroid_update.restype = ctypes.c_int
     L.ctkvr_centroid_update.argtypes = [vp, vp, vp]
     L.ctkvr_free.restype = None
@@ -208,6 +213,20 @@ def ctkvr_decode_step(idx: Index, q, k_pages, v_pages, block_table, out, out_lse
                              _dev(block_table, torch.int32), int(block_table.shape[1]), _dev(out, torch.float32),
                              _dev(out_lse, torch.float32), _dev(out_sel, torch.int32), _dev(out_ncand, torch.int32),
                              _dev(out_probe, torch.int32), _stream())
+    _check(rc)
+
+
+def ctkvr_decode_step_window(idx: Index, q, k_pages, v_pages, block_table, cur_lens, out, out_lse=None, out_sel=None,
+                             out_ncand=None, out_probe=None) -> None:
+    """cur_lens: device int32 [batch] (tokens now in the cache) or None."""
+    import torch
+    L = load_library()
+    td = _torch_dtype(idx.params.dtype)
+    rc = L.ctkvr_decode_step_window(idx.handle, _dev(q, td), _dev(k_pages, td), _dev(v_pages, td),
+                                    _dev(block_table, torch.int32), int(block_table.shape[1]),
+                                    _dev(cur_lens, torch.int32), _dev(out, torch.float32), _dev(out_lse, torch.float32),
+                                    _dev(out_sel, torch.int32), _dev(out_ncand, torch.int32),
+                                    _dev(out_probe, torch.int32), _stream())
     _check(rc)
 
 

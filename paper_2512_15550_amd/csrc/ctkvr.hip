@@ -70,6 +70,7 @@ struct ctkvr_index {
     bool have_step = false;
     unsigned long long *S = nullptr;
     float *z = nullptr, *zsel = nullptr;
+    float *win = nullptr;   // window_attn_kernel's partial results
     uint32_t *m_key = nullptr;
     size_t recall_lds = 0, select_lds = 0, attn_lds = 0, build_select_lds = 0;
     size_t fused_lds = 0;   // non-zero: selection and attention run as one launch (select_attn_kernel)
@@ -132,6 +133,7 @@ int check_params(const ctkvr_params *p, const int32_t *ctx_lens)
     if (p->build_algo != CTKVR_BUILD_EXACT && p->build_algo != CTKVR_BUILD_MFMA)
         return fail(CTKVR_EINVAL, "unknown build_algo %d", p->build_algo);
     if (!(p->sm_scale >= 0.0f)) return fail(CTKVR_EINVAL, "sm_scale must be >= 0");
+    if (p->n_init < 0 || p->n_local < 0) return fail(CTKVR_EINVAL, "n_init and n_local must be >= 0");
     for (int b = 0; b < p->batch; ++b) {
         int s = ctx_lens[b];
         if (s < 1 || s > (1 << 20)) return fail(s < 1 ? CTKVR_EINVAL : CTKVR_EUNSUPPORTED, "ctx_lens[%d] = %d outside 1..2^20", b, s);
@@ -139,7 +141,9 @@ int check_params(const ctkvr_params *p, const int32_t *ctx_lens)
         if (C < 1 || C > s) return fail(CTKVR_EINVAL, "sequence %d: %d centroids for %d tokens", b, C, s);
         if (C > 8192) return fail(CTKVR_EUNSUPPORTED, "sequence %d: %d centroids > 8192", b, C);
         if (p->n_probe > C) return fail(CTKVR_EINVAL, "sequence %d: n_probe %d > centroids %d", b, p->n_probe, C);
-        if (p->list_len > s) return fail(CTKVR_EINVAL, "sequence %d: list_len %d > ctx_len %d", b, p->list_len, s);
+        if (p->list_len > s - p->n_init - p->n_local)
+            return fail(CTKVR_EINVAL, "sequence %d: list_len %d > %d keys outside the resident window", b, p->list_len,
+                        s - p->n_init - p->n_local);
     }
     return CTKVR_OK;
 }
@@ -192,6 +196,7 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
     A(&ix->gcur, U * 4);
     A(&ix->ginfo, U * 16);
     A(&ix->d_dcu_count, 4);
+    A(&ix->win, U * (size_t)kWinSplit * ix->G * (2 + 128) * 4);
     if (p->list_len != p->top_k) {
         A(&ix->dsel, U * (size_t)p->list_len * 4);
         A(&ix->dnsel, U * 4);
@@ -412,6 +417,8 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
         ka.S = S;
         ka.kbuf = kbuf;
         ka.ghist = ghist;
+        ka.n_init = ix->p.n_init;
+        ka.n_local = ix->p.n_local;
         keyhist_kernel<G><<<dim3(std::min((ix->s_max + 4095) / 4096, 8), nu), 1024, 0, st>>>(ka);
         SelectArgs se{};
         se.u = u;
@@ -454,11 +461,27 @@ int build_lists_dispatch(ctkvr_index *ix, const void *k_pages, const int32_t *bt
 
 template <typename T, int G>
 int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const void *v_pages, const int32_t *bt,
-                  int max_pages, float *out, float *out_lse, int32_t *out_sel, int32_t *out_ncand, int32_t *out_probe,
-                  hipStream_t st)
+                  int max_pages, const int32_t *cur_lens, float *out, float *out_lse, int32_t *out_sel, int32_t *out_ncand,
+                  int32_t *out_probe, hipStream_t st)
 {
     const ctkvr_params &p = ix->p;
     const int U = ix->units;
+    // lines 10-11 first: the window's share depends on q, K and V only
+    const bool window = p.n_init + p.n_local > 0 || cur_lens;
+    if (window) {
+        WindowArgs wa{};
+        wa.u = decode_units(ix);
+        wa.q = q;
+        wa.k = Paged{k_pages, bt, max_pages, ix->page_shift};
+        wa.v_pages = v_pages;
+        wa.ctx_lens = ix->d_ctx_lens;
+        wa.cur_lens = cur_lens;
+        wa.n_init = p.n_init;
+        wa.n_local = p.n_local;
+        wa.scale = ix->scale;
+        wa.win = ix->win;
+        window_attn_kernel<T, G><<<dim3(kWinSplit, U), 256, 0, st>>>(wa);
+    }
     CosArgs ca{};
     ca.q = q;
     ca.centroids = ix->centroids;
@@ -603,6 +626,7 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     aa.zsel = ix->zsel;
     aa.out = out;
     aa.out_lse = out_lse;
+    aa.win = window ? ix->win : nullptr;
     if (ix->fused_lds) {
         ix->mark(7, st);   // no separate selection launch: its stage reads as the cost of an event pair
         select_attn_kernel<T, G><<<dim3(4 * U), 1024, ix->fused_lds, st>>>(se, aa);
@@ -623,14 +647,14 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
 }
 
 template <typename T>
-int decode_dispatch(ctkvr_index *ix, const void *q, const void *k, const void *v, const int32_t *bt, int mp, float *out,
-                    float *lse, int32_t *sel, int32_t *ncand, int32_t *probe, hipStream_t st)
+int decode_dispatch(ctkvr_index *ix, const void *q, const void *k, const void *v, const int32_t *bt, int mp,
+                    const int32_t *cur, float *out, float *lse, int32_t *sel, int32_t *ncand, int32_t *probe, hipStream_t st)
 {
     switch (ix->G) {
-        case 1: return decode_launch<T, 1>(ix, q, k, v, bt, mp, out, lse, sel, ncand, probe, st);
-        case 2: return decode_launch<T, 2>(ix, q, k, v, bt, mp, out, lse, sel, ncand, probe, st);
-        case 4: return decode_launch<T, 4>(ix, q, k, v, bt, mp, out, lse, sel, ncand, probe, st);
-        default: return decode_launch<T, 8>(ix, q, k, v, bt, mp, out, lse, sel, ncand, probe, st);
+        case 1: return decode_launch<T, 1>(ix, q, k, v, bt, mp, cur, out, lse, sel, ncand, probe, st);
+        case 2: return decode_launch<T, 2>(ix, q, k, v, bt, mp, cur, out, lse, sel, ncand, probe, st);
+        case 4: return decode_launch<T, 4>(ix, q, k, v, bt, mp, cur, out, lse, sel, ncand, probe, st);
+        default: return decode_launch<T, 8>(ix, q, k, v, bt, mp, cur, out, lse, sel, ncand, probe, st);
     }
 }
 
@@ -901,9 +925,9 @@ int ctkvr_index_load(const ctkvr_params *p, const int32_t *ctx_lens, const void 
     return CTKVR_OK;
 }
 
-int ctkvr_decode_step(ctkvr_index *idx, const void *q, const void *k_pages, const void *v_pages,
-                      const int32_t *block_table, int32_t max_pages, float *out, float *out_lse, int32_t *out_sel,
-                      int32_t *out_ncand, int32_t *out_probe, void *hip_stream)
+int ctkvr_decode_step_window(ctkvr_index *idx, const void *q, const void *k_pages, const void *v_pages,
+                             const int32_t *block_table, int32_t max_pages, const int32_t *cur_lens, float *out,
+                             float *out_lse, int32_t *out_sel, int32_t *out_ncand, int32_t *out_probe, void *hip_stream)
 {
     if (!idx) return fail(CTKVR_EINVAL, "index is NULL");
     if (!q || !k_pages || !v_pages || !block_table || !out) return fail(CTKVR_EINVAL, "a required pointer is NULL");
@@ -911,10 +935,18 @@ int ctkvr_decode_step(ctkvr_index *idx, const void *q, const void *k_pages, cons
         return fail(CTKVR_EINVAL, "max_pages %d < %d pages of the longest sequence", max_pages, min_pages_needed(idx));
     hipStream_t st = (hipStream_t)hip_stream;
     if (idx->p.dtype == CTKVR_BF16)
-        return decode_dispatch<bf16_t>(idx, q, k_pages, v_pages, block_table, max_pages, out, out_lse, out_sel, out_ncand,
-                                       out_probe, st);
-    return decode_dispatch<float>(idx, q, k_pages, v_pages, block_table, max_pages, out, out_lse, out_sel, out_ncand,
-                                  out_probe, st);
+        return decode_dispatch<bf16_t>(idx, q, k_pages, v_pages, block_table, max_pages, cur_lens, out, out_lse, out_sel,
+                                       out_ncand, out_probe, st);
+    return decode_dispatch<float>(idx, q, k_pages, v_pages, block_table, max_pages, cur_lens, out, out_lse, out_sel,
+                                  out_ncand, out_probe, st);
+}
+
+int ctkvr_decode_step(ctkvr_index *idx, const void *q, const void *k_pages, const void *v_pages,
+                      const int32_t *block_table, int32_t max_pages, float *out, float *out_lse, int32_t *out_sel,
+                      int32_t *out_ncand, int32_t *out_probe, void *hip_stream)
+{
+    return ctkvr_decode_step_window(idx, q, k_pages, v_pages, block_table, max_pages, nullptr, out, out_lse, out_sel,
+                                    out_ncand, out_probe, hip_stream);
 }
 
 int ctkvr_centroid_update(ctkvr_index *idx, const void *q, void *hip_stream)

@@ -707,6 +707,7 @@ struct KeyArgs {
     uint32_t *kbuf;     // [units][l_stride]
     uint32_t *ghist;    // [units][kBuckets], zero on entry
     uint32_t *gcur;     // decode only: [units] list cursors of classify_kernel, cleared here
+    int n_init, n_local;   // build only: ids below n_init or from L - n_local on are never listed
 };
 
 template <int G> __global__ __launch_bounds__(1024) void keyhist_kernel(KeyArgs a)
@@ -741,6 +742,8 @@ template <int G> __global__ __launch_bounds__(1024) void keyhist_kernel(KeyArgs 
 #pragma unroll
                 for (int hh = 0; hh < G; ++hh) best = fmaxf(best, (zv[hh] - m[hh]) - ls[hh]);
                 uint32_t ok = ordered_key(best);
+                // keys of the resident window rank below every other key (the image of -inf)
+                if (i < a.n_init || i >= L - a.n_local) ok = 0x007fffffu;
                 kb[i] = ok;
                 atomicAdd(&s_h[key_bucket(ok)], 1u);
             }
@@ -1015,7 +1018,209 @@ struct AttnArgs {
     const float *zsel;
     float *out;  // [batch*h][128]
     float *out_lse;
+    const float *win;   // optional: window_attn_kernel's partial results, [units][kWinSplit][G][2 + 128]
 };
+
+// ------------------------------------------------------------------------------
+// Algorithm 2 lines 10-11: attention over the resident window -- the first n_init keys and the
+// keys from s - n_local to the current end of the cache (the tokens decoded since the index was
+// built join the local window) -- and its merge with the sparse attention.
+// window_attn_kernel: block x of a unit takes every kWinSplit-th run of 64 window rows and leaves
+// a partial result relative to its own maximum: m[G], l[G] = sum of exp(z - m), o[G][128] = sum of
+// exp(z - m) v.  Online softmax over runs of 64 rows (one row per 16-lane group and pass, four
+// passes).  It depends on q, K and V only, so it is the first launch of a step.
+// grid (kWinSplit, units), 256 threads.
+// ------------------------------------------------------------------------------
+constexpr int kWinSplit = 8;
+
+struct WindowArgs {
+    Units u;
+    const void *q;            // [batch][h][128]
+    Paged k;
+    const void *v_pages;
+    const int32_t *ctx_lens;  // [batch] s: the prefix the index was built on
+    const int32_t *cur_lens;  // optional [batch]: tokens in the cache now (>= s)
+    int n_init, n_local;
+    float scale;
+    float *win;               // [units][kWinSplit][G][2 + 128]
+};
+
+template <typename T, int G> __global__ __launch_bounds__(256) void window_attn_kernel(WindowArgs a)
+{
+    __shared__ float s_z[64][G];
+    __shared__ float s_part[4][G][kD];
+    __shared__ float s_ml[G];
+    const int ul = blockIdx.y, b = ul / a.u.g, kv = ul - b * a.u.g;
+    const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4;
+    const int s = a.ctx_lens[b];
+    int cur = a.cur_lens ? a.cur_lens[b] : s;
+    cur = max(s, min(cur, a.k.max_pages << a.k.page_shift));
+    const int ni = min(a.n_init, s), nl = min(a.n_local, s - ni);
+    const int n_w = ni + nl + (cur - s);
+    auto id_of = [&](int r) { return r < ni ? r : s - nl + (r - ni); };
+    float q[G][8];
+    const T *qb = (const T *)a.q + ((size_t)b * a.u.h + kv * G) * kD;
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) unpack(load_chunk(qb + (size_t)hh * kD, lane16), q[hh]);
+    const T *K = (const T *)a.k.pages;
+    const T *V = (const T *)a.v_pages;
+    float m_run[G], l_run[G], acc[G][8];
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+        m_run[hh] = -__builtin_huge_valf();
+        l_run[hh] = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[hh][e] = 0.0f;
+    }
+    for (int r0 = blockIdx.x * 64; r0 < n_w; r0 += kWinSplit * 64) {
+        const int nr = min(64, n_w - r0);
+        uint32_t row[4];
+        Chunk<T> ck[4], cv[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int r = min(p * 16 + grp, nr - 1);
+            row[p] = row_of(a.k.block_table, a.k.max_pages, a.k.page_shift, a.u.g, b, kv, id_of(r0 + r));
+        }
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            ck[p] = load_chunk(K + (size_t)row[p] * kD, lane16);
+            cv[p] = load_chunk(V + (size_t)row[p] * kD, lane16);
+        }
+        __syncthreads();   // the previous run's s_z and s_ml have been read
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            float kx[8];
+            unpack(ck[p], kx);
+#pragma unroll
+            for (int hh = 0; hh < G; ++hh) {
+                float tot = group16_sum(lane_partial(q[hh], kx)) * a.scale;
+                if (lane16 == hh) s_z[p * 16 + grp][hh] = tot;
+            }
+        }
+        __syncthreads();
+        if (tid < 64) {   // the run's maximum per head (one row per lane of the first wave)
+#pragma unroll
+            for (int hh = 0; hh < G; ++hh) {
+                float mx = tid < nr ? s_z[tid][hh] : -__builtin_huge_valf();
+#pragma unroll
+                for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+                if (tid == 0) s_ml[hh] = mx;
+            }
+        }
+        __syncthreads();
+        float corr[G];
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh) {
+            const float m_new = fmaxf(m_run[hh], s_ml[hh]);   // the same in every thread
+            corr[hh] = __expf(m_run[hh] - m_new);          // exp(-inf) = 0 on the first run
+            m_run[hh] = m_new;
+            l_run[hh] *= corr[hh];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[hh][e] *= corr[hh];
+        }
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int r = p * 16 + grp;
+            if (r < nr) {
+                float vx[8];
+                unpack(cv[p], vx);
+#pragma unroll
+                for (int hh = 0; hh < G; ++hh) {
+                    const float pr = __expf(s_z[r][hh] - m_run[hh]);
+                    if (lane16 == 0) l_run[hh] += pr;   // lane 0 of each group carries the group's share of l
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[hh][e] = __fmaf_rn(pr, vx[e], acc[hh][e]);
+                }
+            }
+        }
+    }
+    // the 16 groups hold partial sums over their rows, all relative to the same running maximum:
+    // first the four groups of a wave (lanes l, l+16, l+32, l+48), then the four waves
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float v = acc[hh][e];
+            v += __shfl_xor(v, 16);
+            v += __shfl_xor(v, 32);
+            acc[hh][e] = v;
+        }
+        float l = l_run[hh];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        l_run[hh] = l;
+    }
+    __syncthreads();
+    const int wv = tid >> 6;
+    if ((tid & 63) < 16) {
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s_part[wv][hh][lane16 * 8 + e] = acc[hh][e];
+        }
+        if (lane16 == 0) {
+#pragma unroll
+            for (int hh = 0; hh < G; ++hh) s_z[wv][hh] = l_run[hh];
+        }
+    }
+    __syncthreads();
+    float *dst = a.win + ((size_t)ul * kWinSplit + blockIdx.x) * G * (2 + kD);
+    for (int i = tid; i < G * kD; i += 256) {
+        const int hh = i >> 7, e = i & 127;
+        dst[hh * (2 + kD) + 2 + e] = (s_part[0][hh][e] + s_part[1][hh][e]) + (s_part[2][hh][e] + s_part[3][hh][e]);
+    }
+    if (tid < G) {
+        dst[tid * (2 + kD)] = m_run[tid];
+        dst[tid * (2 + kD) + 1] = (s_z[0][tid] + s_z[1][tid]) + (s_z[2][tid] + s_z[3][tid]);
+    }
+}
+
+// out element `dim` of head hh of a unit: the sparse part (v = sum of exp(z - m_s) * value, l_s = sum of
+// exp(z - m_s); l_s = 0 for an empty part) merged with the window's partial results, if there are any.
+template <int G>
+__device__ __forceinline__ float merge_window(const float *win, int ul, int hh, int dim, float v, float m_s, float l_s, float &lse)
+{
+    // all partial results are requested at once (no load depends on another)
+    float mx[kWinSplit], lx[kWinSplit], ox[kWinSplit];
+#pragma unroll
+    for (int x = 0; x < kWinSplit; ++x) {
+        mx[x] = -__builtin_huge_valf();
+        lx[x] = 0.0f;
+        ox[x] = 0.0f;
+    }
+    if (win) {
+        const float *wp = win + (size_t)ul * kWinSplit * G * (2 + kD) + hh * (2 + kD);
+#pragma unroll
+        for (int x = 0; x < kWinSplit; ++x) {
+            mx[x] = wp[x * G * (2 + kD)];
+            lx[x] = wp[x * G * (2 + kD) + 1];
+            ox[x] = wp[x * G * (2 + kD) + 2 + dim];
+        }
+    }
+    float M = l_s > 0.0f ? m_s : -__builtin_huge_valf();
+#pragma unroll
+    for (int x = 0; x < kWinSplit; ++x)
+        if (lx[x] > 0.0f) M = fmaxf(M, mx[x]);
+    if (M == -__builtin_huge_valf()) {   // nothing to attend over at all: defined output
+        lse = -__builtin_huge_valf();
+        return 0.0f;
+    }
+    float num = 0.0f, den = 0.0f;
+    if (l_s > 0.0f) {
+        const float w = __expf(m_s - M);
+        num = v * w;
+        den = l_s * w;
+    }
+#pragma unroll
+    for (int x = 0; x < kWinSplit; ++x)
+        if (lx[x] > 0.0f) {
+            const float w = __expf(mx[x] - M);
+            num += ox[x] * w;
+            den += lx[x] * w;
+        }
+    lse = M + __logf(den);
+    return num / den;
+}
 
 // Block id -> (unit, slice).  Workgroups go to the 8 XCDs round-robin by linear id; the four slices
 // of a unit read the same 128-byte lines, so they get ids that are congruent modulo 8: one XCD, one L2.
@@ -1056,12 +1261,14 @@ __device__ __forceinline__ void attend_unit(const AttnArgs &a, int ul, int slice
         cv[u] = load_chunk(V + (size_t)row * kD, 0);
     }
     const int nsel = nsel_of();
-    if (nsel == 0) {   // nothing recalled: defined output
+    if (nsel == 0) {   // nothing recalled: the window alone, or zeros
         if (tid < G * 32) {
             int hh = tid >> 5, e = tid & 31;
-            a.out[((size_t)b * a.h + kv * G + hh) * kD + slice * 32 + e] = 0.0f;
+            float lse;
+            const float o = merge_window<G>(a.win, ul, hh, slice * 32 + e, 0.0f, -__builtin_huge_valf(), 0.0f, lse);
+            a.out[((size_t)b * a.h + kv * G + hh) * kD + slice * 32 + e] = o;
+            if (slice == 0 && e == 0 && a.out_lse) a.out_lse[(size_t)b * a.h + kv * G + hh] = lse;
         }
-        if (slice == 0 && a.out_lse && tid < G) a.out_lse[(size_t)b * a.h + kv * G + tid] = -__builtin_huge_valf();
         return;
     }
     // softmax statistics over the selected keys, per head
@@ -1169,9 +1376,11 @@ __device__ __forceinline__ void attend_unit(const AttnArgs &a, int ul, int slice
         float v = 0.0f;
 #pragma unroll
         for (int w = 0; w < 16; ++w) v += s_o[w][hh][e];
-        a.out[((size_t)b * a.h + kv * G + hh) * kD + slice * 32 + e] = v / s_l[hh];
+        float lse;
+        const float o = merge_window<G>(a.win, ul, hh, slice * 32 + e, v, s_m[hh], s_l[hh], lse);
+        a.out[((size_t)b * a.h + kv * G + hh) * kD + slice * 32 + e] = o;
+        if (slice == 0 && e == 0 && a.out_lse) a.out_lse[(size_t)b * a.h + kv * G + hh] = lse;
     }
-    if (slice == 0 && a.out_lse && tid < G) a.out_lse[(size_t)b * a.h + kv * G + tid] = s_m[tid] + __logf(s_l[tid]);
     CTKVR_STAMP(47);
     CTKVR_STAMP_BLK(5);
 }

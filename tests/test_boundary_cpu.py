@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_params_struct_matches_header_layout():
-    assert ctypes.sizeof(binding._CParams) == 16 * 4
+    assert ctypes.sizeof(binding._CParams) == 17 * 4
     assert ctypes.sizeof(binding._CInfo) == 10 * 4 + 2 * 8
 
 
