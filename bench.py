@@ -109,6 +109,10 @@ def main():
     ap.add_argument("--dcu", action="store_true",
                     help="every timed step is followed by the dynamic centroid update (Algorithm 2 line 12)")
     ap.add_argument("--window", default="", help="N_INIT,N_LOCAL: build and decode with a resident window (Algorithm 2 lines 10-11)")
+    ap.add_argument("--sweep", default="", choices=["", "cprime", "c"],
+                    help="step time against the number of probed centroids C' or of centroids C, around the paper's own "
+                         "operating point (32K, C = 2048, C' = 4, rho = 2.5 rho' = 2560) -- the shape of its Figure on "
+                         "time against C and C'")
     ap.add_argument("--skip-128k", action="store_true", help="cfg2 only: do not append the 128K workload's figures")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -135,6 +139,21 @@ def main():
 
     ck.load_library()
     torch.cuda.set_device(0)
+    if args.sweep:
+        import dataclasses
+        base = workload("paper_llama")
+        values = [1, 2, 4, 8, 16, 32] if args.sweep == "cprime" else [256, 512, 1024, 2048, 4096]
+        points = []
+        for v in values:
+            wl = dataclasses.replace(base, n_probe=v) if args.sweep == "cprime" else dataclasses.replace(base, n_centroids=v)
+            r = bench_decode(args, wl, args.steps if args.steps is not None else 64, 0)
+            points.append({"C": wl.n_centroids, "n_probe": wl.n_probe, "us_per_step": r["value"], "L_recall_mean": r["L_recall_mean"],
+                           "alpha": r["alpha"], "achieved_GBps": r["achieved_GBps"], "stage_us": r["stage_us"]})
+        print(json.dumps({"metric": "decode retrieval+sparse-attn us/step against " + ("C'" if args.sweep == "cprime" else "C"),
+                          "unit": "us/step", "n_gpus": 1, "data": "synthetic", "higher_is_better": False,
+                          "config": {"workload": "paper_llama", "ctx_len": 32768, "list_len": base.list_len, "top_k": base.top_k},
+                          "points": points}))
+        return
     wl = workload(args.workload)
     if wl.n_decode == 0:
         return bench_build(args, wl)

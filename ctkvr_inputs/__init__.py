@@ -231,7 +231,7 @@ def _ragged_lengths(seed: int, n: int, lo: int, hi: int) -> List[int]:
 
 
 def workload(name: str) -> Workload:
-    """The five named configurations (list length rho = top_k in all of them)."""
+    """The five benchmark configurations (list length rho = top_k in all of them) and the paper's operating point."""
     if name == "cfg1":   # tiny fp32, GQA 8/2
         return Workload("cfg1", "f32", 8, 2, 128, [4096], [1], 64, 0, 8, 256, 256, 4)
     if name == "cfg2":   # Llama-3-8B-shaped layer, 32K
@@ -245,6 +245,12 @@ def workload(name: str) -> Workload:
                         page_seed=4)
     if name == "cfg5":   # index build only, 128K
         return Workload("cfg5", "bf16", 32, 8, 128, [131072], [5], 2048, 0, 64, 2048, 2048, 0, page_seed=5)
+    # The paper's own operating point (experimental setup of the evaluation section): C = min(2048, s/16),
+    # C' = 4, rho = 2.5 rho', rho' in {512, 1024}; Llama-3-8B (32/8 heads) and Yi-9B (32/4 heads) shapes.
+    if name == "paper_llama":
+        return Workload("paper_llama", "bf16", 32, 8, 128, [32768], [61], 2048, 0, 4, 2560, 1024, 64, page_seed=61)
+    if name == "paper_yi":
+        return Workload("paper_yi", "bf16", 32, 4, 128, [32768], [62], 2048, 0, 4, 1280, 512, 64, page_seed=62)
     raise KeyError(name)
 
 

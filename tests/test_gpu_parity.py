@@ -182,6 +182,16 @@ def test_cfg4_ragged_batch16_sampled(ck):
     _full_size(ck, "cfg4", steps=[0, 3], n_decode=4)
 
 
+def test_paper_operating_point_llama_shape_sampled(ck):
+    """C = 2048, C' = 4, rho = 2.5 rho' = 2560, rho' = 1024 at 32K (the evaluation section's set-up), 32/8 heads."""
+    _full_size(ck, "paper_llama", steps=[0, 3], n_decode=4)
+
+
+def test_paper_operating_point_yi_shape_sampled(ck):
+    """The same operating point with rho' = 512 on the 32/4-head shape (G = 8)."""
+    _full_size(ck, "paper_yi", steps=[0, 3], n_decode=4)
+
+
 # --------------------------------------------------------------------------- #
 # matrix-core list build (Algorithm 1 lines 2-4 with the dot products on MFMA)
 # --------------------------------------------------------------------------- #
