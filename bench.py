@@ -111,8 +111,8 @@ def main():
     ap.add_argument("--window", default="", help="N_INIT,N_LOCAL: build and decode with a resident window (Algorithm 2 lines 10-11)")
     ap.add_argument("--sweep", default="", choices=["", "cprime", "c"],
                     help="step time against the number of probed centroids C' or of centroids C, around the paper's own "
-                         "operating point (32K, C = 2048, C' = 4, rho = 2.5 rho' = 2560) -- the shape of its Figure on "
-                         "time against C and C'")
+                         "operating point (32K, C = 2048, C' = 4, rho = 2.5 rho' = 2560), as in its appendix tables of "
+                         "throughput against C and against C'")
     ap.add_argument("--skip-128k", action="store_true", help="cfg2 only: do not append the 128K workload's figures")
     args = ap.parse_args()
     if args.gpus != 1:
