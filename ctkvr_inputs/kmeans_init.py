@@ -43,3 +43,23 @@ def kmeanspp_for_sequence(q_full: np.ndarray, g: int, C: int, seed: int) -> np.n
     G = h // g
     X = q_full.reshape(s, g, G * d)
     return np.stack([kmeanspp_positions(np.ascontiguousarray(X[:, kv, :]), C, seed * 131 + kv) for kv in range(g)])
+
+
+def centroid_positions(mode: str, s: int, C: int, g: int, seed: int = 0) -> np.ndarray:
+    """Prompt positions [g][C] of the queries kept as centroids under the four placements the
+    paper compares (ablation on the position of the maintained centroids): "final" = the last C
+    (the method's own choice, Algorithm 1 line 1), "init" = the first C, "equi" = evenly spaced,
+    "random" = C distinct positions drawn with Philox(seed), sorted.  The same positions for
+    every KV head."""
+    if mode == "final":
+        pos = np.arange(s - C, s)
+    elif mode == "init":
+        pos = np.arange(C)
+    elif mode == "equi":
+        pos = (np.arange(C, dtype=np.int64) * s) // C + (s // C) // 2
+    elif mode == "random":
+        rng = np.random.Generator(np.random.Philox(np.random.SeedSequence([int(seed), 23, s, C])))
+        pos = np.sort(rng.choice(s, size=C, replace=False))
+    else:
+        raise KeyError(mode)
+    return np.broadcast_to(pos.astype(np.int32), (g, C)).copy()

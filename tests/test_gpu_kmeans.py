@@ -91,6 +91,29 @@ def test_zero_iterations_is_the_start_positions(ck):
     ck.ctkvr_free(idx)
 
 
+@pytest.mark.parametrize("mode", ["final", "init", "equi", "random"])
+def test_centroid_position_modes_build_and_decode_like_the_oracle(ck, mode):
+    """The paper's ablation on where the C kept queries sit (final / random / init / equi): zero
+    Lloyd iterations from the chosen positions.  "final" must reproduce the default build."""
+    from ctkvr_inputs.kmeans_init import centroid_positions
+    s, h, g, C = 1200, 8, 2, 20
+    wl = small_workload("pos_" + mode, "bf16", h, g, (s,), (720,), C, 0, 4, 64, 40, 2)
+    bt = gen_batch(wl, full_walk=True)
+    sq = bt.seqs[0]
+    pos = centroid_positions(mode, s, C, g, seed=9)
+    assert pos.shape == (g, C) and pos.min() >= 0 and pos.max() < s and np.all(np.diff(pos, axis=1) > 0)
+    G = h // g
+    Qc = np.stack([sq.q_full[pos[head // G], head] for head in range(h)])      # [h][C][d]
+    lists = oracle.build_lists(sq.K, Qc, wl.list_len)
+    idx, db, cen = _gpu_kmeans(ck, bt, pos[None], 0)
+    assert np.array_equal(cen[0], Qc)
+    assert np.array_equal(ck.ctkvr_index_lists(idx)[0], lists)
+    if mode == "final":
+        assert np.array_equal(Qc, oracle.centroids_last_c(sq.q_tail, C))
+    H.run_decode_parity(bt, H.OracleIndex([Qc], [lists]), idx, db)
+    ck.ctkvr_free(idx)
+
+
 def test_gaussian_inputs_inertia_tracks_the_oracle_and_never_increases(ck):
     wl = small_workload("km_gauss", "bf16", 8, 2, (3000, 1700), (720, 721), 0, 50, 4, 96, 64, 1)
     bt = gen_batch(wl, full_walk=True)
