@@ -48,7 +48,7 @@ size_t elem_size(int dtype) { return dtype == CTKVR_BF16 ? 2 : 4; }
 
 struct ctkvr_index {
     ctkvr_params p{};
-    int G = 0, c_max = 0, s_max = 0, l_stride = 0, page_shift = 0, nsplit = 0, units = 0;
+    int G = 0, c_max = 0, s_max = 0, l_stride = 0, page_shift = 0, units = 0;
     float scale = 0.f;
     std::vector<int32_t> ctx_lens, n_cent;
     std::vector<void *> allocs;
@@ -169,7 +169,6 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
         long lm = std::min<long>(s, (long)p->n_probe * p->list_len);
         ix->l_stride = std::max<long>(ix->l_stride, lm);
     }
-    ix->nsplit = (p->top_k + 63) / 64;
     const size_t es = elem_size(p->dtype);
     const size_t U = ix->units;
     int rc = CTKVR_OK;

@@ -191,7 +191,7 @@ template <typename T, int G> __global__ __launch_bounds__(256) void centroid_cos
 // recall_gather: every block of a unit finds the same top-C' centroids (keys in
 // registers, C <= 256*KPT, bisection on the key), takes every gridDim.x-th probed list, ORs its ids into a bitmap in shared memory and then
 // ORs the non-empty words into the unit's bitmap in global memory (integer ORs: any
-// order gives the same bitmap).  grid (nsplit, batch*g), 256 threads; dynamic shared
+// order gives the same bitmap).  grid (blocks per unit, batch*g), 256 threads; dynamic shared
 // memory: kSelLds + n_probe + bitmap words.
 // ------------------------------------------------------------------------------
 struct GatherArgs {
