@@ -47,6 +47,7 @@ def _build_rc(p, ctx):
     (dict(head_dim=64), -4), (dict(n_q_heads=6, n_kv_heads=2), -4), (dict(n_q_heads=7), -1),
     (dict(n_probe=9), -1), (dict(list_len=5000), -1), (dict(top_k=0), -1), (dict(page_size=12), -4),
     (dict(dtype=7), -1), (dict(n_centroids=0, centroid_div=0), -1), (dict(sm_scale=-1.0), -1),
+    (dict(n_init=-1), -1), (dict(n_init=2000, n_local=2040), -1),   # the window leaves fewer than list_len keys
 ])
 def test_bad_parameters_are_rejected_on_the_host(change, code):
     base = dict(batch=1, n_q_heads=8, n_kv_heads=2, n_centroids=8, list_len=64, n_probe=4, top_k=32)
@@ -62,3 +63,17 @@ def test_null_arguments():
     assert "NULL" in ck.ctkvr_last_error()
     lib.ctkvr_free(None)   # allowed
     assert lib.ctkvr_index_info(None, None) == -1
+
+
+def test_new_entry_points_reject_null_arguments():
+    lib = ck.load_library()
+    assert lib.ctkvr_decode_step_window(None, None, None, None, None, 0, None, None, None, None, None, None, None) == -1
+    assert lib.ctkvr_centroid_update(None, None, None) == -1
+    assert "NULL" in ck.ctkvr_last_error()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr
