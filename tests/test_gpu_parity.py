@@ -53,6 +53,50 @@ def test_decode_matches_oracle_on_shared_index(ck, case):
     ck.ctkvr_free(idx)
 
 
+EDGE = [
+    # name, dtype, h, g, ctx_lens, C, C', rho, rho'
+    ("s33_one_pick", "bf16", 2, 1, (33,), 2, 1, 5, 1),
+    ("single_head", "f32", 1, 1, (64,), 3, 2, 9, 4),
+    ("every_query_a_centroid", "bf16", 4, 2, (100,), 100, 7, 10, 10),
+    ("list_is_everything", "bf16", 8, 2, (257,), 4, 1, 257, 100),
+    ("tiny_and_long", "bf16", 8, 2, (17, 4097), 5, 2, 16, 12),
+]
+
+
+@pytest.mark.parametrize("case", EDGE, ids=[c[0] for c in EDGE])
+def test_edge_shapes(ck, case):
+    name, dtype, h, g, lens, C, n_probe, rho, top_k = case
+    wl = small_workload(name, dtype, h, g, lens, tuple(range(260, 260 + len(lens))), C, 0, n_probe, rho, top_k, 2)
+    bt = gen_batch(wl)
+    oi = H.oracle_index(bt)
+    db = H.device_batch(bt)
+    idx = ck.ctkvr_build_index(H.params_of(wl), db.q_prefill, db.cu_seqlens, True, db.k_pages, db.block_table,
+                               db.ctx_lens)
+    for b in range(wl.batch):
+        assert np.array_equal(ck.ctkvr_index_lists(idx)[b], oi.lists[b])
+    st = H.run_decode_parity(bt, oi, idx, db)
+    _say(f"[edge {name}] ok {st}")
+    ck.ctkvr_free(idx)
+
+
+@pytest.mark.parametrize("page_size", [1, 4, 64, 256])
+def test_other_page_sizes(ck, page_size):
+    """The KV layout is a parameter: pages of 1 token (every row its own block-table entry), of a
+    few tokens, and pages larger than a 32-id bitmap word."""
+    wl = small_workload(f"page{page_size}", "bf16", 8, 2, (2300, 999), (250, 251), 20, 0, 4, 100, 64, 2,
+                        page_size=page_size)
+    bt = gen_batch(wl)
+    oi = H.oracle_index(bt)
+    db = H.device_batch(bt)
+    idx = ck.ctkvr_build_index(H.params_of(wl), db.q_prefill, db.cu_seqlens, True, db.k_pages, db.block_table,
+                               db.ctx_lens)
+    for b in range(wl.batch):
+        assert np.array_equal(ck.ctkvr_index_lists(idx)[b], oi.lists[b])
+    st = H.run_decode_parity(bt, oi, idx, db)
+    _say(f"[page {page_size}] ok {st}")
+    ck.ctkvr_free(idx)
+
+
 @pytest.mark.parametrize("case", SMALL[:5], ids=[c[0] for c in SMALL[:5]])
 def test_exact_build_matches_oracle_lists(ck, case):
     name, dtype, h, g, lens, C, div, n_probe, rho, top_k = case
