@@ -333,15 +333,15 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
     const size_t per_unit = (size_t)ix->s_max * G * 4;
     int chunk = (int)std::min<size_t>(total_units, std::max<size_t>(1, ((size_t)2 << 30) / per_unit));
     chunk = std::min(chunk, 16384);
-    if (mfma) {   // whole (sequence, KV head) groups per chunk, up to 8 GiB of scores
-        int nbk = (int)std::max<size_t>(1, ((size_t)8 << 30) / (per_unit * ix->c_max));
+    if (mfma) {   // whole (sequence, KV head) groups per chunk; no scores are stored, only 4-byte keys
+        int nbk = (int)std::max<size_t>(1, ((size_t)8 << 30) / ((size_t)ix->s_max * 4 * ix->c_max));
         nbk = std::min(nbk, std::max(1, 16384 / ix->c_max));
         chunk = std::min(ix->units, nbk) * ix->c_max;
     }
     float *z = nullptr;
     uint32_t *m_key = nullptr;
     unsigned long long *S = nullptr;
-    HIP_TRY(hipMalloc((void **)&z, (size_t)chunk * per_unit));
+    if (!mfma) HIP_TRY(hipMalloc((void **)&z, (size_t)chunk * per_unit));
     hipError_t e1 = hipMalloc((void **)&m_key, (size_t)chunk * G * 4);
     hipError_t e2 = hipMalloc((void **)&S, (size_t)chunk * G * 8);
     uint32_t *kbuf = nullptr, *ghist = nullptr;
@@ -387,31 +387,39 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
                 ma.centroids = (const bf16_t *)ix->centroids;
                 ma.k = sa.k;
                 ma.l_stride = ix->s_max;
-                ma.z = z;
                 ma.m_key = m_key;
+                ma.S = S;
+                ma.kbuf = kbuf;
+                ma.n_init = ix->p.n_init;
+                ma.n_local = ix->p.n_local;
                 ma.scale = ix->scale;
-                mfma_score_kernel<G><<<dim3(ma.t_splits, tiles), 256, 0, st>>>(ma);
+                // three passes over the same tiles: maxima, denominators, keys (nothing but the keys is stored)
+                mfma_score_kernel<G, MFMA_MAX><<<dim3(ma.t_splits, tiles), 256, 0, st>>>(ma);
+                mfma_score_kernel<G, MFMA_SUM><<<dim3(ma.t_splits, tiles), 256, 0, st>>>(ma);
+                mfma_score_kernel<G, MFMA_KEY><<<dim3(ma.t_splits, tiles), 256, 0, st>>>(ma);
             } else {
                 score_kernel<T, G, 16><<<dim3((ix->s_max + 255) / 256, nu), 256, 0, st>>>(sa);
             }
         } else {
             score_kernel<T, G, 16><<<dim3((ix->s_max + 255) / 256, nu), 256, 0, st>>>(sa);
         }
-        DenomArgs da{};
-        da.u = u;
-        da.ctx_lens = ix->d_ctx_lens;
-        da.ncand = nullptr;
-        da.l_stride = ix->s_max;
-        da.z = z;
-        da.m_key = m_key;
-        da.S = S;
-        denom_kernel<G><<<dim3(std::min((ix->s_max + 1023) / 1024, 64), nu), 256, 0, st>>>(da);
+        if (!mfma) {
+            DenomArgs da{};
+            da.u = u;
+            da.ctx_lens = ix->d_ctx_lens;
+            da.ncand = nullptr;
+            da.l_stride = ix->s_max;
+            da.z = z;
+            da.m_key = m_key;
+            da.S = S;
+            denom_kernel<G><<<dim3(std::min((ix->s_max + 1023) / 1024, 64), nu), 256, 0, st>>>(da);
+        }
         KeyArgs ka{};
         ka.u = u;
         ka.ctx_lens = ix->d_ctx_lens;
         ka.ncand = nullptr;
         ka.l_stride = ix->s_max;
-        ka.z = z;
+        ka.z = mfma ? nullptr : z;   // the matrix-core passes have written the keys: histogram only
         ka.m_key = m_key;
         ka.S = S;
         ka.kbuf = kbuf;

@@ -540,17 +540,26 @@ struct MfmaScoreArgs {
     const bf16_t *centroids;   // [batch][h][c_max][128]
     Paged k;
     int l_stride;              // s_max
-    float *z;                  // [chunk units][l_stride][G]
-    uint32_t *m_key;           // [chunk units][G]
+    uint32_t *m_key;           // [chunk units][G]   pass MAX writes, passes SUM and KEY read
+    unsigned long long *S;     // [chunk units][G]   pass SUM adds, pass KEY reads
+    uint32_t *kbuf;            // [chunk units][l_stride] ranking keys, pass KEY
+    int n_init, n_local;       // keys of the resident window get the lowest ranking key
     float scale;
 };
 
-template <int G> __global__ __launch_bounds__(256) void mfma_score_kernel(MfmaScoreArgs a)
+// The scores are never stored: the contraction is repeated in three passes over the same tiles,
+// each with its own epilogue -- MFMA_MAX: running maximum per (centroid, head); MFMA_SUM: the
+// integer softmax denominators (exactly denom_kernel's arithmetic on exactly the same scores, the
+// matrix cores being deterministic); MFMA_KEY: ranking keys max_h ((z - m_h) - log S_h), written as
+// ordered uint32 (4 bytes per (centroid, key) instead of 4 G bytes of scores read twice).
+enum { MFMA_MAX = 0, MFMA_SUM = 1, MFMA_KEY = 2 };
+
+template <int G, int MODE> __global__ __launch_bounds__(256) void mfma_score_kernel(MfmaScoreArgs a)
 {
     constexpr int MT = 8 / G;        // 32-centroid sub-tiles per block
     constexpr int CT = 32 * MT;      // centroids per block
-    __shared__ float s_z[CT * 32 * G];
-    __shared__ uint32_t s_row[32];
+    __shared__ float s_z[MODE == MFMA_KEY ? CT * 32 * G : 1];
+    __shared__ __align__(16) unsigned char s_k[2][32 * 272];
     const int tid = threadIdx.x, wv = tid >> 6, ln = tid & 63;
     const int col = ln & 31, half = ln >> 5;
     const int bkl = blockIdx.y / a.tiles_per_bk, jt = blockIdx.y - bkl * a.tiles_per_bk;
@@ -575,21 +584,50 @@ template <int G> __global__ __launch_bounds__(256) void mfma_score_kernel(MfmaSc
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) afrag[q][ks] = *reinterpret_cast<const bf16x8_t *>(row + ks * 16 + 8 * half);
     }
-    float mx[2][16];
+    // per accumulator register r of work item q: the tile row it holds, that row's statistics
+    float mx[2][16];                       // MAX: running maximum; SUM, KEY: the final maximum m
+    float lsv[MODE == MFMA_KEY ? 2 : 1][16];          // KEY: log S
+    unsigned long long sum[MODE == MFMA_SUM ? 2 : 1][16];
 #pragma unroll
     for (int q = 0; q < 2; ++q)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) mx[q][r] = -__builtin_huge_valf();
+        for (int r = 0; r < 16; ++r) {
+            const int jj = mt[q] * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+            const size_t stat = ((size_t)bkl * a.c_max + min(j0 + jj, C - 1)) * G + hh[q];
+            if constexpr (MODE == MFMA_MAX) {
+                mx[q][r] = -__builtin_huge_valf();
+            } else {
+                mx[q][r] = ordered_value(a.m_key[stat]);
+                if constexpr (MODE == MFMA_SUM) sum[q][r] = 0ull;
+                if constexpr (MODE == MFMA_KEY) lsv[q][r] = (float)log_fixed40(a.S[stat]);
+            }
+        }
+    // The 32 key rows of a step (8 KB) go through shared memory once for the four waves, in two
+    // buffers; a step's rows are requested two steps ahead and their block-table entries four
+    // steps ahead, so that neither latency is waited for.  Rows beyond the block's range are
+    // clamped to valid ones and their results dropped.
     const bf16_t *K = (const bf16_t *)a.k.pages;
-    float *zb = a.z + (size_t)bkl * a.c_max * a.l_stride * G;
-    for (int t0 = tbeg; t0 < tend; t0 += 32) {
-        __syncthreads();
-        if (tid < 32) s_row[tid] = row_of(a.k.block_table, a.k.max_pages, a.k.page_shift, a.g, b, kv, min(t0 + tid, s - 1));
-        __syncthreads();
+    constexpr int ROWB = 272;   // bytes per staged key row (256 + padding: fragment reads spread over the banks)
+    const int srow = tid >> 3, spart = tid & 7;
+    auto row_at = [&](int t0) {
+        return row_of(a.k.block_table, a.k.max_pages, a.k.page_shift, a.g, b, kv, min(t0 + srow, s - 1));
+    };
+    uint4 stage[2][2];
+    auto fetch = [&](int set, uint32_t row) {
+        const uint4 *src = reinterpret_cast<const uint4 *>(K + (size_t)row * kD + spart * 16);
+        stage[set][0] = src[0];
+        stage[set][1] = src[1];
+    };
+    auto put = [&](int set, int buf) {
+        uint4 *dst = reinterpret_cast<uint4 *>(&s_k[buf][srow * ROWB + spart * 32]);
+        dst[0] = stage[set][0];
+        dst[1] = stage[set][1];
+    };
+    auto compute = [&](int buf, int t0) {
         bf16x8_t bfrag[8];
-        const bf16_t *krow = K + (size_t)s_row[col] * kD + 8 * half;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) bfrag[ks] = *reinterpret_cast<const bf16x8_t *>(krow + ks * 16);
+        for (int ks = 0; ks < 8; ++ks)
+            bfrag[ks] = *reinterpret_cast<const bf16x8_t *>(&s_k[buf][col * ROWB + ks * 32 + half * 16]);
         const bool tok = (t0 + col) < tend;
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
@@ -600,34 +638,74 @@ template <int G> __global__ __launch_bounds__(256) void mfma_score_kernel(MfmaSc
             for (int ks = 0; ks < 8; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[q][ks], bfrag[ks], acc, 0, 0, 0);
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                int i = 8 * (r >> 2) + 4 * half + (r & 3);   // row of the 32x32 tile held in acc[r]
-                int jj = mt[q] * 32 + i;
-                float v = acc[r] * a.scale;
-                if (tok && (j0 + jj) < C) mx[q][r] = fmaxf(mx[q][r], v);
-                s_z[(jj * 32 + col) * G + hh[q]] = v;
+                const int jj = mt[q] * 32 + 8 * (r >> 2) + 4 * half + (r & 3);   // row of the 32x32 tile held in acc[r]
+                const float v = acc[r] * a.scale;
+                const bool live = tok && (j0 + jj) < C;
+                if constexpr (MODE == MFMA_MAX) {
+                    if (live) mx[q][r] = fmaxf(mx[q][r], v);
+                } else if constexpr (MODE == MFMA_SUM) {
+                    if (live) sum[q][r] += to_fixed40(exp_series(v - mx[q][r]));
+                } else {
+                    s_z[(jj * 32 + col) * G + hh[q]] = (v - mx[q][r]) - lsv[q][r];
+                }
             }
         }
-        __syncthreads();
-        for (int p = tid; p < CT * 32; p += 256) {
-            int n = p & 31, jj = p >> 5;
-            if ((j0 + jj) < C && (t0 + n) < tend) {
-                float zv[G];
+        if constexpr (MODE == MFMA_KEY) {
+            __syncthreads();
+            if (t0 < tend) {
+                for (int p = tid; p < CT * 32; p += 256) {
+                    const int n = p & 31, jj = p >> 5;
+                    const int t = t0 + n;
+                    if ((j0 + jj) < C && t < tend) {
+                        float best = -__builtin_huge_valf();
 #pragma unroll
-                for (int c = 0; c < G; ++c) zv[c] = s_z[p * G + c];
-                store_z<G>(zb + (size_t)(j0 + jj) * a.l_stride * G, t0 + n, zv);
+                        for (int c = 0; c < G; ++c) best = fmaxf(best, s_z[p * G + c]);
+                        uint32_t ok = ordered_key(best);
+                        if (t < a.n_init || t >= s - a.n_local) ok = 0x007fffffu;   // the image of -inf
+                        a.kbuf[((size_t)bkl * a.c_max + j0 + jj) * a.l_stride + t] = ok;
+                    }
+                }
             }
         }
+    };
+    uint32_t row_a = row_at(tbeg + 64), row_b = row_at(tbeg + 96);   // rows of steps 2 and 3
+    fetch(0, row_at(tbeg));
+    fetch(1, row_at(tbeg + 32));
+    put(0, 0);
+    __syncthreads();
+    // two steps per trip, so that register sets and buffers are named at compile time
+    for (int t0 = tbeg; t0 < tend; t0 += 64) {
+        // step i (buffer 0): request step i+2 into set 0, the entry of step i+4; write step i+1 to buffer 1
+        fetch(0, row_a);
+        row_a = row_at(t0 + 128);
+        compute(0, t0);
+        put(1, 1);
+        __syncthreads();
+        // step i+1 (buffer 1): request step i+3 into set 1, the entry of step i+5; write step i+2 to buffer 0
+        fetch(1, row_b);
+        row_b = row_at(t0 + 160);
+        compute(1, t0 + 32);
+        put(0, 0);
+        __syncthreads();
     }
+    if constexpr (MODE == MFMA_KEY) return;
 #pragma unroll
     for (int q = 0; q < 2; ++q)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            float v = mx[q][r];
+            const int jj = mt[q] * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+            const size_t stat = ((size_t)bkl * a.c_max + j0 + jj) * G + hh[q];
+            if constexpr (MODE == MFMA_MAX) {
+                float v = mx[q][r];
 #pragma unroll
-            for (int o = 16; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-            int i = 8 * (r >> 2) + 4 * half + (r & 3);
-            int jj = mt[q] * 32 + i;
-            if (col == 0 && (j0 + jj) < C) atomicMax(&a.m_key[((size_t)bkl * a.c_max + j0 + jj) * G + hh[q]], ordered_key(v));
+                for (int o = 16; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+                if (col == 0 && (j0 + jj) < C) atomicMax(&a.m_key[stat], ordered_key(v));
+            } else {
+                unsigned long long v = sum[q][r];
+#pragma unroll
+                for (int o = 16; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+                if (col == 0 && (j0 + jj) < C && v) atomicAdd(&a.S[stat], v);
+            }
         }
 }
 
@@ -701,7 +779,7 @@ struct KeyArgs {
     Units u;
     const int32_t *ctx_lens, *ncand;   // ncand == nullptr => L = ctx_len
     int l_stride;
-    const float *z;
+    const float *z;     // nullptr: kbuf holds the keys already, only their histogram is taken
     const uint32_t *m_key;
     const unsigned long long *S;
     uint32_t *kbuf;     // [units][l_stride]
@@ -722,10 +800,10 @@ template <int G> __global__ __launch_bounds__(1024) void keyhist_kernel(KeyArgs 
     __shared__ float s_ls[G];
     const int tid = threadIdx.x;
     for (int w = tid; w < kBuckets; w += 1024) s_h[w] = 0u;
-    if (tid < G) s_ls[tid] = (float)log_fixed40(a.S[ul * G + tid]);
+    if (tid < G) s_ls[tid] = a.z ? (float)log_fixed40(a.S[ul * G + tid]) : 0.0f;
     float m[G], ls[G];
 #pragma unroll
-    for (int hh = 0; hh < G; ++hh) m[hh] = ordered_value(a.m_key[ul * G + hh]);
+    for (int hh = 0; hh < G; ++hh) m[hh] = a.z ? ordered_value(a.m_key[ul * G + hh]) : 0.0f;
     __syncthreads();
 #pragma unroll
     for (int hh = 0; hh < G; ++hh) ls[hh] = s_ls[hh];
@@ -736,15 +814,20 @@ template <int G> __global__ __launch_bounds__(1024) void keyhist_kernel(KeyArgs 
         for (int q = 0; q < 4; ++q) {
             int i = c0 + q * 1024 + tid;
             if (i < L) {
-                float zv[G];
-                load_z<G>(zb, i, zv);
-                float best = -__builtin_huge_valf();
+                uint32_t ok;
+                if (a.z) {
+                    float zv[G];
+                    load_z<G>(zb, i, zv);
+                    float best = -__builtin_huge_valf();
 #pragma unroll
-                for (int hh = 0; hh < G; ++hh) best = fmaxf(best, (zv[hh] - m[hh]) - ls[hh]);
-                uint32_t ok = ordered_key(best);
-                // keys of the resident window rank below every other key (the image of -inf)
-                if (i < a.n_init || i >= L - a.n_local) ok = 0x007fffffu;
-                kb[i] = ok;
+                    for (int hh = 0; hh < G; ++hh) best = fmaxf(best, (zv[hh] - m[hh]) - ls[hh]);
+                    ok = ordered_key(best);
+                    // keys of the resident window rank below every other key (the image of -inf)
+                    if (i < a.n_init || i >= L - a.n_local) ok = 0x007fffffu;
+                    kb[i] = ok;
+                } else {   // the keys are there already (matrix-core build): histogram only
+                    ok = kb[i];
+                }
                 atomicAdd(&s_h[key_bucket(ok)], 1u);
             }
         }
