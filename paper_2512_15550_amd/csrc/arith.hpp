@@ -528,7 +528,7 @@ __device__ __forceinline__ void block_resolve_emit(uint32_t nb, uint32_t rem, in
     }
 }
 
-// Same contract as block_select_topk, for keys that are images of log-probabilities (<= 0) and
+// Same contract as block_select_topk, for keys keys[0..n) that are images of log-probabilities (<= 0) and
 // come with a histogram `ghist` (kBuckets counts) over key_bucket(), built beforehand by a
 // chip-wide kernel.  One scan of the histogram names the bucket that holds the k-th key; then ONE
 // pass over the keys writes a bitmap of the ids in higher buckets (ballots, no atomics) and
@@ -540,8 +540,8 @@ __device__ __forceinline__ void block_resolve_emit(uint32_t nb, uint32_t rem, in
 // Returns -1 to every thread, with nothing emitted, when the deciding bucket holds more than
 // kListCap keys (many equal keys, or keys below the histogram's range): the caller then takes
 // block_select_topk.
-template <int NT, typename KeyFn, typename EmitFn>
-__device__ int block_select_hist(KeyFn key, int n, int k, EmitFn emit, uint32_t *s_hist, uint32_t *s_bits,
+template <int NT, typename EmitFn>
+__device__ int block_select_hist(const uint32_t *keys, int n, int k, EmitFn emit, uint32_t *s_hist, uint32_t *s_bits,
                                  uint32_t *s_list, const uint32_t *ghist)
 {
     constexpr int NW = NT / 64;
@@ -554,18 +554,30 @@ __device__ int block_select_hist(KeyFn key, int n, int k, EmitFn emit, uint32_t 
         for (int i = tid; i < n; i += NT) emit(i, i);
         return n;
     }
-    // wave w owns the contiguous ids [beg, end), lane-strided inside; the first CH keys of every
-    // thread are requested before the histogram is looked at, so that both latencies overlap
-    const int per = ((n + NW - 1) / NW + 63) & ~63;
+    // Wave w owns the contiguous ids [beg, end) in groups of 256: slot c of lane l holds the four
+    // ids beg + 256 c + 4 l .. + 3, one 16-byte load (one CU sustains few requests in flight, so
+    // they should be wide).  The first CH slots of every thread are requested before the histogram
+    // is looked at, so that both latencies overlap.
+    const int per = ((n + NW - 1) / NW + 255) & ~255;
     const int beg = wv * per;
     const int end = min(n, beg + per);
-    constexpr int CH = 32;
-    uint32_t kk[CH];
+    constexpr int CH = 8;
+    const bool wide = (reinterpret_cast<uintptr_t>(keys) & 15u) == 0;
+    auto load4 = [&](int i) {
+        uint4 v;
+        if (wide && i + 3 < end) {
+            v = *reinterpret_cast<const uint4 *>(keys + i);
+        } else {
+            v.x = i < end ? keys[i] : 0u;
+            v.y = i + 1 < end ? keys[i + 1] : 0u;
+            v.z = i + 2 < end ? keys[i + 2] : 0u;
+            v.w = i + 3 < end ? keys[i + 3] : 0u;
+        }
+        return v;
+    };
+    uint4 kv[CH];
 #pragma unroll
-    for (int c = 0; c < CH; ++c) {
-        int i = beg + c * 64 + ln;
-        kk[c] = (i < end) ? key(i) : 0u;
-    }
+    for (int c = 0; c < CH; ++c) kv[c] = load4(beg + 256 * c + 4 * ln);
     CTKVR_STAMP(32);
     // the bucket of the k-th key, and how many of its keys are still wanted
     {
@@ -599,40 +611,52 @@ __device__ int block_select_hist(KeyFn key, int n, int k, EmitFn emit, uint32_t 
     CTKVR_STAMP(33);
     const int nw64 = (n + 63) >> 6;
     uint32_t *s_gt = s_bits, *s_eq = s_bits + 2 * nw64;
+    unsigned char *b_gt = reinterpret_cast<unsigned char *>(s_gt), *b_eq = reinterpret_cast<unsigned char *>(s_eq);
     uint2 *l_ent = reinterpret_cast<uint2 *>(s_list);
-    // the one pass over the keys
+    // The one pass over the keys.  A lane's four verdicts are a nibble; neighbouring lanes pair
+    // theirs into the byte of the bitmap that covers their eight ids (even lanes store it, odd lanes
+    // clear the same byte of the second bitmap).
     const uint64_t below = (1ull << ln) - 1ull;
-    for (int base = beg; base < end; base += 64 * CH) {
+    for (int base = beg; base < end; base += 256 * CH) {
         if (base != beg) {
 #pragma unroll
-            for (int c = 0; c < CH; ++c) {
-                int i = base + c * 64 + ln;
-                kk[c] = (i < end) ? key(i) : 0u;
-            }
+            for (int c = 0; c < CH; ++c) kv[c] = load4(base + 256 * c + 4 * ln);
         }
 #pragma unroll
         for (int c = 0; c < CH; ++c) {
-            const int i0 = base + c * 64;
+            const int i0 = base + 256 * c;
             if (i0 < end) {
-                const int i = i0 + ln;
-                const bool valid = i < end;
-                const uint32_t bk = key_bucket(kk[c]);
-                const bool inb = valid && bk == bkt;
-                const uint64_t above = __ballot(valid && bk < bkt);
-                const uint64_t listed = __ballot(inb);
-                if (ln == 0) {
-                    s_gt[2 * (i0 >> 6)] = (uint32_t)above;
-                    s_gt[2 * (i0 >> 6) + 1] = (uint32_t)(above >> 32);
+                const int i = i0 + 4 * ln;
+                const uint32_t k4[4] = {kv[c].x, kv[c].y, kv[c].z, kv[c].w};
+                uint32_t nib = 0;
+                bool inb[4], any_inb = false;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const bool valid = i + e < end;
+                    const uint32_t bk = key_bucket(k4[e]);
+                    nib |= (uint32_t)(valid && bk < bkt) << e;
+                    inb[e] = valid && bk == bkt;
+                    any_inb |= inb[e];
                 }
-                if (ln == 1) {
-                    s_eq[2 * (i0 >> 6)] = 0u;
-                    s_eq[2 * (i0 >> 6) + 1] = 0u;
+                const uint32_t other = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)nib, 0xB1, 0xF, 0xF, false);   // neighbour's
+                const int byte_idx = (i0 >> 3) + (ln >> 1);
+                if (byte_idx < nw64 * 8) {
+                    if (ln & 1)
+                        b_eq[byte_idx] = 0;
+                    else
+                        b_gt[byte_idx] = (unsigned char)(nib | (other << 4));
                 }
-                if (listed) {   // one cursor bump per wave, places by ballot rank
-                    uint32_t at0 = 0;
-                    if (ln == 0) at0 = atomicAdd(&s_x[1], (uint32_t)__popcll(listed));
-                    at0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)at0);
-                    if (inb) l_ent[at0 + (uint32_t)__popcll(listed & below)] = make_uint2(kk[c], (uint32_t)i);
+                if (__ballot(any_inb)) {   // some key of the deciding bucket: one cursor bump per wave and position
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const uint64_t listed = __ballot(inb[e]);
+                        if (listed) {
+                            uint32_t at0 = 0;
+                            if (ln == 0) at0 = atomicAdd(&s_x[1], (uint32_t)__popcll(listed));
+                            at0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)at0);
+                            if (inb[e]) l_ent[at0 + (uint32_t)__popcll(listed & below)] = make_uint2(k4[e], (uint32_t)(i + e));
+                        }
+                    }
                 }
             }
         }

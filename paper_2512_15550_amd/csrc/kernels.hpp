@@ -1053,7 +1053,7 @@ template <int G> __device__ __forceinline__ int select_unit(const SelectArgs &a,
                 n = block_select_classified<1024>(L, a.top_k, info.y, info.z, a.gbm + (size_t)ul * a.bits_stride,
                                                   a.glist + (size_t)ul * kListCap, emit, s_sel, s_bits, s_list);
         } else {
-            n = block_select_hist<1024>(key, L, a.top_k, emit, s_sel, s_bits, s_list, a.ghist + (size_t)ul * kBuckets);
+            n = block_select_hist<1024>(kb, L, a.top_k, emit, s_sel, s_bits, s_list, a.ghist + (size_t)ul * kBuckets);
         }
     }
     if (n < 0) {   // crowded deciding bucket (or no room for the bitmaps): the histogram-free route
