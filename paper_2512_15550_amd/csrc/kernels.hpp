@@ -809,7 +809,25 @@ template <int G> __global__ __launch_bounds__(1024) void keyhist_kernel(KeyArgs 
     for (int hh = 0; hh < G; ++hh) ls[hh] = s_ls[hh];
     const float *zb = a.z + (size_t)ul * a.l_stride * G;
     uint32_t *kb = a.kbuf + (size_t)ul * a.l_stride;
-    for (int c0 = blockIdx.x * 4096; c0 < L; c0 += gridDim.x * 4096) {
+    if (!a.z) {   // the keys are there already (matrix-core build): histogram only, four keys per load
+        const bool wide = (reinterpret_cast<uintptr_t>(kb) & 15u) == 0;
+        for (int c0 = blockIdx.x * 4096; c0 < L; c0 += gridDim.x * 4096) {
+            const int i = c0 + 4 * tid;
+            uint32_t k4[4] = {0u, 0u, 0u, 0u};
+            if (wide && i + 3 < L) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(kb + i);
+                k4[0] = v.x; k4[1] = v.y; k4[2] = v.z; k4[3] = v.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (i + e < L) k4[e] = kb[i + e];
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (i + e < L) atomicAdd(&s_h[key_bucket(k4[e])], 1u);
+        }
+    }
+    for (int c0 = blockIdx.x * 4096; a.z && c0 < L; c0 += gridDim.x * 4096) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             int i = c0 + q * 1024 + tid;
