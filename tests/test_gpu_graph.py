@@ -63,3 +63,48 @@ def test_graph_replays_equal_eager_steps(ck, window):
         torch.cuda.synchronize()
         assert torch.equal(outs[0], ref_out[(rep + 1) % n_steps])
     ck.ctkvr_free(idx)
+
+
+def test_graph_with_centroid_updates_tracks_an_eager_twin(ck):
+    """Steps followed by the dynamic centroid update, captured once and replayed: the FIFO position
+    lives on the device, so every replay continues where the last one stopped -- exactly like a
+    second, eagerly driven index that is given the same sequence of steps."""
+    import torch
+    n_steps = 3
+    wl = small_workload("graph_dcu", "bf16", 8, 2, (2500,), (820,), 6, 0, 3, 64, 64, n_steps)
+    bt = gen_batch(wl)
+    db = H.device_batch(bt)
+
+    def build():
+        return ck.ctkvr_build_index(H.params_of(wl), db.q_prefill, db.cu_seqlens, True, db.k_pages, db.block_table,
+                                    db.ctx_lens)
+
+    eager, graphed = build(), build()
+    B, h, g, d = wl.batch, wl.h, wl.g, wl.d
+    qs = [H.to_dev(np.stack([sq.q_decode[i] for sq in bt.seqs]), wl) for i in range(n_steps)]
+    outs_e = [torch.zeros((B, h, d), dtype=torch.float32, device="cuda") for _ in range(n_steps)]
+    outs_g = [torch.zeros((B, h, d), dtype=torch.float32, device="cuda") for _ in range(n_steps)]
+
+    def steps(idx, outs):
+        for i in range(n_steps):
+            ck.ctkvr_decode_step(idx, qs[i], db.k_pages, db.v_pages, db.block_table, outs[i])
+            ck.ctkvr_centroid_update(idx, qs[i])
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            steps(graphed, outs_g)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for rep in range(3):      # 9 updates on 6 slots: the FIFO wraps
+        steps(eager, outs_e)
+        graph.replay()
+        torch.cuda.synchronize()
+        for i in range(n_steps):
+            assert torch.equal(outs_g[i], outs_e[i]), f"replay {rep} step {i}: output differs from the eager twin"
+        assert np.array_equal(ck.ctkvr_index_lists(graphed), ck.ctkvr_index_lists(eager)), f"replay {rep}: lists differ"
+        assert np.array_equal(ck.ctkvr_index_centroids(graphed), ck.ctkvr_index_centroids(eager))
+    ck.ctkvr_free(eager)
+    ck.ctkvr_free(graphed)
