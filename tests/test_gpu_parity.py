@@ -79,6 +79,42 @@ def test_edge_shapes(ck, case):
     ck.ctkvr_free(idx)
 
 
+def _random_case(seed):
+    """A valid small configuration drawn from a seed: shapes, budgets and batch all vary."""
+    r = np.random.Generator(np.random.Philox(seed))
+    g = int(r.choice([1, 2, 4]))
+    G = int(r.choice([1, 2, 4, 8]))
+    B = int(r.integers(1, 4))
+    lens = tuple(int(x) for x in r.integers(40, 3000, size=B))
+    smin = min(lens)
+    C = int(r.integers(1, min(40, smin) + 1))
+    n_probe = int(r.integers(1, C + 1))
+    rho = int(r.integers(1, min(200, smin) + 1))
+    top_k = int(r.integers(1, 300))
+    dtype = "f32" if r.random() < 0.25 else "bf16"
+    page = int(r.choice([8, 16, 32]))
+    return dtype, G * g, g, lens, C, n_probe, rho, top_k, page
+
+
+@pytest.mark.parametrize("seed", list(range(9000, 9016)))
+def test_random_shapes(ck, seed):
+    dtype, h, g, lens, C, n_probe, rho, top_k, page = _random_case(seed)
+    _say(f"[random {seed}] {dtype} h={h} g={g} lens={lens} C={C} C'={n_probe} rho={rho} rho'={top_k} page={page}")
+    wl = small_workload(f"rnd{seed}", dtype, h, g, lens, tuple(range(seed * 10, seed * 10 + len(lens))), C, 0, n_probe, rho,
+                        top_k, 2, page_size=page)
+    bt = gen_batch(wl)
+    oi = H.oracle_index(bt)
+    db = H.device_batch(bt)
+    idx = ck.ctkvr_build_index(H.params_of(wl), db.q_prefill, db.cu_seqlens, True, db.k_pages, db.block_table,
+                               db.ctx_lens)
+    got = ck.ctkvr_index_lists(idx)
+    for b in range(wl.batch):
+        assert np.array_equal(got[b], oi.lists[b]), f"lists of sequence {b} differ"
+    st = H.run_decode_parity(bt, oi, idx, db, update=(seed % 2 == 0))
+    _say(f"[random {seed}] ok {st}")
+    ck.ctkvr_free(idx)
+
+
 @pytest.mark.parametrize("page_size", [1, 4, 64, 256])
 def test_other_page_sizes(ck, page_size):
     """The KV layout is a parameter: pages of 1 token (every row its own block-table entry), of a

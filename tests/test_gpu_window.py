@@ -31,6 +31,27 @@ CASES = [
 ]
 
 
+def _random_window_case(seed):
+    r = np.random.Generator(np.random.Philox(seed))
+    g = int(r.choice([1, 2, 4]))
+    G = int(r.choice([1, 2, 4, 8]))
+    B = int(r.integers(1, 4))
+    lens = tuple(int(x) for x in r.integers(200, 2500, size=B))
+    smin = min(lens)
+    n_init = int(r.integers(0, 40))
+    n_local = int(r.integers(0, 120))
+    C = int(r.integers(2, 30))
+    n_probe = int(r.integers(1, C + 1))
+    rho = int(r.integers(1, min(150, smin - n_init - n_local) + 1))
+    top_k = int(r.integers(1, 200))
+    grow = int(r.integers(0, 12))
+    dtype = "f32" if r.random() < 0.25 else "bf16"
+    return (f"rnd{seed}", dtype, G * g, g, lens, C, n_probe, rho, top_k, n_init, n_local, grow, 3)
+
+
+CASES += [_random_window_case(s) for s in range(9100, 9108)]
+
+
 def _setup(ck, case):
     name, dtype, h, g, lens, C, n_probe, rho, top_k, n_init, n_local, grow, steps = case
     wl = small_workload(name, dtype, h, g, lens, tuple(range(900, 900 + len(lens))), C, 0, n_probe, rho, top_k, steps)
