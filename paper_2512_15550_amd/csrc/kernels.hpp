@@ -554,7 +554,7 @@ struct MfmaScoreArgs {
 // ordered uint32 (4 bytes per (centroid, key) instead of 4 G bytes of scores read twice).
 enum { MFMA_MAX = 0, MFMA_SUM = 1, MFMA_KEY = 2 };
 
-template <int G, int MODE> __global__ __launch_bounds__(256) void mfma_score_kernel(MfmaScoreArgs a)
+template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_kernel(MfmaScoreArgs a)
 {
     constexpr int MT = 8 / G;        // 32-centroid sub-tiles per block
     constexpr int CT = 32 * MT;      // centroids per block
@@ -612,16 +612,18 @@ template <int G, int MODE> __global__ __launch_bounds__(256) void mfma_score_ker
     auto row_at = [&](int t0) {
         return row_of(a.k.block_table, a.k.max_pages, a.k.page_shift, a.g, b, kv, min(t0 + srow, s - 1));
     };
-    uint4 stage[2][2];
-    auto fetch = [&](int set, uint32_t row) {
+    // staging registers as named variables: an array indexed through the helpers would be kept in
+    // private memory, and every request would then be waited for at once to be stored there
+    uint4 st0a, st0b, st1a, st1b;
+    auto fetch = [&](uint4 &x, uint4 &y, uint32_t row) {
         const uint4 *src = reinterpret_cast<const uint4 *>(K + (size_t)row * kD + spart * 16);
-        stage[set][0] = src[0];
-        stage[set][1] = src[1];
+        x = src[0];
+        y = src[1];
     };
-    auto put = [&](int set, int buf) {
+    auto put = [&](const uint4 &x, const uint4 &y, int buf) {
         uint4 *dst = reinterpret_cast<uint4 *>(&s_k[buf][srow * ROWB + spart * 32]);
-        dst[0] = stage[set][0];
-        dst[1] = stage[set][1];
+        dst[0] = x;
+        dst[1] = y;
     };
     auto compute = [&](int buf, int t0) {
         bf16x8_t bfrag[8];
@@ -669,23 +671,23 @@ template <int G, int MODE> __global__ __launch_bounds__(256) void mfma_score_ker
         }
     };
     uint32_t row_a = row_at(tbeg + 64), row_b = row_at(tbeg + 96);   // rows of steps 2 and 3
-    fetch(0, row_at(tbeg));
-    fetch(1, row_at(tbeg + 32));
-    put(0, 0);
+    fetch(st0a, st0b, row_at(tbeg));
+    fetch(st1a, st1b, row_at(tbeg + 32));
+    put(st0a, st0b, 0);
     __syncthreads();
     // two steps per trip, so that register sets and buffers are named at compile time
     for (int t0 = tbeg; t0 < tend; t0 += 64) {
         // step i (buffer 0): request step i+2 into set 0, the entry of step i+4; write step i+1 to buffer 1
-        fetch(0, row_a);
+        fetch(st0a, st0b, row_a);
         row_a = row_at(t0 + 128);
         compute(0, t0);
-        put(1, 1);
+        put(st1a, st1b, 1);
         __syncthreads();
         // step i+1 (buffer 1): request step i+3 into set 1, the entry of step i+5; write step i+2 to buffer 0
-        fetch(1, row_b);
+        fetch(st1a, st1b, row_b);
         row_b = row_at(t0 + 160);
         compute(1, t0 + 32);
-        put(0, 0);
+        put(st0a, st0b, 0);
         __syncthreads();
     }
     if constexpr (MODE == MFMA_KEY) return;

@@ -93,23 +93,24 @@ template <int G> __global__ __launch_bounds__(512) void kmeans_assign_kernel(Kme
     const bf16_t *cbase = a.centroids + ((size_t)b * a.h + kv * G) * a.c_max * kD;
     // two pieces ahead in registers: piece i+2 is requested while piece i feeds the matrix cores
     // and piece i+1 waits to be written to the other buffer
-    uint4 stage[2][2];
-    auto fetch = [&](int set, int c0, int kc) {
+    // (named variables: an array indexed through the helpers would be kept in private memory)
+    uint4 st0a, st0b, st1a, st1b;
+    auto fetch = [&](uint4 &x, uint4 &y, int c0, int kc) {
         const int c = min(c0 + srow, C - 1);
         const uint4 *src = reinterpret_cast<const uint4 *>(cbase + ((size_t)(kc >> 1) * a.c_max + c) * kD + (kc & 1) * 64 + sq * 16);
-        stage[set][0] = src[0];
-        stage[set][1] = src[1];
+        x = src[0];
+        y = src[1];
     };
-    auto put = [&](int set, int buf) {
+    auto put = [&](const uint4 &x, const uint4 &y, int buf) {
         uint4 *dst = reinterpret_cast<uint4 *>(&s_a[buf][srow * ROWB + sq * 32]);
-        dst[0] = stage[set][0];
-        dst[1] = stage[set][1];
+        dst[0] = x;
+        dst[1] = y;
     };
     float best = -__builtin_huge_valf();
     int bi = 0;
-    fetch(0, 0, 0);
-    fetch(1, 0, 1);
-    put(0, 0);
+    fetch(st0a, st0b, 0, 0);
+    fetch(st1a, st1b, 0, 1);
+    put(st0a, st0b, 0);
     __syncthreads();
     for (int c0 = 0; c0 < C; c0 += 128) {
         f32x16_t acc[4];
@@ -122,7 +123,10 @@ template <int G> __global__ __launch_bounds__(512) void kmeans_assign_kernel(Kme
             const int buf = kc & 1;
             {   // piece i + 2
                 const int c2 = kc + 2 < NKC ? c0 : c0 + 128, k2 = kc + 2 < NKC ? kc + 2 : kc + 2 - NKC;
-                if (c2 < C) fetch(kc & 1, c2, k2);
+                if (c2 < C) {
+                    if ((kc & 1) == 0) fetch(st0a, st0b, c2, k2);
+                    else fetch(st1a, st1b, c2, k2);
+                }
             }
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
@@ -135,7 +139,10 @@ template <int G> __global__ __launch_bounds__(512) void kmeans_assign_kernel(Kme
                     acc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bf, acc[ct], 0, 0, 0);
                 }
             }
-            if (kc + 1 < NKC || c0 + 128 < C) put((kc + 1) & 1, buf ^ 1);   // piece i + 1
+            if (kc + 1 < NKC || c0 + 128 < C) {   // piece i + 1
+                if (((kc + 1) & 1) == 0) put(st0a, st0b, buf ^ 1);
+                else put(st1a, st1b, buf ^ 1);
+            }
             __syncthreads();
         }
 #pragma unroll
