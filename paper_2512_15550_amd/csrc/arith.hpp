@@ -136,6 +136,33 @@ __device__ __forceinline__ uint64_t to_fixed40(float e)
     return ((uint64_t)hi << 24) + lo;
 }
 
+// floor(exp_series(x) * 2^40), x <= 0, as hi * 2^24 + lo with lo < 2^24: the value of
+// to_fixed40(exp_series(x)) in straight-line code.  x is clamped at -30.5 instead of branching
+// (every x below -27.8 gives 0 either way); the power of two enters through the exponent field
+// (n is read from the low bits of t, 2^16 added in the same step: exact, as the products it
+// replaces are); the fraction is split off with v_fract (exact for a 24-bit value).
+__device__ __forceinline__ void exp_fixed40_parts(float x, uint32_t &hi, uint32_t &lo)
+{
+    const float kMagic = 12582912.0f;
+    x = fmaxf(x, -30.5f);
+    float t = __fmaf_rn(x, 1.44269504088896341f, kMagic);
+    float n = t - kMagic;
+    float r = __fmaf_rn(n, -0.693145751953125f, x);
+    r = __fmaf_rn(n, -1.42860682030941723e-6f, r);
+    float p = 1.0f / 5040.0f;
+    p = __fmaf_rn(p, r, 1.0f / 720.0f);
+    p = __fmaf_rn(p, r, 1.0f / 120.0f);
+    p = __fmaf_rn(p, r, 1.0f / 24.0f);
+    p = __fmaf_rn(p, r, 1.0f / 6.0f);
+    p = __fmaf_rn(p, r, 0.5f);
+    p = __fmaf_rn(p, r, 1.0f);
+    p = __fmaf_rn(p, r, 1.0f);
+    // a = p * 2^(n + 16): kMagic's low 23 bits are zero, so (bits(t) + 16) << 23 == (n + 16) << 23 mod 2^32
+    const float a = __uint_as_float(__float_as_uint(p) + ((__float_as_uint(t) + 16u) << 23));
+    hi = (uint32_t)a;
+    lo = (uint32_t)(__builtin_amdgcn_fractf(a) * 16777216.0f);
+}
+
 // log(S * 2^-40), S >= 1: S = 2^k f, f in [sqrt(1/2), sqrt(2)); log f = 2 atanh((f-1)/(f+1))
 __device__ __forceinline__ double log_fixed40(uint64_t S)
 {

@@ -558,7 +558,10 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
 {
     constexpr int MT = 8 / G;        // 32-centroid sub-tiles per block
     constexpr int CT = 32 * MT;      // centroids per block
-    __shared__ float s_z[MODE == MFMA_KEY ? CT * 32 * G : 1];
+    // KEY: the result tiles, [head][key][centroid]; the row length keeps the two half-waves of a
+    // writer on different banks and the keys of a reader on different banks
+    constexpr int ZS = CT + 9;
+    __shared__ float s_z[MODE == MFMA_KEY ? G * 32 * ZS : 1];
     __shared__ __align__(16) unsigned char s_k[2][32 * 272];
     const int tid = threadIdx.x, wv = tid >> 6, ln = tid & 63;
     const int col = ln & 31, half = ln >> 5;
@@ -572,40 +575,35 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
     const int tbeg = blockIdx.x * tper;
     const int tend = min(s, tbeg + tper);
     if (tbeg >= s) return;
+    // The matrix instruction is issued with the keys as its row operand and the centroids as its
+    // column operand: a lane then holds ONE centroid (column `col` of its sub-tile) against 16
+    // keys (rows 8 (r / 4) + 4 half + r % 4), and that centroid's statistics are single registers.
     int hh[2], mt[2];
-    bf16x8_t afrag[2][8];
+    bf16x8_t cfrag[2][8];                  // the centroid fragments, resident
+    float mx[2];                           // MAX: running maximum (unscaled); SUM, KEY: the final maximum m
+    float lsv[2];                          // KEY: log S
+    unsigned long long sum[2];             // SUM
+    size_t stat[2];
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
         int it = wv * 2 + q;
         hh[q] = it / MT;
         mt[q] = it - hh[q] * MT;
-        int j = min(j0 + mt[q] * 32 + col, C - 1);
+        const int j = min(j0 + mt[q] * 32 + col, C - 1);   // columns beyond C repeat centroid C-1 and are dropped at the end
         const bf16_t *row = a.centroids + (((size_t)b * a.h + kv * G + hh[q]) * a.c_max + j) * kD;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) afrag[q][ks] = *reinterpret_cast<const bf16x8_t *>(row + ks * 16 + 8 * half);
+        for (int ks = 0; ks < 8; ++ks) cfrag[q][ks] = *reinterpret_cast<const bf16x8_t *>(row + ks * 16 + 8 * half);
+        stat[q] = ((size_t)bkl * a.c_max + j) * G + hh[q];
+        mx[q] = -__builtin_huge_valf();
+        lsv[q] = 0.0f;
+        sum[q] = 0ull;
+        if constexpr (MODE != MFMA_MAX) mx[q] = ordered_value(a.m_key[stat[q]]);
+        if constexpr (MODE == MFMA_KEY) lsv[q] = (float)log_fixed40(a.S[stat[q]]);
     }
-    // per accumulator register r of work item q: the tile row it holds, that row's statistics
-    float mx[2][16];                       // MAX: running maximum; SUM, KEY: the final maximum m
-    float lsv[MODE == MFMA_KEY ? 2 : 1][16];          // KEY: log S
-    unsigned long long sum[MODE == MFMA_SUM ? 2 : 1][16];
-#pragma unroll
-    for (int q = 0; q < 2; ++q)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int jj = mt[q] * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-            const size_t stat = ((size_t)bkl * a.c_max + min(j0 + jj, C - 1)) * G + hh[q];
-            if constexpr (MODE == MFMA_MAX) {
-                mx[q][r] = -__builtin_huge_valf();
-            } else {
-                mx[q][r] = ordered_value(a.m_key[stat]);
-                if constexpr (MODE == MFMA_SUM) sum[q][r] = 0ull;
-                if constexpr (MODE == MFMA_KEY) lsv[q][r] = (float)log_fixed40(a.S[stat]);
-            }
-        }
     // The 32 key rows of a step (8 KB) go through shared memory once for the four waves, in two
     // buffers; a step's rows are requested two steps ahead and their block-table entries four
-    // steps ahead, so that neither latency is waited for.  Rows beyond the block's range are
-    // clamped to valid ones and their results dropped.
+    // steps ahead, so that neither latency is waited for.  Rows beyond the sequence are clamped
+    // to its last key.
     const bf16_t *K = (const bf16_t *)a.k.pages;
     constexpr int ROWB = 272;   // bytes per staged key row (256 + padding: fragment reads spread over the banks)
     const int srow = tid >> 3, spart = tid & 7;
@@ -625,46 +623,67 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
         dst[0] = x;
         dst[1] = y;
     };
-    auto compute = [&](int buf, int t0) {
-        bf16x8_t bfrag[8];
+    // tail: a step whose keys may reach beyond the block's range (a literal at every call).  Such
+    // keys are real keys of the sequence, repeated: harmless for a maximum, left out of a sum,
+    // not written as ranking keys.
+    auto compute = [&](const bool tail, int buf, int t0) __attribute__((always_inline)) {
+        bf16x8_t kfrag[8];
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks)
-            bfrag[ks] = *reinterpret_cast<const bf16x8_t *>(&s_k[buf][col * ROWB + ks * 32 + half * 16]);
-        const bool tok = (t0 + col) < tend;
+            kfrag[ks] = *reinterpret_cast<const bf16x8_t *>(&s_k[buf][col * ROWB + ks * 32 + half * 16]);
+        // the two work items' chains interleaved: independent back-to-back matrix instructions
+        f32x16_t acc0, acc1;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc0[r] = acc1[r] = 0.0f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag[ks], cfrag[0][ks], acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag[ks], cfrag[1][ks], acc1, 0, 0, 0);
+        }
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
-            f32x16_t acc;
+            const f32x16_t &acc = q == 0 ? acc0 : acc1;
+            if constexpr (MODE == MFMA_MAX) {
+                // kept unscaled: rounding acc * scale is monotonic, scale > 0
+                float m = mx[q];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+                for (int r = 0; r < 16; r += 2) m = fmaxf(fmaxf(acc[r], acc[r + 1]), m);
+                mx[q] = m;
+            } else if constexpr (MODE == MFMA_SUM) {
+                // sixteen terms: hi < 2^17 and lo < 2^24 each, their sums fit 32 bits
+                uint32_t shi = 0u, slo = 0u;
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[q][ks], bfrag[ks], acc, 0, 0, 0);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int jj = mt[q] * 32 + 8 * (r >> 2) + 4 * half + (r & 3);   // row of the 32x32 tile held in acc[r]
-                const float v = acc[r] * a.scale;
-                const bool live = tok && (j0 + jj) < C;
-                if constexpr (MODE == MFMA_MAX) {
-                    if (live) mx[q][r] = fmaxf(mx[q][r], v);
-                } else if constexpr (MODE == MFMA_SUM) {
-                    if (live) sum[q][r] += to_fixed40(exp_series(v - mx[q][r]));
-                } else {
-                    s_z[(jj * 32 + col) * G + hh[q]] = (v - mx[q][r]) - lsv[q][r];
+                for (int r = 0; r < 16; ++r) {
+                    uint32_t hi, lo;
+                    exp_fixed40_parts(acc[r] * a.scale - mx[q], hi, lo);
+                    if (tail) {
+                        const bool ok = (t0 + 8 * (r >> 2) + 4 * half + (r & 3)) < tend;
+                        hi = ok ? hi : 0u;
+                        lo = ok ? lo : 0u;
+                    }
+                    shi += hi;
+                    slo += lo;
                 }
+                sum[q] += ((unsigned long long)shi << 24) + slo;
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    s_z[(hh[q] * 32 + 8 * (r >> 2) + 4 * half + (r & 3)) * ZS + mt[q] * 32 + col] = (acc[r] * a.scale - mx[q]) - lsv[q];
             }
         }
         if constexpr (MODE == MFMA_KEY) {
             __syncthreads();
             if (t0 < tend) {
                 for (int p = tid; p < CT * 32; p += 256) {
-                    const int n = p & 31, jj = p >> 5;
+                    const int n = p & 31, jl = p >> 5;
                     const int t = t0 + n;
-                    if ((j0 + jj) < C && t < tend) {
+                    if ((j0 + jl) < C && t < tend) {
                         float best = -__builtin_huge_valf();
 #pragma unroll
-                        for (int c = 0; c < G; ++c) best = fmaxf(best, s_z[p * G + c]);
+                        for (int c = 0; c < G; ++c) best = fmaxf(best, s_z[(c * 32 + n) * ZS + jl]);
                         uint32_t ok = ordered_key(best);
                         if (t < a.n_init || t >= s - a.n_local) ok = 0x007fffffu;   // the image of -inf
-                        a.kbuf[((size_t)bkl * a.c_max + j0 + jj) * a.l_stride + t] = ok;
+                        a.kbuf[((size_t)bkl * a.c_max + j0 + jl) * a.l_stride + t] = ok;
                     }
                 }
             }
@@ -675,40 +694,37 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
     fetch(st1a, st1b, row_at(tbeg + 32));
     put(st0a, st0b, 0);
     __syncthreads();
-    // two steps per trip, so that register sets and buffers are named at compile time
-    for (int t0 = tbeg; t0 < tend; t0 += 64) {
+    // two steps per trip, so that register sets and buffers are named at compile time; the trips
+    // whose 64 keys all lie in the block's range run without per-lane predicates
+    auto trip = [&](const bool tail, int t0) __attribute__((always_inline)) {
         // step i (buffer 0): request step i+2 into set 0, the entry of step i+4; write step i+1 to buffer 1
         fetch(st0a, st0b, row_a);
         row_a = row_at(t0 + 128);
-        compute(0, t0);
+        compute(tail, 0, t0);
         put(st1a, st1b, 1);
         __syncthreads();
         // step i+1 (buffer 1): request step i+3 into set 1, the entry of step i+5; write step i+2 to buffer 0
         fetch(st1a, st1b, row_b);
         row_b = row_at(t0 + 160);
-        compute(1, t0 + 32);
+        compute(tail, 1, t0 + 32);
         put(st0a, st0b, 0);
         __syncthreads();
-    }
+    };
+    int t0 = tbeg;
+    for (; t0 + 64 <= tend; t0 += 64) trip(false, t0);
+    if (t0 < tend) trip(true, t0);
     if constexpr (MODE == MFMA_KEY) return;
 #pragma unroll
-    for (int q = 0; q < 2; ++q)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int jj = mt[q] * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-            const size_t stat = ((size_t)bkl * a.c_max + j0 + jj) * G + hh[q];
-            if constexpr (MODE == MFMA_MAX) {
-                float v = mx[q][r];
-#pragma unroll
-                for (int o = 16; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-                if (col == 0 && (j0 + jj) < C) atomicMax(&a.m_key[stat], ordered_key(v));
-            } else {
-                unsigned long long v = sum[q][r];
-#pragma unroll
-                for (int o = 16; o >= 1; o >>= 1) v += __shfl_xor(v, o);
-                if (col == 0 && (j0 + jj) < C && v) atomicAdd(&a.S[stat], v);
-            }
+    for (int q = 0; q < 2; ++q) {
+        const bool mine = half == 0 && (j0 + mt[q] * 32 + col) < C;
+        if constexpr (MODE == MFMA_MAX) {
+            const float v = fmaxf(mx[q], __shfl_xor(mx[q], 32));
+            if (mine) atomicMax(&a.m_key[stat[q]], ordered_key(v * a.scale));
+        } else {
+            const unsigned long long v = sum[q] + __shfl_xor(sum[q], 32);
+            if (mine && v) atomicAdd(&a.S[stat[q]], v);
         }
+    }
 }
 
 // ------------------------------------------------------------------------------
