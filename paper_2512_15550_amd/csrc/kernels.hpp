@@ -558,10 +558,10 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
 {
     constexpr int MT = 8 / G;        // 32-centroid sub-tiles per block
     constexpr int CT = 32 * MT;      // centroids per block
-    // KEY: the result tiles, [head][key][centroid]; the row length keeps the two half-waves of a
-    // writer on different banks and the keys of a reader on different banks
-    constexpr int ZS = CT + 9;
-    __shared__ float s_z[MODE == MFMA_KEY ? G * 32 * ZS : 1];
+    // KEY: the result tiles, [head][centroid][key]: a lane's four consecutive keys are one 16-byte
+    // write, a reader's four keys one 16-byte read; 36-word rows spread both over the banks
+    constexpr int ZS = 36;
+    __shared__ __align__(16) float s_z[MODE == MFMA_KEY ? G * CT * ZS : 4];
     __shared__ __align__(16) unsigned char s_k[2][32 * 272];
     const int tid = threadIdx.x, wv = tid >> 6, ln = tid & 63;
     const int col = ln & 31, half = ln >> 5;
@@ -666,24 +666,48 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
                 }
                 sum[q] += ((unsigned long long)shi << 24) + slo;
             } else {
+                float *zrow = &s_z[(hh[q] * CT + mt[q] * 32 + col) * ZS + 4 * half];
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    s_z[(hh[q] * 32 + 8 * (r >> 2) + 4 * half + (r & 3)) * ZS + mt[q] * 32 + col] = (acc[r] * a.scale - mx[q]) - lsv[q];
+                for (int rq = 0; rq < 4; ++rq) {
+                    float4 v;
+                    v.x = (acc[4 * rq + 0] * a.scale - mx[q]) - lsv[q];
+                    v.y = (acc[4 * rq + 1] * a.scale - mx[q]) - lsv[q];
+                    v.z = (acc[4 * rq + 2] * a.scale - mx[q]) - lsv[q];
+                    v.w = (acc[4 * rq + 3] * a.scale - mx[q]) - lsv[q];
+                    *reinterpret_cast<float4 *>(zrow + 8 * rq) = v;
+                }
             }
         }
         if constexpr (MODE == MFMA_KEY) {
             __syncthreads();
+            // four consecutive keys of one centroid per thread: maximum over the heads, one 16-byte
+            // store where the key rows allow it (whole step in range, row length a multiple of four)
+            const bool wide = !tail && (a.l_stride & 3) == 0;
             if (t0 < tend) {
-                for (int p = tid; p < CT * 32; p += 256) {
-                    const int n = p & 31, jl = p >> 5;
-                    const int t = t0 + n;
-                    if ((j0 + jl) < C && t < tend) {
-                        float best = -__builtin_huge_valf();
+                for (int p = tid; p < CT * 8; p += 256) {
+                    const int n4 = (p & 7) * 4, jl = p >> 3;
+                    if ((j0 + jl) >= C) continue;
+                    float4 best = *reinterpret_cast<const float4 *>(&s_z[jl * ZS + n4]);
 #pragma unroll
-                        for (int c = 0; c < G; ++c) best = fmaxf(best, s_z[(c * 32 + n) * ZS + jl]);
-                        uint32_t ok = ordered_key(best);
-                        if (t < a.n_init || t >= s - a.n_local) ok = 0x007fffffu;   // the image of -inf
-                        a.kbuf[((size_t)bkl * a.c_max + j0 + jl) * a.l_stride + t] = ok;
+                    for (int c = 1; c < G; ++c) {
+                        const float4 o = *reinterpret_cast<const float4 *>(&s_z[(c * CT + jl) * ZS + n4]);
+                        best.x = fmaxf(best.x, o.x);
+                        best.y = fmaxf(best.y, o.y);
+                        best.z = fmaxf(best.z, o.z);
+                        best.w = fmaxf(best.w, o.w);
+                    }
+                    const int t = t0 + n4;
+                    uint32_t ok[4] = {ordered_key(best.x), ordered_key(best.y), ordered_key(best.z), ordered_key(best.w)};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if ((t + e) < a.n_init || (t + e) >= s - a.n_local) ok[e] = 0x007fffffu;   // the image of -inf
+                    uint32_t *dst = a.kbuf + ((size_t)bkl * a.c_max + j0 + jl) * a.l_stride + t;
+                    if (wide) {
+                        *reinterpret_cast<uint4 *>(dst) = make_uint4(ok[0], ok[1], ok[2], ok[3]);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if ((t + e) < tend) dst[e] = ok[e];
                     }
                 }
             }
