@@ -669,13 +669,14 @@ int decode_dispatch(ctkvr_index *ix, const void *q, const void *k, const void *v
 template <int G> int run_kmeans_g(ctkvr_index *ix, KmeansArgs ka, hipStream_t st)
 {
     const int U = ix->units;
+    const size_t hn_lds = (size_t)((ix->c_max + 127) & ~127) * 4;
     hipError_t e = hipFuncSetAttribute((const void *)kmeans_assign_kernel<G>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       ix->c_max * 4);
+                                       (int)hn_lds);
     if (e != hipSuccess) return fail(CTKVR_EHIP, "k-means set-up: %s", hipGetErrorString(e));
     kmeans_init_kernel<<<dim3(ix->c_max, ix->p.n_q_heads, ix->p.batch), 128, 0, st>>>(ka, G);
     for (int it = 0; it < ix->p.kmeans_iters; ++it) {
         kmeans_halfnorm_kernel<G><<<dim3((ix->c_max + 15) / 16, U), 256, 0, st>>>(ka);
-        kmeans_assign_kernel<G><<<dim3((ix->s_max + 255) / 256, U), 512, ix->c_max * 4, st>>>(ka);
+        kmeans_assign_kernel<G><<<dim3((ix->s_max + 255) / 256, U), 512, hn_lds, st>>>(ka);
         kmeans_offsets_kernel<<<dim3(U), 1024, 0, st>>>(ka);
         kmeans_scatter_kernel<<<dim3((ix->s_max + 255) / 256, U), 256, 0, st>>>(ka);
         kmeans_reduce_kernel<G><<<dim3(ix->c_max, U), 128, 0, st>>>(ka);

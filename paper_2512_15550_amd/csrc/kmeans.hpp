@@ -64,10 +64,11 @@ template <int G> __global__ __launch_bounds__(256) void kmeans_halfnorm_kernel(K
 // for the eight waves (double-buffered, requested two pieces ahead; rows padded to 144 bytes so that the 16-byte fragment reads of a
 // wave spread over the banks).  With G = 8 the fragments do not fit the registers and are
 // re-read from memory.  Counts the members of every centre as it goes.
-// grid (ceil(s_max/256), batch*g), 512 threads; dynamic shared memory: c_max floats.
+// grid (ceil(s_max/256), batch*g), 512 threads; dynamic shared memory: c_max rounded up to 128, floats.
+// The accumulators start from -|mu_c|^2/2, so the result tile is the score itself.
 template <int G> __global__ __launch_bounds__(512) void kmeans_assign_kernel(KmeansArgs a)
 {
-    extern __shared__ float s_hn[];
+    extern __shared__ __align__(16) float s_hn[];   // c_max rounded up to 128 floats
     constexpr int KS = 8 * G;                 // k-steps of 16 dims
     constexpr bool REG_B = (G <= 4);
     constexpr int ROWB = 144;                 // bytes per staged centre row (64 dims + padding)
@@ -76,7 +77,9 @@ template <int G> __global__ __launch_bounds__(512) void kmeans_assign_kernel(Kme
     const int C = a.n_cent[b], s = a.ctx_lens[b];
     if ((int)blockIdx.x * 256 >= s) return;
     const int tid = threadIdx.x, wv = tid >> 6, ln = tid & 63, col = ln & 31, half = ln >> 5;
-    for (int c = tid; c < C; c += 512) s_hn[c] = a.half_norm[(size_t)ul * a.c_max + c];
+    // -|mu_c|^2 / 2, the value every accumulator starts from; -inf for the padding up to a whole tile
+    for (int c = tid; c < ((C + 127) & ~127); c += 512)
+        s_hn[c] = c < C ? -a.half_norm[(size_t)ul * a.c_max + c] : -__builtin_huge_valf();
     const int p0 = blockIdx.x * 256 + wv * 32;
     const int t = min(p0 + col, s - 1);
     const bf16_t *xrow = a.q + ((size_t)(a.first_row[b] + t) * a.h + kv * G) * kD + 8 * half;
@@ -117,7 +120,13 @@ template <int G> __global__ __launch_bounds__(512) void kmeans_assign_kernel(Kme
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[ct][r] = 0.0f;
+            for (int rq = 0; rq < 4; ++rq) {
+                const float4 v = *reinterpret_cast<const float4 *>(&s_hn[c0 + ct * 32 + 8 * rq + 4 * half]);
+                acc[ct][4 * rq + 0] = v.x;
+                acc[ct][4 * rq + 1] = v.y;
+                acc[ct][4 * rq + 2] = v.z;
+                acc[ct][4 * rq + 3] = v.w;
+            }
 #pragma unroll
         for (int kc = 0; kc < NKC; ++kc) {
             const int buf = kc & 1;
@@ -149,11 +158,8 @@ template <int G> __global__ __launch_bounds__(512) void kmeans_assign_kernel(Kme
         for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                int c = c0 + ct * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                if (c < C) {
-                    float sc = acc[ct][r] - s_hn[c];
-                    if (sc > best) { best = sc; bi = c; }
-                }
+                const int c = c0 + ct * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                if (acc[ct][r] > best) { best = acc[ct][r]; bi = c; }
             }
     }
     float ob = __shfl_xor(best, 32);
