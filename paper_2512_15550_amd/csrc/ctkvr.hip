@@ -679,7 +679,7 @@ template <int G> int run_kmeans_g(ctkvr_index *ix, KmeansArgs ka, hipStream_t st
         kmeans_assign_kernel<G><<<dim3((ix->s_max + 255) / 256, U), 512, hn_lds, st>>>(ka);
         kmeans_offsets_kernel<<<dim3(U), 1024, 0, st>>>(ka);
         kmeans_scatter_kernel<<<dim3((ix->s_max + 255) / 256, U), 256, 0, st>>>(ka);
-        kmeans_reduce_kernel<G><<<dim3(ix->c_max, U), 128, 0, st>>>(ka);
+        kmeans_reduce_kernel<G><<<dim3(ix->c_max, U), 512, 0, st>>>(ka);
     }
     HIP_TRY(hipGetLastError());
     return CTKVR_OK;

@@ -212,51 +212,84 @@ __global__ __launch_bounds__(256) void kmeans_scatter_kernel(KmeansArgs a)
 
 // One block per centre: sum_c = sum of llrint(x * 2^20) over its members (int64 per element, in
 // registers), mu_c = sum / count (fp64 divide, rounded to fp32, then to bf16 nearest-even); an
-// empty centre keeps its place.  Thread e owns the G consecutive elements e*G .. e*G+G-1 of the
-// G*128-element point.  Clears the count for the next iteration.  grid (c_max, batch*g), 128 threads
-template <int G> __global__ __launch_bounds__(128) void kmeans_reduce_kernel(KmeansArgs a)
+// empty centre keeps its place.  Four groups of 128 threads take the members eight at a time in
+// turn (their ids are requested one round ahead of their rows); thread e of a group owns the G
+// consecutive elements e*G .. e*G+G-1 of the G*128-element point, and the groups' integer sums
+// are added through shared memory.  Clears the count for the next iteration.
+// grid (c_max, batch*g), 512 threads
+template <int G> __global__ __launch_bounds__(512) void kmeans_reduce_kernel(KmeansArgs a)
 {
+    __shared__ long long s_part[3][128][G];
     const int ul = blockIdx.y, b = ul / a.g, kv = ul - b * a.g;
     const int c = blockIdx.x;
     if (c >= a.n_cent[b]) return;
     const uint32_t n = a.counts[(size_t)ul * a.c_max + c];
     const uint32_t st = a.start[(size_t)ul * a.c_max + c];
     const int32_t *ord = a.order + (size_t)ul * a.s_max + st;
-    const int e = threadIdx.x;
+    const int e = threadIdx.x & 127, grp = threadIdx.x >> 7;
     const bf16_t *base = a.q + ((size_t)a.first_row[b] * a.h + kv * G) * kD + e * G;
     const size_t rstride = (size_t)a.h * kD;
     long long acc[G];
 #pragma unroll
     for (int r = 0; r < G; ++r) acc[r] = 0;
-    for (uint32_t m0 = 0; m0 < n; m0 += 8) {
-        int t[8];
+    int t[8];
+    if (n) {
 #pragma unroll
-        for (int u = 0; u < 8; ++u) t[u] = ord[min(m0 + u, n - 1)];
+        for (int u = 0; u < 8; ++u) t[u] = ord[min((uint32_t)(grp * 8 + u), n - 1)];
+    }
+    for (uint32_t m0 = grp * 8; m0 < n; m0 += 32) {
+        int tn[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) tn[u] = ord[min(m0 + 32 + u, n - 1)];
         bf16_t x[8][G];
 #pragma unroll
         for (int u = 0; u < 8; ++u)
 #pragma unroll
             for (int r = 0; r < G; ++r) x[u][r] = base[(size_t)t[u] * rstride + r];
+        // x * 2^20 is exact in fp32 (a bf16 value, an exponent shift); below 2^30 it converts with
+        // the one-instruction fp32 -> int32 rounding, and the wave checks that together
+        bool small = true;
 #pragma unroll
         for (int u = 0; u < 8; ++u)
-            if (m0 + u < n) {
 #pragma unroll
-                for (int r = 0; r < G; ++r)
-                    acc[r] += __float2ll_rn(__uint_as_float((uint32_t)x[u][r] << 16) * 1048576.0f);
-            }
+            for (int r = 0; r < G; ++r) small = small && ((uint32_t)x[u][r] & 0x7fffu) < 0x4480u;   // |x| < 1024
+        if (__all(small)) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (m0 + u < n) {
+#pragma unroll
+                    for (int r = 0; r < G; ++r)
+                        acc[r] += (long long)__float2int_rn(__uint_as_float((uint32_t)x[u][r] << 16) * 1048576.0f);
+                }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (m0 + u < n) {
+#pragma unroll
+                    for (int r = 0; r < G; ++r)
+                        acc[r] += __float2ll_rn(__uint_as_float((uint32_t)x[u][r] << 16) * 1048576.0f);
+                }
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = tn[u];
     }
-    if (n) {
+    if (grp) {
+#pragma unroll
+        for (int r = 0; r < G; ++r) s_part[grp - 1][e][r] = acc[r];
+    }
+    __syncthreads();
+    if (grp == 0 && n) {
 #pragma unroll
         for (int r = 0; r < G; ++r) {
+            const long long tot = acc[r] + s_part[0][e][r] + s_part[1][e][r] + s_part[2][e][r];
             const int ee = e * G + r, hh = ee >> 7, dim = ee & 127;
-            float m = (float)((double)acc[r] * (1.0 / 1048576.0) / (double)n);
+            float m = (float)((double)tot * (1.0 / 1048576.0) / (double)n);
             uint32_t u = __float_as_uint(m);
             u += 0x7fffu + ((u >> 16) & 1u);
             a.centroids[(((size_t)b * a.h + kv * G + hh) * a.c_max + c) * kD + dim] = (bf16_t)(u >> 16);
         }
     }
-    __syncthreads();
-    if (e == 0) a.counts[(size_t)ul * a.c_max + c] = 0u;
+    if (threadIdx.x == 0) a.counts[(size_t)ul * a.c_max + c] = 0u;
 }
 
 }  // namespace ctkvr
