@@ -76,6 +76,22 @@ def test_first_update_on_lattice_inputs_is_bit_exact_and_decodes_like_the_oracle
     ck.ctkvr_free(idx)
 
 
+def test_first_update_with_large_magnitudes_is_bit_exact(ck):
+    """Queries of magnitude up to 2048 (still exact products and sums): the update's fixed-point sums leave
+    the 32-bit range of its fast rounding path, mixed with members that stay inside it."""
+    s, C, h, g = 1100, 24, 8, 2
+    bt = _lattice_batch(731, s, h, g, C, 48, 3, 32)
+    sq = bt.seqs[0]
+    big = np.random.Generator(np.random.Philox(732)).random(s) < 0.3
+    sq.q_full[big] *= np.float32(2048.0)
+    sq.q_tail = sq.q_full[s - C:]
+    init = kmeanspp_for_sequence(sq.q_full, g, C, seed=6)
+    Qc, _, _ = oracle.kmeans_centroids(sq.q_full, g, init, iters=1)
+    idx, db, cen = _gpu_kmeans(ck, bt, init[None], 1)
+    assert np.array_equal(cen[0], Qc), "centres after the first update differ"
+    ck.ctkvr_free(idx)
+
+
 def test_zero_iterations_is_the_start_positions(ck):
     wl = small_workload("km0", "bf16", 8, 2, (900,), (710,), 24, 0, 4, 64, 32, 1)
     bt = gen_batch(wl, full_walk=True)
