@@ -217,6 +217,15 @@ int ctkvr_profile_enable(ctkvr_index *idx, int32_t max_steps);
  * their number in *n_steps and restarts recording at step 0. */
 int ctkvr_profile_collect(ctkvr_index *idx, float *ms_host, int32_t capacity_steps, int32_t *n_steps);
 
+/* Self-check of the fixed-point exponential that the softmax denominators are summed in (the
+ * integer S of the score normalisation, Algorithm 1 line 2 and Algorithm 2 line 6): the library
+ * holds it in two forms, a branching one and a straight-line one for the matrix-core pass, which
+ * must agree bit for bit.  Evaluates both on the device for EVERY fp32 value in [-32, 0] (about
+ * 1.1e9 inputs, -0 and +0 included), synchronises, and stores the number of inputs on which they
+ * differ in *mismatches_host (HOST; 0 is the only acceptable value).  Allocates and frees 8 bytes
+ * of device memory.  Returns a status code. */
+int ctkvr_selftest_exp(uint64_t *mismatches_host, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

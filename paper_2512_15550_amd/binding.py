@@ -75,7 +75,8 @@ _lib = None
 
 EXPORTS = ["ctkvr_build_index", "ctkvr_index_load", "ctkvr_decode_step", "ctkvr_free", "ctkvr_last_error",
            "ctkvr_index_info", "ctkvr_index_lists", "ctkvr_index_centroids", "ctkvr_index_last_candidates",
-           "ctkvr_profile_enable", "ctkvr_profile_collect", "ctkvr_centroid_update", "ctkvr_decode_step_window"]
+           "ctkvr_profile_enable", "ctkvr_profile_collect", "ctkvr_centroid_update", "ctkvr_decode_step_window",
+           "ctkvr_selftest_exp"]
 N_STAGES = 9
 STAGE_NAMES = ["centroid_cos", "recall_gather", "score", "denom", "keyhist", "classify",
                "rerank_select", "sparse_attn", "null"]
@@ -118,6 +119,8 @@ def load_library() -> ctypes.CDLL:
     L.ctkvr_profile_enable.argtypes = [vp, ctypes.c_int32]
     L.ctkvr_profile_collect.restype = ctypes.c_int
     L.ctkvr_profile_collect.argtypes = [vp, vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
+    L.ctkvr_selftest_exp.restype = ctypes.c_int
+    L.ctkvr_selftest_exp.argtypes = [ctypes.POINTER(ctypes.c_uint64), vp]
     _lib = L
     return L
 
@@ -279,3 +282,10 @@ def ctkvr_profile_collect(idx: Index, capacity_steps: int) -> np.ndarray:
     n = ctypes.c_int32(0)
     _check(load_library().ctkvr_profile_collect(idx.handle, out.ctypes.data, int(capacity_steps), ctypes.byref(n)))
     return out[:n.value]
+
+
+def ctkvr_selftest_exp() -> int:
+    """Number of fp32 inputs in [-32, 0] on which the library's two forms of the fixed-point exponential differ."""
+    n = ctypes.c_uint64(0)
+    _check(load_library().ctkvr_selftest_exp(ctypes.byref(n), _stream()))
+    return int(n.value)

@@ -1005,6 +1005,26 @@ int ctkvr_profile_collect(ctkvr_index *idx, float *ms_host, int32_t capacity_ste
     return CTKVR_OK;
 }
 
+int ctkvr_selftest_exp(uint64_t *mismatches_host, void *stream)
+{
+    if (!mismatches_host) return fail(CTKVR_EINVAL, "NULL argument");
+    hipStream_t st = (hipStream_t)stream;
+    unsigned long long *bad = nullptr;
+    HIP_TRY(hipMalloc(&bad, sizeof(*bad)));
+    fill_u32_kernel<<<1, 64, 0, st>>>((uint32_t *)bad, 0u, 2);
+    // the negative values from -0 down to -32 have the bit patterns 0x80000000 .. 0xC2000000; then +0
+    exp_selftest_kernel<<<4096, 256, 0, st>>>(0x80000000u, 0x42000001u, bad);
+    exp_selftest_kernel<<<1, 256, 0, st>>>(0u, 1u, bad);
+    unsigned long long h = ~0ull;
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipMemcpyAsync(&h, bad, sizeof(h), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    (void)hipFree(bad);
+    if (e != hipSuccess) return fail(CTKVR_EHIP, "exp self-check: %s", hipGetErrorString(e));
+    *mismatches_host = h;
+    return CTKVR_OK;
+}
+
 int ctkvr_index_info(const ctkvr_index *idx, ctkvr_index_info_t *out)
 {
     if (!idx || !out) return fail(CTKVR_EINVAL, "NULL argument");

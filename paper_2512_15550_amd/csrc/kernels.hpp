@@ -752,6 +752,22 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
 }
 
 // ------------------------------------------------------------------------------
+// self-check: to_fixed40(exp_series(x)) against exp_fixed40_parts(x) on the fp32 values whose bit
+// patterns are first .. first + n - 1; counts the inputs on which they differ.
+// ------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void exp_selftest_kernel(uint32_t first, uint32_t n, unsigned long long *bad)
+{
+    uint32_t mine = 0;
+    for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < n; i += gridDim.x * 256u) {
+        const float x = __uint_as_float(first + i);
+        uint32_t hi, lo;
+        exp_fixed40_parts(x, hi, lo);
+        mine += (to_fixed40(exp_series(x)) != (((uint64_t)hi << 24) + lo)) ? 1u : 0u;
+    }
+    if (mine) atomicAdd(bad, (unsigned long long)mine);
+}
+
+// ------------------------------------------------------------------------------
 // softmax denominators: S[h] += sum_i floor(exp(z[h][i] - m[h]) * 2^40), integer
 // adds, hence the same value in any order.  grid (nbx, units), 256 threads, each
 // block walks chunks of 1024 ids with stride gridDim.x.

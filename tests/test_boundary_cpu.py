@@ -69,6 +69,7 @@ def test_new_entry_points_reject_null_arguments():
     lib = ck.load_library()
     assert lib.ctkvr_decode_step_window(None, None, None, None, None, 0, None, None, None, None, None, None, None) == -1
     assert lib.ctkvr_centroid_update(None, None, None) == -1
+    assert lib.ctkvr_selftest_exp(None, None) == -1
     assert "NULL" in ck.ctkvr_last_error()
 
 

@@ -24,6 +24,11 @@ def _say(msg):
     print(msg, flush=True)
 
 
+def test_both_forms_of_the_fixed_point_exponential_agree_on_every_input(ck):
+    # the branching form (exact build, decode) and the straight-line form (matrix-core SUM pass): all 1.1e9 fp32 values in [-32, 0]
+    assert ck.ctkvr_selftest_exp() == 0
+
+
 SMALL = [
     # name, dtype, h, g, ctx_lens, C, div, C', rho, rho'
     ("g4_bf16", "bf16", 8, 2, (1000,), 24, 0, 4, 96, 64),
