@@ -219,8 +219,8 @@ int ctkvr_profile_collect(ctkvr_index *idx, float *ms_host, int32_t capacity_ste
 
 /* Self-check of the fixed-point exponential that the softmax denominators are summed in (the
  * integer S of the score normalisation, Algorithm 1 line 2 and Algorithm 2 line 6): the library
- * holds it in two forms, a branching one and a straight-line one for the matrix-core pass, which
- * must agree bit for bit.  Evaluates both on the device for EVERY fp32 value in [-32, 0] (about
+ * holds it in two forms, one written out step by step after its definition and the straight-line
+ * one its kernels use, which must agree bit for bit.  Evaluates both on the device for EVERY fp32 value in [-32, 0] (about
  * 1.1e9 inputs, -0 and +0 included), synchronises, and stores the number of inputs on which they
  * differ in *mismatches_host (HOST; 0 is the only acceptable value).  Allocates and frees 8 bytes
  * of device memory.  Returns a status code. */

@@ -805,6 +805,10 @@ template <int G> __global__ __launch_bounds__(256) void denom_kernel(DenomArgs a
     }
     const float *zb = a.z + (size_t)ul * a.l_stride * G;
     for (int c0 = blockIdx.x * 1024; c0 < L; c0 += gridDim.x * 1024) {
+        // four terms per head as 32-bit partial sums (hi < 2^17, lo < 2^24 each), then one 64-bit add
+        uint32_t shi[G], slo[G];
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh) shi[hh] = slo[hh] = 0u;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             int i = c0 + q * 256 + tid;
@@ -812,9 +816,16 @@ template <int G> __global__ __launch_bounds__(256) void denom_kernel(DenomArgs a
                 float zv[G];
                 load_z<G>(zb, i, zv);
 #pragma unroll
-                for (int hh = 0; hh < G; ++hh) acc[hh] += to_fixed40(exp_series(zv[hh] - m[hh]));
+                for (int hh = 0; hh < G; ++hh) {
+                    uint32_t hi, lo;
+                    exp_fixed40_parts(zv[hh] - m[hh], hi, lo);
+                    shi[hh] += hi;
+                    slo[hh] += lo;
+                }
             }
         }
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh) acc[hh] += ((unsigned long long)shi[hh] << 24) + slo[hh];
     }
 #pragma unroll
     for (int hh = 0; hh < G; ++hh) {

@@ -25,7 +25,7 @@ def _say(msg):
 
 
 def test_both_forms_of_the_fixed_point_exponential_agree_on_every_input(ck):
-    # the branching form (exact build, decode) and the straight-line form (matrix-core SUM pass): all 1.1e9 fp32 values in [-32, 0]
+    # the form written after the definition and the straight-line form the kernels use: all 1.1e9 fp32 values in [-32, 0]
     assert ck.ctkvr_selftest_exp() == 0
 
 
