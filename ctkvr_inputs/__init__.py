@@ -251,6 +251,9 @@ def workload(name: str) -> Workload:
         return Workload("paper_llama", "bf16", 32, 8, 128, [32768], [61], 2048, 0, 4, 2560, 1024, 64, page_seed=61)
     if name == "paper_yi":
         return Workload("paper_yi", "bf16", 32, 4, 128, [32768], [62], 2048, 0, 4, 1280, 512, 64, page_seed=62)
+    # The dynamic budget of the appendix comparison at equal sparsity: rho' = 4 % of the context, rho = 2.5 rho'.
+    if name == "paper_budget4":
+        return Workload("paper_budget4", "bf16", 32, 8, 128, [32768], [63], 2048, 0, 4, 3277, 1311, 64, page_seed=63)
     raise KeyError(name)
 
 

@@ -277,6 +277,12 @@ def test_paper_operating_point_yi_shape_sampled(ck):
     _full_size(ck, "paper_yi", steps=[0, 3], n_decode=4)
 
 
+def test_dynamic_budget_four_percent_of_the_context_sampled(ck):
+    """rho' = 0.04 s = 1311 and rho = 2.5 rho' = 3277 at 32K (the budget of the appendix's equal-sparsity comparison):
+    neither is a power of two or a multiple of a tile."""
+    _full_size(ck, "paper_budget4", steps=[0, 3], n_decode=4)
+
+
 # --------------------------------------------------------------------------- #
 # matrix-core list build (Algorithm 1 lines 2-4 with the dot products on MFMA)
 # --------------------------------------------------------------------------- #
