@@ -322,6 +322,25 @@ def test_mfma_build_is_bit_exact_on_lattice_inputs(ck):
     ck.ctkvr_free(idx)
 
 
+@pytest.mark.parametrize("s,h,g", [(2500, 8, 2), (2501, 4, 2), (1999, 8, 1)])
+def test_mfma_build_without_the_resident_window_is_bit_exact_on_lattice_inputs(ck, s, h, g):
+    """Lists that leave out the initial and local keys (Algorithm 1 lines 5-6), by the matrix-core route: row lengths
+    that do and do not allow the 16-byte key stores, window edges inside a group of four keys, group sizes 4, 2, 8."""
+    n_init, n_local = 7, 45
+    wl = small_workload("lattice_mfma_win", "bf16", h, g, (s,), (511,), 70, 0, 4, 120, 60, 1)
+    sq = gen_lattice_sequence(511 + s, s, h, g, 128, 70, 1)
+    bt = Batch(wl=wl, seqs=[sq], paged=paginate([sq], wl.page_size, 7))
+    Qc = oracle.centroids_last_c(sq.q_tail, 70)
+    ref = oracle.build_lists(sq.K, Qc, wl.list_len, n_init=n_init, n_local=n_local)
+    db = H.device_batch(bt)
+    idx = ck.ctkvr_build_index(H.params_of(wl, build_algo=ck.BUILD_MFMA, n_init=n_init, n_local=n_local), db.q_prefill,
+                               db.cu_seqlens, True, db.k_pages, db.block_table, db.ctx_lens)
+    got = ck.ctkvr_index_lists(idx)[0]
+    assert got.min() >= n_init and got.max() < s - n_local
+    assert np.array_equal(got, ref)
+    ck.ctkvr_free(idx)
+
+
 @pytest.mark.parametrize("case", [SMALL[0], SMALL[1], SMALL[3], SMALL[4], SMALL[7]],
                          ids=[SMALL[i][0] for i in (0, 1, 3, 4, 7)])
 def test_mfma_build_matches_oracle_up_to_ties(ck, case):
