@@ -607,8 +607,13 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
     const bf16_t *K = (const bf16_t *)a.k.pages;
     constexpr int ROWB = 272;   // bytes per staged key row (256 + padding: fragment reads spread over the banks)
     const int srow = tid >> 3, spart = tid & 7;
-    auto row_at = [&](int t0) {
-        return row_of(a.k.block_table, a.k.max_pages, a.k.page_shift, a.g, b, kv, min(t0 + srow, s - 1));
+    // A row's block-table entry is requested four steps ahead and turned into the row only when
+    // the row itself is requested: computing it at once would wait for the entry, and with it for
+    // every key request still in flight.
+    const int32_t *bt_row = a.k.block_table + (size_t)b * a.k.max_pages;
+    auto page_at = [&](int t0) { return bt_row[min(t0 + srow, s - 1) >> a.k.page_shift]; };
+    auto row_from = [&](int page, int t0) {
+        return (uint32_t)((page * a.g + kv) << a.k.page_shift) + (uint32_t)(min(t0 + srow, s - 1) & ((1 << a.k.page_shift) - 1));
     };
     // staging registers as named variables: an array indexed through the helpers would be kept in
     // private memory, and every request would then be waited for at once to be stored there
@@ -713,30 +718,71 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
             }
         }
     };
-    uint32_t row_a = row_at(tbeg + 64), row_b = row_at(tbeg + 96);   // rows of steps 2 and 3
-    fetch(st0a, st0b, row_at(tbeg));
-    fetch(st1a, st1b, row_at(tbeg + 32));
-    put(st0a, st0b, 0);
-    __syncthreads();
-    // two steps per trip, so that register sets and buffers are named at compile time; the trips
-    // whose 64 keys all lie in the block's range run without per-lane predicates
-    auto trip = [&](const bool tail, int t0) __attribute__((always_inline)) {
-        // step i (buffer 0): request step i+2 into set 0, the entry of step i+4; write step i+1 to buffer 1
-        fetch(st0a, st0b, row_a);
-        row_a = row_at(t0 + 128);
-        compute(tail, 0, t0);
-        put(st1a, st1b, 1);
-        __syncthreads();
-        // step i+1 (buffer 1): request step i+3 into set 1, the entry of step i+5; write step i+2 to buffer 0
-        fetch(st1a, st1b, row_b);
-        row_b = row_at(t0 + 160);
-        compute(tail, 1, t0 + 32);
+    // The SUM pass has no registers to spare and is bound by its arithmetic: two sets, a step's rows
+    // requested two steps ahead.  The other passes request them four steps ahead (four sets).
+    constexpr bool DEEP = MODE != MFMA_SUM;
+    if constexpr (!DEEP) {
+        int pg_a = page_at(tbeg + 64), pg_b = page_at(tbeg + 96);   // entries of steps 2 and 3
+        fetch(st0a, st0b, row_from(page_at(tbeg), tbeg));
+        fetch(st1a, st1b, row_from(page_at(tbeg + 32), tbeg + 32));
         put(st0a, st0b, 0);
         __syncthreads();
-    };
-    int t0 = tbeg;
-    for (; t0 + 64 <= tend; t0 += 64) trip(false, t0);
-    if (t0 < tend) trip(true, t0);
+        // two steps per trip, so that register sets and buffers are named at compile time; the trips
+        // whose keys all lie in the block's range run without per-lane predicates
+        auto trip = [&](const bool tail, int t0) __attribute__((always_inline)) {
+            // step i (buffer 0): request step i+2 into set 0, the entry of step i+4; write step i+1 to buffer 1
+            fetch(st0a, st0b, row_from(pg_a, t0 + 64));
+            pg_a = page_at(t0 + 128);
+            compute(tail, 0, t0);
+            put(st1a, st1b, 1);
+            __syncthreads();
+            // step i+1 (buffer 1): request step i+3 into set 1, the entry of step i+5; write step i+2 to buffer 0
+            fetch(st1a, st1b, row_from(pg_b, t0 + 96));
+            pg_b = page_at(t0 + 160);
+            compute(tail, 1, t0 + 32);
+            put(st0a, st0b, 0);
+            __syncthreads();
+        };
+        int t0 = tbeg;
+        for (; t0 + 64 <= tend; t0 += 64) trip(false, t0);
+        if (t0 < tend) trip(true, t0);
+    } else {
+        uint4 st2a, st2b, st3a, st3b;
+        int pg_a = page_at(tbeg + 128), pg_b = page_at(tbeg + 160), pg_c = page_at(tbeg + 192), pg_d = page_at(tbeg + 224);
+        fetch(st0a, st0b, row_from(page_at(tbeg), tbeg));
+        fetch(st1a, st1b, row_from(page_at(tbeg + 32), tbeg + 32));
+        fetch(st2a, st2b, row_from(page_at(tbeg + 64), tbeg + 64));
+        fetch(st3a, st3b, row_from(page_at(tbeg + 96), tbeg + 96));
+        put(st0a, st0b, 0);
+        __syncthreads();
+        // four steps per trip.  Step i (set i % 4, buffer i % 2): request step i+4 into the set it
+        // frees and the entry of step i+8, compute, write step i+1 to the other buffer.
+        auto trip = [&](const bool tail, int t0) __attribute__((always_inline)) {
+            fetch(st0a, st0b, row_from(pg_a, t0 + 128));
+            pg_a = page_at(t0 + 256);
+            compute(tail, 0, t0);
+            put(st1a, st1b, 1);
+            __syncthreads();
+            fetch(st1a, st1b, row_from(pg_b, t0 + 160));
+            pg_b = page_at(t0 + 288);
+            compute(tail, 1, t0 + 32);
+            put(st2a, st2b, 0);
+            __syncthreads();
+            fetch(st2a, st2b, row_from(pg_c, t0 + 192));
+            pg_c = page_at(t0 + 320);
+            compute(tail, 0, t0 + 64);
+            put(st3a, st3b, 1);
+            __syncthreads();
+            fetch(st3a, st3b, row_from(pg_d, t0 + 224));
+            pg_d = page_at(t0 + 352);
+            compute(tail, 1, t0 + 96);
+            put(st0a, st0b, 0);
+            __syncthreads();
+        };
+        int t0 = tbeg;
+        for (; t0 + 128 <= tend; t0 += 128) trip(false, t0);
+        if (t0 < tend) trip(true, t0);
+    }
     if constexpr (MODE == MFMA_KEY) return;
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
