@@ -1470,12 +1470,14 @@ __device__ __forceinline__ void attend_unit(const AttnArgs &a, int ul, int slice
     const T *V = (const T *)a.v_pages + slice * 32 + quad * 8;
     // The first 1024 value rows are requested before anything else (rows beyond nsel are valid
     // stale ones whose products get weight 0).
+    // The four row numbers first, then the four rows: taken in turn, each row number would be
+    // waited for together with the row requested just before it.
     Chunk<T> cv[4];
+    uint32_t vrow[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        uint32_t row = row_of(min(u * 256 + rin, a.top_k - 1));
-        cv[u] = load_chunk(V + (size_t)row * kD, 0);
-    }
+    for (int u = 0; u < 4; ++u) vrow[u] = row_of(min(u * 256 + rin, a.top_k - 1));
+#pragma unroll
+    for (int u = 0; u < 4; ++u) cv[u] = load_chunk(V + (size_t)vrow[u] * kD, 0);
     const int nsel = nsel_of();
     if (nsel == 0) {   // nothing recalled: the window alone, or zeros
         if (tid < G * 32) {
@@ -1554,10 +1556,9 @@ __device__ __forceinline__ void attend_unit(const AttnArgs &a, int ul, int slice
     for (int r0 = 0; r0 < nsel; r0 += 1024) {
         if (r0 > 0) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                uint32_t row = row_of(min(r0 + u * 256 + rin, a.top_k - 1));
-                cv[u] = load_chunk(V + (size_t)row * kD, 0);
-            }
+            for (int u = 0; u < 4; ++u) vrow[u] = row_of(min(r0 + u * 256 + rin, a.top_k - 1));
+#pragma unroll
+            for (int u = 0; u < 4; ++u) cv[u] = load_chunk(V + (size_t)vrow[u] * kD, 0);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -1645,8 +1646,14 @@ template <typename T, int G> __global__ __launch_bounds__(1024) void select_attn
         }
         if (threadIdx.x == 0) sa.nsel[ul] = n;
     }
-    // positions beyond n repeat the last pick (or candidate 0 when nothing was recalled: never loaded then)
-    attend_unit<T, G>(a, ul, slice, s_p, [&](int t) { return n > 0 ? rb[s_idx[min(t, n - 1)]] : 0u; },
+    // positions beyond n repeat the last pick; when nothing was recalled every position reads slot 0 of
+    // the row table and then names row 0 of the pool (selects, not a branch: the four row numbers of a
+    // pass are then requested together)
+    attend_unit<T, G>(a, ul, slice, s_p,
+                      [&](int t) {
+                          const uint32_t r = rb[n > 0 ? s_idx[min(t, n - 1)] : 0];
+                          return n > 0 ? r : 0u;
+                      },
                       [&](int t, float(&zv)[G]) { load_z<G>(zb, s_idx[t], zv); }, [&]() { return n; });
 }
 
