@@ -1502,6 +1502,7 @@ __device__ __forceinline__ void attend_unit(const AttnArgs &a, int ul, int slice
             mx[hh] = fmaxf(mx[hh], zv[hh]);
         }
     }
+    CTKVR_STAMP(48);
 #pragma unroll
     for (int hh = 0; hh < G; ++hh) {
         float v = mx[hh];
@@ -1510,6 +1511,7 @@ __device__ __forceinline__ void attend_unit(const AttnArgs &a, int ul, int slice
         if (ln == 0) s_red[wv][hh] = v;
     }
     __syncthreads();
+    CTKVR_STAMP(49);
     if (tid < G) {
         float v = s_red[0][tid];
 #pragma unroll
@@ -1531,6 +1533,7 @@ __device__ __forceinline__ void attend_unit(const AttnArgs &a, int ul, int slice
             sm[hh] += p;
         }
     }
+    CTKVR_STAMP(50);
 #pragma unroll
     for (int hh = 0; hh < G; ++hh) {
         float v = sm[hh];
