@@ -855,19 +855,20 @@ template <int G> __global__ __launch_bounds__(256) void denom_kernel(DenomArgs a
         uint32_t shi[G], slo[G];
 #pragma unroll
         for (int hh = 0; hh < G; ++hh) shi[hh] = slo[hh] = 0u;
+        // the four loads first (ids beyond L read entry L-1 and are left out below): taken one at a
+        // time, each would be waited for before the next is requested
+        float zv[4][G];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) load_z<G>(zb, min(c0 + q * 256 + tid, L - 1), zv[q]);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            int i = c0 + q * 256 + tid;
-            if (i < L) {
-                float zv[G];
-                load_z<G>(zb, i, zv);
+            const bool ok = (c0 + q * 256 + tid) < L;
 #pragma unroll
-                for (int hh = 0; hh < G; ++hh) {
-                    uint32_t hi, lo;
-                    exp_fixed40_parts(zv[hh] - m[hh], hi, lo);
-                    shi[hh] += hi;
-                    slo[hh] += lo;
-                }
+            for (int hh = 0; hh < G; ++hh) {
+                uint32_t hi, lo;
+                exp_fixed40_parts(zv[q][hh] - m[hh], hi, lo);
+                shi[hh] += ok ? hi : 0u;
+                slo[hh] += ok ? lo : 0u;
             }
         }
 #pragma unroll
@@ -943,24 +944,21 @@ template <int G> __global__ __launch_bounds__(1024) void keyhist_kernel(KeyArgs 
         }
     }
     for (int c0 = blockIdx.x * 4096; a.z && c0 < L; c0 += gridDim.x * 4096) {
+        // the four loads first (ids beyond L read entry L-1 and are dropped): see denom_kernel
+        float zv[4][G];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) load_z<G>(zb, min(c0 + q * 1024 + tid, L - 1), zv[q]);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            int i = c0 + q * 1024 + tid;
+            const int i = c0 + q * 1024 + tid;
             if (i < L) {
-                uint32_t ok;
-                if (a.z) {
-                    float zv[G];
-                    load_z<G>(zb, i, zv);
-                    float best = -__builtin_huge_valf();
+                float best = -__builtin_huge_valf();
 #pragma unroll
-                    for (int hh = 0; hh < G; ++hh) best = fmaxf(best, (zv[hh] - m[hh]) - ls[hh]);
-                    ok = ordered_key(best);
-                    // keys of the resident window rank below every other key (the image of -inf)
-                    if (i < a.n_init || i >= L - a.n_local) ok = 0x007fffffu;
-                    kb[i] = ok;
-                } else {   // the keys are there already (matrix-core build): histogram only
-                    ok = kb[i];
-                }
+                for (int hh = 0; hh < G; ++hh) best = fmaxf(best, (zv[q][hh] - m[hh]) - ls[hh]);
+                uint32_t ok = ordered_key(best);
+                // keys of the resident window rank below every other key (the image of -inf)
+                if (i < a.n_init || i >= L - a.n_local) ok = 0x007fffffu;
+                kb[i] = ok;
                 atomicAdd(&s_h[key_bucket(ok)], 1u);
             }
         }
