@@ -834,11 +834,17 @@ template <int G> __global__ __launch_bounds__(256) void denom_kernel(DenomArgs a
     int b, kv, j;
     const int ul = blockIdx.y;
     if (!decode_unit(a.u, ul, b, kv, j)) return;
+    // everything the block needs to know is requested at once (the maxima before L decides whether
+    // the block has work: one round trip instead of three)
+    uint32_t mk[G];
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) mk[hh] = a.m_key[ul * G + hh];
+    const int s_len = a.ctx_lens[b];
+    const int L = a.ncand ? a.ncand[ul] : s_len;
     if (a.gbits) {
-        const int W = (a.ctx_lens[b] + 31) >> 5;
+        const int W = (s_len + 31) >> 5;
         for (int w = blockIdx.x * 256 + threadIdx.x; w < W; w += gridDim.x * 256) a.gbits[(size_t)ul * a.bitmap_words + w] = 0u;
     }
-    const int L = a.ncand ? a.ncand[ul] : a.ctx_lens[b];
     if ((int)blockIdx.x * 1024 >= L) return;
     const int tid = threadIdx.x;
     __shared__ unsigned long long s_acc[4][G];
@@ -846,7 +852,7 @@ template <int G> __global__ __launch_bounds__(256) void denom_kernel(DenomArgs a
     unsigned long long acc[G];
 #pragma unroll
     for (int hh = 0; hh < G; ++hh) {
-        m[hh] = ordered_value(a.m_key[ul * G + hh]);
+        m[hh] = ordered_value(mk[hh]);
         acc[hh] = 0ull;
     }
     const float *zb = a.z + (size_t)ul * a.l_stride * G;
@@ -909,17 +915,22 @@ template <int G> __global__ __launch_bounds__(1024) void keyhist_kernel(KeyArgs 
     int b, kv, j;
     const int ul = blockIdx.y;
     if (!decode_unit(a.u, ul, b, kv, j)) return;
+    const int tid = threadIdx.x;
+    // the unit's statistics are requested together with L, before L decides whether the block has work
+    uint32_t mk[G];
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) mk[hh] = a.z ? a.m_key[ul * G + hh] : 0u;
+    const unsigned long long S_mine = (a.z && tid < G) ? a.S[ul * G + tid] : 1ull;
     const int L = a.ncand ? a.ncand[ul] : a.ctx_lens[b];
     if (a.gcur && blockIdx.x == 0 && threadIdx.x == 0) a.gcur[ul] = 0u;
     if ((int)blockIdx.x * 4096 >= L) return;
     __shared__ uint32_t s_h[kBuckets];
     __shared__ float s_ls[G];
-    const int tid = threadIdx.x;
     for (int w = tid; w < kBuckets; w += 1024) s_h[w] = 0u;
-    if (tid < G) s_ls[tid] = a.z ? (float)log_fixed40(a.S[ul * G + tid]) : 0.0f;
+    if (tid < G) s_ls[tid] = a.z ? (float)log_fixed40(S_mine) : 0.0f;
     float m[G], ls[G];
 #pragma unroll
-    for (int hh = 0; hh < G; ++hh) m[hh] = a.z ? ordered_value(a.m_key[ul * G + hh]) : 0.0f;
+    for (int hh = 0; hh < G; ++hh) m[hh] = a.z ? ordered_value(mk[hh]) : 0.0f;
     __syncthreads();
 #pragma unroll
     for (int hh = 0; hh < G; ++hh) ls[hh] = s_ls[hh];
