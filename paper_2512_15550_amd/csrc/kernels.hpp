@@ -242,18 +242,14 @@ template <int KPT> __global__ __launch_bounds__(256) void recall_gather_kernel(G
             const int4 *s0 = reinterpret_cast<const int4 *>(l0), *s1 = reinterpret_cast<const int4 *>(l1);
             const int rho4 = a.rho >> 2;
             for (int r0 = 0; r0 < rho4; r0 += 64 * 8) {
+                // (entries beyond the list's end re-read its last one and are not marked: a load under
+                // a per-lane condition is waited for before the next is requested)
                 int4 t0[8], t1[8];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int r = r0 + u * 64 + ln;
-                    if (r < rho4) t0[u] = s0[r];
-                }
+                for (int u = 0; u < 8; ++u) t0[u] = s0[min(r0 + u * 64 + ln, rho4 - 1)];
                 if (two) {
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        const int r = r0 + u * 64 + ln;
-                        if (r < rho4) t1[u] = s1[r];
-                    }
+                    for (int u = 0; u < 8; ++u) t1[u] = s1[min(r0 + u * 64 + ln, rho4 - 1)];
                 }
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
