@@ -383,10 +383,10 @@ __device__ int block_select_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t 
     uint32_t kreg[KPT > 0 ? KPT : 1];
     if constexpr (KPT > 0) {
 #pragma unroll
-        for (int it = 0; it < KPT; ++it) {
-            int i = beg + it * 64 + ln;
-            kreg[it] = (i < end) ? key(i) : 0u;
-        }
+        for (int it = 0; it < KPT; ++it) kreg[it] = key(min(beg + it * 64 + ln, n - 1));   // clamped, then masked: the loads go out together
+#pragma unroll
+        for (int it = 0; it < KPT; ++it)
+            if (beg + it * 64 + ln >= end) kreg[it] = 0u;
     }
     // f(i, valid, key) for every slot of this thread, wave-uniform trip count
     auto for_slots = [&](auto f) __attribute__((always_inline)) {
@@ -402,10 +402,10 @@ __device__ int block_select_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t 
             for (int base = beg; base < end; base += 64 * CH) {
                 uint32_t kk[CH];
 #pragma unroll
-                for (int c = 0; c < CH; ++c) {
-                    int i = base + c * 64 + ln;
-                    kk[c] = (i < end) ? key(i) : 0u;
-                }
+                for (int c = 0; c < CH; ++c) kk[c] = key(min(base + c * 64 + ln, n - 1));
+#pragma unroll
+                for (int c = 0; c < CH; ++c)
+                    if (base + c * 64 + ln >= end) kk[c] = 0u;
 #pragma unroll
                 for (int c = 0; c < CH; ++c) {
                     if (base + c * 64 >= end) break;
@@ -750,12 +750,14 @@ __device__ __forceinline__ void block_bisect_topk(KeyFn key, int n, int k, EmitF
         return;
     }
     // slots beyond n hold key 0: below every candidate (candidates are >= 1) and below every real key
+    // (loaded at clamped ids and then masked: a load under a per-lane condition would be waited for
+    // before the next one is requested)
     uint32_t kreg[KPT];
 #pragma unroll
-    for (int it = 0; it < KPT; ++it) {
-        int i = it * NT + tid;
-        kreg[it] = (i < n) ? key(i) : 0u;
-    }
+    for (int it = 0; it < KPT; ++it) kreg[it] = key(min(it * NT + tid, n - 1));
+#pragma unroll
+    for (int it = 0; it < KPT; ++it)
+        if (it * NT + tid >= n) kreg[it] = 0u;
     CTKVR_STAMP(13);
     // two bits per round: the counts for the three candidates T|01, T|10, T|11 (times 2^b) are
     // monotone, so the largest candidate still reaching k keys fixes both bits

@@ -226,7 +226,11 @@ template <int KPT> __global__ __launch_bounds__(256) void recall_gather_kernel(G
         }
     };
     // line 3
-    block_bisect_topk<256, KPT>([&](int j) { return ordered_key(cosv[j]); }, C, a.n_probe, keep, s_sel);
+    // (thousands of centroids: 11-bit radix rounds instead of sixteen rounds of 3 x KPT ballots)
+    if constexpr (KPT > 8)
+        block_select_topk<256, KPT>([&](int j) { return ordered_key(cosv[j]); }, C, a.n_probe, keep, s_sel);
+    else
+        block_bisect_topk<256, KPT>([&](int j) { return ordered_key(cosv[j]); }, C, a.n_probe, keep, s_sel);
     __syncthreads();
     CTKVR_STAMP(9);
     // line 4: this block's share of the probed lists, one list per wave at a time
