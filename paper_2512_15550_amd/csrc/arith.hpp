@@ -836,4 +836,65 @@ __device__ __forceinline__ void block_bisect_topk(KeyFn key, int n, int k, EmitF
     }
 }
 
+// ---- top-k for very small k (k <= 8) by repeated extraction ---------------------------------
+// Same contract as block_bisect_topk.  Each round takes the block-wide maximum of (key, lowest id)
+// (a 64-bit composite: wave reduction, one barrier), records it and retires it in its owner's
+// register; k rounds instead of sixteen rounds of ballot counts.  The picks are then written in
+// ascending id order.  s_tmp: 4 * (NT / 64) words.  Every thread of the block takes part.
+template <int NT, int KPT, typename KeyFn, typename EmitFn>
+__device__ __forceinline__ void block_extract_topk(KeyFn key, int n, int k, EmitFn emit, uint32_t *s_tmp)
+{
+    constexpr int NW = NT / 64, KMAX = 8;
+    const int tid = threadIdx.x, wv = tid >> 6, ln = lane_id();
+    if (k >= n) {
+        for (int i = tid; i < n; i += NT) emit(i, i);
+        return;
+    }
+    uint32_t kreg[KPT];
+#pragma unroll
+    for (int it = 0; it < KPT; ++it) kreg[it] = key(min(it * NT + tid, n - 1));
+#pragma unroll
+    for (int it = 0; it < KPT; ++it)
+        if (it * NT + tid >= n) kreg[it] = 0u;   // below every real key (their images are >= 1)
+    unsigned long long *s_best = reinterpret_cast<unsigned long long *>(s_tmp);
+    uint32_t picks[KMAX];
+#pragma unroll
+    for (int r = 0; r < KMAX; ++r) picks[r] = 0xffffffffu;
+#pragma unroll
+    for (int r = 0; r < KMAX; ++r) {
+        if (r >= k) break;   // uniform
+        unsigned long long best = 0ull;
+#pragma unroll
+        for (int it = 0; it < KPT; ++it) {
+            const unsigned long long c = ((unsigned long long)kreg[it] << 32) | (uint32_t)~(uint32_t)(it * NT + tid);
+            best = c > best ? c : best;
+        }
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) {
+            const unsigned long long other = __shfl_xor(best, o);
+            best = other > best ? other : best;
+        }
+        unsigned long long *buf = s_best + (r & 1) * NW;
+        if (ln == 0) buf[wv] = best;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < NW; ++w) best = buf[w] > best ? buf[w] : best;
+        const uint32_t id = ~(uint32_t)best;
+        picks[r] = id;
+#pragma unroll
+        for (int it = 0; it < KPT; ++it)
+            if ((uint32_t)(it * NT + tid) == id) kreg[it] = 0u;
+    }
+    // thread r < k places pick r: its position is the number of picks with a smaller id
+#pragma unroll
+    for (int r = 0; r < KMAX; ++r) {
+        if (r < k && tid == r) {
+            int pos = 0;
+#pragma unroll
+            for (int q = 0; q < KMAX; ++q) pos += (q < k && picks[q] < picks[r]);
+            emit(pos, (int)picks[r]);
+        }
+    }
+}
+
 }  // namespace ctkvr

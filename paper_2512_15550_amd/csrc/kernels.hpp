@@ -226,8 +226,11 @@ template <int KPT> __global__ __launch_bounds__(256) void recall_gather_kernel(G
         }
     };
     // line 3
-    // (thousands of centroids: 11-bit radix rounds instead of sixteen rounds of 3 x KPT ballots)
-    if constexpr (KPT > 8)
+    // (a handful of probes, the paper's C' = 4: one block-wide maximum per probe; thousands of
+    // centroids: 11-bit radix rounds instead of sixteen rounds of 3 x KPT ballots)
+    if (a.n_probe <= 8)
+        block_extract_topk<256, KPT>([&](int j) { return ordered_key(cosv[j]); }, C, a.n_probe, keep, s_sel);
+    else if constexpr (KPT > 8)
         block_select_topk<256, KPT>([&](int j) { return ordered_key(cosv[j]); }, C, a.n_probe, keep, s_sel);
     else
         block_bisect_topk<256, KPT>([&](int j) { return ordered_key(cosv[j]); }, C, a.n_probe, keep, s_sel);
