@@ -229,6 +229,32 @@ template <int NT> __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v
     return r;
 }
 
+// Two exclusive scans at once (same barriers as one).  s_tmp: 2 * (NT / 64 + 1) words.
+template <int NT>
+__device__ __forceinline__ void block_excl_scan2(uint32_t va, uint32_t vb, uint32_t *s_tmp, uint32_t &ra, uint32_t &rb)
+{
+    constexpr int NW = NT / 64;
+    const uint32_t ia = wave_incl_scan(va), ib = wave_incl_scan(vb);
+    const int w = threadIdx.x >> 6;
+    __syncthreads();
+    if (lane_id() == 63) {
+        s_tmp[w] = ia;
+        s_tmp[NW + 1 + w] = ib;
+    }
+    __syncthreads();
+    if (w == 0) {
+        const uint32_t ta = (lane_id() < NW) ? s_tmp[lane_id()] : 0u, tb = (lane_id() < NW) ? s_tmp[NW + 1 + lane_id()] : 0u;
+        const uint32_t sa = wave_incl_scan(ta), sb = wave_incl_scan(tb);
+        if (lane_id() < NW) {
+            s_tmp[lane_id()] = sa - ta;
+            s_tmp[NW + 1 + lane_id()] = sb - tb;
+        }
+    }
+    __syncthreads();
+    ra = s_tmp[w] + ia - va;
+    rb = s_tmp[NW + 1 + w] + ib - vb;
+}
+
 // ---- block-wide top-k selection ---------------------------------------------------
 // Shared-memory words the selection routines need at `s_hist`: 2048 histogram bins, then
 // [0] lo, [1] hi, [2] bin, [3] remaining, scan scratch, wave counts, and two words at +56.
@@ -532,10 +558,8 @@ __device__ __forceinline__ void block_resolve_emit(uint32_t nb, uint32_t rem, in
         cgt += (uint32_t)__popc(s_gt[w]);
         ceq += (uint32_t)__popc(s_eq[w]);
     }
-    uint32_t tot;
-    uint32_t gt_before = block_excl_scan<NT>(cgt, s_scan, &tot);
-    __syncthreads();
-    uint32_t eq_before = block_excl_scan<NT>(ceq, s_scan, &tot);
+    uint32_t gt_before, eq_before;
+    block_excl_scan2<NT>(cgt, ceq, s_scan, gt_before, eq_before);
     uint32_t pos = gt_before + min(eq_before, need_eq);
     CTKVR_STAMP(38);
     for (int w = w0; w < w1; ++w) {
