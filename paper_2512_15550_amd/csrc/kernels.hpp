@@ -267,11 +267,22 @@ template <int KPT> __global__ __launch_bounds__(256) void recall_gather_kernel(G
                     }
                 }
             }
-        } else {
-#pragma unroll 8
-            for (int r = ln; r < a.rho; r += 64) {
-                mark(l0[r]);
-                if (two) mark(l1[r]);
+        } else {   // list rows not 16-byte aligned: the same rounds with 4-byte loads
+            for (int r0 = 0; r0 < a.rho; r0 += 64 * 8) {
+                int32_t t0[8], t1[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) t0[u] = l0[min(r0 + u * 64 + ln, a.rho - 1)];
+                if (two) {
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) t1[u] = l1[min(r0 + u * 64 + ln, a.rho - 1)];
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    if (r0 + u * 64 + ln < a.rho) {
+                        mark(t0[u]);
+                        if (two) mark(t1[u]);
+                    }
+                }
             }
         }
     }
