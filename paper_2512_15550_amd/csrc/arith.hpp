@@ -57,6 +57,25 @@ __device__ __forceinline__ Chunk<bf16_t> load_chunk(const bf16_t *row, int lane1
     c.w = *reinterpret_cast<const uint4 *>(row + 8 * lane16);
     return c;
 }
+// the same chunks with a non-temporal hint: rows that are read once per step and never again
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ Chunk<float> load_chunk_nt(const float *row, int lane16)
+{
+    const f32x4_t *p = reinterpret_cast<const f32x4_t *>(row + 8 * lane16);
+    const f32x4_t a = __builtin_nontemporal_load(p), b = __builtin_nontemporal_load(p + 1);
+    Chunk<float> c;
+    c.a = make_float4(a.x, a.y, a.z, a.w);
+    c.b = make_float4(b.x, b.y, b.z, b.w);
+    return c;
+}
+__device__ __forceinline__ Chunk<bf16_t> load_chunk_nt(const bf16_t *row, int lane16)
+{
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(row + 8 * lane16));
+    Chunk<bf16_t> c;
+    c.w = make_uint4(v.x, v.y, v.z, v.w);
+    return c;
+}
 __device__ __forceinline__ void unpack(const Chunk<float> &c, float (&x)[8])
 {
     x[0] = c.a.x; x[1] = c.a.y; x[2] = c.a.z; x[3] = c.a.w;

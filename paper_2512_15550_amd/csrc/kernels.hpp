@@ -416,6 +416,7 @@ struct RecallScoreArgs {
     uint32_t *m_key;          // [units][G] ordered-key running max (atomicMax)
     uint32_t *ghist;          // [units][kBuckets] key histogram, cleared here for keyhist
     float scale;
+    int stream_k;             // the keys of all sequences exceed what the memory-side cache holds: load them non-temporal
 };
 
 template <typename T, int G> __global__ __launch_bounds__(256) void recall_score_kernel(RecallScoreArgs a)
@@ -499,8 +500,16 @@ template <typename T, int G> __global__ __launch_bounds__(256) void recall_score
     const int last = (int)n_blk - 1;
     for (int t0 = 0; t0 < (int)n_blk; t0 += TILE) {
         Chunk<T> ck[R];
+        const T *krow[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r) ck[r] = load_chunk(K + (size_t)s_ids[min(t0 + r * 16 + grp, last)] * kD, lane16);
+        for (int r = 0; r < R; ++r) krow[r] = K + (size_t)s_ids[min(t0 + r * 16 + grp, last)] * kD;
+        if (a.stream_k) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) ck[r] = load_chunk_nt(krow[r], lane16);
+        } else {
+#pragma unroll
+            for (int r = 0; r < R; ++r) ck[r] = load_chunk(krow[r], lane16);
+        }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             float kx[8];
