@@ -731,7 +731,9 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
                         if ((t + e) < a.n_init || (t + e) >= s - a.n_local) ok[e] = 0x007fffffu;   // the image of -inf
                     uint32_t *dst = a.kbuf + ((size_t)bkl * a.c_max + j0 + jl) * a.l_stride + t;
                     if (wide) {
-                        *reinterpret_cast<uint4 *>(dst) = make_uint4(ok[0], ok[1], ok[2], ok[3]);
+                        // written once, read much later by other kernels: kept out of the caches that hold the keys
+                        u32x4_t v4 = {ok[0], ok[1], ok[2], ok[3]};
+                        __builtin_nontemporal_store(v4, reinterpret_cast<u32x4_t *>(dst));
                     } else {
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
