@@ -974,9 +974,18 @@ template <int G> __global__ __launch_bounds__(1024) void keyhist_kernel(KeyArgs 
                 for (int e = 0; e < 4; ++e)
                     if (i + e < L) k4[e] = kb[i + e];
             }
+            // The last bucket takes every key below the histogram's range, often most of them: its
+            // count is taken per wave with a ballot (64 lanes adding to one word would be served
+            // one after the other); the other buckets are added to directly.
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (i + e < L) atomicAdd(&s_h[key_bucket(k4[e])], 1u);
+            for (int e = 0; e < 4; ++e) {
+                const bool valid = i + e < L;
+                const uint32_t bk = key_bucket(k4[e]);
+                const bool tail = valid && bk == (uint32_t)(kBuckets - 1);
+                const uint64_t mt = __ballot(tail);
+                if (valid && !tail) atomicAdd(&s_h[bk], 1u);
+                if (mt && lane_id() == 0) atomicAdd(&s_h[kBuckets - 1], (uint32_t)__popcll(mt));
+            }
         }
     }
     for (int c0 = blockIdx.x * 4096; a.z && c0 < L; c0 += gridDim.x * 4096) {
@@ -987,16 +996,19 @@ template <int G> __global__ __launch_bounds__(1024) void keyhist_kernel(KeyArgs 
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int i = c0 + q * 1024 + tid;
-            if (i < L) {
-                float best = -__builtin_huge_valf();
+            const bool valid = i < L;
+            float best = -__builtin_huge_valf();
 #pragma unroll
-                for (int hh = 0; hh < G; ++hh) best = fmaxf(best, (zv[q][hh] - m[hh]) - ls[hh]);
-                uint32_t ok = ordered_key(best);
-                // keys of the resident window rank below every other key (the image of -inf)
-                if (i < a.n_init || i >= L - a.n_local) ok = 0x007fffffu;
-                kb[i] = ok;
-                atomicAdd(&s_h[key_bucket(ok)], 1u);
-            }
+            for (int hh = 0; hh < G; ++hh) best = fmaxf(best, (zv[q][hh] - m[hh]) - ls[hh]);
+            uint32_t ok = ordered_key(best);
+            // keys of the resident window rank below every other key (the image of -inf)
+            if (i < a.n_init || i >= L - a.n_local) ok = 0x007fffffu;
+            if (valid) kb[i] = ok;
+            const uint32_t bk = key_bucket(ok);
+            const bool tail = valid && bk == (uint32_t)(kBuckets - 1);   // counted per wave, as above
+            const uint64_t mt = __ballot(tail);
+            if (valid && !tail) atomicAdd(&s_h[bk], 1u);
+            if (mt && lane_id() == 0) atomicAdd(&s_h[kBuckets - 1], (uint32_t)__popcll(mt));
         }
     }
     __syncthreads();
