@@ -645,9 +645,16 @@ __device__ int block_select_hist(const uint32_t *keys, int n, int k, EmitFn emit
         }
         return v;
     };
+    // A round that lies wholly inside the wave's range takes plain 16-byte loads, all requested
+    // together (a load under a per-lane condition is waited for before the next is requested).
     uint4 kv[CH];
+    if (wide && beg + 256 * CH <= end) {
 #pragma unroll
-    for (int c = 0; c < CH; ++c) kv[c] = load4(beg + 256 * c + 4 * ln);
+        for (int c = 0; c < CH; ++c) kv[c] = *reinterpret_cast<const uint4 *>(keys + beg + 256 * c + 4 * ln);
+    } else {
+#pragma unroll
+        for (int c = 0; c < CH; ++c) kv[c] = load4(beg + 256 * c + 4 * ln);
+    }
     CTKVR_STAMP(32);
     // the bucket of the k-th key, and how many of its keys are still wanted
     {
@@ -689,8 +696,13 @@ __device__ int block_select_hist(const uint32_t *keys, int n, int k, EmitFn emit
     const uint64_t below = (1ull << ln) - 1ull;
     for (int base = beg; base < end; base += 256 * CH) {
         if (base != beg) {
+            if (wide && base + 256 * CH <= end) {
 #pragma unroll
-            for (int c = 0; c < CH; ++c) kv[c] = load4(base + 256 * c + 4 * ln);
+                for (int c = 0; c < CH; ++c) kv[c] = *reinterpret_cast<const uint4 *>(keys + base + 256 * c + 4 * ln);
+            } else {
+#pragma unroll
+                for (int c = 0; c < CH; ++c) kv[c] = load4(base + 256 * c + 4 * ln);
+            }
         }
 #pragma unroll
         for (int c = 0; c < CH; ++c) {
