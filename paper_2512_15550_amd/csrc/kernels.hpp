@@ -963,20 +963,10 @@ template <int G> __global__ __launch_bounds__(1024) void keyhist_kernel(KeyArgs 
     uint32_t *kb = a.kbuf + (size_t)ul * a.l_stride;
     if (!a.z) {   // the keys are there already (matrix-core build): histogram only, four keys per load
         const bool wide = (reinterpret_cast<uintptr_t>(kb) & 15u) == 0;
-        for (int c0 = blockIdx.x * 4096; c0 < L; c0 += gridDim.x * 4096) {
-            const int i = c0 + 4 * tid;
-            uint32_t k4[4] = {0u, 0u, 0u, 0u};
-            if (wide && i + 3 < L) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(kb + i);
-                k4[0] = v.x; k4[1] = v.y; k4[2] = v.z; k4[3] = v.w;
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (i + e < L) k4[e] = kb[i + e];
-            }
-            // The last bucket takes every key below the histogram's range, often most of them: its
-            // count is taken per wave with a ballot (64 lanes adding to one word would be served
-            // one after the other); the other buckets are added to directly.
+        // The last bucket takes every key below the histogram's range, often most of them: its
+        // count is taken per wave with a ballot (64 lanes adding to one word would be served
+        // one after the other); the other buckets are added to directly.
+        auto count4 = [&](const uint32_t(&k4)[4], int i) __attribute__((always_inline)) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const bool valid = i + e < L;
@@ -985,6 +975,37 @@ template <int G> __global__ __launch_bounds__(1024) void keyhist_kernel(KeyArgs 
                 const uint64_t mt = __ballot(tail);
                 if (valid && !tail) atomicAdd(&s_h[bk], 1u);
                 if (mt && lane_id() == 0) atomicAdd(&s_h[kBuckets - 1], (uint32_t)__popcll(mt));
+            }
+        };
+        // four chunks of 4096 keys per trip; when all four lie wholly below L their loads are plain
+        // and go out together
+        const int stride = gridDim.x * 4096;
+        for (int c0 = blockIdx.x * 4096; c0 < L; c0 += 4 * stride) {
+            if (wide && c0 + 3 * stride + 4096 <= L) {
+                uint4 v[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) v[q] = *reinterpret_cast<const uint4 *>(kb + c0 + q * stride + 4 * tid);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t k4[4] = {v[q].x, v[q].y, v[q].z, v[q].w};
+                    count4(k4, c0 + q * stride + 4 * tid);
+                }
+            } else {
+                for (int q = 0; q < 4; ++q) {
+                    const int cq = c0 + q * stride;
+                    if (cq >= L) break;   // uniform
+                    const int i = cq + 4 * tid;
+                    uint32_t k4[4] = {0u, 0u, 0u, 0u};
+                    if (wide && i + 3 < L) {
+                        const uint4 v = *reinterpret_cast<const uint4 *>(kb + i);
+                        k4[0] = v.x; k4[1] = v.y; k4[2] = v.z; k4[3] = v.w;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (i + e < L) k4[e] = kb[i + e];
+                    }
+                    count4(k4, i);
+                }
             }
         }
     }
