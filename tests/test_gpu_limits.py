@@ -74,3 +74,16 @@ def test_largest_group_ragged_batch_with_updates(ck):
     st = H.run_decode_parity(bt, oi, idx, db, update=True)
     _say(f"[g8_all] ok {st}")
     ck.ctkvr_free(idx)
+
+
+def test_few_probes_among_thousands_of_centroids(ck):
+    # C' = 4 of C = 3000 centroids (more than 2048): the one-maximum-per-probe selection with 32 keys per thread
+    wl = small_workload("c3000_p4", "bf16", 2, 1, (3100,), (275,), 3000, 0, 4, 16, 32, 3)
+    bt = gen_batch(wl)
+    oi = H.oracle_index(bt)
+    db = H.device_batch(bt)
+    cen, lst = oi.padded(wl)
+    idx = ck.ctkvr_index_load(H.params_of(wl), db.ctx_lens, cen, lst)
+    st = H.run_decode_parity(bt, oi, idx, db)
+    _say(f"[c3000_p4] ok {st}")
+    ck.ctkvr_free(idx)
