@@ -87,3 +87,17 @@ def test_few_probes_among_thousands_of_centroids(ck):
     st = H.run_decode_parity(bt, oi, idx, db)
     _say(f"[c3000_p4] ok {st}")
     ck.ctkvr_free(idx)
+
+
+def test_fp32_keys_beyond_the_cache_size(ck):
+    # 138 MB of fp32 keys for one KV head: the scoring kernel takes its non-temporal loads in the fp32 form
+    wl = small_workload("f32_stream", "f32", 1, 1, (270000,), (276,), 8, 0, 2, 64, 32, 2)
+    _say("[f32_stream] generating")
+    bt = gen_batch(wl)
+    oi = H.oracle_index(bt)
+    db = H.device_batch(bt)
+    cen, lst = oi.padded(wl)
+    idx = ck.ctkvr_index_load(H.params_of(wl), db.ctx_lens, cen, lst)
+    st = H.run_decode_parity(bt, oi, idx, db)
+    _say(f"[f32_stream] ok {st}")
+    ck.ctkvr_free(idx)
