@@ -41,7 +41,7 @@ def bench_build(args, wl):
     import torch
     import paper_2512_15550_amd as ck
     from ctkvr_inputs import gen_batch
-    from tests import harness as H
+    from ctkvr_inputs import device as H
     K = args.steps if args.steps is not None else 3
     W = min(args.warmup, 1)
     bt = gen_batch(wl, n_decode=1, full_walk=bool(args.kmeans))
@@ -172,7 +172,7 @@ def bench_decode(args, wl, steps, cpu_steps):
     import torch
     import paper_2512_15550_amd as ck
     from ctkvr_inputs import gen_batch
-    from tests import harness as H   # device upload helpers only
+    from ctkvr_inputs import device as H   # device upload helpers; the CPU checker is imported in the cpu_baseline leg only
 
     K = steps if steps is not None else max(1, wl.n_decode)
     W = args.warmup

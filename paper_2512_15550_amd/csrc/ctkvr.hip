@@ -530,8 +530,9 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     Units u = decode_units(ix);
     RecallScoreArgs sa{};
     sa.u = u;
-    {   // key bytes the batch can touch per step; beyond the 256 MB memory-side cache no row survives to the next step,
-        // and a non-temporal hint keeps the centroid table, the lists and the step's own buffers there instead
+    {   // key bytes the batch can touch per step: above 128 MiB (half of the 256 MB memory-side cache) few rows
+        // survive to the next step, and a non-temporal hint keeps the centroid table, the lists and the step's
+        // own buffers cached instead
         size_t kbytes = 0;
         for (int sl : ix->ctx_lens) kbytes += (size_t)sl * p.n_kv_heads * 128 * elem_size(p.dtype);
         sa.stream_k = kbytes > ((size_t)128 << 20);

@@ -77,3 +77,24 @@ def test_fifo_replaces_the_oldest_mapping_first_and_wraps():
         assert np.array_equal(Qc[:, j], sq.q_decode[n])
     # every list stays well-formed: rho ascending distinct ids inside the context
     assert np.all(np.diff(lists, axis=2) > 0) and lists.min() >= 0 and lists.max() < s
+
+
+def test_fewer_recalled_keys_than_rho_repeat_the_last_id():
+    """Reading D-4: a list always holds rho entries.  While every list holds rho distinct ids the
+    recalled set has at least rho keys and the rule cannot fire from a decode step, so it is pinned
+    on a hand-made step result: 5 recalled keys for a list of 8, scores planted so that the order by
+    score differs from the order by id."""
+    g, C, rho, h = 2, 4, 8, 4
+    lists = np.full((g, C, rho), -7, np.int32)
+    Qc = np.zeros((h, C, 128), np.float32)
+    q = np.arange(h * 128, dtype=np.float32).reshape(h, 128)
+    cand = [np.array([3, 10, 11, 40, 90], np.int32), np.array([], np.int32)]
+    key = [np.array([-5.0, -1.0, -9.0, -2.0, -3.0], np.float32), np.array([], np.float32)]
+    res = oracle.DecodeResult(cos_kv=None, probe=None, cand=cand, ncand=np.array([5, 0], np.int32), rerank_key=key,
+                              sel=None, out=None, lse=None)
+    slot = oracle.centroid_update(q, Qc, lists, res, n_updates=6)
+    assert slot == 2
+    assert lists[0, 2].tolist() == [3, 10, 11, 40, 90, 90, 90, 90]     # all five, ascending, the last one repeated
+    assert np.all(lists[1, 2] == -7)                                   # nothing recalled: the list is left alone
+    assert np.all(lists[:, [0, 1, 3]] == -7)
+    assert np.array_equal(Qc[:, 2], q) and not Qc[:, [0, 1, 3]].any()

@@ -86,3 +86,46 @@ def test_kmeanspp_positions_are_distinct_and_seeded():
     c = kmeanspp_for_sequence(sq.q_full, 2, 16, seed=2)
     assert np.array_equal(a, b) and not np.array_equal(a, c)
     assert all(len(set(row.tolist())) == 16 for row in a)
+
+
+def test_tied_centres_send_points_to_the_lowest_id():
+    """Two start positions naming the SAME point give two identical centres: every point is
+    exactly as far from both, and the assignment must go to the lower centre id (a `>=` in the
+    scan would send all of them to the higher one).  The higher one then has no members."""
+    sq = _seq(7, 120, 2, 1)
+    init = np.array([[5, 5, 60]], np.int32)          # centres 0 and 1 coincide
+    _, assign0, _ = oracle.kmeans_centroids(sq.q_full, 1, init, iters=0, dtype="f32")
+    assert not np.any(assign0[0] == 1)
+    assert np.any(assign0[0] == 0) and np.any(assign0[0] == 2)
+    X = oracle.group_points(sq.q_full, 1)[0].astype(np.float64)
+    d0 = np.sum((X - X[5]) ** 2, axis=1)
+    d2 = np.sum((X - X[60]) ** 2, axis=1)
+    assert np.array_equal(assign0[0], np.where(d2 < d0, 2, 0))       # brute force, ties to the lower id
+    # the same with the duplicate in the highest slots: the lower of the two still wins
+    init = np.array([[60, 5, 5]], np.int32)
+    _, assign0, _ = oracle.kmeans_centroids(sq.q_full, 1, init, iters=0, dtype="f32")
+    assert not np.any(assign0[0] == 2)
+    assert np.array_equal(assign0[0], np.where(d2 < d0, 0, 1))
+
+
+def test_a_centre_without_members_keeps_its_position():
+    """The duplicate centre of the case above receives no point; after an update it must still be
+    where it started (not zero, not NaN, not moved to a mean), while its twin has moved to the mean
+    of its members; and it stays there over further iterations as long as it stays empty."""
+    sq = _seq(8, 150, 2, 1)
+    init = np.array([[9, 9, 100]], np.int32)
+    X = oracle.group_points(sq.q_full, 1)[0]
+    for iters in (1, 3):
+        Qc, assign, inertia = oracle.kmeans_centroids(sq.q_full, 1, init, iters=iters, dtype="f32")
+        cent = Qc.transpose(1, 0, 2).reshape(3, -1)
+        assert np.all(np.isfinite(cent))
+        if not np.any(assign[0] == 1):                    # still empty on the final centres
+            assert np.array_equal(cent[1], X[9])
+        assert not np.array_equal(cent[0], X[9])          # the twin took the members and moved
+        assert np.all(inertia[:, 1:] <= inertia[:, :-1] * (1 + 1e-7))
+    _, assign0, _ = oracle.kmeans_centroids(sq.q_full, 1, init, iters=0, dtype="f32")
+    Qc1, _, _ = oracle.kmeans_centroids(sq.q_full, 1, init, iters=1, dtype="f32")
+    cent1 = Qc1.transpose(1, 0, 2).reshape(3, -1)
+    assert np.array_equal(cent1[1], X[9])                 # one update: the empty centre has not moved at all
+    mean0 = X[assign0[0] == 0].astype(np.float64).mean(axis=0)
+    assert np.max(np.abs(cent1[0] - mean0)) <= 2e-6 * max(1.0, np.max(np.abs(mean0)))
