@@ -44,10 +44,11 @@ WALK_STEP = 0.05
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     """Round fp32 to bf16 (nearest even), returned as uint16 bit patterns."""
     x = np.ascontiguousarray(x, dtype=np.float32)
-    u = x.view(np.uint32).astype(np.uint64)
-    lsb = (u >> 16) & 1
-    u = u + 0x7FFF + lsb
-    return (u >> 16).astype(np.uint16)
+    u = x.view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    # no generated value comes near the top of the exponent range, so the 32-bit sum cannot wrap
+    u = u + np.uint32(0x7FFF) + lsb
+    return (u >> np.uint32(16)).astype(np.uint16)
 
 
 def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
@@ -69,14 +70,20 @@ def round_to_dtype(x64: np.ndarray, dtype: str) -> np.ndarray:
 # --------------------------------------------------------------------------- #
 # RoPE (applied to generated vectors; the library itself takes post-RoPE data)
 # --------------------------------------------------------------------------- #
-def rope(x: np.ndarray, pos: np.ndarray, base: float = ROPE_BASE) -> np.ndarray:
-    """Rotate ``x[..., d]`` (fp64) by the angles of positions ``pos`` (broadcast
-    against the leading axes of ``x``), rotate-half pairing."""
-    d = x.shape[-1]
+def rope_tables(pos: np.ndarray, d: int, base: float = ROPE_BASE):
+    """cos and sin of the rotation angles of positions ``pos`` for head dimension ``d`` (fp64)."""
     half = d // 2
     theta = base ** (-2.0 * np.arange(half, dtype=np.float64) / d)
     ang = np.asarray(pos, dtype=np.float64)[..., None] * theta
-    c, s = np.cos(ang), np.sin(ang)
+    return np.cos(ang), np.sin(ang)
+
+
+def rope(x: np.ndarray, pos: np.ndarray, base: float = ROPE_BASE, tables=None) -> np.ndarray:
+    """Rotate ``x[..., d]`` (fp64) by the angles of positions ``pos`` (broadcast
+    against the leading axes of ``x``), rotate-half pairing.  ``tables`` may carry
+    ``rope_tables(pos, d)`` computed once for many calls at the same positions."""
+    half = x.shape[-1] // 2
+    c, s = rope_tables(pos, x.shape[-1], base) if tables is None else tables
     x1, x2 = x[..., :half], x[..., half:]
     return np.concatenate([x1 * c - x2 * s, x2 * c + x1 * s], axis=-1)
 
@@ -98,6 +105,15 @@ class Sequence:
     q_full: Optional[np.ndarray] = None   # [s, h, d] all prefill queries (only if asked for)
 
 
+class _Done:
+    """Result holder for work run in place (short sequences need no thread pool)."""
+    def __init__(self, value):
+        self.value = value
+
+    def result(self):
+        return self.value
+
+
 def gen_sequence(seed: int, s: int, h: int, g: int, d: int, n_tail: int, n_decode: int,
                  dtype: str = "bf16", full_walk: bool = False,
                  walk_step: float = WALK_STEP) -> Sequence:
@@ -116,23 +132,47 @@ def gen_sequence(seed: int, s: int, h: int, g: int, d: int, n_tail: int, n_decod
     rv = np.random.Generator(np.random.Philox(ss_v))
     rq = np.random.Generator(np.random.Philox(ss_q))
 
+    # The draws are taken in a fixed order (keys and values head by head, then the walk of every
+    # query head); rotating and rounding a head's draws does not touch the generators and runs on
+    # a small thread pool for long sequences.
+    from concurrent.futures import ThreadPoolExecutor
+    pool = ThreadPoolExecutor(max_workers=4) if s * d >= (1 << 22) else None
+    run = pool.submit if pool else (lambda f, *a: _Done(f(*a)))
     pos = np.arange(s)
+    ktab = rope_tables(pos, d)
     K = np.empty((g, s, d), dtype=np.float32)
     V = np.empty((g, s, d), dtype=np.float32)
+
+    def put_kv(j, kraw, vraw):
+        K[j] = round_to_dtype(rope(kraw, pos, tables=ktab), dtype)
+        V[j] = round_to_dtype(vraw, dtype)
+
+    jobs = []
     for j in range(g):
-        K[j] = round_to_dtype(rope(rk.standard_normal((s, d)), pos), dtype)
-        V[j] = round_to_dtype(rv.standard_normal((s, d)), dtype)
+        jobs.append(run(put_kv, j, rk.standard_normal((s, d)), rv.standard_normal((s, d))))
+        if len(jobs) >= 6:
+            jobs.pop(0).result()
 
     start = 0 if full_walk else s - n_tail
     n_pos = s + n_decode - start
     qpos = np.arange(start, s + n_decode)
+    qtab = rope_tables(qpos, d)
     q_all = np.empty((n_pos, h, d), dtype=np.float32)
-    for i in range(h):
-        inc = rq.standard_normal((n_pos, d))
+
+    def put_q(i, inc):
         inc[0] *= np.sqrt(1.0 + walk_step * walk_step * start)
         inc[1:] *= walk_step
         w = np.cumsum(inc, axis=0)
-        q_all[:, i, :] = round_to_dtype(rope(w, qpos), dtype)
+        q_all[:, i, :] = round_to_dtype(rope(w, qpos, tables=qtab), dtype)
+
+    for i in range(h):
+        jobs.append(run(put_q, i, rq.standard_normal((n_pos, d))))
+        if len(jobs) >= 6:
+            jobs.pop(0).result()
+    for j in jobs:
+        j.result()
+    if pool:
+        pool.shutdown()
     n_pref = s - start
     q_pref = q_all[:n_pref]
     return Sequence(seed=seed, dtype=dtype, s=s, K=K, V=V,

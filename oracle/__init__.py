@@ -306,6 +306,25 @@ def kmeans_centroids(q_full: np.ndarray, g: int, init_pos: np.ndarray, iters: in
     return Qc, assign, inertia
 
 
+def kmeans_from_centres(q_full: np.ndarray, g: int, Qc0: np.ndarray, iters: int, dtype: str = "bf16"):
+    """The same Lloyd iterations started from explicit centres Qc0 [h][C][d] (per KV head the
+    concatenation of its G heads' rows) instead of prompt positions.  Same returns as
+    kmeans_centroids."""
+    s, h, d = q_full.shape
+    G = h // g
+    C = Qc0.shape[1]
+    X = group_points(q_full, g)
+    Qc = np.empty((h, C, d), np.float32)
+    assign = np.empty((g, s), np.int32)
+    inertia = np.empty((g, iters + 1), np.float64)
+    for kv in range(g):
+        cent = np.ascontiguousarray(np.asarray(Qc0[kv * G:(kv + 1) * G], np.float32).transpose(1, 0, 2).reshape(C, G * d))
+        lib().ctkvr_oracle_kmeans(_f(X[kv]), s, G * d, _f(cent), C, iters, int(dtype == "bf16"), _i(assign[kv]),
+                                  _d(inertia[kv]))
+        Qc[kv * G:(kv + 1) * G] = cent.reshape(C, G, d).transpose(1, 0, 2)
+    return Qc, assign, inertia
+
+
 def num_threads() -> int:
     return int(lib().ctkvr_oracle_num_threads())
 

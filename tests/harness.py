@@ -155,3 +155,75 @@ def run_sampled_parity(bt: Batch, idx, db: DeviceBatch, steps: List[int], n_list
             alphas.append(float(np.mean(nc)) / (wl.n_probe * wl.list_len))
         say(f"  step {st}: all {B} sequences bit-equal, worst rel err so far {worst:.2e}")
     return {"max_rel_err": worst, "alpha": float(np.mean(alphas)), "lists_checked": n_checked}
+
+
+def run_sampled_parity_next(bt: Batch, idx, db: DeviceBatch, steps: List[int], n_init: int = 0, n_local: int = 0,
+                            update: bool = False, say=print) -> dict:
+    """run_sampled_parity for the rows that follow the core path, at sizes where the oracle cannot
+    afford the whole index: the resident window (index built with n_init / n_local; the step attends
+    over the window too) and the dynamic centroid update after every step.  The oracle keeps the
+    lists it knows -- those it has rebuilt because a step probed them, and those an update wrote --
+    and every one of them must equal the GPU's list at the moment it is probed; after the last
+    step the GPU's centroid table and all known lists are compared once more."""
+    import torch
+    import paper_2512_15550_amd as ck
+    wl = bt.wl
+    B, h, g, d = wl.batch, wl.h, wl.g, wl.d
+    Qc = [oracle.centroids_last_c(sq.q_tail, wl.centroids_of(sq.s)).copy() for sq in bt.seqs]
+    Qc0 = [q.copy() for q in Qc]                       # the prompt's centroids: what unknown lists are rebuilt from
+    lists = [np.zeros((g, wl.centroids_of(sq.s), wl.list_len), np.int32) for sq in bt.seqs]
+    known = [np.zeros((g, wl.centroids_of(sq.s)), bool) for sq in bt.seqs]
+    out = torch.empty((B, h, d), dtype=torch.float32, device="cuda")
+    lse = torch.empty((B, h), dtype=torch.float32, device="cuda")
+    sel = torch.empty((B, g, wl.top_k), dtype=torch.int32, device="cuda")
+    ncand = torch.empty((B, g), dtype=torch.int32, device="cuda")
+    probe = torch.empty((B, g, wl.n_probe), dtype=torch.int32, device="cuda")
+    worst, n_updates, n_built = 0.0, 0, 0
+    gl = ck.ctkvr_index_lists(idx)
+    for st in steps:
+        q = np.stack([sq.q_decode[st] for sq in bt.seqs])
+        q_dev = to_dev(q, wl)
+        ck.ctkvr_decode_step(idx, q_dev, db.k_pages, db.v_pages, db.block_table, out, lse, sel, ncand, probe)
+        torch.cuda.synchronize()
+        g_out, g_lse = out.cpu().numpy(), lse.cpu().numpy()
+        g_sel, g_ncand, g_probe = sel.cpu().numpy(), ncand.cpu().numpy(), probe.cpu().numpy()
+        for b, sq in enumerate(bt.seqs):
+            tag = f"step {st} seq {b}"
+            _, pr = oracle.recall(q[b], Qc[b], g, wl.n_probe)
+            assert np.array_equal(g_probe[b], pr), f"{tag}: probed centroids differ"
+            need = np.array([[kv, j] for kv in range(g) for j in pr[kv] if not known[b][kv, j]], np.int32).reshape(-1, 2)
+            if len(need):   # never probed before and not written by an update: still the prompt's list
+                built = oracle.build_lists(sq.K, Qc0[b], wl.list_len, pairs=need, n_init=n_init, n_local=n_local)
+                for (kv, j), row in zip(need, built):
+                    lists[b][kv, j] = row
+                    known[b][kv, j] = True
+                n_built += len(need)
+            for kv in range(g):
+                for j in pr[kv]:
+                    assert np.array_equal(gl[b, kv, j], lists[b][kv, j]), f"{tag}: probed list (kv {kv}, centroid {j}) differs"
+            if n_init + n_local:
+                r = oracle.decode_step_window(q[b], sq.K, sq.V, Qc[b], lists[b], wl.n_probe, wl.top_k, sq.s, n_init, n_local)
+            else:
+                r = oracle.decode_step(q[b], sq.K, sq.V, Qc[b], lists[b], wl.n_probe, wl.top_k)
+            assert np.array_equal(g_ncand[b], r.ncand), f"{tag}: L differs {g_ncand[b]} vs {r.ncand}"
+            assert np.array_equal(g_sel[b], r.sel), f"{tag}: selected ids differ ({int(np.sum(g_sel[b] != r.sel))} slots)"
+            e = rel_err(g_out[b], r.out)
+            assert e <= REL_TOL, f"{tag}: output relative error {e:.3e}"
+            worst = max(worst, e)
+            assert float(np.max(np.abs(g_lse[b] - r.lse) / np.maximum(1.0, np.abs(r.lse)))) <= 1e-4, f"{tag}: lse"
+            if update:
+                slot = oracle.centroid_update(q[b], Qc[b], lists[b], r, n_updates)
+                known[b][:, slot] = True
+        if update:
+            ck.ctkvr_centroid_update(idx, q_dev)
+            n_updates += 1
+            gl = ck.ctkvr_index_lists(idx)
+        say(f"  step {st}: all {B} sequences bit-equal, worst rel err so far {worst:.2e}, {n_built} lists rebuilt so far")
+    if update:
+        cen = ck.ctkvr_index_centroids(idx)
+        for b, sq in enumerate(bt.seqs):
+            Cb = wl.centroids_of(sq.s)
+            ref = f32_to_bf16_bits(Qc[b]) if wl.dtype == "bf16" else Qc[b]
+            assert np.array_equal(cen[b, :, :Cb], ref), f"centroid table of sequence {b} differs after {n_updates} updates"
+            assert np.array_equal(gl[b, :, :Cb][known[b]], lists[b][known[b]]), f"known lists of sequence {b} differ at the end"
+    return {"max_rel_err": worst, "lists_rebuilt": n_built, "updates": n_updates}

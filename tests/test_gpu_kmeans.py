@@ -2,7 +2,9 @@
 against the oracle's Lloyd iterations from the same seeded start positions.
 Bit-exact where the arithmetic is exact (lattice inputs, first update); beyond
 that a tie in the assignment may resolve differently and the runs drift:
-compared through inertia and through the argmin property of the final centres."""
+compared through inertia, and through the argmin property: iteration T of the GPU
+must be one exact Lloyd step of the oracle from the GPU's own centres after
+iteration T-1, except for the centres that a near-tie (brute force, fp64) touches."""
 import numpy as np
 import pytest
 
@@ -26,8 +28,9 @@ def ck():
 def _gpu_kmeans(ck, bt, init_pos, iters, algo=None):
     import torch
     wl = bt.wl
-    db = H.device_batch(bt)
-    qf, cu = H.device_full_queries(bt)
+    if "dev" not in bt.extra:      # one upload per batch, however many builds follow
+        bt.extra["dev"] = (H.device_batch(bt),) + tuple(H.device_full_queries(bt))
+    db, qf, cu = bt.extra["dev"]
     p = H.params_of(wl, centroid_mode=ck.KMEANS, kmeans_iters=iters)
     if algo is not None:
         p.build_algo = algo
@@ -181,3 +184,132 @@ def test_kmeans_argument_errors(ck):
     ip = torch.zeros((1, 2, 8), dtype=torch.int32, device="cuda")
     with pytest.raises(ck.CtkvrError):       # needs all prompt queries
         ck.ctkvr_build_index(p, db.q_prefill, db.cu_seqlens, True, db.k_pages, db.block_table, db.ctx_lens, init_pos=ip)
+
+
+# --------------------------------------------------------------------------- #
+# more than one tile of 128 centres, a ragged last tile, every group size; full size
+# --------------------------------------------------------------------------- #
+def _touched_centres(X, M, rel=1e-5, chunk=8192):
+    """Brute force in fp64: which centres could a point's assignment move to or from when the
+    scores x.m - |m|^2/2 carry an error of up to rel * (|x| |m|_max + |m|_max^2 / 2)?  (The
+    matrix cores accumulate n = 512..1024 exact bf16 products in fp32: the expected rounding is
+    sqrt(n) 2^-24 ~ 2e-6 of |x||m|, the worst case n 2^-24 ~ 6e-5; 1e-5 sits between.)
+    Returns (touched [C] bool, number of ambiguous points, inertia)."""
+    X = np.asarray(X, np.float64)
+    M = np.asarray(M, np.float64)
+    m2 = (M * M).sum(1)
+    mmax = float(np.sqrt(m2.max()))
+    touched = np.zeros(M.shape[0], bool)
+    n_amb, inertia = 0, 0.0
+    for i0 in range(0, X.shape[0], chunk):
+        x = X[i0:i0 + chunk]
+        sc = x @ M.T - 0.5 * m2
+        best = sc.max(1)
+        x2 = (x * x).sum(1)
+        near = sc >= (best - rel * (np.sqrt(x2) * mmax + 0.5 * mmax * mmax))[:, None]
+        amb = near.sum(1) >= 2
+        n_amb += int(amb.sum())
+        touched |= near[amb].any(0)
+        inertia += float(np.maximum(x2 - 2.0 * best, 0.0).sum())
+    return touched, n_amb, inertia
+
+
+def _flat(Qc, kv, G):
+    """[h][C][d] -> the G*d-dimensional centres of KV head kv, [C][G*d]."""
+    return Qc[kv * G:(kv + 1) * G].transpose(1, 0, 2).reshape(Qc.shape[1], -1)
+
+
+def _check_one_lloyd_step(q_full, g, cen_prev, cen_next, tag, max_touched=0.25):
+    """cen_next must be the oracle's Lloyd step from cen_prev for every centre no near-tie touches."""
+    s, h, d = q_full.shape
+    G = h // g
+    ref, _, _ = oracle.kmeans_from_centres(q_full, g, cen_prev, iters=1)
+    stats = []
+    for kv in range(g):
+        X = q_full[:, kv * G:(kv + 1) * G].reshape(s, G * d)
+        touched, n_amb, in_prev = _touched_centres(X, _flat(cen_prev, kv, G))
+        same = np.all(_flat(cen_next, kv, G) == _flat(ref, kv, G), axis=1)
+        bad = np.flatnonzero(~same & ~touched)
+        assert bad.size == 0, f"{tag} kv {kv}: centres {bad[:8].tolist()} differ from the oracle's step with no near-tie in reach"
+        frac = float(touched.mean())
+        assert frac <= max_touched, f"{tag} kv {kv}: {frac:.2%} of the centres lie within the tie band: the check has no teeth"
+        _, _, in_next = _touched_centres(X, _flat(cen_next, kv, G))
+        assert in_next <= in_prev * (1 + 1e-3), f"{tag} kv {kv}: inertia rose {in_prev} -> {in_next}"
+        stats.append((n_amb, int(touched.sum()), int((~same).sum())))
+    return stats
+
+
+def _random_positions(seed, s, g, C):
+    r = np.random.Generator(np.random.Philox(seed))
+    return np.stack([np.sort(r.choice(s, size=C, replace=False)) for _ in range(g)]).astype(np.int32)
+
+
+@pytest.mark.parametrize("h,g,C", [(2, 2, 300), (8, 2, 300), (8, 1, 300), (8, 2, 1100), (8, 1, 1100), (4, 4, 1100)])
+def test_many_centres_first_update_on_lattice_inputs_is_bit_exact(ck, h, g, C):
+    """300 and 1100 centres: three and nine tiles of 128 in the assignment kernel, the last one
+    ragged (44 and 76 centres); group sizes 1, 4 and 8."""
+    s = 6000
+    bt = _lattice_batch(800 + h + g + C, s, h, g, C, 64, 4, 48)
+    sq = bt.seqs[0]
+    init = _random_positions(801 + C, s, g, C)
+    print(f"[kmeans lattice h{h} g{g} C{C}] oracle", flush=True)
+    Qc, _, _ = oracle.kmeans_centroids(sq.q_full, g, init, iters=1)
+    print(f"[kmeans lattice h{h} g{g} C{C}] GPU", flush=True)
+    idx, db, cen = _gpu_kmeans(ck, bt, init[None], 1)
+    ck.ctkvr_free(idx)
+    assert np.array_equal(cen[0], Qc), "centres after the first update differ"
+    assert not np.array_equal(cen[0], np.stack([sq.q_full[init[head // (h // g)], head] for head in range(h)]))
+
+
+@pytest.mark.parametrize("h,g,C", [(8, 2, 300), (8, 1, 1100), (2, 2, 1100)])
+def test_many_centres_every_iteration_is_a_lloyd_step_of_the_previous_centres(ck, h, g, C):
+    """Gaussian random-walk queries: iterations 1, 2 and 5 of the GPU, each checked as ONE oracle step
+    from the GPU's own previous centres (the argmin property, with a band for near-ties)."""
+    s = 6000
+    wl = small_workload(f"km_many_{h}_{g}_{C}", "bf16", h, g, (s,), (760 + C + h,), C, 0, 4, 64, 48, 1)
+    bt = gen_batch(wl, full_walk=True)
+    sq = bt.seqs[0]
+    init = _random_positions(761 + C, s, g, C)
+    cen = {}
+    for iters in (0, 1, 2, 4, 5):
+        idx, _, c = _gpu_kmeans(ck, bt, init[None], iters)
+        ck.ctkvr_free(idx)
+        cen[iters] = c[0]
+    for a, b in ((0, 1), (1, 2), (4, 5)):
+        st = _check_one_lloyd_step(sq.q_full, g, cen[a], cen[b], f"h{h} g{g} C{C} iteration {b}")
+        print(f"[kmeans many h{h} g{g} C{C}] iteration {b}: (ambiguous points, touched centres, differing centres) per KV head {st}", flush=True)
+
+
+def test_cfg5_full_size_lloyd_iterations_sampled(ck):
+    """The index-build benchmark configuration at full size (131072 positions, 32/8 heads, 2048 centres,
+    10 Lloyd iterations), in the launch shape bench.py times.  One KV head is checked on the oracle:
+    the first iteration from the shared start positions, and the tenth as a Lloyd step from the GPU's
+    own centres after nine; the inertia of the GPU's centres tracks the oracle's."""
+    from ctkvr_inputs import workload
+    wl = workload("cfg5")
+    print("[kmeans cfg5] generating all prompt queries", flush=True)
+    bt = gen_batch(wl, n_decode=1, full_walk=True)
+    sq = bt.seqs[0]
+    g, G, C, s = wl.g, wl.h // wl.g, wl.n_centroids, sq.s
+    init = _random_positions(55, s, g, C)
+    cen = {}
+    for iters in (0, 1, 9, 10):
+        print(f"[kmeans cfg5] GPU build with {iters} iterations", flush=True)
+        idx, _, c = _gpu_kmeans(ck, bt, init[None], iters, algo=ck.BUILD_MFMA)
+        ck.ctkvr_free(idx)
+        cen[iters] = c[0]
+    kv = 5
+    qh = np.ascontiguousarray(sq.q_full[:, kv * G:(kv + 1) * G])
+    sl = slice(kv * G, (kv + 1) * G)
+    assert np.array_equal(cen[0][sl], np.stack([sq.q_full[init[kv], kv * G + hh] for hh in range(G)]))
+    print("[kmeans cfg5] oracle: first iteration of one KV head", flush=True)
+    st = _check_one_lloyd_step(qh, 1, cen[0][sl], cen[1][sl], "cfg5 iteration 1", max_touched=0.10)
+    print(f"[kmeans cfg5] iteration 1: (ambiguous points, touched centres, differing centres) {st}", flush=True)
+    _, _, o_in = oracle.kmeans_centroids(qh, 1, init[kv:kv + 1], iters=1)
+    _, _, g_in = _touched_centres(qh.reshape(s, -1), _flat(cen[1][sl], 0, G))
+    assert abs(g_in - o_in[0, 1]) <= 1e-3 * o_in[0, 1], (g_in, o_in)
+    print("[kmeans cfg5] oracle: tenth iteration of the same head from the GPU's ninth", flush=True)
+    st = _check_one_lloyd_step(qh, 1, cen[9][sl], cen[10][sl], "cfg5 iteration 10", max_touched=0.10)
+    print(f"[kmeans cfg5] iteration 10: (ambiguous points, touched centres, differing centres) {st}", flush=True)
+    _, _, in10 = _touched_centres(qh.reshape(s, -1), _flat(cen[10][sl], 0, G))
+    assert in10 < 0.9 * g_in, "ten iterations should have lowered the inertia well below the first"

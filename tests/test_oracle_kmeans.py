@@ -129,3 +129,16 @@ def test_a_centre_without_members_keeps_its_position():
     assert np.array_equal(cent1[1], X[9])                 # one update: the empty centre has not moved at all
     mean0 = X[assign0[0] == 0].astype(np.float64).mean(axis=0)
     assert np.max(np.abs(cent1[0] - mean0)) <= 2e-6 * max(1.0, np.max(np.abs(mean0)))
+
+
+def test_starting_from_explicit_centres_equals_starting_from_their_positions():
+    sq = _seq(9, 400, 4, 2, "bf16")
+    init = kmeanspp_for_sequence(sq.q_full, 2, 10, seed=4)
+    a = oracle.kmeans_centroids(sq.q_full, 2, init, iters=3)
+    Qc0 = np.stack([sq.q_full[init[head // 2], head] for head in range(4)])
+    b = oracle.kmeans_from_centres(sq.q_full, 2, Qc0, iters=3)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    assert np.allclose(a[2], b[2], rtol=1e-12, atol=0)    # the inertia is a threaded fp64 sum: order may differ
+    # and two iterations then one more equal three in one go (the centres are the whole state)
+    mid = oracle.kmeans_from_centres(sq.q_full, 2, Qc0, iters=2)[0]
+    assert np.array_equal(oracle.kmeans_from_centres(sq.q_full, 2, mid, iters=1)[0], a[0])
