@@ -160,6 +160,29 @@ int ctkvr_decode_step_window(ctkvr_index *idx, const void *q, const void *k_page
                              float *out_lse, int32_t *out_sel, int32_t *out_ncand, int32_t *out_probe, void *hip_stream);
 
 /*
+ * ctkvr_decode_step for callers that cannot allocate device memory or tolerate a call that
+ * does (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc):
+ * the same step with the same arguments, results and errors, but every intermediate buffer of
+ * the step (cosines, recall bitmap, recalled ids and rows, logits, ranking keys and their
+ * histogram, the selection's bitmap and list, the selected rows and logits) lives in a static
+ * device array of the library, 16 MiB per GPU, instead of the workspace `idx` owns.  The call
+ * allocates and frees nothing, on the host side of HIP or through it; the array's device
+ * address is looked up on the first call on each device.
+ *   - The step's buffers must fit: about
+ *       units * (l_stride * (12 + 4 G) + 4 C_max + s_max / 8 + top_k * (8 + 4 G) + 30 KiB)
+ *     bytes, units = batch * g (the 32K benchmark workload takes 7.6 MiB).  Larger geometries
+ *     return CTKVR_EUNSUPPORTED before anything is launched.
+ *   - Every call on a GPU shares that GPU's array, whichever index it serves: calls that
+ *     overlap on one GPU (different streams, different threads) race.  The call clears what a
+ *     step expects to find zero, so it may follow a call for any other index.
+ *   - ctkvr_centroid_update and ctkvr_index_last_candidates read the workspace `idx` owns: they
+ *     follow ctkvr_decode_step, not this call.
+ */
+int ctkvr_decode_step_static(ctkvr_index *idx, const void *q, const void *k_pages, const void *v_pages,
+                             const int32_t *block_table, int32_t max_pages, float *out, float *out_lse, int32_t *out_sel,
+                             int32_t *out_ncand, int32_t *out_probe, void *hip_stream);
+
+/*
  * Dynamic centroid update (Algorithm 2 line 12; Section 3.1.2, "Dynamic Centroid Update"),
  * to be called after ctkvr_decode_step with the same q, on the same stream, before the next
  * step: for every sequence and KV head the query vectors of the group's heads replace the

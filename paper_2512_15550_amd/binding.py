@@ -76,7 +76,7 @@ _lib = None
 EXPORTS = ["ctkvr_build_index", "ctkvr_index_load", "ctkvr_decode_step", "ctkvr_free", "ctkvr_last_error",
            "ctkvr_index_info", "ctkvr_index_lists", "ctkvr_index_centroids", "ctkvr_index_last_candidates",
            "ctkvr_profile_enable", "ctkvr_profile_collect", "ctkvr_centroid_update", "ctkvr_decode_step_window",
-           "ctkvr_selftest_exp"]
+           "ctkvr_selftest_exp", "ctkvr_decode_step_static"]
 N_STAGES = 9
 STAGE_NAMES = ["centroid_cos", "recall_gather", "score", "denom", "keyhist", "classify",
                "rerank_select", "sparse_attn", "null"]
@@ -104,6 +104,8 @@ def load_library() -> ctypes.CDLL:
     L.ctkvr_index_load.argtypes = [ctypes.POINTER(_CParams), ip, vp, ip, vp, ctypes.POINTER(ctypes.c_void_p)]
     L.ctkvr_decode_step.restype = ctypes.c_int
     L.ctkvr_decode_step.argtypes = [vp, vp, vp, vp, ip, ctypes.c_int32, fp, fp, ip, ip, ip, vp]
+    L.ctkvr_decode_step_static.restype = ctypes.c_int
+    L.ctkvr_decode_step_static.argtypes = L.ctkvr_decode_step.argtypes
     L.ctkvr_decode_step_window.restype = ctypes.c_int
     L.ctkvr_decode_step_window.argtypes = [vp, vp, vp, vp, ip, ctypes.c_int32, ip, fp, fp, ip, ip, ip, vp]
     L.ctkvr_centroid_update.restype = ctypes.c_int
@@ -216,6 +218,19 @@ def ctkvr_decode_step(idx: Index, q, k_pages, v_pages, block_table, out, out_lse
                              _dev(block_table, torch.int32), int(block_table.shape[1]), _dev(out, torch.float32),
                              _dev(out_lse, torch.float32), _dev(out_sel, torch.int32), _dev(out_ncand, torch.int32),
                              _dev(out_probe, torch.int32), _stream())
+    _check(rc)
+
+
+def ctkvr_decode_step_static(idx: Index, q, k_pages, v_pages, block_table, out, out_lse=None, out_sel=None,
+                             out_ncand=None, out_probe=None) -> None:
+    """The decode step on the library's static scratch array (allocates nothing)."""
+    import torch
+    L = load_library()
+    td = _torch_dtype(idx.params.dtype)
+    rc = L.ctkvr_decode_step_static(idx.handle, _dev(q, td), _dev(k_pages, td), _dev(v_pages, td),
+                                    _dev(block_table, torch.int32), int(block_table.shape[1]), _dev(out, torch.float32),
+                                    _dev(out_lse, torch.float32), _dev(out_sel, torch.int32),
+                                    _dev(out_ncand, torch.int32), _dev(out_probe, torch.int32), _stream())
     _check(rc)
 
 

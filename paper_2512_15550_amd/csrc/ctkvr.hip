@@ -9,6 +9,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <type_traits>
@@ -46,6 +47,50 @@ size_t elem_size(int dtype) { return dtype == CTKVR_BF16 ? 2 : 4; }
 
 }  // namespace
 
+// Scratch of the entry point that allocates nothing (ctkvr_decode_step_static): one array per GPU, held
+// until the process ends.  Host code never uses the array's name as an address: the device address
+// is looked up once per device and kept.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+unsigned char *g_scratch_ptr[kMaxDevices] = {};
+
+// device address of the current device's copy of `scratch`
+int static_scratch(unsigned char **out)
+{
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(CTKVR_EUNSUPPORTED, "device ordinal %d outside 0..%d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        unsigned char *ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(CTKVR_EHIP, "hipGetSymbolAddress returned a null address for the scratch array");
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return CTKVR_OK;
+}
+}  // namespace
+
+// Buffers of one decode step for every (sequence, KV head) unit: everything ctkvr_decode_step
+// writes apart from the caller's outputs.  An index owns one set; the entry point that allocates
+// nothing lays the same set out in the library's static scratch array.
+struct StepWs {
+    float *cos = nullptr;
+    int32_t *probe = nullptr, *cand = nullptr, *ncand = nullptr, *sel = nullptr, *nsel = nullptr;
+    uint32_t *crow = nullptr, *srow = nullptr, *kbuf = nullptr, *gbits = nullptr, *ghist = nullptr;
+    uint32_t *gbm = nullptr, *gcur = nullptr, *ginfo = nullptr;   // classify_kernel's outputs
+    uint2 *glist = nullptr;
+    unsigned long long *S = nullptr;
+    float *z = nullptr, *zsel = nullptr;
+    float *win = nullptr;   // window_attn_kernel's partial results
+    uint32_t *m_key = nullptr;
+};
+
 struct ctkvr_index {
     ctkvr_params p{};
     int G = 0, c_max = 0, s_max = 0, l_stride = 0, page_shift = 0, units = 0;
@@ -58,20 +103,11 @@ struct ctkvr_index {
     float *inv_norm_c = nullptr;
     int32_t *lists = nullptr;
     int32_t *d_ctx_lens = nullptr, *d_n_cent = nullptr;
-    // decode workspace
-    float *cos = nullptr;
-    int32_t *probe = nullptr, *cand = nullptr, *ncand = nullptr, *sel = nullptr, *nsel = nullptr;
-    uint32_t *crow = nullptr, *srow = nullptr, *kbuf = nullptr, *gbits = nullptr, *ghist = nullptr;
-    uint32_t *gbm = nullptr, *gcur = nullptr, *ginfo = nullptr;   // classify_kernel's outputs
-    uint2 *glist = nullptr;
+    StepWs ws;   // decode workspace
     // dynamic centroid update
     uint32_t *d_dcu_count = nullptr;   // updates so far (device side, so that captured graphs replay correctly)
     int32_t *dsel = nullptr, *dnsel = nullptr;   // top-rho ids of the second ranking (only when rho != rho')
     bool have_step = false;
-    unsigned long long *S = nullptr;
-    float *z = nullptr, *zsel = nullptr;
-    float *win = nullptr;   // window_attn_kernel's partial results
-    uint32_t *m_key = nullptr;
     size_t recall_lds = 0, select_lds = 0, attn_lds = 0, build_select_lds = 0;
     size_t fused_lds = 0;   // non-zero: selection and attention run as one launch (select_attn_kernel)
     int sel_bits = 0, build_bits = 0;   // words for the selection's id bitmaps (0: histogram route off)
@@ -148,6 +184,41 @@ int check_params(const ctkvr_params *p, const int32_t *ctx_lens)
     return CTKVR_OK;
 }
 
+// Lays the step's buffers out from `base` (each 256-byte aligned) and returns the bytes they take;
+// with base == nullptr only the size is computed.  The geometry is the index's.
+size_t carve_step_ws(StepWs &w, unsigned char *base, const ctkvr_index *ix)
+{
+    size_t off = 0;
+    auto take = [&](auto **ptr, size_t bytes) {
+        using P = std::remove_reference_t<decltype(**ptr)>;
+        if (base) *ptr = reinterpret_cast<P *>(base + off);
+        off += (std::max<size_t>(bytes, 16) + 255) & ~(size_t)255;
+    };
+    const ctkvr_params &p = ix->p;
+    const size_t U = ix->units, L = ix->l_stride, G = ix->G;
+    take(&w.cos, U * ix->c_max * 4);
+    take(&w.probe, U * p.n_probe * 4);
+    take(&w.cand, U * L * 4);
+    take(&w.ncand, U * 4);
+    take(&w.z, U * L * G * 4);
+    take(&w.m_key, U * G * 4);
+    take(&w.crow, U * L * 4);
+    take(&w.gbits, U * (size_t)((ix->s_max + 31) / 32) * 4);
+    take(&w.kbuf, U * L * 4);
+    take(&w.ghist, U * (size_t)kBuckets * 4);
+    take(&w.gbm, U * (size_t)(2 * ((L + 63) / 64)) * 4);
+    take(&w.glist, U * (size_t)kListCap * 8);
+    take(&w.gcur, U * 4);
+    take(&w.ginfo, U * 16);
+    take(&w.win, U * (size_t)kWinSplit * G * (2 + 128) * 4);
+    take(&w.srow, U * p.top_k * 4);
+    take(&w.S, U * G * 8);
+    take(&w.sel, U * p.top_k * 4);
+    take(&w.zsel, U * p.top_k * G * 4);
+    take(&w.nsel, U * 4);
+    return off;
+}
+
 // allocate everything an index holds; fills the host-side geometry
 int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **out)
 {
@@ -180,31 +251,16 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
     A(&ix->lists, U * ix->c_max * p->list_len * 4);
     A(&ix->d_ctx_lens, (size_t)B * 4);
     A(&ix->d_n_cent, (size_t)B * 4);
-    A(&ix->cos, U * ix->c_max * 4);
-    A(&ix->probe, U * p->n_probe * 4);
-    A(&ix->cand, U * ix->l_stride * 4);
-    A(&ix->ncand, U * 4);
-    A(&ix->z, U * ix->l_stride * ix->G * 4);
-    A(&ix->m_key, U * ix->G * 4);
-    A(&ix->crow, U * ix->l_stride * 4);
-    A(&ix->gbits, U * (size_t)((ix->s_max + 31) / 32) * 4);
-    A(&ix->kbuf, U * ix->l_stride * 4);
-    A(&ix->ghist, U * (size_t)kBuckets * 4);
-    A(&ix->gbm, U * (size_t)(2 * ((ix->l_stride + 63) / 64)) * 4);
-    A(&ix->glist, U * (size_t)kListCap * 8);
-    A(&ix->gcur, U * 4);
-    A(&ix->ginfo, U * 16);
     A(&ix->d_dcu_count, 4);
-    A(&ix->win, U * (size_t)kWinSplit * ix->G * (2 + 128) * 4);
     if (p->list_len != p->top_k) {
         A(&ix->dsel, U * (size_t)p->list_len * 4);
         A(&ix->dnsel, U * 4);
     }
-    A(&ix->srow, U * p->top_k * 4);
-    A(&ix->S, U * ix->G * 8);
-    A(&ix->sel, U * p->top_k * 4);
-    A(&ix->zsel, U * p->top_k * ix->G * 4);
-    A(&ix->nsel, U * 4);
+    {
+        unsigned char *wsmem = nullptr;
+        A(&wsmem, carve_step_ws(ix->ws, nullptr, ix));
+        if (rc == CTKVR_OK) carve_step_ws(ix->ws, wsmem, ix);
+    }
     if (rc != CTKVR_OK) {
         delete ix;
         return rc;
@@ -285,10 +341,10 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
             ix->num_cu = cus;
     }
-    if (e == hipSuccess) e = hipMemset(ix->ghist, 0, U * (size_t)kBuckets * 4);
+    if (e == hipSuccess) e = hipMemset(ix->ws.ghist, 0, U * (size_t)kBuckets * 4);
     if (e == hipSuccess) e = hipMemset(ix->d_dcu_count, 0, 4);
-    if (e == hipSuccess) e = hipMemset(ix->gbits, 0, U * (size_t)ix->bitmap_words * 4);
-    if (e == hipSuccess) e = hipMemset(ix->srow, 0, U * p->top_k * 4);   // always valid rows (see sparse_attn_kernel)
+    if (e == hipSuccess) e = hipMemset(ix->ws.gbits, 0, U * (size_t)ix->bitmap_words * 4);
+    if (e == hipSuccess) e = hipMemset(ix->ws.srow, 0, U * p->top_k * 4);   // always valid rows (see sparse_attn_kernel)
     if (e == hipSuccess) e = hipMemcpy(ix->d_ctx_lens, ix->ctx_lens.data(), (size_t)B * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(ix->d_n_cent, ix->n_cent.data(), (size_t)B * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(ix->lists, 0, U * ix->c_max * p->list_len * 4);
@@ -467,7 +523,7 @@ int build_lists_dispatch(ctkvr_index *ix, const void *k_pages, const int32_t *bt
 }
 
 template <typename T, int G>
-int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const void *v_pages, const int32_t *bt,
+int decode_launch(ctkvr_index *ix, const StepWs &w, const void *q, const void *k_pages, const void *v_pages, const int32_t *bt,
                   int max_pages, const int32_t *cur_lens, float *out, float *out_lse, int32_t *out_sel, int32_t *out_ncand,
                   int32_t *out_probe, hipStream_t st)
 {
@@ -486,7 +542,7 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
         wa.n_init = p.n_init;
         wa.n_local = p.n_local;
         wa.scale = ix->scale;
-        wa.win = ix->win;
+        wa.win = w.win;
         window_attn_kernel<T, G><<<dim3(kWinSplit, U), 256, 0, st>>>(wa);
     }
     CosArgs ca{};
@@ -494,9 +550,9 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     ca.centroids = ix->centroids;
     ca.inv_norm_c = ix->inv_norm_c;
     ca.n_cent = ix->d_n_cent;
-    ca.cos = ix->cos;
-    ca.m_key = ix->m_key;
-    ca.S = ix->S;
+    ca.cos = w.cos;
+    ca.m_key = w.m_key;
+    ca.S = w.S;
     ca.g = p.n_kv_heads;
     ca.h = p.n_q_heads;
     ca.c_max = ix->c_max;
@@ -505,13 +561,13 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     ix->mark(1, st);
 
     GatherArgs ga{};
-    ga.cos = ix->cos;
+    ga.cos = w.cos;
     ga.lists = ix->lists;
     ga.n_cent = ix->d_n_cent;
     ga.ctx_lens = ix->d_ctx_lens;
-    ga.probe = ix->probe;
+    ga.probe = w.probe;
     ga.out_probe = out_probe;
-    ga.gbits = ix->gbits;
+    ga.gbits = w.gbits;
     ga.g = p.n_kv_heads;
     ga.c_max = ix->c_max;
     ga.rho = p.list_len;
@@ -540,16 +596,16 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     sa.q = q;
     sa.k = Paged{k_pages, bt, max_pages, ix->page_shift};
     sa.ctx_lens = ix->d_ctx_lens;
-    sa.gbits = ix->gbits;
+    sa.gbits = w.gbits;
     sa.bitmap_words = ix->bitmap_words;
     sa.l_stride = ix->l_stride;
-    sa.cand = ix->cand;
-    sa.crow = ix->crow;
-    sa.ncand = ix->ncand;
+    sa.cand = w.cand;
+    sa.crow = w.crow;
+    sa.ncand = w.ncand;
     sa.out_ncand = out_ncand;
-    sa.z = ix->z;
-    sa.m_key = ix->m_key;
-    sa.ghist = ix->ghist;
+    sa.z = w.z;
+    sa.m_key = w.m_key;
+    sa.ghist = w.ghist;
     sa.scale = ix->scale;
     {   // enough blocks to fill the chip a few times over (at least 32 per unit, so that the long
         // units of a ragged batch do not set the pace), each owning 8..64 words of the bitmap
@@ -563,12 +619,12 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     DenomArgs da{};
     da.u = u;
     da.ctx_lens = ix->d_ctx_lens;
-    da.ncand = ix->ncand;
+    da.ncand = w.ncand;
     da.l_stride = ix->l_stride;
-    da.z = ix->z;
-    da.m_key = ix->m_key;
-    da.S = ix->S;
-    da.gbits = ix->gbits;
+    da.z = w.z;
+    da.m_key = w.m_key;
+    da.S = w.S;
+    da.gbits = w.gbits;
     da.bitmap_words = ix->bitmap_words;
     const int chunks = (ix->l_stride + 1023) / 1024;
     denom_kernel<G><<<dim3(std::max(1, std::min(chunks, (4 * ix->num_cu + U - 1) / U)), U), 256, 0, st>>>(da);
@@ -577,14 +633,14 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     KeyArgs ka{};
     ka.u = u;
     ka.ctx_lens = ix->d_ctx_lens;
-    ka.ncand = ix->ncand;
+    ka.ncand = w.ncand;
     ka.l_stride = ix->l_stride;
-    ka.z = ix->z;
-    ka.m_key = ix->m_key;
-    ka.S = ix->S;
-    ka.kbuf = ix->kbuf;
-    ka.ghist = ix->ghist;
-    ka.gcur = ix->gcur;
+    ka.z = w.z;
+    ka.m_key = w.m_key;
+    ka.S = w.S;
+    ka.kbuf = w.kbuf;
+    ka.ghist = w.ghist;
+    ka.gcur = w.gcur;
     keyhist_kernel<G><<<dim3(std::max(1, std::min((ix->l_stride + 4095) / 4096, (2 * ix->num_cu + U - 1) / U)), U), 1024, 0, st>>>(ka);
     ix->mark(5, st);
 
@@ -592,16 +648,16 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
         ClassifyArgs ca{};
         ca.u = u;
         ca.ctx_lens = ix->d_ctx_lens;
-        ca.ncand = ix->ncand;
+        ca.ncand = w.ncand;
         ca.l_stride = ix->l_stride;
         ca.top_k = p.top_k;
-        ca.kbuf = ix->kbuf;
-        ca.ghist = ix->ghist;
+        ca.kbuf = w.kbuf;
+        ca.ghist = w.ghist;
         ca.bits_stride = 2 * ((ix->l_stride + 63) / 64);
-        ca.gbm = ix->gbm;
-        ca.glist = ix->glist;
-        ca.gcur = ix->gcur;
-        ca.ginfo = ix->ginfo;
+        ca.gbm = w.gbm;
+        ca.glist = w.glist;
+        ca.gcur = w.gcur;
+        ca.ginfo = w.ginfo;
         classify_kernel<<<dim3(std::max(1, std::min(chunks, (4 * ix->num_cu + U - 1) / U)), U), 256, 0, st>>>(ca);
     }
     ix->mark(6, st);
@@ -609,38 +665,38 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     SelectArgs se{};
     se.u = u;
     se.ctx_lens = ix->d_ctx_lens;
-    se.ncand = ix->ncand;
-    se.cand = ix->cand;
-    se.crow = ix->crow;
+    se.ncand = w.ncand;
+    se.cand = w.cand;
+    se.crow = w.crow;
     se.l_stride = ix->l_stride;
     se.top_k = p.top_k;
-    se.z = ix->z;
-    se.m_key = ix->m_key;
-    se.kbuf = ix->kbuf;
-    se.ghist = ix->ghist;
+    se.z = w.z;
+    se.m_key = w.m_key;
+    se.kbuf = w.kbuf;
+    se.ghist = w.ghist;
     se.bits_words = ix->sel_bits;
     if (ix->sel_bits) {
-        se.gbm = ix->gbm;
-        se.glist = ix->glist;
-        se.ginfo = ix->ginfo;
+        se.gbm = w.gbm;
+        se.glist = w.glist;
+        se.ginfo = w.ginfo;
         se.bits_stride = 2 * ((ix->l_stride + 63) / 64);
     }
-    se.sel = ix->sel;
-    se.srow = ix->srow;
-    se.zsel = ix->zsel;
-    se.nsel = ix->nsel;
+    se.sel = w.sel;
+    se.srow = w.srow;
+    se.zsel = w.zsel;
+    se.nsel = w.nsel;
     se.out_sel = out_sel;
     AttnArgs aa{};
     aa.v_pages = v_pages;
     aa.g = p.n_kv_heads;
     aa.h = p.n_q_heads;
     aa.top_k = p.top_k;
-    aa.srow = ix->srow;
-    aa.nsel = ix->nsel;
-    aa.zsel = ix->zsel;
+    aa.srow = w.srow;
+    aa.nsel = w.nsel;
+    aa.zsel = w.zsel;
     aa.out = out;
     aa.out_lse = out_lse;
-    aa.win = window ? ix->win : nullptr;
+    aa.win = window ? w.win : nullptr;
     if (ix->fused_lds) {
         ix->mark(7, st);   // no separate selection launch: its stage reads as the cost of an event pair
         select_attn_kernel<T, G><<<dim3(4 * U), 1024, ix->fused_lds, st>>>(se, aa);
@@ -651,24 +707,24 @@ int decode_launch(ctkvr_index *ix, const void *q, const void *k_pages, const voi
     }
     ix->mark(8, st);
     if (ix->prof_step < ix->prof_max) {   // a null kernel between two events: what the bracketing itself costs
-        fill_u32_kernel<<<dim3(1), 64, 0, st>>>((uint32_t *)ix->nsel, 0u, 0);
+        fill_u32_kernel<<<dim3(1), 64, 0, st>>>((uint32_t *)w.nsel, 0u, 0);
         ix->mark(9, st);
     }
     if (ix->prof_step < ix->prof_max) ix->prof_step++;
     HIP_TRY(hipGetLastError());
-    ix->have_step = true;
+    ix->have_step = &w == &ix->ws;   // the update reads the index's own workspace
     return CTKVR_OK;
 }
 
 template <typename T>
-int decode_dispatch(ctkvr_index *ix, const void *q, const void *k, const void *v, const int32_t *bt, int mp,
+int decode_dispatch(ctkvr_index *ix, const StepWs &w, const void *q, const void *k, const void *v, const int32_t *bt, int mp,
                     const int32_t *cur, float *out, float *lse, int32_t *sel, int32_t *ncand, int32_t *probe, hipStream_t st)
 {
     switch (ix->G) {
-        case 1: return decode_launch<T, 1>(ix, q, k, v, bt, mp, cur, out, lse, sel, ncand, probe, st);
-        case 2: return decode_launch<T, 2>(ix, q, k, v, bt, mp, cur, out, lse, sel, ncand, probe, st);
-        case 4: return decode_launch<T, 4>(ix, q, k, v, bt, mp, cur, out, lse, sel, ncand, probe, st);
-        default: return decode_launch<T, 8>(ix, q, k, v, bt, mp, cur, out, lse, sel, ncand, probe, st);
+        case 1: return decode_launch<T, 1>(ix, w, q, k, v, bt, mp, cur, out, lse, sel, ncand, probe, st);
+        case 2: return decode_launch<T, 2>(ix, w, q, k, v, bt, mp, cur, out, lse, sel, ncand, probe, st);
+        case 4: return decode_launch<T, 4>(ix, w, q, k, v, bt, mp, cur, out, lse, sel, ncand, probe, st);
+        default: return decode_launch<T, 8>(ix, w, q, k, v, bt, mp, cur, out, lse, sel, ncand, probe, st);
     }
 }
 
@@ -755,8 +811,8 @@ template <typename T, int G> int update_launch(ctkvr_index *ix, const void *q, h
     da.inv_norm_c = ix->inv_norm_c;
     da.lists = ix->lists;
     if (p.list_len == p.top_k) {   // the list is the selection of line 6
-        da.src = ix->sel;
-        da.nsrc = ix->nsel;
+        da.src = ix->ws.sel;
+        da.nsrc = ix->ws.nsel;
         da.src_stride = p.top_k;
     } else {                       // the same ranking once more, with budget rho
         Units u = decode_units(ix);
@@ -764,37 +820,37 @@ template <typename T, int G> int update_launch(ctkvr_index *ix, const void *q, h
         SelectArgs se{};
         se.u = u;
         se.ctx_lens = ix->d_ctx_lens;
-        se.ncand = ix->ncand;
-        se.cand = ix->cand;
+        se.ncand = ix->ws.ncand;
+        se.cand = ix->ws.cand;
         se.l_stride = ix->l_stride;
         se.top_k = p.list_len;
-        se.z = ix->z;
-        se.m_key = ix->m_key;
-        se.kbuf = ix->kbuf;
-        se.ghist = ix->ghist;
+        se.z = ix->ws.z;
+        se.m_key = ix->ws.m_key;
+        se.kbuf = ix->ws.kbuf;
+        se.ghist = ix->ws.ghist;
         se.bits_words = ix->sel_bits;
         se.sel = ix->dsel;
         se.nsel = ix->dnsel;
         se.ids_only = 1;
         if (ix->sel_bits) {
-            fill_u32_kernel<<<dim3((U + 255) / 256), 256, 0, st>>>(ix->gcur, 0u, (size_t)U);
+            fill_u32_kernel<<<dim3((U + 255) / 256), 256, 0, st>>>(ix->ws.gcur, 0u, (size_t)U);
             ClassifyArgs ca{};
             ca.u = u;
             ca.ctx_lens = ix->d_ctx_lens;
-            ca.ncand = ix->ncand;
+            ca.ncand = ix->ws.ncand;
             ca.l_stride = ix->l_stride;
             ca.top_k = p.list_len;
-            ca.kbuf = ix->kbuf;
-            ca.ghist = ix->ghist;
+            ca.kbuf = ix->ws.kbuf;
+            ca.ghist = ix->ws.ghist;
             ca.bits_stride = 2 * ((ix->l_stride + 63) / 64);
-            ca.gbm = ix->gbm;
-            ca.glist = ix->glist;
-            ca.gcur = ix->gcur;
-            ca.ginfo = ix->ginfo;
+            ca.gbm = ix->ws.gbm;
+            ca.glist = ix->ws.glist;
+            ca.gcur = ix->ws.gcur;
+            ca.ginfo = ix->ws.ginfo;
             classify_kernel<<<dim3(std::max(1, std::min(chunks, (4 * ix->num_cu + U - 1) / U)), U), 256, 0, st>>>(ca);
-            se.gbm = ix->gbm;
-            se.glist = ix->glist;
-            se.ginfo = ix->ginfo;
+            se.gbm = ix->ws.gbm;
+            se.glist = ix->ws.glist;
+            se.ginfo = ix->ws.ginfo;
             se.bits_stride = ca.bits_stride;
         }
         rerank_select_kernel<G><<<dim3(U), 1024, ix->select_lds, st>>>(se);
@@ -950,9 +1006,9 @@ int ctkvr_decode_step_window(ctkvr_index *idx, const void *q, const void *k_page
         return fail(CTKVR_EINVAL, "max_pages %d < %d pages of the longest sequence", max_pages, min_pages_needed(idx));
     hipStream_t st = (hipStream_t)hip_stream;
     if (idx->p.dtype == CTKVR_BF16)
-        return decode_dispatch<bf16_t>(idx, q, k_pages, v_pages, block_table, max_pages, cur_lens, out, out_lse, out_sel,
-                                       out_ncand, out_probe, st);
-    return decode_dispatch<float>(idx, q, k_pages, v_pages, block_table, max_pages, cur_lens, out, out_lse, out_sel,
+        return decode_dispatch<bf16_t>(idx, idx->ws, q, k_pages, v_pages, block_table, max_pages, cur_lens, out, out_lse,
+                                       out_sel, out_ncand, out_probe, st);
+    return decode_dispatch<float>(idx, idx->ws, q, k_pages, v_pages, block_table, max_pages, cur_lens, out, out_lse, out_sel,
                                   out_ncand, out_probe, st);
 }
 
@@ -962,6 +1018,36 @@ int ctkvr_decode_step(ctkvr_index *idx, const void *q, const void *k_pages, cons
 {
     return ctkvr_decode_step_window(idx, q, k_pages, v_pages, block_table, max_pages, nullptr, out, out_lse, out_sel,
                                     out_ncand, out_probe, hip_stream);
+}
+
+int ctkvr_decode_step_static(ctkvr_index *idx, const void *q, const void *k_pages, const void *v_pages,
+                             const int32_t *block_table, int32_t max_pages, float *out, float *out_lse, int32_t *out_sel,
+                             int32_t *out_ncand, int32_t *out_probe, void *hip_stream)
+{
+    if (!idx) return fail(CTKVR_EINVAL, "index is NULL");
+    if (!q || !k_pages || !v_pages || !block_table || !out) return fail(CTKVR_EINVAL, "a required pointer is NULL");
+    if (max_pages < min_pages_needed(idx))
+        return fail(CTKVR_EINVAL, "max_pages %d < %d pages of the longest sequence", max_pages, min_pages_needed(idx));
+    StepWs w;
+    const size_t need = carve_step_ws(w, nullptr, idx);
+    if (need > kStaticScratchBytes)
+        return fail(CTKVR_EUNSUPPORTED, "the step's workspace (%zu bytes) exceeds the static scratch of %zu bytes", need,
+                    kStaticScratchBytes);
+    unsigned char *base = nullptr;
+    TRY(static_scratch(&base));
+    carve_step_ws(w, base, idx);
+    hipStream_t st = (hipStream_t)hip_stream;
+    // The array keeps the last call's contents, possibly of another index: what a step expects to find
+    // zero is cleared here (fill kernels, so that a captured call replays correctly): the recall bitmap, and
+    // the selected rows (slots beyond the selection are read as valid row numbers).
+    const size_t nbits = (size_t)idx->units * idx->bitmap_words, nrow = (size_t)idx->units * idx->p.top_k;
+    fill_u32_kernel<<<dim3((unsigned)((nbits + 255) / 256)), 256, 0, st>>>(w.gbits, 0u, nbits);
+    fill_u32_kernel<<<dim3((unsigned)((nrow + 255) / 256)), 256, 0, st>>>(w.srow, 0u, nrow);
+    if (idx->p.dtype == CTKVR_BF16)
+        return decode_dispatch<bf16_t>(idx, w, q, k_pages, v_pages, block_table, max_pages, nullptr, out, out_lse, out_sel,
+                                       out_ncand, out_probe, st);
+    return decode_dispatch<float>(idx, w, q, k_pages, v_pages, block_table, max_pages, nullptr, out, out_lse, out_sel,
+                                  out_ncand, out_probe, st);
 }
 
 int ctkvr_centroid_update(ctkvr_index *idx, const void *q, void *hip_stream)
@@ -1072,7 +1158,7 @@ int ctkvr_index_last_candidates(const ctkvr_index *idx, int32_t *dst_host)
 {
     if (!idx || !dst_host) return fail(CTKVR_EINVAL, "NULL argument");
     HIP_TRY(hipDeviceSynchronize());
-    HIP_TRY(hipMemcpy(dst_host, idx->cand, (size_t)idx->units * idx->l_stride * 4, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(dst_host, idx->ws.cand, (size_t)idx->units * idx->l_stride * 4, hipMemcpyDeviceToHost));
     return CTKVR_OK;
 }
 
