@@ -27,6 +27,17 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 
 
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def step_bytes(wl, C, L_sum_per_seq, e):
     """Algorithmic bytes one decode step must move for one sequence: centroid table
     and inverse norms, the probed lists, each recalled key row once per KV head,
@@ -36,7 +47,7 @@ def step_bytes(wl, C, L_sum_per_seq, e):
             + (L_sum_per_seq + g * wl.top_k) * 4 + g * wl.top_k * d * e + 2 * h * d * 4)
 
 
-def bench_build(args, wl):
+def bench_build(args, wl, emit=True):
     """Index build only (Algorithm 1 lines 1-4): a "step" is one complete build."""
     import torch
     import paper_2512_15550_amd as ck
@@ -48,9 +59,13 @@ def bench_build(args, wl):
     db = H.device_batch(bt)
     res = {}
     if args.kmeans:   # k-means centroid mode: 10 Lloyd iterations from k-means++ positions (drawn on the host, untimed)
-        from ctkvr_inputs.kmeans_init import kmeanspp_for_sequence
+        from ctkvr_inputs.kmeans_init import centroid_positions, kmeanspp_for_sequence
         t0 = time.time()
-        init = np.stack([kmeanspp_for_sequence(sq.q_full, wl.g, wl.centroids_of(sq.s), seed=sq.seed) for sq in bt.seqs])
+        if emit:
+            init = np.stack([kmeanspp_for_sequence(sq.q_full, wl.g, wl.centroids_of(sq.s), seed=sq.seed) for sq in bt.seqs])
+        else:   # riding along in the default line: seeded random start positions (k-means++ takes minutes on the host
+                # and is outside the timed region either way; the Lloyd iterations cost the same from any start)
+            init = np.stack([centroid_positions("random", sq.s, wl.centroids_of(sq.s), wl.g, seed=sq.seed) for sq in bt.seqs])
         t_pp = time.time() - t0
         qf, cu = H.device_full_queries(bt)
         ip = torch.from_numpy(np.ascontiguousarray(init, np.int32)).cuda()
@@ -67,7 +82,8 @@ def bench_build(args, wl):
         lloyd_flops = sum(10 * 2.0 * s * wl.centroids_of(s) * wl.h * wl.d for s in wl.ctx_lens)
         res["kmeans"] = {"build_ms_with_10_lloyd_iterations": res["kmeans10"], "lloyd_ms": lloyd_ms,
                          "assignment_gemm_flops": lloyd_flops, "lloyd_TFLOPs": lloyd_flops / (lloyd_ms * 1e-3) / 1e12,
-                         "kmeanspp_host_s": t_pp}
+                         "lloyd_mfma_frac": lloyd_flops / (lloyd_ms * 1e-3) / 1e12 / 2500.0,
+                         "start_positions": "k-means++ (host)" if emit else "seeded random", "start_positions_host_s": t_pp}
     for name, algo in (("mfma", ck.BUILD_MFMA), ("exact", ck.BUILD_EXACT)):
         p = H.params_of(wl, build_algo=algo)
         for _ in range(W):
@@ -92,6 +108,10 @@ def bench_build(args, wl):
                         {"kernel": "whole build (score GEMM + denominators + selection)", "bound": "mfma", "achieved": tf,
                          "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None}),
            "cpu_baseline": None}
+    if not emit:
+        return {"mfma_build_ms": res["mfma"], "exact_build_ms": res["exact"], "score_gemm_flops": flops,
+                "whole_build_TFLOPs": tf, "whole_build_mfma_frac": tf / 2500.0, "kmeans": res.get("kmeans"),
+                "config": rec["config"]}
     print(json.dumps(rec))
 
 
@@ -113,7 +133,9 @@ def main():
                     help="step time against the number of probed centroids C' or of centroids C, around the paper's own "
                          "operating point (32K, C = 2048, C' = 4, rho = 2.5 rho' = 2560), as in its appendix tables of "
                          "throughput against C and against C'")
-    ap.add_argument("--skip-128k", action="store_true", help="cfg2 only: do not append the 128K workload's figures")
+    ap.add_argument("--skip-128k", action="store_true", help="cfg2 only: do not append the other workloads' figures")
+    ap.add_argument("--repeats", type=int, default=7, help="timed repeats of the K steps (median and p95 are reported)")
+    ap.add_argument("--path", default="", choices=["", "auto", "staged", "fused"], help="how a decode step is launched")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
@@ -159,11 +181,18 @@ def main():
         return bench_build(args, wl)
     rec = bench_decode(args, wl, args.steps, args.cpu_steps)
     if wl.name == "cfg2" and not args.skip_128k:
-        # the metric is quoted at 32K and at 128K: the 128K workload rides along in the same line
+        # the metric is quoted at 32K and at 128K; the ragged batch and the index build ride along in the same line
+        keep = ("value", "us_per_step_p95", "unit", "steps", "repeats", "config", "tokens_per_s", "achieved_GBps", "hbm_frac",
+                "algorithmic_bytes_per_step", "L_recall_mean", "alpha", "index_build_ms", "decode_path", "stage_us",
+                "phase_us_first_block", "roofline")
         r3 = bench_decode(args, workload("cfg3"), args.steps, 0)
-        rec["at_128k"] = {k: r3[k] for k in ("value", "unit", "steps", "config", "tokens_per_s", "achieved_GBps", "hbm_frac",
-                                             "algorithmic_bytes_per_step", "L_recall_mean", "alpha", "index_build_ms",
-                                             "stage_us", "roofline")}
+        rec["at_128k"] = {k: r3[k] for k in keep}
+        r4 = bench_decode(args, workload("cfg4"), args.steps, 0)
+        rec["at_cfg4"] = {k: r4[k] for k in keep}
+        import copy
+        a5 = copy.copy(args)
+        a5.steps, a5.kmeans = 3, True
+        rec["build_cfg5"] = bench_build(a5, workload("cfg5"), emit=False)
     print(json.dumps(rec))
 
 
@@ -192,6 +221,8 @@ def bench_decode(args, wl, steps, cpu_steps):
                                db.k_pages, db.block_table, db.ctx_lens)
     torch.cuda.synchronize()
     build_ms = (time.time() - t0) * 1e3
+    if args.path:
+        ck.ctkvr_index_set_decode_path(idx, {"auto": ck.PATH_AUTO, "staged": ck.PATH_STAGED, "fused": ck.PATH_FUSED}[args.path])
 
     out = torch.empty((B, h, d), dtype=torch.float32, device="cuda")
     ncand = torch.zeros((K, B, g), dtype=torch.int32, device="cuda")
@@ -225,15 +256,27 @@ def bench_decode(args, wl, steps, cpu_steps):
         except Exception as exc:      # capture not possible: time plain launches instead
             print(f"bench.py: graph capture failed ({exc}); timing eager launches", file=sys.stderr)
             graph, mode = None, "eager"
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    if graph is not None:
-        graph.replay()
-    else:
-        run_steps(K)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    us_per_step = dt / K * 1e6
+    # R repeats of the same K steps, each bracketed by a synchronize on both sides (wall clock) and by a pair of
+    # HIP events on the launch stream; value = the median repeat
+    R = max(1, args.repeats)
+    wall, evt = [], []
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(R):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev0.record()
+        if graph is not None:
+            graph.replay()
+        else:
+            run_steps(K)
+        ev1.record()
+        torch.cuda.synchronize()
+        wall.append((time.perf_counter() - t0) / K * 1e6)
+        evt.append(ev0.elapsed_time(ev1) / K * 1e3)
+    ck.ctkvr_index_check(idx)
+    us_per_step = float(np.median(wall))
+    dt = us_per_step * K * 1e-6
+    ev_us = float(np.median(evt))
     out_timed = out.clone()
     L = ncand.cpu().numpy().astype(np.int64)          # [K][B][g]
 
@@ -245,30 +288,47 @@ def bench_decode(args, wl, steps, cpu_steps):
         raise SystemExit("bench.py: timed-region output differs from an eager re-run of the same step")
 
     # ---- per-kernel durations with HIP events on the launch stream, same K steps ----
+    fused = ck.ctkvr_index_decode_path(idx) == ck.PATH_FUSED
     ck.ctkvr_profile_enable(idx, K)
     run_steps(K, record=False)
     stage_ms = ck.ctkvr_profile_collect(idx, K)
     ck.ctkvr_profile_enable(idx, 0)
     stage_us = {n: float(stage_ms[:, i].mean() * 1e3) for i, n in enumerate(ck.STAGE_NAMES)}
+    floor_us = ck.ctkvr_measure_dispatch_floor(200)     # an empty kernel behind another one, in a graph, this run
 
     # ---- bytes --------------------------------------------------------------------
     L_step = L.sum(axis=2)                             # [K][B] recalled keys per sequence (all KV heads)
     bytes_step = np.array([sum(step_bytes(wl, wl.centroids_of(s), int(L_step[k, b]), e)
                                for b, s in enumerate(wl.ctx_lens)) for k in range(K)], dtype=np.float64)
     achieved = float(bytes_step.mean() / (dt / K)) / 1e9
-    score_bytes = float(L.sum(axis=(1, 2)).mean()) * (d * e + 4)   # key row + its physical row index
-    # a pair of events around a kernel that does nothing reads stage_us["null"]; such a kernel, launched
-    # behind another one, lasts NULL_KERNEL_US in a rocprofv3 kernel trace (profiles/decode_*_kernel_trace.md),
-    # the rest is the bracketing's own cost
-    NULL_KERNEL_US = 3.4
-    event_overhead = max(0.0, stage_us["null"] - NULL_KERNEL_US)
-    score_us = max(stage_us["score"] - event_overhead, 1e-3)
-    score_gbps = score_bytes / (score_us * 1e-6) / 1e9
+    phases = None
+    if fused:
+        # ONE launch per step: the dominant kernel is the step.  Its average duration is the event-bracketed time
+        # of the K back-to-back launches of the timed region divided by K, i.e. duration plus the dispatch gap
+        # (floor_us bounds the gap from above), so the rate below is on the low side.
+        kernel, kbytes, k_us, k_between = "decode_fused_kernel", float(bytes_step.mean()), ev_us, ev_us
+        stage_us = {"fused_step": stage_us["centroid_cos"], "null": stage_us["null"]}
+        ck.ctkvr_profile_phases(idx, True)
+        run_steps(min(K, 8), record=False)
+        t = ck.ctkvr_profile_phases(idx, False).astype(np.float64)
+        names = ["cos", "probe+gather", "expand+score", "denominators", "keys+histogram", "classify+attend", "select+merge"]
+        phases = {n: float((t[i + 1] - t[i]) / 100.0) for i, n in enumerate(names)}   # 100 MHz ticks -> us
+        phases["own_work_before_each_barrier"] = [float((t[8 + i] - t[i]) / 100.0) for i in range(6)]
+        phases["detail_us_since_entry"] = {str(i): float((t[i] - t[0]) / 100.0) for i in range(64) if t[i] > 0}
+    else:
+        # a pair of events around a kernel that does nothing reads stage_us["null"]; that kernel itself lasts about
+        # floor_us; the rest is the bracketing's own cost
+        kernel = "recall_score_kernel"
+        kbytes = float(L.sum(axis=(1, 2)).mean()) * (d * e + 4)   # key row + its physical row index
+        event_overhead = max(0.0, stage_us["null"] - floor_us)
+        k_between = stage_us["score"]
+        k_us = max(k_between - event_overhead, 1e-3)
+    k_gbps = kbytes / (k_us * 1e-6) / 1e9
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"traffic_score_{wl.name}.json")
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{kernel}_{wl.name}.json")
     if os.path.exists(tpath):
         with open(tpath) as fh:
-            traffic = json.load(fh).get("traffic_bytes_per_launch")
+            traffic = json.load(fh)
 
     # ---- CPU oracle on a bounded sample (reported baseline) -------------------------
     cpu = None
@@ -306,9 +366,22 @@ def bench_decode(args, wl, steps, cpu_steps):
                     oracle.rerank_attend(qv, sq.K, sq.V, lst, probe, wl.top_k)
                     t_dec += time.perf_counter() - t1
         cpu_us = t_dec / n_cpu * 1e6 * (B / nb)
+        # the same oracle on ONE thread, first step only
+        one = None
+        if lists is not None:
+            nthr = oracle.num_threads()
+            oracle.set_threads(1)
+            t1 = time.perf_counter()
+            for b in range(nb):
+                sq = bt.seqs[b]
+                oracle.decode_step(sq.q_decode[0], sq.K, sq.V, Qc[b], lists[b], wl.n_probe, wl.top_k)
+            one = (time.perf_counter() - t1) * 1e6 * (B / nb)
+            oracle.set_threads(nthr)
         cpu = {"value": cpu_us, "unit": "us/step", "cores": oracle.num_threads(), "kind": "oracle",
+               "one_thread_us_per_step": one, "cpu_model": cpu_model(),
                "sample": f"{n_cpu} decode steps of {wl.name} on {nb} of {B} sequences"
-                         + ("" if nb == B else f", scaled x{B // nb}") + f"; oracle index build {t_obuild:.1f} s not included"}
+                         + ("" if nb == B else f", scaled x{B // nb}") + f"; oracle index build {t_obuild:.1f} s not included"
+                         + ("; one-thread figure from the first step" if one is not None else "")}
 
     rec = {
         "metric": "decode retrieval+sparse-attn us/step (and achieved HBM GB/s)",
@@ -320,15 +393,19 @@ def bench_decode(args, wl, steps, cpu_steps):
                    "centroids": wl.n_centroids or f"ctx/{wl.centroid_div}", "n_probe": wl.n_probe,
                    "list_len": wl.list_len, "top_k": wl.top_k, "launch": mode, "centroid_update": bool(args.dcu),
                    "window": [n_init, n_local]},
+        "us_per_step_p95": float(np.percentile(wall, 95)), "us_per_step_min": float(np.min(wall)), "repeats": R,
+        "us_per_step_repeats": [float(x) for x in wall], "us_per_step_between_events": ev_us,
         "tokens_per_s": B / (dt / K), "tokens_per_s_32_layers": B / (dt / K) / 32,
         "achieved_GBps": achieved, "hbm_frac": achieved / HBM_PEAK_GBPS,
         "algorithmic_bytes_per_step": float(bytes_step.mean()),
         "L_recall_mean": float(L.mean()), "alpha": float(L.mean()) / (wl.n_probe * wl.list_len),
-        "index_build_ms": build_ms, "stage_us": stage_us,
-        "roofline": {"kernel": "recall_score_kernel", "bound": "hbm", "achieved": score_gbps, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": score_gbps / HBM_PEAK_GBPS, "traffic": traffic,
-                     "bytes_per_launch": score_bytes, "avg_us": score_us, "avg_us_between_events": stage_us["score"],
-                     "event_overhead_us": event_overhead},
+        "index_build_ms": build_ms, "decode_path": "fused" if fused else "staged", "stage_us": stage_us,
+        "phase_us_first_block": phases, "dispatch_floor_us": floor_us,
+        "roofline": {"kernel": kernel, "bound": "hbm", "achieved": k_gbps, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": k_gbps / HBM_PEAK_GBPS,
+                     "traffic": traffic.get("traffic_bytes_per_launch") if traffic else None,
+                     "traffic_from_profile": traffic, "bytes_per_launch": kbytes, "avg_us": k_us,
+                     "avg_us_between_events": k_between},
         "cpu_baseline": cpu,
         "input_gen_s": t_gen,
     }

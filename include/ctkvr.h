@@ -240,6 +240,38 @@ int ctkvr_profile_enable(ctkvr_index *idx, int32_t max_steps);
  * their number in *n_steps and restarts recording at step 0. */
 int ctkvr_profile_collect(ctkvr_index *idx, float *ms_host, int32_t capacity_steps, int32_t *n_steps);
 
+/* ---- how a decode step is launched ----------------------------------------- */
+/* Algorithm 2 lines 1-9 run either as a sequence of launches (one per stage; any geometry) or as
+ * ONE launch whose blocks walk the stages together, a fixed group of co-resident blocks per
+ * (sequence, KV head) separated by barriers in device memory (batch * g at most the number of
+ * compute units, and a shared-memory plan that fits; about half the step time at batch 1).  Both
+ * give the same integers bit for bit; outputs agree within rounding.  AUTO takes the single
+ * launch where the geometry allows it.  The single launch needs all its blocks resident at once:
+ * two such steps (two indexes, two streams) must not run on one GPU at the same time -- their
+ * waits are bounded, and an expired wait is reported by ctkvr_index_check -- callers that overlap
+ * steps choose STAGED.  The environment variable CTKVR_DECODE_PATH = staged | fused | auto sets
+ * the default of indexes created afterwards. */
+typedef enum { CTKVR_PATH_AUTO = 0, CTKVR_PATH_STAGED = 1, CTKVR_PATH_FUSED = 2 } ctkvr_decode_path;
+/* Errors: EINVAL (unknown path), EUNSUPPORTED (FUSED on a geometry that does not allow it). */
+int ctkvr_index_set_decode_path(ctkvr_index *idx, int32_t path);
+/* The path the next step will take: CTKVR_PATH_STAGED or CTKVR_PATH_FUSED (negative: error). */
+int ctkvr_index_decode_path(const ctkvr_index *idx);
+/* Synchronises the device and reports whether any single-launch step on `idx` gave up a wait
+ * (CTKVR_EHIP; the index must then be freed) -- CTKVR_OK otherwise. */
+int ctkvr_index_check(ctkvr_index *idx);
+/* Measurement aid for the single launch: with enable != 0 the first block of the first unit
+ * stamps the 100 MHz wall clock at kernel entry and after each of its seven phases (entries 0-7:
+ * when it leaves the phase's barrier) and when its own work of each of the first six phases is
+ * done (entries 8-13: when it arrives at the barrier); the call synchronises and copies the 16
+ * entries of the last step to ticks_host (HOST, may be NULL). */
+int ctkvr_profile_phases(ctkvr_index *idx, int32_t enable, long long *ticks_host);
+
+/* Measurement aid: what a launch costs when the kernel does nothing.  Captures n_launches empty
+ * kernels, one behind the other, in a HIP graph on a stream of its own, replays it once untimed and
+ * once between two events, and stores the microseconds per launch in *us_per_launch_host (HOST).
+ * Creates and destroys a stream, a graph and two events; synchronises that stream only. */
+int ctkvr_measure_dispatch_floor(int32_t n_launches, float *us_per_launch_host, void *hip_stream);
+
 /* Self-check of the fixed-point exponential that the softmax denominators are summed in (the
  * integer S of the score normalisation, Algorithm 1 line 2 and Algorithm 2 line 6): the library
  * holds it in two forms, one written out step by step after its definition and the straight-line

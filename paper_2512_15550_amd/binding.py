@@ -76,7 +76,9 @@ _lib = None
 EXPORTS = ["ctkvr_build_index", "ctkvr_index_load", "ctkvr_decode_step", "ctkvr_free", "ctkvr_last_error",
            "ctkvr_index_info", "ctkvr_index_lists", "ctkvr_index_centroids", "ctkvr_index_last_candidates",
            "ctkvr_profile_enable", "ctkvr_profile_collect", "ctkvr_centroid_update", "ctkvr_decode_step_window",
-           "ctkvr_selftest_exp", "ctkvr_decode_step_static"]
+           "ctkvr_selftest_exp", "ctkvr_decode_step_static", "ctkvr_index_set_decode_path", "ctkvr_index_decode_path",
+           "ctkvr_index_check", "ctkvr_profile_phases", "ctkvr_measure_dispatch_floor"]
+PATH_AUTO, PATH_STAGED, PATH_FUSED = 0, 1, 2
 N_STAGES = 9
 STAGE_NAMES = ["centroid_cos", "recall_gather", "score", "denom", "keyhist", "classify",
                "rerank_select", "sparse_attn", "null"]
@@ -121,6 +123,16 @@ def load_library() -> ctypes.CDLL:
     L.ctkvr_profile_enable.argtypes = [vp, ctypes.c_int32]
     L.ctkvr_profile_collect.restype = ctypes.c_int
     L.ctkvr_profile_collect.argtypes = [vp, vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
+    L.ctkvr_index_set_decode_path.restype = ctypes.c_int
+    L.ctkvr_index_set_decode_path.argtypes = [vp, ctypes.c_int32]
+    L.ctkvr_index_decode_path.restype = ctypes.c_int
+    L.ctkvr_index_decode_path.argtypes = [vp]
+    L.ctkvr_index_check.restype = ctypes.c_int
+    L.ctkvr_index_check.argtypes = [vp]
+    L.ctkvr_profile_phases.restype = ctypes.c_int
+    L.ctkvr_profile_phases.argtypes = [vp, ctypes.c_int32, vp]
+    L.ctkvr_measure_dispatch_floor.restype = ctypes.c_int
+    L.ctkvr_measure_dispatch_floor.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_float), vp]
     L.ctkvr_selftest_exp.restype = ctypes.c_int
     L.ctkvr_selftest_exp.argtypes = [ctypes.POINTER(ctypes.c_uint64), vp]
     _lib = L
@@ -304,3 +316,35 @@ def ctkvr_selftest_exp() -> int:
     n = ctypes.c_uint64(0)
     _check(load_library().ctkvr_selftest_exp(ctypes.byref(n), _stream()))
     return int(n.value)
+
+
+def ctkvr_index_set_decode_path(idx: Index, path: int) -> None:
+    """PATH_AUTO, PATH_STAGED (one launch per stage) or PATH_FUSED (the whole step in one launch)."""
+    _check(load_library().ctkvr_index_set_decode_path(idx.handle, int(path)))
+
+
+def ctkvr_index_decode_path(idx: Index) -> int:
+    rc = load_library().ctkvr_index_decode_path(idx.handle)
+    if rc < 0:
+        _check(rc)
+    return rc
+
+
+def ctkvr_index_check(idx: Index) -> None:
+    """Synchronises; raises if a single-launch step on this index gave up a wait."""
+    _check(load_library().ctkvr_index_check(idx.handle))
+
+
+def ctkvr_profile_phases(idx: Index, enable: bool = True) -> np.ndarray:
+    """The 16 wall-clock stamps (100 MHz ticks) of the last single-launch step's first block (0-7 leaving each
+    phase, 8-13 arriving at each barrier); sets stamping on or off."""
+    out = np.zeros(64, np.int64)
+    _check(load_library().ctkvr_profile_phases(idx.handle, int(bool(enable)), out.ctypes.data))
+    return out
+
+
+def ctkvr_measure_dispatch_floor(n_launches: int = 200) -> float:
+    """Microseconds per launch of a graph of empty kernels launched one behind the other."""
+    us = ctypes.c_float(0.0)
+    _check(load_library().ctkvr_measure_dispatch_floor(int(n_launches), ctypes.byref(us), _stream()))
+    return float(us.value)

@@ -8,6 +8,7 @@
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -17,6 +18,7 @@
 
 #include "kernels.hpp"
 #include "kmeans.hpp"
+#include "fused_args.hpp"
 
 using namespace ctkvr;
 
@@ -89,6 +91,9 @@ struct StepWs {
     float *z = nullptr, *zsel = nullptr;
     float *win = nullptr;   // window_attn_kernel's partial results
     uint32_t *m_key = nullptr;
+    // single-launch step only
+    float *part = nullptr;      // [units][blocks per unit][G][2 + 128] partial attention results
+    uint32_t *bar = nullptr;    // [units][kFusedBarriers] barrier counters, zero between steps
 };
 
 struct ctkvr_index {
@@ -112,6 +117,13 @@ struct ctkvr_index {
     size_t fused_lds = 0;   // non-zero: selection and attention run as one launch (select_attn_kernel)
     int sel_bits = 0, build_bits = 0;   // words for the selection's id bitmaps (0: histogram route off)
     int bitmap_words = 0, recall_split = 1, num_cu = 256;
+    // single-launch step (decode_fused_kernel): blocks per unit (0: the geometry does not allow it), its shared memory,
+    // the path in use (CTKVR_PATH_*), the sticky error word and the phase stamps
+    int fused_bpu = 0, fused_nt = 1024, decode_path = CTKVR_PATH_AUTO;
+    size_t fused_smem = 0;
+    uint32_t *d_err = nullptr;
+    long long *d_prof = nullptr;
+    bool prof_phases = false;
     // per-kernel timing
     std::vector<hipEvent_t> events;
     int prof_max = 0, prof_step = 0;
@@ -216,6 +228,8 @@ size_t carve_step_ws(StepWs &w, unsigned char *base, const ctkvr_index *ix)
     take(&w.sel, U * p.top_k * 4);
     take(&w.zsel, U * p.top_k * G * 4);
     take(&w.nsel, U * 4);
+    take(&w.part, U * (size_t)std::max(1, ix->fused_bpu) * G * (2 + 128) * 4);
+    take(&w.bar, U * (size_t)kFusedBarriers * 4);
     return off;
 }
 
@@ -252,6 +266,35 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
     A(&ix->d_ctx_lens, (size_t)B * 4);
     A(&ix->d_n_cent, (size_t)B * 4);
     A(&ix->d_dcu_count, 4);
+    A(&ix->d_err, 4);
+    A(&ix->d_prof, 64 * 8);
+    {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+            ix->num_cu = cus;
+    }
+    ix->bitmap_words = (ix->s_max + 31) / 32;
+    // The single-launch step needs all its blocks resident at once (one 1024-thread block per CU) and
+    // its shared-memory plan to fit; up to 32 blocks work on a unit.
+    if ((int)U <= ix->num_cu) {
+        const size_t words = fused_smem_words(p->n_probe, ix->bitmap_words, ix->l_stride, p->top_k, ix->G);
+        if (words * 4 <= (size_t)150 * 1024) {
+            ix->fused_bpu = std::max(1, std::min(32, ix->num_cu / (int)U));
+            ix->fused_smem = words * 4;
+            // Few recalled keys per block: four waves walk the serial parts of every phase (selections, scans,
+            // reductions) four times faster than sixteen; many keys per block: sixteen waves keep more rows in flight.
+            ix->fused_nt = ix->l_stride / ix->fused_bpu <= 2048 ? 256 : 1024;
+            if (const char *e = getenv("CTKVR_FUSED_THREADS")) {
+                if (!strcmp(e, "256")) ix->fused_nt = 256;
+                else if (!strcmp(e, "1024")) ix->fused_nt = 1024;
+            }
+        }
+    }
+    if (const char *e = getenv("CTKVR_DECODE_PATH")) {
+        if (!strcmp(e, "staged")) ix->decode_path = CTKVR_PATH_STAGED;
+        else if (!strcmp(e, "fused") && ix->fused_bpu) ix->decode_path = CTKVR_PATH_FUSED;
+    }
     if (p->list_len != p->top_k) {
         A(&ix->dsel, U * (size_t)p->list_len * 4);
         A(&ix->dnsel, U * 4);
@@ -324,6 +367,7 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
             want((const void *)select_attn_kernel<float, 8>, ix->fused_lds);
         }
     }
+    if (ix->fused_bpu && e == hipSuccess) e = fused_set_smem(p->dtype == CTKVR_BF16, ix->G, ix->fused_nt, ix->fused_smem);
     if (p->dtype == CTKVR_BF16) {
         want((const void *)sparse_attn_kernel<bf16_t, 1>, ix->attn_lds);
         want((const void *)sparse_attn_kernel<bf16_t, 2>, ix->attn_lds);
@@ -343,6 +387,10 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
     }
     if (e == hipSuccess) e = hipMemset(ix->ws.ghist, 0, U * (size_t)kBuckets * 4);
     if (e == hipSuccess) e = hipMemset(ix->d_dcu_count, 0, 4);
+    if (e == hipSuccess) e = hipMemset(ix->d_err, 0, 4);
+    if (e == hipSuccess) e = hipMemset(ix->d_prof, 0, 64 * 8);
+    if (e == hipSuccess) e = hipMemset(ix->ws.bar, 0, U * (size_t)kFusedBarriers * 4);
+    if (e == hipSuccess) e = hipMemset(ix->ws.gbm, 0, U * (size_t)(2 * ((ix->l_stride + 63) / 64)) * 4);
     if (e == hipSuccess) e = hipMemset(ix->ws.gbits, 0, U * (size_t)ix->bitmap_words * 4);
     if (e == hipSuccess) e = hipMemset(ix->ws.srow, 0, U * p->top_k * 4);   // always valid rows (see sparse_attn_kernel)
     if (e == hipSuccess) e = hipMemcpy(ix->d_ctx_lens, ix->ctx_lens.data(), (size_t)B * 4, hipMemcpyHostToDevice);
@@ -545,6 +593,75 @@ int decode_launch(ctkvr_index *ix, const StepWs &w, const void *q, const void *k
         wa.win = w.win;
         window_attn_kernel<T, G><<<dim3(kWinSplit, U), 256, 0, st>>>(wa);
     }
+    const bool stream_k = [&] {
+        // key bytes the batch can touch per step: above 128 MiB (half of the 256 MB memory-side cache) few rows
+        // survive to the next step, and a non-temporal hint keeps the centroid table, the lists and the step's
+        // own buffers cached instead
+        size_t kbytes = 0;
+        for (int sl : ix->ctx_lens) kbytes += (size_t)sl * p.n_kv_heads * 128 * elem_size(p.dtype);
+        return kbytes > ((size_t)128 << 20);
+    }();
+    if (ix->fused_bpu && ix->decode_path != CTKVR_PATH_STAGED) {
+        FusedArgs fa{};
+        fa.g = p.n_kv_heads;
+        fa.h = p.n_q_heads;
+        fa.c_max = ix->c_max;
+        fa.rho = p.list_len;
+        fa.n_probe = p.n_probe;
+        fa.top_k = p.top_k;
+        fa.bitmap_words = ix->bitmap_words;
+        fa.l_stride = ix->l_stride;
+        fa.bits_stride = 2 * ((ix->l_stride + 63) / 64);
+        fa.bpu = ix->fused_bpu;
+        fa.units = U;
+        fa.stream_k = stream_k;
+        fa.scale = ix->scale;
+        fa.n_cent = ix->d_n_cent;
+        fa.ctx_lens = ix->d_ctx_lens;
+        fa.q = q;
+        fa.centroids = ix->centroids;
+        fa.inv_norm_c = ix->inv_norm_c;
+        fa.lists = ix->lists;
+        fa.k = Paged{k_pages, bt, max_pages, ix->page_shift};
+        fa.v_pages = v_pages;
+        fa.cos = w.cos;
+        fa.probe = w.probe;
+        fa.out_probe = out_probe;
+        fa.gbits = w.gbits;
+        fa.cand = w.cand;
+        fa.crow = w.crow;
+        fa.ncand = w.ncand;
+        fa.out_ncand = out_ncand;
+        fa.z = w.z;
+        fa.m_key = w.m_key;
+        fa.S = w.S;
+        fa.kbuf = w.kbuf;
+        fa.ghist = w.ghist;
+        fa.gbm = w.gbm;
+        fa.glist = w.glist;
+        fa.gcur = w.gcur;
+        fa.part = w.part;
+        fa.sel = w.sel;
+        fa.nsel = w.nsel;
+        fa.out_sel = out_sel;
+        fa.out = out;
+        fa.out_lse = out_lse;
+        fa.win = window ? w.win : nullptr;
+        fa.bar = w.bar;
+        fa.err = ix->d_err;
+        fa.prof = ix->prof_phases ? ix->d_prof : nullptr;
+        ix->mark(0, st);
+        HIP_TRY(fused_launch(p.dtype == CTKVR_BF16, G, ix->fused_nt, (unsigned)(U * ix->fused_bpu), ix->fused_smem, st, fa));
+        for (int k = 1; k <= 8; ++k) ix->mark(k, st);   // the whole step reads as stage 0
+        if (ix->prof_step < ix->prof_max) {
+            fill_u32_kernel<<<dim3(1), 64, 0, st>>>((uint32_t *)w.nsel, 0u, 0);
+            ix->mark(9, st);
+            ix->prof_step++;
+        }
+        HIP_TRY(hipGetLastError());
+        ix->have_step = &w == &ix->ws;
+        return CTKVR_OK;
+    }
     CosArgs ca{};
     ca.q = q;
     ca.centroids = ix->centroids;
@@ -586,13 +703,7 @@ int decode_launch(ctkvr_index *ix, const StepWs &w, const void *q, const void *k
     Units u = decode_units(ix);
     RecallScoreArgs sa{};
     sa.u = u;
-    {   // key bytes the batch can touch per step: above 128 MiB (half of the 256 MB memory-side cache) few rows
-        // survive to the next step, and a non-temporal hint keeps the centroid table, the lists and the step's
-        // own buffers cached instead
-        size_t kbytes = 0;
-        for (int sl : ix->ctx_lens) kbytes += (size_t)sl * p.n_kv_heads * 128 * elem_size(p.dtype);
-        sa.stream_k = kbytes > ((size_t)128 << 20);
-    }
+    sa.stream_k = stream_k;
     sa.q = q;
     sa.k = Paged{k_pages, bt, max_pages, ix->page_shift};
     sa.ctx_lens = ix->d_ctx_lens;
@@ -1043,6 +1154,8 @@ int ctkvr_decode_step_static(ctkvr_index *idx, const void *q, const void *k_page
     const size_t nbits = (size_t)idx->units * idx->bitmap_words, nrow = (size_t)idx->units * idx->p.top_k;
     fill_u32_kernel<<<dim3((unsigned)((nbits + 255) / 256)), 256, 0, st>>>(w.gbits, 0u, nbits);
     fill_u32_kernel<<<dim3((unsigned)((nrow + 255) / 256)), 256, 0, st>>>(w.srow, 0u, nrow);
+    const size_t nbar = (size_t)idx->units * kFusedBarriers;
+    fill_u32_kernel<<<dim3((unsigned)((nbar + 255) / 256)), 256, 0, st>>>(w.bar, 0u, nbar);
     if (idx->p.dtype == CTKVR_BF16)
         return decode_dispatch<bf16_t>(idx, w, q, k_pages, v_pages, block_table, max_pages, nullptr, out, out_lse, out_sel,
                                        out_ncand, out_probe, st);
@@ -1096,6 +1209,83 @@ int ctkvr_profile_collect(ctkvr_index *idx, float *ms_host, int32_t capacity_ste
     *n_steps = n;
     idx->prof_step = 0;
     return CTKVR_OK;
+}
+
+int ctkvr_index_set_decode_path(ctkvr_index *idx, int32_t path)
+{
+    if (!idx) return fail(CTKVR_EINVAL, "index is NULL");
+    if (path != CTKVR_PATH_AUTO && path != CTKVR_PATH_STAGED && path != CTKVR_PATH_FUSED)
+        return fail(CTKVR_EINVAL, "unknown decode path %d", path);
+    if (path == CTKVR_PATH_FUSED && !idx->fused_bpu)
+        return fail(CTKVR_EUNSUPPORTED, "the single-launch step does not fit this geometry (%d units on %d CUs, or its shared memory)",
+                    idx->units, idx->num_cu);
+    idx->decode_path = path;
+    return CTKVR_OK;
+}
+
+int ctkvr_index_decode_path(const ctkvr_index *idx)
+{
+    if (!idx) return fail(CTKVR_EINVAL, "index is NULL");
+    return (idx->fused_bpu && idx->decode_path != CTKVR_PATH_STAGED) ? CTKVR_PATH_FUSED : CTKVR_PATH_STAGED;
+}
+
+int ctkvr_index_check(ctkvr_index *idx)
+{
+    if (!idx) return fail(CTKVR_EINVAL, "index is NULL");
+    HIP_TRY(hipDeviceSynchronize());
+    uint32_t e = 0;
+    HIP_TRY(hipMemcpy(&e, idx->d_err, 4, hipMemcpyDeviceToHost));
+    if (e)
+        return fail(CTKVR_EHIP, "a single-launch decode step gave up waiting for its sibling blocks (were two such steps "
+                                "running on this GPU at once?); results since then are invalid");
+    return CTKVR_OK;
+}
+
+int ctkvr_profile_phases(ctkvr_index *idx, int32_t enable, long long *ticks_host)
+{
+    if (!idx) return fail(CTKVR_EINVAL, "index is NULL");
+    HIP_TRY(hipDeviceSynchronize());
+    if (ticks_host) HIP_TRY(hipMemcpy(ticks_host, idx->d_prof, 64 * sizeof(long long), hipMemcpyDeviceToHost));
+    idx->prof_phases = enable != 0;
+    return CTKVR_OK;
+}
+
+int ctkvr_measure_dispatch_floor(int32_t n_launches, float *us_per_launch_host, void *hip_stream)
+{
+    if (n_launches < 1 || n_launches > 100000 || !us_per_launch_host) return fail(CTKVR_EINVAL, "bad argument");
+    hipStream_t st = nullptr;
+    (void)hip_stream;
+    HIP_TRY(hipStreamCreate(&st));   // capture needs a stream of its own (not the legacy default stream)
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    int rc = CTKVR_OK;
+    auto step = [&](hipError_t e, const char *what) {
+        if (rc == CTKVR_OK && e != hipSuccess) rc = fail(CTKVR_EHIP, "%s: %s", what, hipGetErrorString(e));
+        return rc == CTKVR_OK;
+    };
+    if (step(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal), "begin capture")) {
+        for (int i = 0; i < n_launches; ++i) fill_u32_kernel<<<dim3(1), 64, 0, st>>>(nullptr, 0u, 0);
+        step(hipStreamEndCapture(st, &graph), "end capture");
+    }
+    if (rc == CTKVR_OK) step(hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0), "instantiate");
+    if (rc == CTKVR_OK) step(hipEventCreate(&e0), "event");
+    if (rc == CTKVR_OK) step(hipEventCreate(&e1), "event");
+    if (rc == CTKVR_OK) step(hipGraphLaunch(exec, st), "warm-up launch");
+    if (rc == CTKVR_OK) step(hipStreamSynchronize(st), "sync");
+    if (rc == CTKVR_OK) step(hipEventRecord(e0, st), "record");
+    if (rc == CTKVR_OK) step(hipGraphLaunch(exec, st), "launch");
+    if (rc == CTKVR_OK) step(hipEventRecord(e1, st), "record");
+    if (rc == CTKVR_OK) step(hipEventSynchronize(e1), "sync");
+    float ms = 0.0f;
+    if (rc == CTKVR_OK) step(hipEventElapsedTime(&ms, e0, e1), "elapsed");
+    if (rc == CTKVR_OK) *us_per_launch_host = ms * 1e3f / (float)n_launches;
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (exec) (void)hipGraphExecDestroy(exec);
+    if (graph) (void)hipGraphDestroy(graph);
+    (void)hipStreamDestroy(st);
+    return rc;
 }
 
 int ctkvr_selftest_exp(uint64_t *mismatches_host, void *stream)

@@ -93,6 +93,7 @@ def run_decode_parity(bt: Batch, oi: OracleIndex, idx, db: DeviceBatch, steps: O
         if update:
             ck.ctkvr_centroid_update(idx, q_dev)
             n_updates += 1
+    ck.ctkvr_index_check(idx)
     return {"max_rel_err": worst, "max_lse_err": worst_lse, "alpha": float(np.mean(alphas))}
 
 
@@ -154,6 +155,7 @@ def run_sampled_parity(bt: Batch, idx, db: DeviceBatch, steps: List[int], n_list
             assert float(np.max(np.abs(g_lse[b] - o_lse) / np.maximum(1.0, np.abs(o_lse)))) <= 1e-4, f"{tag}: lse"
             alphas.append(float(np.mean(nc)) / (wl.n_probe * wl.list_len))
         say(f"  step {st}: all {B} sequences bit-equal, worst rel err so far {worst:.2e}")
+    ck.ctkvr_index_check(idx)
     return {"max_rel_err": worst, "alpha": float(np.mean(alphas)), "lists_checked": n_checked}
 
 
@@ -226,4 +228,5 @@ def run_sampled_parity_next(bt: Batch, idx, db: DeviceBatch, steps: List[int], n
             ref = f32_to_bf16_bits(Qc[b]) if wl.dtype == "bf16" else Qc[b]
             assert np.array_equal(cen[b, :, :Cb], ref), f"centroid table of sequence {b} differs after {n_updates} updates"
             assert np.array_equal(gl[b, :, :Cb][known[b]], lists[b][known[b]]), f"known lists of sequence {b} differ at the end"
+    ck.ctkvr_index_check(idx)
     return {"max_rel_err": worst, "lists_rebuilt": n_built, "updates": n_updates}
