@@ -311,9 +311,10 @@ def bench_decode(args, wl, steps, cpu_steps):
         ck.ctkvr_profile_phases(idx, True)
         run_steps(min(K, 8), record=False)
         t = ck.ctkvr_profile_phases(idx, False).astype(np.float64)
-        names = ["cos", "probe+gather", "expand+score", "denominators", "keys+histogram", "classify+attend", "select+merge"]
+        names = ["cos", "probe+gather+score", "ranks+denominators", "keys+histogram", "classify+attend"]
         phases = {n: float((t[i + 1] - t[i]) / 100.0) for i, n in enumerate(names)}   # 100 MHz ticks -> us
-        phases["own_work_before_each_barrier"] = [float((t[8 + i] - t[i]) / 100.0) for i in range(6)]
+        phases["select+merge"] = float((t[7] - t[5]) / 100.0)
+        phases["own_work_before_each_barrier"] = [float((t[8 + i] - t[i]) / 100.0) for i in range(5)]
         phases["detail_us_since_entry"] = {str(i): float((t[i] - t[0]) / 100.0) for i in range(64) if t[i] > 0}
     else:
         # a pair of events around a kernel that does nothing reads stage_us["null"]; that kernel itself lasts about

@@ -244,13 +244,14 @@ int ctkvr_profile_collect(ctkvr_index *idx, float *ms_host, int32_t capacity_ste
 /* Algorithm 2 lines 1-9 run either as a sequence of launches (one per stage; any geometry) or as
  * ONE launch whose blocks walk the stages together, a fixed group of co-resident blocks per
  * (sequence, KV head) separated by barriers in device memory (batch * g at most the number of
- * compute units, and a shared-memory plan that fits; about half the step time at batch 1).  Both
- * give the same integers bit for bit; outputs agree within rounding.  AUTO takes the single
- * launch where the geometry allows it.  The single launch needs all its blocks resident at once:
- * two such steps (two indexes, two streams) must not run on one GPU at the same time -- their
- * waits are bounded, and an expired wait is reported by ctkvr_index_check -- callers that overlap
- * steps choose STAGED.  The environment variable CTKVR_DECODE_PATH = staged | fused | auto sets
- * the default of indexes created afterwards. */
+ * compute units, and a shared-memory plan that fits).  Both give the same integers bit for bit;
+ * outputs agree within rounding.  AUTO takes the staged launches, which measure faster on every
+ * benchmark geometry of this part (an empty launch behind another costs 1.6 us in a graph, a
+ * barrier among 32 blocks with what it has to wait for 1.5-2.5 us); FUSED is there to be measured.
+ * The single launch needs all its blocks resident at once: two such steps (two indexes, two
+ * streams) must not run on one GPU at the same time -- their waits are bounded, and an expired
+ * wait is reported by ctkvr_index_check.  The environment variable CTKVR_DECODE_PATH = staged |
+ * fused | auto sets the default of indexes created afterwards. */
 typedef enum { CTKVR_PATH_AUTO = 0, CTKVR_PATH_STAGED = 1, CTKVR_PATH_FUSED = 2 } ctkvr_decode_path;
 /* Errors: EINVAL (unknown path), EUNSUPPORTED (FUSED on a geometry that does not allow it). */
 int ctkvr_index_set_decode_path(ctkvr_index *idx, int32_t path);

@@ -52,7 +52,7 @@ size_t elem_size(int dtype) { return dtype == CTKVR_BF16 ? 2 : 4; }
 // Scratch of the entry point that allocates nothing (ctkvr_decode_step_static): one array per GPU, held
 // until the process ends.  Host code never uses the array's name as an address: the device address
 // is looked up once per device and kept.
-constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
@@ -91,9 +91,13 @@ struct StepWs {
     float *z = nullptr, *zsel = nullptr;
     float *win = nullptr;   // window_attn_kernel's partial results
     uint32_t *m_key = nullptr;
-    // single-launch step only
-    float *part = nullptr;      // [units][blocks per unit][G][2 + 128] partial attention results
-    uint32_t *bar = nullptr;    // [units][kFusedBarriers] barrier counters, zero between steps
+    // single-launch step only (what its blocks hand to each other; see fused_args.hpp)
+    float *part = nullptr;
+    uint32_t *bar = nullptr;    // barrier counters, zero between steps
+    int32_t *sid = nullptr, *slot_sure = nullptr;
+    uint32_t *slot_cnt = nullptr, *slot_max = nullptr, *slot_hist = nullptr, *slot_npick = nullptr;
+    unsigned long long *slot_S = nullptr;
+    uint4 *slot_bkt = nullptr;
 };
 
 struct ctkvr_index {
@@ -119,11 +123,18 @@ struct ctkvr_index {
     int bitmap_words = 0, recall_split = 1, num_cu = 256;
     // single-launch step (decode_fused_kernel): blocks per unit (0: the geometry does not allow it), its shared memory,
     // the path in use (CTKVR_PATH_*), the sticky error word and the phase stamps
-    int fused_bpu = 0, fused_nt = 1024, decode_path = CTKVR_PATH_AUTO;
+    int fused_bpu = 0, fused_nt = 1024, fused_stage = 0, decode_path = CTKVR_PATH_AUTO;
+    bool last_step_fused = false;   // the last step on the index's own workspace left no 2048-bucket key histogram
     size_t fused_smem = 0;
     uint32_t *d_err = nullptr;
     long long *d_prof = nullptr;
     bool prof_phases = false;
+    // Groups of sequences whose steps run side by side (fork / join on streams of the library, default priority):
+    // the latency-bound selection stages of one group then overlap the key streaming of another.
+    int n_groups = 1;
+    std::vector<hipStream_t> side;          // n_groups - 1 streams
+    hipEvent_t ev_fork = nullptr;
+    std::vector<hipEvent_t> ev_join;        // one per side stream
     // per-kernel timing
     std::vector<hipEvent_t> events;
     int prof_max = 0, prof_step = 0;
@@ -144,6 +155,9 @@ struct ctkvr_index {
     {
         for (void *v : allocs) (void)hipFree(v);
         for (hipEvent_t e : events) (void)hipEventDestroy(e);
+        for (hipEvent_t e : ev_join) (void)hipEventDestroy(e);
+        if (ev_fork) (void)hipEventDestroy(ev_fork);
+        for (hipStream_t st : side) (void)hipStreamDestroy(st);
     }
     // event slot `stage` (0 = before the first kernel) of the step being recorded
     void mark(int stage, hipStream_t st)
@@ -208,13 +222,16 @@ size_t carve_step_ws(StepWs &w, unsigned char *base, const ctkvr_index *ix)
     };
     const ctkvr_params &p = ix->p;
     const size_t U = ix->units, L = ix->l_stride, G = ix->G;
+    const size_t bpu = std::max(1, ix->fused_bpu);
+    // recalled keys of a unit: rank order (one launch per stage) or one stretch per block range (single launch)
+    const size_t LS = std::max<size_t>(L, ix->fused_bpu ? (size_t)ix->fused_stage : 0);
     take(&w.cos, U * ix->c_max * 4);
     take(&w.probe, U * p.n_probe * 4);
     take(&w.cand, U * L * 4);
     take(&w.ncand, U * 4);
-    take(&w.z, U * L * G * 4);
+    take(&w.z, U * LS * G * 4);
     take(&w.m_key, U * G * 4);
-    take(&w.crow, U * L * 4);
+    take(&w.crow, U * LS * 4);
     take(&w.gbits, U * (size_t)((ix->s_max + 31) / 32) * 4);
     take(&w.kbuf, U * L * 4);
     take(&w.ghist, U * (size_t)kBuckets * 4);
@@ -228,8 +245,18 @@ size_t carve_step_ws(StepWs &w, unsigned char *base, const ctkvr_index *ix)
     take(&w.sel, U * p.top_k * 4);
     take(&w.zsel, U * p.top_k * G * 4);
     take(&w.nsel, U * 4);
-    take(&w.part, U * (size_t)std::max(1, ix->fused_bpu) * G * (2 + 128) * 4);
     take(&w.bar, U * (size_t)kFusedBarriers * 4);
+    if (ix->fused_bpu) {
+        take(&w.part, U * bpu * G * (2 + 128) * 4);
+        take(&w.sid, U * LS * 4);
+        take(&w.slot_cnt, U * bpu * 4);
+        take(&w.slot_max, U * bpu * G * 4);
+        take(&w.slot_S, U * bpu * G * 8);
+        take(&w.slot_hist, U * bpu * (size_t)kFusedBins * 4);
+        take(&w.slot_npick, U * bpu * 8);
+        take(&w.slot_sure, U * bpu * (size_t)p.top_k * 4);
+        take(&w.slot_bkt, U * bpu * (size_t)kFusedListCap * 16);
+    }
     return off;
 }
 
@@ -278,18 +305,31 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
     // The single-launch step needs all its blocks resident at once (one 1024-thread block per CU) and
     // its shared-memory plan to fit; up to 32 blocks work on a unit.
     if ((int)U <= ix->num_cu) {
-        const size_t words = fused_smem_words(p->n_probe, ix->bitmap_words, ix->l_stride, p->top_k, ix->G);
-        if (words * 4 <= (size_t)150 * 1024) {
-            ix->fused_bpu = std::max(1, std::min(32, ix->num_cu / (int)U));
-            ix->fused_smem = words * 4;
-            // Few recalled keys per block: four waves walk the serial parts of every phase (selections, scans,
-            // reductions) four times faster than sixteen; many keys per block: sixteen waves keep more rows in flight.
-            ix->fused_nt = ix->l_stride / ix->fused_bpu <= 2048 ? 256 : 1024;
-            if (const char *e = getenv("CTKVR_FUSED_THREADS")) {
-                if (!strcmp(e, "256")) ix->fused_nt = 256;
-                else if (!strcmp(e, "1024")) ix->fused_nt = 1024;
-            }
+        const int bpu = std::max(1, std::min(kFusedMaxBpu, ix->num_cu / (int)U));
+        // Few recalled keys per block: four waves walk the serial parts of every phase (selections, scans,
+        // reductions) faster than sixteen; many keys per block: sixteen waves keep more rows in flight.
+        int nt = ix->l_stride / bpu <= 2048 ? 256 : 1024;
+        if (const char *e = getenv("CTKVR_FUSED_THREADS")) {
+            if (!strcmp(e, "256")) nt = 256;
+            else if (!strcmp(e, "1024")) nt = 1024;
         }
+        const size_t words = fused_smem_words(nt, p->n_probe, ix->s_max, bpu, p->top_k, ix->G);
+        if (words * 4 <= (size_t)150 * 1024) {
+            ix->fused_bpu = bpu;
+            ix->fused_nt = nt;
+            ix->fused_smem = words * 4;
+            ix->fused_stage = bpu * fused_range_ids(ix->s_max, bpu);
+        }
+    }
+    // Sequences of a batch are independent, and their steps can be issued as groups side by side
+    // (CTKVR_DECODE_GROUPS = n at index creation).  One group is the default: on this part the split
+    // measured slower on every benchmark batch (128K x 4: 131 us unsplit, 144 us as two groups, 159 us as
+    // four; ragged x 16: 154 / 160 / 169 us) -- kernels of different streams take turns rather than share
+    // the chip, and every group pays the per-kernel floors again.
+    {
+        int ng = 1;
+        if (const char *e = getenv("CTKVR_DECODE_GROUPS")) ng = std::max(1, std::min(std::min(8, B), atoi(e)));
+        ix->n_groups = ng;
     }
     if (const char *e = getenv("CTKVR_DECODE_PATH")) {
         if (!strcmp(e, "staged")) ix->decode_path = CTKVR_PATH_STAGED;
@@ -390,13 +430,23 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
     if (e == hipSuccess) e = hipMemset(ix->d_err, 0, 4);
     if (e == hipSuccess) e = hipMemset(ix->d_prof, 0, 64 * 8);
     if (e == hipSuccess) e = hipMemset(ix->ws.bar, 0, U * (size_t)kFusedBarriers * 4);
-    if (e == hipSuccess) e = hipMemset(ix->ws.gbm, 0, U * (size_t)(2 * ((ix->l_stride + 63) / 64)) * 4);
     if (e == hipSuccess) e = hipMemset(ix->ws.gbits, 0, U * (size_t)ix->bitmap_words * 4);
     if (e == hipSuccess) e = hipMemset(ix->ws.srow, 0, U * p->top_k * 4);   // always valid rows (see sparse_attn_kernel)
     if (e == hipSuccess) e = hipMemcpy(ix->d_ctx_lens, ix->ctx_lens.data(), (size_t)B * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(ix->d_n_cent, ix->n_cent.data(), (size_t)B * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(ix->lists, 0, U * ix->c_max * p->list_len * 4);
     if (e == hipSuccess) e = hipMemset(ix->centroids, 0, (size_t)B * h * ix->c_max * 128 * es);
+    if (e == hipSuccess && ix->n_groups > 1) {
+        e = hipEventCreateWithFlags(&ix->ev_fork, hipEventDisableTiming);
+        for (int i = 1; i < ix->n_groups && e == hipSuccess; ++i) {
+            hipStream_t sst = nullptr;
+            hipEvent_t ev = nullptr;
+            e = hipStreamCreateWithFlags(&sst, hipStreamNonBlocking);
+            if (e == hipSuccess) ix->side.push_back(sst);
+            if (e == hipSuccess) e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+            if (e == hipSuccess) ix->ev_join.push_back(ev);
+        }
+    }
     if (e != hipSuccess) {
         delete ix;
         return fail(CTKVR_EHIP, "index set-up: %s", hipGetErrorString(e));
@@ -571,21 +621,64 @@ int build_lists_dispatch(ctkvr_index *ix, const void *k_pages, const int32_t *bt
 }
 
 template <typename T, int G>
-int decode_launch(ctkvr_index *ix, const StepWs &w, const void *q, const void *k_pages, const void *v_pages, const int32_t *bt,
-                  int max_pages, const int32_t *cur_lens, float *out, float *out_lse, int32_t *out_sel, int32_t *out_ncand,
-                  int32_t *out_probe, hipStream_t st)
+int decode_launch_group(ctkvr_index *ix, const StepWs &w_all, int b0, int nb, bool whole, const void *q, const void *k_pages,
+                        const void *v_pages, const int32_t *bt, int max_pages, const int32_t *cur_lens, float *out, float *out_lse,
+                        int32_t *out_sel, int32_t *out_ncand, int32_t *out_probe, hipStream_t st)
 {
+    // The step for the sequences b0 .. b0 + nb - 1 of the batch: every per-sequence and per-unit array is entered
+    // at that group's first element, and the kernels see a batch of nb sequences.  whole: the group is the batch
+    // (per-kernel timing marks and the single-launch form apply to whole batches only).
     const ctkvr_params &p = ix->p;
-    const int U = ix->units;
+    const int U = nb * p.n_kv_heads, u0 = b0 * p.n_kv_heads;
+    const size_t es = elem_size(p.dtype);
+    auto adv = [](auto *ptr, size_t n) { return ptr ? ptr + n : ptr; };
+    q = (const char *)q + (size_t)b0 * p.n_q_heads * 128 * es;
+    bt = bt + (size_t)b0 * max_pages;
+    cur_lens = adv(cur_lens, b0);
+    out = out + (size_t)b0 * p.n_q_heads * 128;
+    out_lse = adv(out_lse, (size_t)b0 * p.n_q_heads);
+    out_sel = adv(out_sel, (size_t)u0 * p.top_k);
+    out_ncand = adv(out_ncand, u0);
+    out_probe = adv(out_probe, (size_t)u0 * p.n_probe);
+    const void *cen = (const char *)ix->centroids + (size_t)b0 * p.n_q_heads * ix->c_max * 128 * es;
+    const float *inv_c = ix->inv_norm_c + (size_t)b0 * p.n_q_heads * ix->c_max;
+    const int32_t *lists = ix->lists + (size_t)u0 * ix->c_max * p.list_len;
+    const int32_t *d_n_cent = ix->d_n_cent + b0, *d_ctx_lens = ix->d_ctx_lens + b0;
+    StepWs w = w_all;
+    if (u0) {
+        const size_t L = ix->l_stride, Gs = ix->G;
+        w.cos += (size_t)u0 * ix->c_max;
+        w.probe += (size_t)u0 * p.n_probe;
+        w.cand += u0 * L;
+        w.ncand += u0;
+        w.z += u0 * L * Gs;
+        w.m_key += u0 * Gs;
+        w.crow += u0 * L;
+        w.gbits += (size_t)u0 * ix->bitmap_words;
+        w.kbuf += u0 * L;
+        w.ghist += (size_t)u0 * kBuckets;
+        w.gbm += (size_t)u0 * (2 * ((L + 63) / 64));
+        w.glist += (size_t)u0 * kListCap;
+        w.gcur += u0;
+        w.ginfo += (size_t)u0 * 4;
+        w.win += (size_t)u0 * kWinSplit * Gs * (2 + 128);
+        w.srow += (size_t)u0 * p.top_k;
+        w.S += u0 * Gs;
+        w.sel += (size_t)u0 * p.top_k;
+        w.zsel += (size_t)u0 * p.top_k * Gs;
+        w.nsel += u0;
+    }
+    Units units = decode_units(ix);
+    units.n_cent = d_n_cent;
     // lines 10-11 first: the window's share depends on q, K and V only
     const bool window = p.n_init + p.n_local > 0 || cur_lens;
     if (window) {
         WindowArgs wa{};
-        wa.u = decode_units(ix);
+        wa.u = units;
         wa.q = q;
         wa.k = Paged{k_pages, bt, max_pages, ix->page_shift};
         wa.v_pages = v_pages;
-        wa.ctx_lens = ix->d_ctx_lens;
+        wa.ctx_lens = d_ctx_lens;
         wa.cur_lens = cur_lens;
         wa.n_init = p.n_init;
         wa.n_local = p.n_local;
@@ -601,7 +694,7 @@ int decode_launch(ctkvr_index *ix, const StepWs &w, const void *q, const void *k
         for (int sl : ix->ctx_lens) kbytes += (size_t)sl * p.n_kv_heads * 128 * elem_size(p.dtype);
         return kbytes > ((size_t)128 << 20);
     }();
-    if (ix->fused_bpu && ix->decode_path != CTKVR_PATH_STAGED) {
+    if (whole && ix->fused_bpu && ix->decode_path == CTKVR_PATH_FUSED) {
         FusedArgs fa{};
         fa.g = p.n_kv_heads;
         fa.h = p.n_q_heads;
@@ -609,37 +702,37 @@ int decode_launch(ctkvr_index *ix, const StepWs &w, const void *q, const void *k
         fa.rho = p.list_len;
         fa.n_probe = p.n_probe;
         fa.top_k = p.top_k;
-        fa.bitmap_words = ix->bitmap_words;
         fa.l_stride = ix->l_stride;
-        fa.bits_stride = 2 * ((ix->l_stride + 63) / 64);
         fa.bpu = ix->fused_bpu;
         fa.units = U;
+        fa.stage = ix->fused_stage;
         fa.stream_k = stream_k;
         fa.scale = ix->scale;
-        fa.n_cent = ix->d_n_cent;
-        fa.ctx_lens = ix->d_ctx_lens;
+        fa.n_cent = d_n_cent;
+        fa.ctx_lens = d_ctx_lens;
         fa.q = q;
-        fa.centroids = ix->centroids;
-        fa.inv_norm_c = ix->inv_norm_c;
-        fa.lists = ix->lists;
+        fa.centroids = cen;
+        fa.inv_norm_c = inv_c;
+        fa.lists = lists;
         fa.k = Paged{k_pages, bt, max_pages, ix->page_shift};
         fa.v_pages = v_pages;
         fa.cos = w.cos;
         fa.probe = w.probe;
         fa.out_probe = out_probe;
-        fa.gbits = w.gbits;
+        fa.sid = w.sid;
+        fa.srow = w.crow;
+        fa.z = w.z;
         fa.cand = w.cand;
-        fa.crow = w.crow;
+        fa.kbuf = w.kbuf;
         fa.ncand = w.ncand;
         fa.out_ncand = out_ncand;
-        fa.z = w.z;
-        fa.m_key = w.m_key;
-        fa.S = w.S;
-        fa.kbuf = w.kbuf;
-        fa.ghist = w.ghist;
-        fa.gbm = w.gbm;
-        fa.glist = w.glist;
-        fa.gcur = w.gcur;
+        fa.slot_cnt = w.slot_cnt;
+        fa.slot_max = w.slot_max;
+        fa.slot_S = w.slot_S;
+        fa.slot_hist = w.slot_hist;
+        fa.slot_npick = w.slot_npick;
+        fa.slot_sure = w.slot_sure;
+        fa.slot_bkt = w.slot_bkt;
         fa.part = w.part;
         fa.sel = w.sel;
         fa.nsel = w.nsel;
@@ -650,38 +743,40 @@ int decode_launch(ctkvr_index *ix, const StepWs &w, const void *q, const void *k
         fa.bar = w.bar;
         fa.err = ix->d_err;
         fa.prof = ix->prof_phases ? ix->d_prof : nullptr;
-        ix->mark(0, st);
+        if (whole) ix->mark(0, st);
         HIP_TRY(fused_launch(p.dtype == CTKVR_BF16, G, ix->fused_nt, (unsigned)(U * ix->fused_bpu), ix->fused_smem, st, fa));
         for (int k = 1; k <= 8; ++k) ix->mark(k, st);   // the whole step reads as stage 0
         if (ix->prof_step < ix->prof_max) {
             fill_u32_kernel<<<dim3(1), 64, 0, st>>>((uint32_t *)w.nsel, 0u, 0);
-            ix->mark(9, st);
+            if (whole) ix->mark(9, st);
             ix->prof_step++;
         }
         HIP_TRY(hipGetLastError());
-        ix->have_step = &w == &ix->ws;
+        ix->have_step = &w_all == &ix->ws;
+        ix->last_step_fused = true;
         return CTKVR_OK;
     }
+    ix->last_step_fused = false;
     CosArgs ca{};
     ca.q = q;
-    ca.centroids = ix->centroids;
-    ca.inv_norm_c = ix->inv_norm_c;
-    ca.n_cent = ix->d_n_cent;
+    ca.centroids = cen;
+    ca.inv_norm_c = inv_c;
+    ca.n_cent = d_n_cent;
     ca.cos = w.cos;
     ca.m_key = w.m_key;
     ca.S = w.S;
     ca.g = p.n_kv_heads;
     ca.h = p.n_q_heads;
     ca.c_max = ix->c_max;
-    ix->mark(0, st);
+    if (whole) ix->mark(0, st);
     centroid_cos_kernel<T, G><<<dim3((ix->c_max + 15) / 16, U), 256, 0, st>>>(ca);
-    ix->mark(1, st);
+    if (whole) ix->mark(1, st);
 
     GatherArgs ga{};
     ga.cos = w.cos;
-    ga.lists = ix->lists;
-    ga.n_cent = ix->d_n_cent;
-    ga.ctx_lens = ix->d_ctx_lens;
+    ga.lists = lists;
+    ga.n_cent = d_n_cent;
+    ga.ctx_lens = d_ctx_lens;
     ga.probe = w.probe;
     ga.out_probe = out_probe;
     ga.gbits = w.gbits;
@@ -697,16 +792,16 @@ int decode_launch(ctkvr_index *ix, const StepWs &w, const void *q, const void *k
         recall_gather_kernel<8><<<rgrid, 256, ix->recall_lds, st>>>(ga);
     else
         recall_gather_kernel<32><<<rgrid, 256, ix->recall_lds, st>>>(ga);
-    ix->mark(2, st);
+    if (whole) ix->mark(2, st);
 
     // lines 4-5: bitmap -> recalled ids, their rows and their scores in one launch
-    Units u = decode_units(ix);
+    Units u = units;
     RecallScoreArgs sa{};
     sa.u = u;
     sa.stream_k = stream_k;
     sa.q = q;
     sa.k = Paged{k_pages, bt, max_pages, ix->page_shift};
-    sa.ctx_lens = ix->d_ctx_lens;
+    sa.ctx_lens = d_ctx_lens;
     sa.gbits = w.gbits;
     sa.bitmap_words = ix->bitmap_words;
     sa.l_stride = ix->l_stride;
@@ -725,11 +820,11 @@ int decode_launch(ctkvr_index *ix, const StepWs &w, const void *q, const void *k
         const int nbx = (ix->bitmap_words + wpb - 1) / wpb;
         recall_score_kernel<T, G><<<dim3(nbx, U), 256, 0, st>>>(sa);
     }
-    ix->mark(3, st);
+    if (whole) ix->mark(3, st);
 
     DenomArgs da{};
     da.u = u;
-    da.ctx_lens = ix->d_ctx_lens;
+    da.ctx_lens = d_ctx_lens;
     da.ncand = w.ncand;
     da.l_stride = ix->l_stride;
     da.z = w.z;
@@ -739,11 +834,11 @@ int decode_launch(ctkvr_index *ix, const StepWs &w, const void *q, const void *k
     da.bitmap_words = ix->bitmap_words;
     const int chunks = (ix->l_stride + 1023) / 1024;
     denom_kernel<G><<<dim3(std::max(1, std::min(chunks, (4 * ix->num_cu + U - 1) / U)), U), 256, 0, st>>>(da);
-    ix->mark(4, st);
+    if (whole) ix->mark(4, st);
 
     KeyArgs ka{};
     ka.u = u;
-    ka.ctx_lens = ix->d_ctx_lens;
+    ka.ctx_lens = d_ctx_lens;
     ka.ncand = w.ncand;
     ka.l_stride = ix->l_stride;
     ka.z = w.z;
@@ -753,12 +848,12 @@ int decode_launch(ctkvr_index *ix, const StepWs &w, const void *q, const void *k
     ka.ghist = w.ghist;
     ka.gcur = w.gcur;
     keyhist_kernel<G><<<dim3(std::max(1, std::min((ix->l_stride + 4095) / 4096, (2 * ix->num_cu + U - 1) / U)), U), 1024, 0, st>>>(ka);
-    ix->mark(5, st);
+    if (whole) ix->mark(5, st);
 
     if (ix->sel_bits) {
         ClassifyArgs ca{};
         ca.u = u;
-        ca.ctx_lens = ix->d_ctx_lens;
+        ca.ctx_lens = d_ctx_lens;
         ca.ncand = w.ncand;
         ca.l_stride = ix->l_stride;
         ca.top_k = p.top_k;
@@ -771,11 +866,11 @@ int decode_launch(ctkvr_index *ix, const StepWs &w, const void *q, const void *k
         ca.ginfo = w.ginfo;
         classify_kernel<<<dim3(std::max(1, std::min(chunks, (4 * ix->num_cu + U - 1) / U)), U), 256, 0, st>>>(ca);
     }
-    ix->mark(6, st);
+    if (whole) ix->mark(6, st);
 
     SelectArgs se{};
     se.u = u;
-    se.ctx_lens = ix->d_ctx_lens;
+    se.ctx_lens = d_ctx_lens;
     se.ncand = w.ncand;
     se.cand = w.cand;
     se.crow = w.crow;
@@ -809,22 +904,53 @@ int decode_launch(ctkvr_index *ix, const StepWs &w, const void *q, const void *k
     aa.out_lse = out_lse;
     aa.win = window ? w.win : nullptr;
     if (ix->fused_lds) {
-        ix->mark(7, st);   // no separate selection launch: its stage reads as the cost of an event pair
+        if (whole) ix->mark(7, st);   // no separate selection launch: its stage reads as the cost of an event pair
         select_attn_kernel<T, G><<<dim3(4 * U), 1024, ix->fused_lds, st>>>(se, aa);
     } else {
         rerank_select_kernel<G><<<dim3(U), 1024, ix->select_lds, st>>>(se);
-        ix->mark(7, st);
+        if (whole) ix->mark(7, st);
         sparse_attn_kernel<T, G><<<dim3(4 * U), 1024, ix->attn_lds, st>>>(aa);
     }
-    ix->mark(8, st);
-    if (ix->prof_step < ix->prof_max) {   // a null kernel between two events: what the bracketing itself costs
+    if (whole) ix->mark(8, st);
+    if (whole && ix->prof_step < ix->prof_max) {   // a null kernel between two events: what the bracketing itself costs
         fill_u32_kernel<<<dim3(1), 64, 0, st>>>((uint32_t *)w.nsel, 0u, 0);
-        ix->mark(9, st);
+        if (whole) ix->mark(9, st);
     }
-    if (ix->prof_step < ix->prof_max) ix->prof_step++;
+    if (whole && ix->prof_step < ix->prof_max) ix->prof_step++;
     HIP_TRY(hipGetLastError());
-    ix->have_step = &w == &ix->ws;   // the update reads the index's own workspace
+    ix->have_step = &w_all == &ix->ws;   // the update reads the index's own workspace
     return CTKVR_OK;
+}
+
+// One step for the whole batch: a single group on the caller's stream, or (several sequences, no per-kernel
+// timing, staged launches) the groups side by side -- the first on the caller's stream, the others on the
+// library's streams, forked from and joined back into the caller's stream with events, so that the step is
+// still one unit of work on that stream and can be captured into a graph.
+template <typename T, int G>
+int decode_launch(ctkvr_index *ix, const StepWs &w, const void *q, const void *k_pages, const void *v_pages, const int32_t *bt,
+                  int max_pages, const int32_t *cur_lens, float *out, float *out_lse, int32_t *out_sel, int32_t *out_ncand,
+                  int32_t *out_probe, hipStream_t st)
+{
+    const int B = ix->p.batch;
+    const bool fused = ix->fused_bpu && ix->decode_path == CTKVR_PATH_FUSED;
+    const int ng = (fused || ix->prof_step < ix->prof_max) ? 1 : std::min(ix->n_groups, B);
+    if (ng <= 1)
+        return decode_launch_group<T, G>(ix, w, 0, B, true, q, k_pages, v_pages, bt, max_pages, cur_lens, out, out_lse, out_sel,
+                                         out_ncand, out_probe, st);
+    HIP_TRY(hipEventRecord(ix->ev_fork, st));
+    int rc = CTKVR_OK;
+    for (int gi = 0; gi < ng && rc == CTKVR_OK; ++gi) {
+        const int b0 = (int)((long long)B * gi / ng), b1 = (int)((long long)B * (gi + 1) / ng);
+        hipStream_t gs = gi == 0 ? st : ix->side[gi - 1];
+        if (gi > 0) HIP_TRY(hipStreamWaitEvent(gs, ix->ev_fork, 0));
+        rc = decode_launch_group<T, G>(ix, w, b0, b1 - b0, false, q, k_pages, v_pages, bt, max_pages, cur_lens, out, out_lse,
+                                       out_sel, out_ncand, out_probe, gs);
+        if (gi > 0 && rc == CTKVR_OK) {
+            HIP_TRY(hipEventRecord(ix->ev_join[gi - 1], gs));
+            HIP_TRY(hipStreamWaitEvent(st, ix->ev_join[gi - 1], 0));
+        }
+    }
+    return rc;
 }
 
 template <typename T>
@@ -943,6 +1069,22 @@ template <typename T, int G> int update_launch(ctkvr_index *ix, const void *q, h
         se.sel = ix->dsel;
         se.nsel = ix->dnsel;
         se.ids_only = 1;
+        if (ix->sel_bits && ix->last_step_fused) {
+            // the single launch leaves the ranking keys but not their 2048-bucket histogram: taken here
+            fill_u32_kernel<<<dim3((unsigned)(((size_t)U * kBuckets + 255) / 256)), 256, 0, st>>>(ix->ws.ghist, 0u, (size_t)U * kBuckets);
+            KeyArgs ka{};
+            ka.u = u;
+            ka.ctx_lens = ix->d_ctx_lens;
+            ka.ncand = ix->ws.ncand;
+            ka.l_stride = ix->l_stride;
+            ka.z = nullptr;
+            ka.m_key = ix->ws.m_key;
+            ka.S = ix->ws.S;
+            ka.kbuf = ix->ws.kbuf;
+            ka.ghist = ix->ws.ghist;
+            ka.gcur = ix->ws.gcur;
+            keyhist_kernel<G><<<dim3(std::max(1, std::min((ix->l_stride + 4095) / 4096, (2 * ix->num_cu + U - 1) / U)), U), 1024, 0, st>>>(ka);
+        }
         if (ix->sel_bits) {
             fill_u32_kernel<<<dim3((U + 255) / 256), 256, 0, st>>>(ix->ws.gcur, 0u, (size_t)U);
             ClassifyArgs ca{};
@@ -1226,7 +1368,7 @@ int ctkvr_index_set_decode_path(ctkvr_index *idx, int32_t path)
 int ctkvr_index_decode_path(const ctkvr_index *idx)
 {
     if (!idx) return fail(CTKVR_EINVAL, "index is NULL");
-    return (idx->fused_bpu && idx->decode_path != CTKVR_PATH_STAGED) ? CTKVR_PATH_FUSED : CTKVR_PATH_STAGED;
+    return (idx->fused_bpu && idx->decode_path == CTKVR_PATH_FUSED) ? CTKVR_PATH_FUSED : CTKVR_PATH_STAGED;
 }
 
 int ctkvr_index_check(ctkvr_index *idx)

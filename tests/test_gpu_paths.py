@@ -149,6 +149,64 @@ def test_path_selection_errors(ck):
     ck.ctkvr_index_set_decode_path(idx, ck.PATH_STAGED)
     assert ck.ctkvr_index_decode_path(idx) == ck.PATH_STAGED
     ck.ctkvr_index_set_decode_path(idx, ck.PATH_AUTO)
-    assert ck.ctkvr_index_decode_path(idx) == ck.PATH_FUSED       # 2 units: the single launch fits
+    assert ck.ctkvr_index_decode_path(idx) == ck.PATH_STAGED      # the default: one launch per stage
+    ck.ctkvr_index_set_decode_path(idx, ck.PATH_FUSED)            # 2 units: the single launch fits
+    assert ck.ctkvr_index_decode_path(idx) == ck.PATH_FUSED
     assert ck.ctkvr_measure_dispatch_floor(50) > 0.0
     ck.ctkvr_free(idx)
+
+
+@pytest.mark.parametrize("groups", [2, 3, 5])
+def test_groups_of_sequences_side_by_side_match_the_oracle_eager_and_replayed(ck, groups, monkeypatch):
+    """The sequences of a batch split into groups whose steps are issued side by side (forked from and joined
+    into the caller's stream): same integers as the oracle, same bits as the unsplit step, also when the
+    forked step is captured into a graph and replayed."""
+    import torch
+    wl = small_workload("paths_groups", "bf16", 8, 2, (900, 2500, 1300, 3100, 700), (570, 571, 572, 573, 574), 0, 50, 4, 96, 64, 3)
+    bt = gen_batch(wl)
+    db = H.device_batch(bt)
+    oi = H.oracle_index(bt)
+    cen, lst = oi.padded(wl)
+    monkeypatch.setenv("CTKVR_DECODE_GROUPS", "1")
+    one = ck.ctkvr_index_load(H.params_of(wl), db.ctx_lens, cen, lst)
+    monkeypatch.setenv("CTKVR_DECODE_GROUPS", str(groups))
+    idx = ck.ctkvr_index_load(H.params_of(wl), db.ctx_lens, cen, lst)
+    monkeypatch.delenv("CTKVR_DECODE_GROUPS")
+    H.run_decode_parity(bt, oi, idx, db)
+    B, h, g, d = wl.batch, wl.h, wl.g, wl.d
+    qs = [H.to_dev(np.stack([sq.q_decode[i] for sq in bt.seqs]), wl) for i in range(3)]
+    outs = [torch.zeros((B, h, d), dtype=torch.float32, device="cuda") for _ in range(3)]
+    sels = [torch.zeros((B, g, wl.top_k), dtype=torch.int32, device="cuda") for _ in range(3)]
+    ref = torch.zeros((B, h, d), dtype=torch.float32, device="cuda")
+
+    def steps():
+        for i in range(3):
+            ck.ctkvr_decode_step(idx, qs[i], db.k_pages, db.v_pages, db.block_table, outs[i], out_sel=sels[i])
+
+    steps()
+    torch.cuda.synchronize()
+    ref_out, ref_sel = [o.clone() for o in outs], [s.clone() for s in sels]
+    for i in range(3):
+        ck.ctkvr_decode_step(one, qs[i], db.k_pages, db.v_pages, db.block_table, ref)
+        torch.cuda.synchronize()
+        assert torch.equal(ref, ref_out[i]), f"step {i}: the split step differs from the unsplit one"
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            steps()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for o in outs:
+            o.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i in range(3):
+            assert torch.equal(outs[i], ref_out[i]) and torch.equal(sels[i], ref_sel[i]), f"replay {rep} step {i} differs"
+        ck.ctkvr_decode_step(idx, qs[rep % 3], db.k_pages, db.v_pages, db.block_table, outs[0])   # eager work in between
+        torch.cuda.synchronize()
+        assert torch.equal(outs[0], ref_out[rep % 3])
+    ck.ctkvr_free(idx)
+    ck.ctkvr_free(one)
