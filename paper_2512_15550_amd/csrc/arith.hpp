@@ -504,20 +504,14 @@ __device__ __forceinline__ uint32_t key_bucket(uint32_t kk)
     return (uint32_t)fmaxf(t, 0.0f);
 }
 
-// Second half of the histogram-helped selection, on data already in shared memory: s_gt = bitmap
-// of the ids above the deciding bucket, s_eq = zeroed bitmap, l_ent[0..nb) = the (key, id) pairs
-// of the deciding bucket, of which the `rem` largest keys are still wanted (ties: lowest ids).
-// n ids in all (both bitmaps have 2*ceil(n/64) words).  Starts with the data as written by other
-// threads: the caller places a barrier before the call.
-template <int NT, typename EmitFn>
-__device__ __forceinline__ void block_resolve_emit(uint32_t nb, uint32_t rem, int n, uint32_t *s_hist, uint32_t *s_gt,
-                                                   uint32_t *s_eq, const uint2 *l_ent, EmitFn emit)
+// T = the rem-th largest of the keys l_ent[0..nb).x (in shared memory), and need_eq = how many of the
+// keys equal to T belong to the rem largest.  Every thread of the block takes part; barriers inside.
+// s_hist: the 2048 + 64 words of the selection routines.  1 <= rem <= nb <= kListCap.
+template <int NT>
+__device__ __forceinline__ void block_list_threshold(uint32_t nb, uint32_t rem, uint32_t *s_hist, const uint2 *l_ent, uint32_t &T,
+                                                     uint32_t &need_eq)
 {
     const int tid = threadIdx.x;
-    uint32_t *s_scan = s_hist + 2048 + 4;
-    const int nw64 = (n + 63) >> 6;
-    // T among the nb listed keys (rem-th largest)
-    uint32_t T, need_eq;
     static_assert(NT <= 1024, "rank counters live in the two halves of the 2048-word histogram");
     if (nb <= (uint32_t)NT / 2) {
         // Few enough to rank every listed key against all the others: the comparisons of one key
@@ -559,6 +553,22 @@ __device__ __forceinline__ void block_resolve_emit(uint32_t nb, uint32_t rem, in
         };
         block_kth_largest<NT>(for_list, rem, s_hist, T, need_eq);
     }
+}
+
+// Second half of the histogram-helped selection, on data already in shared memory: s_gt = bitmap
+// of the ids above the deciding bucket, s_eq = zeroed bitmap, l_ent[0..nb) = the (key, id) pairs
+// of the deciding bucket, of which the `rem` largest keys are still wanted (ties: lowest ids).
+// n ids in all (both bitmaps have 2*ceil(n/64) words).  Starts with the data as written by other
+// threads: the caller places a barrier before the call.
+template <int NT, typename EmitFn>
+__device__ __forceinline__ void block_resolve_emit(uint32_t nb, uint32_t rem, int n, uint32_t *s_hist, uint32_t *s_gt,
+                                                   uint32_t *s_eq, const uint2 *l_ent, EmitFn emit)
+{
+    const int tid = threadIdx.x;
+    uint32_t *s_scan = s_hist + 2048 + 4;
+    const int nw64 = (n + 63) >> 6;
+    uint32_t T, need_eq;
+    block_list_threshold<NT>(nb, rem, s_hist, l_ent, T, need_eq);
     __syncthreads();
     CTKVR_STAMP(35);
     for (uint32_t e = tid; e < nb; e += NT) {

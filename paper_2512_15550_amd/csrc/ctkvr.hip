@@ -903,6 +903,7 @@ int decode_launch_group(ctkvr_index *ix, const StepWs &w_all, int b0, int nb, bo
     aa.out = out;
     aa.out_lse = out_lse;
     aa.win = window ? w.win : nullptr;
+    aa.m_key = w.m_key;
     if (ix->fused_lds) {
         if (whole) ix->mark(7, st);   // no separate selection launch: its stage reads as the cost of an event pair
         select_attn_kernel<T, G><<<dim3(4 * U), 1024, ix->fused_lds, st>>>(se, aa);

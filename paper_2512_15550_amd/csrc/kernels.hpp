@@ -1258,6 +1258,7 @@ struct AttnArgs {
     float *out;  // [batch*h][128]
     float *out_lse;
     const float *win;   // optional: window_attn_kernel's partial results, [units][kWinSplit][G][2 + 128]
+    const uint32_t *m_key;   // [units][G] ordered-key maxima of the logits over all recalled keys
 };
 
 // ------------------------------------------------------------------------------
@@ -1500,6 +1501,10 @@ __device__ __forceinline__ void attend_unit(const AttnArgs &a, int ul, int slice
     for (int u = 0; u < 4; ++u) vrow[u] = row_of(min(u * 256 + rin, a.top_k - 1));
 #pragma unroll
     for (int u = 0; u < 4; ++u) cv[u] = load_chunk(V + (size_t)vrow[u] * kD, 0);
+    // the first 1024 keys' logits travel with their value rows
+    float zq[4][G];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) z_of(min(u * 256 + rin, a.top_k - 1), zq[u]);
     const int nsel = nsel_of();
     if (nsel == 0) {   // nothing recalled: the window alone, or zeros
         if (tid < G * 32) {
@@ -1511,56 +1516,48 @@ __device__ __forceinline__ void attend_unit(const AttnArgs &a, int ul, int slice
         }
         return;
     }
-    // softmax statistics over the selected keys, per head
-    float mx[G];
+    // One pass: weights relative to the unit's maxima over ALL its recalled keys, known since the scoring
+    // (every selected logit is at most that maximum), so that no statistics of the selected keys have to be
+    // gathered before their value rows can be used.  Lane groups that share a key row compute the same
+    // weights; the lanes of a wave's first row carry them into the denominators.
+    float acc[G][8], lsum[G], mref[G];
 #pragma unroll
-    for (int hh = 0; hh < G; ++hh) mx[hh] = -__builtin_huge_valf();
-    for (int t = tid; t < nsel; t += 1024) {
-        float zv[G];
-        z_of(t, zv);
+    for (int hh = 0; hh < G; ++hh) {
+        mref[hh] = ordered_value(a.m_key[ul * G + hh]);
+        lsum[hh] = 0.0f;
 #pragma unroll
-        for (int hh = 0; hh < G; ++hh) {
-            s_p[t * G + hh] = zv[hh];
-            mx[hh] = fmaxf(mx[hh], zv[hh]);
+        for (int e = 0; e < 8; ++e) acc[hh][e] = 0.0f;
+    }
+    for (int r0 = 0; r0 < nsel; r0 += 1024) {
+        if (r0 > 0) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) vrow[u] = row_of(min(r0 + u * 256 + rin, a.top_k - 1));
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                cv[u] = load_chunk(V + (size_t)vrow[u] * kD, 0);
+                z_of(min(r0 + u * 256 + rin, a.top_k - 1), zq[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int t = r0 + u * 256 + rin;
+            if (t < nsel) {
+                float vx[8];
+                unpack(cv[u], vx);
+#pragma unroll
+                for (int hh = 0; hh < G; ++hh) {
+                    const float pw = __expf(zq[u][hh] - mref[hh]);
+                    lsum[hh] += quad == 0 ? pw : 0.0f;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[hh][e] = __fmaf_rn(pw, vx[e], acc[hh][e]);
+                }
+            }
         }
     }
     CTKVR_STAMP(48);
 #pragma unroll
     for (int hh = 0; hh < G; ++hh) {
-        float v = mx[hh];
-#pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-        if (ln == 0) s_red[wv][hh] = v;
-    }
-    __syncthreads();
-    CTKVR_STAMP(49);
-    if (tid < G) {
-        float v = s_red[0][tid];
-#pragma unroll
-        for (int w = 1; w < 16; ++w) v = fmaxf(v, s_red[w][tid]);
-        s_m[tid] = v;
-    }
-    __syncthreads();
-    float sm[G];
-#pragma unroll
-    for (int hh = 0; hh < G; ++hh) {
-        mx[hh] = s_m[hh];
-        sm[hh] = 0.0f;
-    }
-    for (int t = tid; t < nsel; t += 1024) {
-#pragma unroll
-        for (int hh = 0; hh < G; ++hh) {
-            float p = __expf(s_p[t * G + hh] - mx[hh]);
-            s_p[t * G + hh] = p;
-            sm[hh] += p;
-        }
-    }
-    CTKVR_STAMP(50);
-#pragma unroll
-    for (int hh = 0; hh < G; ++hh) {
-        float v = sm[hh];
-#pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+        const float v = group16_sum(lsum[hh]);   // rows 1-3 of the wave hold zeros
         if (ln == 0) s_red[wv][hh] = v;
     }
     __syncthreads();
@@ -1569,34 +1566,105 @@ __device__ __forceinline__ void attend_unit(const AttnArgs &a, int ul, int slice
 #pragma unroll
         for (int w = 0; w < 16; ++w) v += s_red[w][tid];
         s_l[tid] = v;
+        s_m[tid] = mref[0];
+#pragma unroll
+        for (int c = 1; c < G; ++c)
+            if (tid == c) s_m[tid] = mref[c];
     }
     __syncthreads();
     CTKVR_STAMP(45);
-    // weighted sum of the value rows
-    float acc[G][8];
+    bool underflow = false;   // a head whose selected logits all lie far below its maximum: the same for every thread
 #pragma unroll
-    for (int hh = 0; hh < G; ++hh)
+    for (int hh = 0; hh < G; ++hh) underflow |= !(s_l[hh] >= 1e-30f);
+    if (underflow) {
+        // two passes instead: the selected keys' own maxima first, then weights relative to them
+        __syncthreads();
+        // softmax statistics over the selected keys, per head
+        float mx[G];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[hh][e] = 0.0f;
-    for (int r0 = 0; r0 < nsel; r0 += 1024) {
-        if (r0 > 0) {
+        for (int hh = 0; hh < G; ++hh) mx[hh] = -__builtin_huge_valf();
+        for (int t = tid; t < nsel; t += 1024) {
+            float zv[G];
+            z_of(t, zv);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) vrow[u] = row_of(min(r0 + u * 256 + rin, a.top_k - 1));
-#pragma unroll
-            for (int u = 0; u < 4; ++u) cv[u] = load_chunk(V + (size_t)vrow[u] * kD, 0);
+            for (int hh = 0; hh < G; ++hh) {
+                s_p[t * G + hh] = zv[hh];
+                mx[hh] = fmaxf(mx[hh], zv[hh]);
+            }
         }
+        CTKVR_STAMP(48);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            int t = r0 + u * 256 + rin;
-            if (t < nsel) {
-                float vx[8];
-                unpack(cv[u], vx);
-                float pv[G];
-                load_z<G>(s_p, t, pv);
+        for (int hh = 0; hh < G; ++hh) {
+            float v = mx[hh];
 #pragma unroll
-                for (int hh = 0; hh < G; ++hh)
+            for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+            if (ln == 0) s_red[wv][hh] = v;
+        }
+        __syncthreads();
+        CTKVR_STAMP(49);
+        if (tid < G) {
+            float v = s_red[0][tid];
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[hh][e] = __fmaf_rn(pv[hh], vx[e], acc[hh][e]);
+            for (int w = 1; w < 16; ++w) v = fmaxf(v, s_red[w][tid]);
+            s_m[tid] = v;
+        }
+        __syncthreads();
+        float sm[G];
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh) {
+            mx[hh] = s_m[hh];
+            sm[hh] = 0.0f;
+        }
+        for (int t = tid; t < nsel; t += 1024) {
+#pragma unroll
+            for (int hh = 0; hh < G; ++hh) {
+                float p = __expf(s_p[t * G + hh] - mx[hh]);
+                s_p[t * G + hh] = p;
+                sm[hh] += p;
+            }
+        }
+        CTKVR_STAMP(50);
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh) {
+            float v = sm[hh];
+#pragma unroll
+            for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+            if (ln == 0) s_red[wv][hh] = v;
+        }
+        __syncthreads();
+        if (tid < G) {
+            float v = 0.0f;
+#pragma unroll
+            for (int w = 0; w < 16; ++w) v += s_red[w][tid];
+            s_l[tid] = v;
+        }
+        __syncthreads();
+        CTKVR_STAMP(45);
+        // weighted sum of the value rows
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[hh][e] = 0.0f;
+        for (int r0 = 0; r0 < nsel; r0 += 1024) {
+            {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) vrow[u] = row_of(min(r0 + u * 256 + rin, a.top_k - 1));
+#pragma unroll
+                for (int u = 0; u < 4; ++u) cv[u] = load_chunk(V + (size_t)vrow[u] * kD, 0);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                int t = r0 + u * 256 + rin;
+                if (t < nsel) {
+                    float vx[8];
+                    unpack(cv[u], vx);
+                    float pv[G];
+                    load_z<G>(s_p, t, pv);
+#pragma unroll
+                    for (int hh = 0; hh < G; ++hh)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) acc[hh][e] = __fmaf_rn(pv[hh], vx[e], acc[hh][e]);
+                }
             }
         }
     }
@@ -1679,7 +1747,7 @@ template <typename T, int G> __global__ __launch_bounds__(1024) void select_attn
                           const uint32_t r = rb[n > 0 ? s_idx[min(t, n - 1)] : 0];
                           return n > 0 ? r : 0u;
                       },
-                      [&](int t, float(&zv)[G]) { load_z<G>(zb, s_idx[t], zv); }, [&]() { return n; });
+                      [&](int t, float(&zv)[G]) { load_z<G>(zb, n > 0 ? s_idx[min(t, n - 1)] : 0, zv); }, [&]() { return n; });
 }
 
 // ------------------------------------------------------------------------------
