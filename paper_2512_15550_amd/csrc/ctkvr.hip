@@ -119,6 +119,7 @@ struct ctkvr_index {
     bool have_step = false;
     size_t recall_lds = 0, select_lds = 0, attn_lds = 0, build_select_lds = 0;
     size_t fused_lds = 0;   // non-zero: selection and attention run as one launch (select_attn_kernel)
+    int score_by_rank = -1;   // how the scoring kernel splits a unit's recalled ids over its blocks: -1 chosen per batch, 0 by id range, 1 by rank
     int sel_bits = 0, build_bits = 0;   // words for the selection's id bitmaps (0: histogram route off)
     int bitmap_words = 0, recall_split = 1, num_cu = 256;
     // single-launch step (decode_fused_kernel): blocks per unit (0: the geometry does not allow it), its shared memory,
@@ -329,6 +330,7 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
     {
         int ng = 1;
         if (const char *e = getenv("CTKVR_DECODE_GROUPS")) ng = std::max(1, std::min(std::min(8, B), atoi(e)));
+        if (const char *e = getenv("CTKVR_SCORE_BY_RANK")) ix->score_by_rank = atoi(e) != 0;
         ix->n_groups = ng;
     }
     if (const char *e = getenv("CTKVR_DECODE_PATH")) {
@@ -499,6 +501,10 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
     hipError_t e1 = hipMalloc((void **)&m_key, (size_t)chunk * G * 4);
     hipError_t e2 = hipMalloc((void **)&S, (size_t)chunk * G * 8);
     uint32_t *kbuf = nullptr, *ghist = nullptr;
+    float2 *part = nullptr;   // matrix-core route: one (maximum, sum) pair per unit, head and block of the statistics pass
+    constexpr int kMaxSplits = 64;
+    if (mfma && hipMalloc((void **)&part, (size_t)chunk * G * kMaxSplits * sizeof(float2)) != hipSuccess)
+        return fail(CTKVR_ENOMEM, "build scratch allocation failed");
     hipError_t e3 = hipMalloc((void **)&kbuf, (size_t)chunk * ix->s_max * 4);
     hipError_t e4 = hipMalloc((void **)&ghist, (size_t)chunk * kBuckets * 4);
     int rc = CTKVR_OK;
@@ -535,21 +541,19 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
                 ma.bk0 = u0 / ix->c_max;
                 ma.tiles_per_bk = (ix->c_max + CT - 1) / CT;
                 const int tiles = (nu / ix->c_max) * ma.tiles_per_bk;
-                ma.t_splits = std::max(1, std::min((ix->s_max + 1023) / 1024, (4 * ix->num_cu + tiles - 1) / tiles));
+                ma.t_splits = std::max(1, std::min({(ix->s_max + 1023) / 1024, (4 * ix->num_cu + tiles - 1) / tiles, kMaxSplits}));
                 ma.n_cent = ix->d_n_cent;
                 ma.ctx_lens = ix->d_ctx_lens;
                 ma.centroids = (const bf16_t *)ix->centroids;
                 ma.k = sa.k;
                 ma.l_stride = ix->s_max;
-                ma.m_key = m_key;
-                ma.S = S;
+                ma.part = part;
                 ma.kbuf = kbuf;
                 ma.n_init = ix->p.n_init;
                 ma.n_local = ix->p.n_local;
                 ma.scale = ix->scale;
-                // three passes over the same tiles: maxima, denominators, keys (nothing but the keys is stored)
-                mfma_score_kernel<G, MFMA_MAX><<<dim3(ma.t_splits, tiles), 256, 0, st>>>(ma);
-                mfma_score_kernel<G, MFMA_SUM><<<dim3(ma.t_splits, tiles), 256, 0, st>>>(ma);
+                // two passes over the same tiles: softmax statistics, keys (nothing but the keys is stored)
+                mfma_score_kernel<G, MFMA_STAT><<<dim3(ma.t_splits, tiles), 256, 0, st>>>(ma);
                 mfma_score_kernel<G, MFMA_KEY><<<dim3(ma.t_splits, tiles), 256, 0, st>>>(ma);
             } else {
                 score_kernel<T, G, 16><<<dim3((ix->s_max + 255) / 256, nu), 256, 0, st>>>(sa);
@@ -606,6 +610,7 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
     (void)hipFree(S);
     (void)hipFree(kbuf);
     (void)hipFree(ghist);
+    (void)hipFree(part);
     return rc;
 }
 
@@ -813,11 +818,22 @@ int decode_launch_group(ctkvr_index *ix, const StepWs &w_all, int b0, int nb, bo
     sa.m_key = w.m_key;
     sa.ghist = w.ghist;
     sa.scale = ix->scale;
-    {   // enough blocks to fill the chip a few times over (at least 32 per unit, so that the long
-        // units of a ragged batch do not set the pace), each owning 8..64 words of the bitmap
-        const int target = std::max(32, (8 * ix->num_cu + U - 1) / U);
-        const int wpb = std::max(8, std::min(kRecallWpb, (ix->bitmap_words + target - 1) / target));
-        const int nbx = (ix->bitmap_words + wpb - 1) / wpb;
+    {
+        // Few rows per CU (a small batch): a block's rows are one round trip to memory and the slowest block
+        // is the launch, so the ids are split by rank -- two blocks per CU, at least 32 per unit and 64 ranks
+        // per block.  Otherwise by id range: enough blocks to fill the chip a few times over, each owning
+        // 8..64 words of the bitmap.
+        const bool by_rank = ix->score_by_rank < 0 ? (long long)ix->l_stride * U <= 2048ll * ix->num_cu : ix->score_by_rank != 0;
+        sa.by_rank = by_rank;
+        int nbx;
+        if (by_rank) {
+            nbx = std::min(std::max(32, (2 * ix->num_cu + U - 1) / U), (ix->l_stride + 63) / 64);
+            nbx = std::max({1, nbx, (ix->l_stride + kRecallCap - 1) / kRecallCap});
+        } else {
+            const int target = std::max(32, (8 * ix->num_cu + U - 1) / U);
+            const int wpb = std::max(8, std::min(kRecallWpb, (ix->bitmap_words + target - 1) / target));
+            nbx = (ix->bitmap_words + wpb - 1) / wpb;
+        }
         recall_score_kernel<T, G><<<dim3(nbx, U), 256, 0, st>>>(sa);
     }
     if (whole) ix->mark(3, st);

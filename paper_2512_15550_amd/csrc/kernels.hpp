@@ -346,16 +346,25 @@ template <typename T, int G, int R> __global__ __launch_bounds__(256) void score
 }
 
 // ------------------------------------------------------------------------------
-// Algorithm 2 lines 4-5 in one launch (decode): block x of a unit owns words
-// [x*wpb, (x+1)*wpb) of the unit's recall bitmap.  It counts the ids before its range (the
-// bitmap is a few KB), turns its own words into ascending ids in shared memory (one word per
-// thread, positions by a block scan), writes them and their physical rows to their ranks of
-// the recalled list (consecutive lanes, consecutive ranks), and scores them like score_kernel:
-// z[rank][G], running maximum per head.  The block owning the last word also writes L.
-// grid (nbx, units), 256 threads, with nbx >= W_max / kRecallWpb; a unit with W words gives
-// ceil(W / nbx) of them to each block.
+// Algorithm 2 lines 4-5 in one launch (decode).  A unit's bitmap of recalled ids is split over the
+// unit's blocks; a block turns its part into ascending ids 64 words at a time (one byte per thread,
+// positions by a block scan), writes them and their physical rows to their ranks of the recalled
+// list, and scores the rows like score_kernel: z[rank][G], running maximum per head.
+// Two ways to split, chosen by the host:
+//   by id range -- block x owns words [x wpb, (x + 1) wpb), wpb <= 64, and counts the ids in the words
+//     before its own (coalesced 4-byte loads, no scan).  The cheapest prologue; recalled keys cluster,
+//     so some blocks get several times the rows of others, which does not matter while every CU has
+//     many blocks' worth of rows to stream.
+//   by rank -- block x takes ranks [x q, (x + 1) q), q = ceil(L / blocks): every block counts the whole
+//     bitmap (a contiguous stretch of words per thread, one block scan), which gives L and tells the
+//     two threads whose stretches hold the block's first and last rank to name their words.  One more
+//     round trip to the cache, but every block then has the same number of rows: for small batches,
+//     where a block's rows are one or two round trips to memory and the slowest block is the launch.
+// The block that sees the unit's last word (by id) or block 0 (by rank) also writes L.
+// grid (nbx, units), 256 threads; by id nbx >= W_max / 64, by rank nbx >= l_stride / kRecallCap.
 // ------------------------------------------------------------------------------
-constexpr int kRecallWpb = 64;   // at most 2048 ids per block
+constexpr int kRecallWpb = 64;     // by id range: at most 2048 ids per block
+constexpr int kRecallCap = 2048;   // ids per block at most
 
 struct RecallScoreArgs {
     Units u;
@@ -373,65 +382,133 @@ struct RecallScoreArgs {
     uint32_t *ghist;          // [units][kBuckets] key histogram, cleared here for keyhist
     float scale;
     int stream_k;             // the keys of all sequences exceed what the memory-side cache holds: load them non-temporal
+    int by_rank;              // how the bitmap is split over a unit's blocks
 };
 
 template <typename T, int G> __global__ __launch_bounds__(256) void recall_score_kernel(RecallScoreArgs a)
 {
     constexpr int R = 8, TILE = 16 * R;
-    __shared__ uint32_t s_ids[kRecallWpb * 32];   // ids of this block's range, then their rows
-    __shared__ int32_t s_page[256];               // block-table entries of the range's pages
-    __shared__ uint32_t s_tmp[8], s_bef[4];
+    __shared__ uint32_t s_ids[kRecallCap];        // ids of this block's ranks, then their rows
+    __shared__ int32_t s_page[256];               // block-table entries of the pages its ids lie in
+    __shared__ uint32_t s_tmp[8];
+    __shared__ uint32_t s_edge[3];                // first word, ids before it, last word
     __shared__ uint32_t s_max[G];
     const int ul = blockIdx.y, b = ul / a.u.g, kv = ul - b * a.u.g;
-    const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4, ln = lane_id();
+    const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4;
     CTKVR_STAMP_BLK(6);
     const int s_len = a.ctx_lens[b];
     const int W = (s_len + 31) >> 5;
-    // the unit's own words split evenly over the blocks of its row (a short sequence of a ragged
-    // batch still uses all of them)
-    const int wpb = min(kRecallWpb, (W + (int)gridDim.x - 1) / (int)gridDim.x);
-    const int w_beg = blockIdx.x * wpb;
     for (int w = blockIdx.x * 256 + tid; w < kBuckets; w += gridDim.x * 256) a.ghist[(size_t)ul * kBuckets + w] = 0u;
-    if (w_beg >= W) return;
-    const int w_end = min(W, w_beg + wpb);
     const uint32_t *gb = a.gbits + (size_t)ul * a.bitmap_words;
-    // Requested together: this thread's byte of the range (four threads per word), the block-table
-    // entries of the pages the range covers, the queries, and the words before the range.
-    const uint32_t myword = ((tid >> 2) < w_end - w_beg) ? gb[w_beg + (tid >> 2)] : 0u;
-    const int page0 = (w_beg << 5) >> a.k.page_shift;
-    const int npages = ((min(w_end << 5, s_len) - 1) >> a.k.page_shift) - page0 + 1;   // ids stop at s_len - 1
-    const bool lds_pages = npages <= 256;
-    if (lds_pages && tid < npages) s_page[tid] = a.k.block_table[(size_t)b * a.k.max_pages + page0 + tid];
-    float q[G][8];
-    const T *qb = (const T *)a.q + ((size_t)b * a.u.h + kv * G) * kD;
-#pragma unroll
-    for (int hh = 0; hh < G; ++hh) unpack(load_chunk(qb + (size_t)hh * kD, lane16), q[hh]);
-    uint32_t before = 0;
-#pragma unroll 4
-    for (int w = tid; w < w_beg; w += 256) before += (uint32_t)__popc(gb[w]);
-    before = wave_sum_uniform(before);
     if (tid < G) s_max[tid] = 0u;
-    if (ln == 0) s_bef[tid >> 6] = before;
-    const uint32_t mine = (myword >> ((tid & 3) << 3)) & 0xffu;
-    uint32_t n_blk;
-    uint32_t pos = block_excl_scan<256>((uint32_t)__popc(mine), s_tmp, &n_blk);   // barriers inside
-    const uint32_t base = s_bef[0] + s_bef[1] + s_bef[2] + s_bef[3];
-    if (w_end == W && tid == 0) {
-        a.ncand[ul] = (int32_t)(base + n_blk);
-        if (a.out_ncand) a.out_ncand[ul] = (int32_t)(base + n_blk);
+    uint32_t r0, r1;   // the block's ranks
+    if (a.by_rank) {
+        // thread t counts words [t wpt, (t + 1) wpt), wpt a multiple of four: 16-byte loads where the
+        // unit's words start on a 16-byte boundary (words from W up to the row's end are zero)
+        const int wpt = ((((W + 255) >> 8) + 3) >> 2) << 2;
+        const int w0 = tid * wpt;
+        uint32_t cnt = 0;
+        if (((reinterpret_cast<uintptr_t>(gb) | ((uintptr_t)a.bitmap_words << 2)) & 15u) == 0) {
+#pragma unroll 4
+            for (int w = w0; w < min(w0 + wpt, a.bitmap_words); w += 4) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(gb + w);
+                cnt += (uint32_t)(__popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w));
+            }
+        } else {
+#pragma unroll 4
+            for (int w = w0; w < min(w0 + wpt, W); ++w) cnt += (uint32_t)__popc(gb[w]);
+        }
+        uint32_t L;
+        const uint32_t pre = block_excl_scan<256>(cnt, s_tmp, &L);   // barriers inside
+        if (blockIdx.x == 0 && tid == 0) {
+            a.ncand[ul] = (int32_t)L;
+            if (a.out_ncand) a.out_ncand[ul] = (int32_t)L;
+        }
+        const uint32_t qn = (L + gridDim.x - 1) / gridDim.x;
+        r0 = blockIdx.x * qn;
+        if (r0 >= L) return;
+        r1 = min(L, r0 + qn);
+        // the threads whose stretches hold ranks r0 and r1 - 1 walk their words (cached) to the one that holds it
+        if (cnt && pre <= r0 && r0 < pre + cnt) {
+            uint32_t p = pre;
+            for (int w = w0; w < w0 + wpt; ++w) {
+                const uint32_t c = (uint32_t)__popc(gb[w]);
+                if (r0 < p + c) {
+                    s_edge[0] = (uint32_t)w;
+                    s_edge[1] = p;
+                    break;
+                }
+                p += c;
+            }
+        }
+        if (cnt && pre < r1 && r1 <= pre + cnt) {
+            uint32_t p = pre;
+            for (int w = w0; w < w0 + wpt; ++w) {
+                p += (uint32_t)__popc(gb[w]);
+                if (r1 <= p) {
+                    s_edge[2] = (uint32_t)w;
+                    break;
+                }
+            }
+        }
+    } else {
+        // the unit's own words split evenly over the blocks of its row (a short sequence of a ragged
+        // batch still uses all of them)
+        const int wpb = min(kRecallWpb, (W + (int)gridDim.x - 1) / (int)gridDim.x);
+        const int w_beg = blockIdx.x * wpb;
+        if (w_beg >= W) return;
+        uint32_t before = 0;
+#pragma unroll 4
+        for (int w = tid; w < w_beg; w += 256) before += (uint32_t)__popc(gb[w]);
+        before = wave_sum_uniform(before);
+        if ((tid & 63) == 0) s_tmp[tid >> 6] = before;
+        __syncthreads();
+        if (tid == 0) {
+            s_edge[0] = (uint32_t)w_beg;
+            s_edge[1] = s_tmp[0] + s_tmp[1] + s_tmp[2] + s_tmp[3];
+            s_edge[2] = (uint32_t)(min(W, w_beg + wpb) - 1);
+        }
+        r0 = r1 = 0u;   // known after the (single) pass over the block's words
+    }
+    __syncthreads();
+    const int wa = (int)s_edge[0], wb = (int)s_edge[2];
+    uint32_t rank0 = s_edge[1];   // ids before the pass's first word
+    if (!a.by_rank) {
+        r0 = rank0;
+        r1 = 0xffffffffu;
     }
     CTKVR_STAMP_BLK(7);
-    if (n_blk == 0) return;
-    {
-        uint32_t m = mine;
-        const uint32_t id0 = ((uint32_t)(w_beg + (tid >> 2)) << 5) + ((uint32_t)(tid & 3) << 3);
+    // requested together: the first pass's words and the block-table entries of the pages between the two words
+    uint32_t myword = (wa + (tid >> 2) <= wb) ? gb[wa + (tid >> 2)] : 0u;
+    const int page0 = (wa << 5) >> a.k.page_shift;
+    const int npages = ((min((wb << 5) + 31, s_len - 1)) >> a.k.page_shift) - page0 + 1;
+    const bool lds_pages = npages <= 256;
+    if (lds_pages && tid < npages) s_page[tid] = a.k.block_table[(size_t)b * a.k.max_pages + page0 + tid];
+    for (int wp = wa; wp <= wb; wp += 64) {
+        if (wp != wa) myword = (wp + (tid >> 2) <= wb) ? gb[wp + (tid >> 2)] : 0u;
+        uint32_t m = (myword >> ((tid & 3) << 3)) & 0xffu;
+        uint32_t n_pass;
+        uint32_t rk = rank0 + block_excl_scan<256>((uint32_t)__popc(m), s_tmp, &n_pass);   // barriers inside
+        const uint32_t id0 = ((uint32_t)(wp + (tid >> 2)) << 5) + ((uint32_t)(tid & 3) << 3);
         while (m) {
             const int bit = __ffs((int)m) - 1;
             m &= m - 1u;
-            s_ids[pos++] = id0 + (uint32_t)bit;
+            if (rk >= r0 && rk < r1) s_ids[rk - r0] = id0 + (uint32_t)bit;
+            ++rk;
         }
+        rank0 += n_pass;
     }
+    if (!a.by_rank) {   // one pass: the block's ids are all the ids of its words
+        r1 = rank0;
+        if (wb == W - 1 && tid == 0) {
+            a.ncand[ul] = (int32_t)r1;
+            if (a.out_ncand) a.out_ncand[ul] = (int32_t)r1;
+        }
+        if (r1 == r0) return;
+    }
+    const uint32_t n_blk = r1 - r0;
     __syncthreads();
+    const uint32_t base = r0;
     int32_t *cd = a.cand + (size_t)ul * a.l_stride + base;
     uint32_t *rw = a.crow + (size_t)ul * a.l_stride + base;
     const int pmask = (1 << a.k.page_shift) - 1;
@@ -450,6 +527,11 @@ template <typename T, int G> __global__ __launch_bounds__(256) void recall_score
     CTKVR_STAMP_BLK(2);
     const T *K = (const T *)a.k.pages;
     float *zb = a.z + ((size_t)ul * a.l_stride + base) * G;
+    // the queries are requested with the first rows (cached, they arrive well before the rows do)
+    float q[G][8];
+    const T *qb = (const T *)a.q + ((size_t)b * a.u.h + kv * G) * kD;
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) unpack(load_chunk(qb + (size_t)hh * kD, lane16), q[hh]);
     // lane l of a 16-lane group keeps head (l mod G): its score, and that head's running maximum
     float mxl = -__builtin_huge_valf();
     const int myh = lane16 & (G - 1);
@@ -519,19 +601,20 @@ struct MfmaScoreArgs {
     const bf16_t *centroids;   // [batch][h][c_max][128]
     Paged k;
     int l_stride;              // s_max
-    uint32_t *m_key;           // [chunk units][G]   pass MAX writes, passes SUM and KEY read
-    unsigned long long *S;     // [chunk units][G]   pass SUM adds, pass KEY reads
+    float2 *part;              // [chunk units][G][t_splits] (maximum, sum of exp(z - maximum)) over a block's keys
     uint32_t *kbuf;            // [chunk units][l_stride] ranking keys, pass KEY
     int n_init, n_local;       // keys of the resident window get the lowest ranking key
     float scale;
 };
 
-// The scores are never stored: the contraction is repeated in three passes over the same tiles,
-// each with its own epilogue -- MFMA_MAX: running maximum per (centroid, head); MFMA_SUM: the
-// integer softmax denominators (exactly denom_kernel's arithmetic on exactly the same scores, the
-// matrix cores being deterministic); MFMA_KEY: ranking keys max_h ((z - m_h) - log S_h), written as
+// The scores are never stored: the contraction is repeated in two passes over the same tiles, each
+// with its own epilogue -- MFMA_STAT: per (centroid, head) the running maximum m of the scores and the
+// running sum of exp(z - m), rescaled whenever the maximum moves, in fp32 with the hardware
+// exponential (this route's lists are compared with the fixed arithmetic inside an error band anyway,
+// and the band has room for a denominator that is a few 1e-5 off); one (m, sum) pair per block, merged
+// in block order by the next pass.  MFMA_KEY: ranking keys max_h ((z - m_h) - log S_h), written as
 // ordered uint32 (4 bytes per (centroid, key) instead of 4 G bytes of scores read twice).
-enum { MFMA_MAX = 0, MFMA_SUM = 1, MFMA_KEY = 2 };
+enum { MFMA_STAT = 0, MFMA_KEY = 2 };
 
 template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_kernel(MfmaScoreArgs a)
 {
@@ -559,9 +642,8 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
     // keys (rows 8 (r / 4) + 4 half + r % 4), and that centroid's statistics are single registers.
     int hh[2], mt[2];
     bf16x8_t cfrag[2][8];                  // the centroid fragments, resident
-    float mx[2];                           // MAX: running maximum (unscaled); SUM, KEY: the final maximum m
-    float lsv[2];                          // KEY: log S
-    unsigned long long sum[2];             // SUM
+    float mx[2];                           // STAT: running maximum; KEY: the final maximum m
+    float lsv[2];                          // STAT: running sum of exp(z - mx); KEY: log S
     size_t stat[2];
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
@@ -575,9 +657,16 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
         stat[q] = ((size_t)bkl * a.c_max + j) * G + hh[q];
         mx[q] = -__builtin_huge_valf();
         lsv[q] = 0.0f;
-        sum[q] = 0ull;
-        if constexpr (MODE != MFMA_MAX) mx[q] = ordered_value(a.m_key[stat[q]]);
-        if constexpr (MODE == MFMA_KEY) lsv[q] = (float)log_fixed40(a.S[stat[q]]);
+        if constexpr (MODE == MFMA_KEY) {
+            // the blocks' pairs in block order: the same value in every block that reads them
+            const float2 *pp = a.part + stat[q] * a.t_splits;
+            float m = -__builtin_huge_valf();
+            for (int x = 0; x < a.t_splits && x * tper < s; ++x) m = fmaxf(m, pp[x].x);
+            float S = 0.0f;
+            for (int x = 0; x < a.t_splits && x * tper < s; ++x) S += pp[x].y * __expf(pp[x].x - m);
+            mx[q] = m;
+            lsv[q] = logf(S);
+        }
     }
     // The 32 key rows of a step (8 KB) go through shared memory once for the four waves, in two
     // buffers; a step's rows are requested two steps ahead and their block-table entries four
@@ -627,28 +716,27 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
             const f32x16_t &acc = q == 0 ? acc0 : acc1;
-            if constexpr (MODE == MFMA_MAX) {
-                // kept unscaled: rounding acc * scale is monotonic, scale > 0
+            if constexpr (MODE == MFMA_STAT) {
+                // the step's maximum first (repeated keys of a tail are real keys: harmless), then its sixteen
+                // terms relative to the new running maximum, summed as a tree, and the old sum rescaled
+                float zs[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) zs[r] = acc[r] * a.scale;
                 float m = mx[q];
 #pragma unroll
-                for (int r = 0; r < 16; r += 2) m = fmaxf(fmaxf(acc[r], acc[r + 1]), m);
-                mx[q] = m;
-            } else if constexpr (MODE == MFMA_SUM) {
-                // sixteen terms: hi < 2^17 and lo < 2^24 each, their sums fit 32 bits
-                uint32_t shi = 0u, slo = 0u;
+                for (int r = 0; r < 16; r += 2) m = fmaxf(fmaxf(zs[r], zs[r + 1]), m);
+                float e[16];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    uint32_t hi, lo;
-                    exp_fixed40_parts(acc[r] * a.scale - mx[q], hi, lo);
-                    if (tail) {
-                        const bool ok = (t0 + 8 * (r >> 2) + 4 * half + (r & 3)) < tend;
-                        hi = ok ? hi : 0u;
-                        lo = ok ? lo : 0u;
-                    }
-                    shi += hi;
-                    slo += lo;
+                    e[r] = __expf(zs[r] - m);
+                    if (tail) e[r] = (t0 + 8 * (r >> 2) + 4 * half + (r & 3)) < tend ? e[r] : 0.0f;
                 }
-                sum[q] += ((unsigned long long)shi << 24) + slo;
+#pragma unroll
+                for (int w = 8; w >= 1; w >>= 1)
+#pragma unroll
+                    for (int r = 0; r < w; ++r) e[r] += e[r + w];
+                lsv[q] = __fmaf_rn(lsv[q], __expf(mx[q] - m), e[0]);   // first step: 0 * exp(-inf) = 0
+                mx[q] = m;
             } else {
                 float *zrow = &s_z[(hh[q] * CT + mt[q] * 32 + col) * ZS + 4 * half];
 #pragma unroll
@@ -699,35 +787,8 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
             }
         }
     };
-    // The SUM pass has no registers to spare and is bound by its arithmetic: two sets, a step's rows
-    // requested two steps ahead.  The other passes request them four steps ahead (four sets).
-    constexpr bool DEEP = MODE != MFMA_SUM;
-    if constexpr (!DEEP) {
-        int pg_a = page_at(tbeg + 64), pg_b = page_at(tbeg + 96);   // entries of steps 2 and 3
-        fetch(st0a, st0b, row_from(page_at(tbeg), tbeg));
-        fetch(st1a, st1b, row_from(page_at(tbeg + 32), tbeg + 32));
-        put(st0a, st0b, 0);
-        __syncthreads();
-        // two steps per trip, so that register sets and buffers are named at compile time; the trips
-        // whose keys all lie in the block's range run without per-lane predicates
-        auto trip = [&](const bool tail, int t0) __attribute__((always_inline)) {
-            // step i (buffer 0): request step i+2 into set 0, the entry of step i+4; write step i+1 to buffer 1
-            fetch(st0a, st0b, row_from(pg_a, t0 + 64));
-            pg_a = page_at(t0 + 128);
-            compute(tail, 0, t0);
-            put(st1a, st1b, 1);
-            __syncthreads();
-            // step i+1 (buffer 1): request step i+3 into set 1, the entry of step i+5; write step i+2 to buffer 0
-            fetch(st1a, st1b, row_from(pg_b, t0 + 96));
-            pg_b = page_at(t0 + 160);
-            compute(tail, 1, t0 + 32);
-            put(st0a, st0b, 0);
-            __syncthreads();
-        };
-        int t0 = tbeg;
-        for (; t0 + 64 <= tend; t0 += 64) trip(false, t0);
-        if (t0 < tend) trip(true, t0);
-    } else {
+    // A step's rows are requested four steps ahead (four register sets).
+    {
         uint4 st2a, st2b, st3a, st3b;
         int pg_a = page_at(tbeg + 128), pg_b = page_at(tbeg + 160), pg_c = page_at(tbeg + 192), pg_d = page_at(tbeg + 224);
         fetch(st0a, st0b, row_from(page_at(tbeg), tbeg));
@@ -765,16 +826,15 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
         if (t0 < tend) trip(true, t0);
     }
     if constexpr (MODE == MFMA_KEY) return;
+    // the two halves of a wave hold different keys of the same (centroid, head): merged (the same value
+    // on both sides, a sum of two products), then one pair per block
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
         const bool mine = half == 0 && (j0 + mt[q] * 32 + col) < C;
-        if constexpr (MODE == MFMA_MAX) {
-            const float v = fmaxf(mx[q], __shfl_xor(mx[q], 32));
-            if (mine) atomicMax(&a.m_key[stat[q]], ordered_key(v * a.scale));
-        } else {
-            const unsigned long long v = sum[q] + __shfl_xor(sum[q], 32);
-            if (mine && v) atomicAdd(&a.S[stat[q]], v);
-        }
+        const float m_o = __shfl_xor(mx[q], 32), l_o = __shfl_xor(lsv[q], 32);
+        const float m = fmaxf(mx[q], m_o);
+        const float l = lsv[q] * __expf(mx[q] - m) + l_o * __expf(m_o - m);
+        if (mine) a.part[stat[q] * a.t_splits + blockIdx.x] = make_float2(m, l);
     }
 }
 

@@ -66,6 +66,23 @@ def test_staged_step_matches_the_oracle(ck, case):
     _run(ck, case, ck.PATH_STAGED)
 
 
+SPLIT_CASES = CASES[:5] + [CASES[5], CASES[6], CASES[11]] + [
+    # recalled ids far apart (L / s about 1 %): a block's ranks spread over several passes of 64 bitmap words
+    ("sparse_recall", "bf16", 8, 2, (60000,), (530,), 32, 0, 2, 300, 100, 2),
+    ("ragged_sparse", "bf16", 8, 2, (40000, 3000, 17000), (531, 532, 533), 0, 200, 3, 150, 100, 2),
+]
+
+
+@pytest.mark.parametrize("by_rank", [0, 1])
+@pytest.mark.parametrize("case", SPLIT_CASES, ids=[c[0] for c in SPLIT_CASES])
+def test_both_ways_of_splitting_the_recalled_ids_over_blocks_match_the_oracle(ck, case, by_rank, monkeypatch):
+    """The scoring launch gives a unit's blocks equal id ranges or equal numbers of ranks, chosen per batch; here each
+    is forced in turn (read when the index is created)."""
+    monkeypatch.setenv("CTKVR_SCORE_BY_RANK", str(by_rank))
+    print(f"[paths {case[0]}] split by {'rank' if by_rank else 'id range'}", flush=True)
+    _run(ck, case, ck.PATH_STAGED)
+
+
 def test_exact_ties_through_the_single_launch(ck):
     """Duplicated keys and centroids (planted exact ties) and lattice inputs crowd the deciding
     bucket: the unit's first block then selects alone (the histogram-free route)."""

@@ -127,6 +127,29 @@ def test_lists_on_lattice_inputs_are_exact_and_ties_go_to_lowest_id():
     assert np.array_equal(lists2, np.broadcast_to(np.arange(rho, dtype=np.int32), (g, C, rho)))
 
 
+def test_fixed_order_keys_lie_within_the_derived_bound_of_the_exact_ones():
+    """The bound that the matrix-core parity test allows is derived, not chosen: here the one-route half of it is
+    checked on the CPU, oracle keys (fp32, fixed order) against the definition in fp64, on inputs with the norms of
+    the short workloads and, scaled up, of the long ones (query norms near 200)."""
+    from tests.bands import key_error_bound, U_NEAREST
+    for seed, s, gain in ((31, 700, 1.0), (32, 512, 16.0)):     # a power of two keeps the bf16 values exact
+        h, g, C = 8, 2, 6
+        sq = gen_sequence(seed, s, h, g, 128, C, 1, "bf16")
+        Qc = oracle.centroids_last_c(sq.q_tail, C) * np.float32(gain)
+        _, keys = oracle.build_lists(sq.K, Qc, 16, SCALE, return_keys=True)
+        keys = keys.reshape(g, C, s)
+        worst = 0.0
+        for kv in range(g):
+            for j in range(C):
+                grp = Qc[kv * 4:(kv + 1) * 4, j]
+                exact = np.log(brute.group_softmax_max(grp, sq.K[kv], SCALE))
+                bound = key_error_bound(grp, sq.K[kv], SCALE, U_NEAREST)
+                err = np.abs(keys[kv, j].astype(np.float64) - exact).max()
+                assert err <= bound, (err, bound)
+                worst = max(worst, err / bound)
+        assert worst > 1e-4      # the bound is an error bound of this arithmetic, not a number of another scale
+
+
 def test_index_bytes_closed_form_printed_in_paper():
     # the printed example, evaluated by the formula ...
     assert 1 * 4 * 512 * 2560 * 4 == int(GOLD["index_bytes_b1_g4_C512_rho2560"]) == 20 * 2 ** 20
