@@ -240,6 +240,18 @@ int ctkvr_profile_enable(ctkvr_index *idx, int32_t max_steps);
  * their number in *n_steps and restarts recording at step 0. */
 int ctkvr_profile_collect(ctkvr_index *idx, float *ms_host, int32_t capacity_steps, int32_t *n_steps);
 
+/* ---- how the matrix-core list build chose a unit's top-rho (Algorithm 1 line 4) ---------- */
+/* CTKVR_BUILD_MFMA ranks either all s keys of a (KV head, centroid) unit (their 4-byte ranking keys
+ * written once, read for a histogram and read again for the selection) or only the keys at or above
+ * a per-unit threshold taken from a 1-in-16 sample of the positions (a few thousand candidates per
+ * unit; taken when every sequence is at least 32 rho long, rho is 256..2048 and the context at most
+ * 2^18).  The second route yields exactly the same lists: a chunk of units in which a unit ends
+ * with fewer than rho candidates, or more than fit, is redone by the first route.
+ * by_candidates_host: 1 if the index was built by the candidate route; chunks_redone_host: how many
+ * chunks it handed back.  Both HOST, either may be NULL.  The environment variable
+ * CTKVR_BUILD_CANDIDATES = 0 | 1, read at build time, forces the choice where the geometry allows it. */
+int ctkvr_index_build_route(const ctkvr_index *idx, int32_t *by_candidates_host, int32_t *chunks_redone_host);
+
 /* ---- how a decode step is launched ----------------------------------------- */
 /* Algorithm 2 lines 1-9 run either as a sequence of launches (one per stage; any geometry) or as
  * ONE launch whose blocks walk the stages together, a fixed group of co-resident blocks per

@@ -11,5 +11,5 @@ from .binding import (CtkvrError, Index, Params, ctkvr_build_index, ctkvr_decode
                       ctkvr_index_load, ctkvr_last_error, library_path, load_library, BF16, F32, LAST_C, KMEANS,
                       BUILD_EXACT, BUILD_MFMA, ctkvr_profile_enable, ctkvr_profile_collect, ctkvr_selftest_exp, STAGE_NAMES,
                       ctkvr_centroid_update, ctkvr_decode_step_window, ctkvr_decode_step_static,
-                      ctkvr_index_set_decode_path, ctkvr_index_decode_path, ctkvr_index_check, ctkvr_profile_phases,
+                      ctkvr_index_set_decode_path, ctkvr_index_decode_path, ctkvr_index_check, ctkvr_index_build_route, ctkvr_profile_phases,
                       ctkvr_measure_dispatch_floor, PATH_AUTO, PATH_STAGED, PATH_FUSED)

@@ -43,5 +43,31 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+PROBES = ["sync_probe", "latency_probe"]
+PROBE_DIR = os.path.join(HERE, "probes")
+
+
+def build_probes(verbose: bool = False):
+    """The stand-alone measurement programs under csrc/probes (launch floor, in-launch barriers, visibility,
+    latencies): executables in probes/, not used by the library."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(PROBE_DIR, exist_ok=True)
+    out = []
+    for name in PROBES:
+        exe = os.path.join(PROBE_DIR, name)
+        cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               "-o", exe, os.path.join(CSRC, "probes", name + ".hip")]
+        if verbose:
+            print(" ".join(cmd))
+        proc = subprocess.run(cmd, capture_output=True, text=True)
+        if proc.returncode != 0:
+            raise RuntimeError("hipcc failed: " + " ".join(cmd) + "\n" + proc.stdout + proc.stderr)
+        out.append(exe)
+    return out
+
+
 if __name__ == "__main__":
+    import sys
     print(build_library(verbose=True))
+    if "--probes" in sys.argv:
+        print("\n".join(build_probes(verbose=True)))

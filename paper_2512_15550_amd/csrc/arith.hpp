@@ -506,8 +506,8 @@ __device__ __forceinline__ uint32_t key_bucket(uint32_t kk)
 
 // T = the rem-th largest of the keys l_ent[0..nb).x (in shared memory), and need_eq = how many of the
 // keys equal to T belong to the rem largest.  Every thread of the block takes part; barriers inside.
-// s_hist: the 2048 + 64 words of the selection routines.  1 <= rem <= nb <= kListCap.
-template <int NT>
+// s_hist: the 2048 + 64 words of the selection routines.  1 <= rem <= nb <= CAP.
+template <int NT, int CAP = kListCap>
 __device__ __forceinline__ void block_list_threshold(uint32_t nb, uint32_t rem, uint32_t *s_hist, const uint2 *l_ent, uint32_t &T,
                                                      uint32_t &need_eq)
 {
@@ -545,7 +545,7 @@ __device__ __forceinline__ void block_list_threshold(uint32_t nb, uint32_t rem, 
     } else {
         auto for_list = [&](auto f) __attribute__((always_inline)) {
 #pragma unroll
-            for (int q = 0; q < kListCap / NT; ++q) {
+            for (int q = 0; q < CAP / NT; ++q) {
                 const uint32_t e = (uint32_t)(q * NT + tid);
                 const bool valid = e < nb;
                 f((int)e, valid, valid ? l_ent[e].x : 0u);
@@ -560,7 +560,7 @@ __device__ __forceinline__ void block_list_threshold(uint32_t nb, uint32_t rem, 
 // of the deciding bucket, of which the `rem` largest keys are still wanted (ties: lowest ids).
 // n ids in all (both bitmaps have 2*ceil(n/64) words).  Starts with the data as written by other
 // threads: the caller places a barrier before the call.
-template <int NT, typename EmitFn>
+template <int NT, int CAP = kListCap, typename EmitFn>
 __device__ __forceinline__ void block_resolve_emit(uint32_t nb, uint32_t rem, int n, uint32_t *s_hist, uint32_t *s_gt,
                                                    uint32_t *s_eq, const uint2 *l_ent, EmitFn emit)
 {
@@ -568,7 +568,7 @@ __device__ __forceinline__ void block_resolve_emit(uint32_t nb, uint32_t rem, in
     uint32_t *s_scan = s_hist + 2048 + 4;
     const int nw64 = (n + 63) >> 6;
     uint32_t T, need_eq;
-    block_list_threshold<NT>(nb, rem, s_hist, l_ent, T, need_eq);
+    block_list_threshold<NT, CAP>(nb, rem, s_hist, l_ent, T, need_eq);
     __syncthreads();
     CTKVR_STAMP(35);
     for (uint32_t e = tid; e < nb; e += NT) {

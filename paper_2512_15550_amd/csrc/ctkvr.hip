@@ -119,6 +119,8 @@ struct ctkvr_index {
     bool have_step = false;
     size_t recall_lds = 0, select_lds = 0, attn_lds = 0, build_select_lds = 0;
     size_t fused_lds = 0;   // non-zero: selection and attention run as one launch (select_attn_kernel)
+    int build_redone = 0;   // chunks of the matrix-core list build that the candidate route had to hand back
+    int build_by_cand = 0;  // the matrix-core list build took the candidate route
     int score_by_rank = -1;   // how the scoring kernel splits a unit's recalled ids over its blocks: -1 chosen per batch, 0 by id range, 1 by rank
     int sel_bits = 0, build_bits = 0;   // words for the selection's id bitmaps (0: histogram route off)
     int bitmap_words = 0, recall_split = 1, num_cu = 256;
@@ -503,12 +505,46 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
     uint32_t *kbuf = nullptr, *ghist = nullptr;
     float2 *part = nullptr;   // matrix-core route: one (maximum, sum) pair per unit, head and block of the statistics pass
     constexpr int kMaxSplits = 64;
-    if (mfma && hipMalloc((void **)&part, (size_t)chunk * G * kMaxSplits * sizeof(float2)) != hipSuccess)
-        return fail(CTKVR_ENOMEM, "build scratch allocation failed");
-    hipError_t e3 = hipMalloc((void **)&kbuf, (size_t)chunk * ix->s_max * 4);
-    hipError_t e4 = hipMalloc((void **)&ghist, (size_t)chunk * kBuckets * 4);
+    hipError_t e5 = hipSuccess;
+    if (mfma) e5 = hipMalloc((void **)&part, (size_t)chunk * G * kMaxSplits * sizeof(float2));
+    // Matrix-core route, candidates only (see mfma_score_kernel): when every sequence is long against rho, so that
+    // about 2 rho candidates are a small part of its keys and a 1-in-16 sample of the positions places the threshold
+    // well, and the selection's bitmaps and candidate list fit the shared memory.  CTKVR_BUILD_CANDIDATES=0/1 forces
+    // the choice where the second condition allows it (1 on short sequences mostly ends in the redo below).
+    const int rho = ix->p.list_len;
+    const int step_stride = std::max(16, ((ix->s_max + 31) / 32 + 255) / 256);
+    const int sample_stride = ((ix->s_max + 32 * step_stride - 1) / (32 * step_stride)) * 32;
+    const int cand_cap = std::min(kCandCap, 4 * rho);
+    const size_t cand_lds = ((size_t)2112 + 2 * (size_t)cand_cap + 4 * (size_t)((ix->s_max + 63) / 64)) * 4;
+    bool by_cand = false;
+    if (mfma && cand_lds <= 150 * 1024 && sample_stride <= kSampleCap && cand_cap >= rho) {
+        const int s_min = *std::min_element(ix->ctx_lens.begin(), ix->ctx_lens.end());
+        by_cand = rho >= 256 && 4 * rho <= kCandCap && (long long)s_min >= 32ll * rho;
+        if (const char *e = getenv("CTKVR_BUILD_CANDIDATES")) by_cand = atoi(e) != 0;
+    }
+    ix->build_by_cand = by_cand;
+    const bool redo_always = by_cand && getenv("CTKVR_BUILD_CANDIDATES_REDO") != nullptr;   // tests: take the redo path
+    uint32_t *ksamp = nullptr, *tau = nullptr, *cursor = nullptr, *d_fail = nullptr;
+    uint2 *cand = nullptr;
+    hipError_t e3 = hipSuccess, e4 = hipSuccess;
+    auto alloc_full = [&]() {   // the buffers of the route that keeps every key
+        if (!kbuf) e3 = hipMalloc((void **)&kbuf, (size_t)chunk * ix->s_max * 4);
+        if (!ghist) e4 = hipMalloc((void **)&ghist, (size_t)chunk * kBuckets * 4);
+        return e3 == hipSuccess && e4 == hipSuccess;
+    };
+    if (by_cand && e5 == hipSuccess) {
+        // a segment per block of the statistics split: room for twice an even share, at least 256 entries
+        if (hipMalloc((void **)&ksamp, (size_t)chunk * sample_stride * 4) != hipSuccess ||
+            hipMalloc((void **)&tau, (size_t)chunk * 4) != hipSuccess ||
+            hipMalloc((void **)&cursor, (size_t)chunk * kMaxSplits * 4) != hipSuccess || hipMalloc((void **)&d_fail, 4) != hipSuccess ||
+            hipMalloc((void **)&cand, (size_t)chunk * 2 * std::max(cand_cap, 128 * kMaxSplits) * sizeof(uint2)) != hipSuccess)
+            e5 = hipErrorOutOfMemory;
+        if (e5 == hipSuccess) e5 = hipFuncSetAttribute((const void *)cand_select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)cand_lds);
+    } else {
+        alloc_full();
+    }
     int rc = CTKVR_OK;
-    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess || e4 != hipSuccess)
+    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess || e4 != hipSuccess || e5 != hipSuccess)
         rc = fail(CTKVR_ENOMEM, "build scratch allocation failed");
     for (int u0 = 0; rc == CTKVR_OK && u0 < total_units; u0 += chunk) {
         const int nu = std::min(chunk, total_units - u0);
@@ -517,7 +553,8 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
         u.unit0 = u0;
         fill_u32_kernel<<<dim3((unsigned)((nu * G + 255) / 256)), 256, 0, st>>>(m_key, 0u, (size_t)nu * G);
         fill_u32_kernel<<<dim3((unsigned)((nu * G * 2 + 255) / 256)), 256, 0, st>>>((uint32_t *)S, 0u, (size_t)nu * G * 2);
-        fill_u32_kernel<<<dim3((unsigned)(((size_t)nu * kBuckets + 255) / 256)), 256, 0, st>>>(ghist, 0u, (size_t)nu * kBuckets);
+        if (ghist) fill_u32_kernel<<<dim3((unsigned)(((size_t)nu * kBuckets + 255) / 256)), 256, 0, st>>>(ghist, 0u, (size_t)nu * kBuckets);
+        bool keys_written = false;   // kbuf holds this chunk's ranking keys (matrix-core route)
         ScoreArgs sa{};
         sa.u = u;
         sa.q = ix->centroids;
@@ -552,9 +589,67 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
                 ma.n_init = ix->p.n_init;
                 ma.n_local = ix->p.n_local;
                 ma.scale = ix->scale;
-                // two passes over the same tiles: softmax statistics, keys (nothing but the keys is stored)
+                ma.step_stride = 1;
+                // passes over the same tiles: softmax statistics first
                 mfma_score_kernel<G, MFMA_STAT><<<dim3(ma.t_splits, tiles), 256, 0, st>>>(ma);
-                mfma_score_kernel<G, MFMA_KEY><<<dim3(ma.t_splits, tiles), 256, 0, st>>>(ma);
+                bool redo = !by_cand;
+                if (by_cand) {
+                    // keys of a sample of the positions -> a threshold per unit -> all keys again, those at or above
+                    // the threshold kept -> the rho largest of them, exactly
+                    ma.kbuf = ksamp;
+                    ma.step_stride = step_stride;
+                    ma.sample_stride = sample_stride;
+                    mfma_score_kernel<G, MFMA_SAMPLE><<<dim3(ma.t_splits, tiles), 256, 0, st>>>(ma);
+                    CandArgs ca{};
+                    ca.u = u;
+                    ca.ctx_lens = ix->d_ctx_lens;
+                    ca.rho = rho;
+                    ca.step_stride = step_stride;
+                    ca.sample_stride = sample_stride;
+                    ca.cand_cap = cand_cap;
+                    ca.n_init = ix->p.n_init;
+                    ca.n_local = ix->p.n_local;
+                    ca.ksamp = ksamp;
+                    ca.tau = tau;
+                    const int seg_cap = std::min(cand_cap, std::max(256, 2 * cand_cap / ma.t_splits));   // t_splits * seg_cap <= 2 max(cand_cap, 128 t_splits)
+                    ca.cand = cand;
+                    ca.seg_cnt = cursor;
+                    ca.t_splits = ma.t_splits;
+                    ca.seg_cap = seg_cap;
+                    ca.lists = ix->lists;
+                    ca.fail = d_fail;
+                    fill_u32_kernel<<<dim3(1), 64, 0, st>>>(d_fail, 0u, 1);
+                    fill_u32_kernel<<<dim3((unsigned)(((size_t)nu * ma.t_splits + 255) / 256)), 256, 0, st>>>(cursor, 0u, (size_t)nu * ma.t_splits);
+                    sample_threshold_kernel<<<dim3(nu), 1024, 0, st>>>(ca);
+                    ma.step_stride = 1;
+                    ma.tau = tau;
+                    ma.cand = cand;
+                    ma.seg_cnt = cursor;
+                    ma.seg_cap = seg_cap;
+                    mfma_score_kernel<G, MFMA_PICK><<<dim3(ma.t_splits, tiles), 256, 0, st>>>(ma);
+                    cand_select_kernel<<<dim3(nu), 1024, cand_lds, st>>>(ca);
+                    uint32_t failed = 0;
+                    hipError_t ec = hipMemcpyAsync(&failed, d_fail, 4, hipMemcpyDeviceToHost, st);
+                    if (ec == hipSuccess) ec = hipStreamSynchronize(st);
+                    if (ec != hipSuccess) {
+                        rc = fail(CTKVR_EHIP, "build: %s", hipGetErrorString(ec));
+                        break;
+                    }
+                    redo = failed != 0 || redo_always;
+                    if (redo) {
+                        ix->build_redone++;
+                        if (!alloc_full()) {
+                            rc = fail(CTKVR_ENOMEM, "build scratch allocation failed");
+                            break;
+                        }
+                        fill_u32_kernel<<<dim3((unsigned)(((size_t)nu * kBuckets + 255) / 256)), 256, 0, st>>>(ghist, 0u, (size_t)nu * kBuckets);
+                    }
+                }
+                if (redo) {   // every key stored, then histogram and selection over all of them
+                    ma.kbuf = kbuf;
+                    mfma_score_kernel<G, MFMA_KEY><<<dim3(ma.t_splits, tiles), 256, 0, st>>>(ma);
+                    keys_written = true;
+                }
             } else {
                 score_kernel<T, G, 16><<<dim3((ix->s_max + 255) / 256, nu), 256, 0, st>>>(sa);
             }
@@ -571,6 +666,11 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
             da.m_key = m_key;
             da.S = S;
             denom_kernel<G><<<dim3(std::min((ix->s_max + 1023) / 1024, 64), nu), 256, 0, st>>>(da);
+        }
+        if (mfma && !keys_written) {   // the candidate route has written this chunk's lists
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) rc = fail(CTKVR_EHIP, "build launch: %s", hipGetErrorString(e));
+            continue;
         }
         KeyArgs ka{};
         ka.u = u;
@@ -611,6 +711,11 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
     (void)hipFree(kbuf);
     (void)hipFree(ghist);
     (void)hipFree(part);
+    (void)hipFree(ksamp);
+    (void)hipFree(tau);
+    (void)hipFree(cursor);
+    (void)hipFree(d_fail);
+    (void)hipFree(cand);
     return rc;
 }
 
@@ -1379,6 +1484,14 @@ int ctkvr_index_set_decode_path(ctkvr_index *idx, int32_t path)
         return fail(CTKVR_EUNSUPPORTED, "the single-launch step does not fit this geometry (%d units on %d CUs, or its shared memory)",
                     idx->units, idx->num_cu);
     idx->decode_path = path;
+    return CTKVR_OK;
+}
+
+int ctkvr_index_build_route(const ctkvr_index *idx, int32_t *by_candidates_host, int32_t *chunks_redone_host)
+{
+    if (!idx) return fail(CTKVR_EINVAL, "null index");
+    if (by_candidates_host) *by_candidates_host = idx->build_by_cand;
+    if (chunks_redone_host) *chunks_redone_host = idx->build_redone;
     return CTKVR_OK;
 }
 

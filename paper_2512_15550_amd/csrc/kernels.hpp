@@ -602,9 +602,15 @@ struct MfmaScoreArgs {
     Paged k;
     int l_stride;              // s_max
     float2 *part;              // [chunk units][G][t_splits] (maximum, sum of exp(z - maximum)) over a block's keys
-    uint32_t *kbuf;            // [chunk units][l_stride] ranking keys, pass KEY
+    uint32_t *kbuf;            // KEY: [chunk units][l_stride] ranking keys; SAMPLE: [chunk units][sample_stride]
     int n_init, n_local;       // keys of the resident window get the lowest ranking key
     float scale;
+    int step_stride;           // SAMPLE: every step_stride-th step of 32 keys is taken (1 in the other passes)
+    int sample_stride;         // SAMPLE: keys per unit in kbuf
+    const uint32_t *tau;       // PICK: [chunk units] keys at or above it are candidates
+    uint2 *cand;               // PICK: [chunk units][t_splits][seg_cap] (key, id): block x of a tile fills segment x of its units
+    uint32_t *seg_cnt;         // PICK: [chunk units][t_splits] candidates of the segment (may exceed seg_cap: the excess is not stored)
+    int seg_cap;
 };
 
 // The scores are never stored: the contraction is repeated in two passes over the same tiles, each
@@ -614,7 +620,14 @@ struct MfmaScoreArgs {
 // and the band has room for a denominator that is a few 1e-5 off); one (m, sum) pair per block, merged
 // in block order by the next pass.  MFMA_KEY: ranking keys max_h ((z - m_h) - log S_h), written as
 // ordered uint32 (4 bytes per (centroid, key) instead of 4 G bytes of scores read twice).
-enum { MFMA_STAT = 0, MFMA_KEY = 2 };
+// Writing, and twice re-reading, a key for every (centroid, key) pair is most of that route's time, and only
+// rho of a unit's s keys are wanted.  MFMA_SAMPLE computes the keys of every step_stride-th step only (a
+// systematic sample of the positions) into a small buffer, from which a threshold tau per unit is taken
+// (a sample rank chosen so that about 2 rho keys of the unit lie at or above it); MFMA_PICK then computes all
+// keys again and keeps the (key, id) pairs at or above tau -- a few thousand per unit -- from which the rho
+// largest are selected exactly.  Should a unit end with fewer than rho candidates, or more than fit, the
+// chunk is redone by the KEY route: the result never depends on the sample.
+enum { MFMA_STAT = 0, MFMA_KEY = 2, MFMA_SAMPLE = 3, MFMA_PICK = 4 };
 
 template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_kernel(MfmaScoreArgs a)
 {
@@ -623,7 +636,12 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
     // KEY: the result tiles, [head][centroid][key]: a lane's four consecutive keys are one 16-byte
     // write, a reader's four keys one 16-byte read; 36-word rows spread both over the banks
     constexpr int ZS = 36;
-    __shared__ __align__(16) float s_z[MODE == MFMA_KEY ? G * CT * ZS : 4];
+    constexpr bool KEYS = MODE != MFMA_STAT;   // the passes that form ranking keys
+    __shared__ __align__(16) float s_z[KEYS ? G * CT * ZS : 4];
+    // PICK: the tile's thresholds and how many candidates this block has found for each of its centroids.  A block
+    // owns a segment of every unit's candidate list, so positions are handed out by shared-memory counters: no
+    // atomic on device memory (on this part those are served beyond the XCD's cache, a round trip each).
+    __shared__ uint32_t s_tau[MODE == MFMA_PICK ? CT : 1], s_cnt[MODE == MFMA_PICK ? CT : 1];
     __shared__ __align__(16) unsigned char s_k[2][32 * 272];
     const int tid = threadIdx.x, wv = tid >> 6, ln = tid & 63;
     const int col = ln & 31, half = ln >> 5;
@@ -634,9 +652,17 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
     const int j0 = jt * CT;
     if (j0 >= C) return;
     const int tper = (((s + a.t_splits - 1) / a.t_splits) + 31) & ~31;
-    const int tbeg = blockIdx.x * tper;
-    const int tend = min(s, tbeg + tper);
-    if (tbeg >= s) return;
+    const int ST = MODE == MFMA_SAMPLE ? 32 * a.step_stride : 32;   // keys from one step to the next
+    // SAMPLE: the steps taken are those that start at a multiple of ST; a block starts at the first one in its range
+    const int tbeg = MODE == MFMA_SAMPLE ? ((int)(blockIdx.x * tper) + ST - 1) / ST * ST : (int)(blockIdx.x * tper);
+    const int tend = min(s, (int)(blockIdx.x * tper) + tper);
+    if (tbeg >= tend) return;
+    if constexpr (MODE == MFMA_PICK) {
+        if (tid < CT) {
+            s_tau[tid] = a.tau[(size_t)bkl * a.c_max + min(j0 + tid, C - 1)];
+            s_cnt[tid] = 0u;
+        }
+    }
     // The matrix instruction is issued with the keys as its row operand and the centroids as its
     // column operand: a lane then holds ONE centroid (column `col` of its sub-tile) against 16
     // keys (rows 8 (r / 4) + 4 half + r % 4), and that centroid's statistics are single registers.
@@ -657,7 +683,7 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
         stat[q] = ((size_t)bkl * a.c_max + j) * G + hh[q];
         mx[q] = -__builtin_huge_valf();
         lsv[q] = 0.0f;
-        if constexpr (MODE == MFMA_KEY) {
+        if constexpr (KEYS) {
             // the blocks' pairs in block order: the same value in every block that reads them
             const float2 *pp = a.part + stat[q] * a.t_splits;
             float m = -__builtin_huge_valf();
@@ -737,7 +763,7 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
                     for (int r = 0; r < w; ++r) e[r] += e[r + w];
                 lsv[q] = __fmaf_rn(lsv[q], __expf(mx[q] - m), e[0]);   // first step: 0 * exp(-inf) = 0
                 mx[q] = m;
-            } else {
+            } else {   // KEY, SAMPLE, PICK
                 float *zrow = &s_z[(hh[q] * CT + mt[q] * 32 + col) * ZS + 4 * half];
 #pragma unroll
                 for (int rq = 0; rq < 4; ++rq) {
@@ -750,12 +776,65 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
                 }
             }
         }
-        if constexpr (MODE == MFMA_KEY) {
+        if constexpr (KEYS) {
             __syncthreads();
             // four consecutive keys of one centroid per thread: maximum over the heads, one 16-byte
             // store where the key rows allow it (whole step in range, row length a multiple of four)
-            const bool wide = !tail && (a.l_stride & 3) == 0;
-            if (t0 < tend) {
+            const bool wide = !tail && ((MODE == MFMA_SAMPLE ? a.sample_stride : a.l_stride) & 3) == 0;
+            if constexpr (MODE == MFMA_PICK) {
+                // Few keys pass (a few per cent): the verdicts of all of a thread's keys first, then one
+                // shared-memory counter bump per (thread, centroid) for the whole group of four, then the stores.
+                constexpr int NP = CT * 8 / 256;
+                uint32_t okv[NP][4], msk[NP], at[NP];
+                if (t0 < tend) {
+#pragma unroll
+                    for (int it = 0; it < NP; ++it) {
+                        const int p = tid + 256 * it, n4 = (p & 7) * 4, jl = p >> 3;
+                        float4 best = *reinterpret_cast<const float4 *>(&s_z[jl * ZS + n4]);
+#pragma unroll
+                        for (int c = 1; c < G; ++c) {
+                            const float4 o = *reinterpret_cast<const float4 *>(&s_z[(c * CT + jl) * ZS + n4]);
+                            best.x = fmaxf(best.x, o.x);
+                            best.y = fmaxf(best.y, o.y);
+                            best.z = fmaxf(best.z, o.z);
+                            best.w = fmaxf(best.w, o.w);
+                        }
+                        const int t = t0 + n4;
+                        okv[it][0] = ordered_key(best.x);
+                        okv[it][1] = ordered_key(best.y);
+                        okv[it][2] = ordered_key(best.z);
+                        okv[it][3] = ordered_key(best.w);
+                        const uint32_t tau = s_tau[jl];
+                        uint32_t m = 0;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const bool in = (t + e) < tend && (t + e) >= a.n_init && (t + e) < s - a.n_local && (j0 + jl) < C;
+                            m |= (uint32_t)(in && okv[it][e] >= tau) << e;
+                        }
+                        msk[it] = m;
+                    }
+#pragma unroll
+                    for (int it = 0; it < NP; ++it) {
+                        at[it] = 0u;
+                        if (msk[it]) at[it] = atomicAdd(&s_cnt[(tid + 256 * it) >> 3], (uint32_t)__popc(msk[it]));
+                    }
+#pragma unroll
+                    for (int it = 0; it < NP; ++it) {
+                        if (msk[it]) {
+                            const int p = tid + 256 * it, n4 = (p & 7) * 4, jl = p >> 3;
+                            uint2 *seg = a.cand + (((size_t)bkl * a.c_max + j0 + jl) * a.t_splits + blockIdx.x) * a.seg_cap;
+                            uint32_t w = at[it];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                if ((msk[it] >> e) & 1u) {
+                                    if (w < (uint32_t)a.seg_cap) seg[w] = make_uint2(okv[it][e], (uint32_t)(t0 + n4 + e));
+                                    ++w;
+                                }
+                            }
+                        }
+                    }
+                }
+            } else if (t0 < tend) {
                 for (int p = tid; p < CT * 8; p += 256) {
                     const int n4 = (p & 7) * 4, jl = p >> 3;
                     if ((j0 + jl) >= C) continue;
@@ -770,18 +849,25 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
                     }
                     const int t = t0 + n4;
                     uint32_t ok[4] = {ordered_key(best.x), ordered_key(best.y), ordered_key(best.z), ordered_key(best.w)};
+                    bool win[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if ((t + e) < a.n_init || (t + e) >= s - a.n_local) ok[e] = 0x007fffffu;   // the image of -inf
-                    uint32_t *dst = a.kbuf + ((size_t)bkl * a.c_max + j0 + jl) * a.l_stride + t;
-                    if (wide) {
-                        // written once, read much later by other kernels: kept out of the caches that hold the keys
-                        u32x4_t v4 = {ok[0], ok[1], ok[2], ok[3]};
-                        __builtin_nontemporal_store(v4, reinterpret_cast<u32x4_t *>(dst));
-                    } else {
+                    for (int e = 0; e < 4; ++e) {
+                        win[e] = (t + e) < a.n_init || (t + e) >= s - a.n_local;
+                        if (win[e]) ok[e] = 0x007fffffu;   // the image of -inf
+                    }
+                    const size_t unit = (size_t)bkl * a.c_max + j0 + jl;
+                    {
+                        uint32_t *dst = MODE == MFMA_SAMPLE ? a.kbuf + unit * a.sample_stride + (t0 / ST) * 32 + n4
+                                                            : a.kbuf + unit * a.l_stride + t;
+                        if (wide) {
+                            // written once, read much later by other kernels: kept out of the caches that hold the keys
+                            u32x4_t v4 = {ok[0], ok[1], ok[2], ok[3]};
+                            __builtin_nontemporal_store(v4, reinterpret_cast<u32x4_t *>(dst));
+                        } else {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if ((t + e) < tend) dst[e] = ok[e];
+                            for (int e = 0; e < 4; ++e)
+                                if ((t + e) < tend) dst[e] = ok[e];
+                        }
                     }
                 }
             }
@@ -790,42 +876,45 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
     // A step's rows are requested four steps ahead (four register sets).
     {
         uint4 st2a, st2b, st3a, st3b;
-        int pg_a = page_at(tbeg + 128), pg_b = page_at(tbeg + 160), pg_c = page_at(tbeg + 192), pg_d = page_at(tbeg + 224);
+        int pg_a = page_at(tbeg + 4 * ST), pg_b = page_at(tbeg + 5 * ST), pg_c = page_at(tbeg + 6 * ST), pg_d = page_at(tbeg + 7 * ST);
         fetch(st0a, st0b, row_from(page_at(tbeg), tbeg));
-        fetch(st1a, st1b, row_from(page_at(tbeg + 32), tbeg + 32));
-        fetch(st2a, st2b, row_from(page_at(tbeg + 64), tbeg + 64));
-        fetch(st3a, st3b, row_from(page_at(tbeg + 96), tbeg + 96));
+        fetch(st1a, st1b, row_from(page_at(tbeg + ST), tbeg + ST));
+        fetch(st2a, st2b, row_from(page_at(tbeg + 2 * ST), tbeg + 2 * ST));
+        fetch(st3a, st3b, row_from(page_at(tbeg + 3 * ST), tbeg + 3 * ST));
         put(st0a, st0b, 0);
         __syncthreads();
         // four steps per trip.  Step i (set i % 4, buffer i % 2): request step i+4 into the set it
         // frees and the entry of step i+8, compute, write step i+1 to the other buffer.
         auto trip = [&](const bool tail, int t0) __attribute__((always_inline)) {
-            fetch(st0a, st0b, row_from(pg_a, t0 + 128));
-            pg_a = page_at(t0 + 256);
+            fetch(st0a, st0b, row_from(pg_a, t0 + 4 * ST));
+            pg_a = page_at(t0 + 8 * ST);
             compute(tail, 0, t0);
             put(st1a, st1b, 1);
             __syncthreads();
-            fetch(st1a, st1b, row_from(pg_b, t0 + 160));
-            pg_b = page_at(t0 + 288);
-            compute(tail, 1, t0 + 32);
+            fetch(st1a, st1b, row_from(pg_b, t0 + 5 * ST));
+            pg_b = page_at(t0 + 9 * ST);
+            compute(tail, 1, t0 + ST);
             put(st2a, st2b, 0);
             __syncthreads();
-            fetch(st2a, st2b, row_from(pg_c, t0 + 192));
-            pg_c = page_at(t0 + 320);
-            compute(tail, 0, t0 + 64);
+            fetch(st2a, st2b, row_from(pg_c, t0 + 6 * ST));
+            pg_c = page_at(t0 + 10 * ST);
+            compute(tail, 0, t0 + 2 * ST);
             put(st3a, st3b, 1);
             __syncthreads();
-            fetch(st3a, st3b, row_from(pg_d, t0 + 224));
-            pg_d = page_at(t0 + 352);
-            compute(tail, 1, t0 + 96);
+            fetch(st3a, st3b, row_from(pg_d, t0 + 7 * ST));
+            pg_d = page_at(t0 + 11 * ST);
+            compute(tail, 1, t0 + 3 * ST);
             put(st0a, st0b, 0);
             __syncthreads();
         };
         int t0 = tbeg;
-        for (; t0 + 128 <= tend; t0 += 128) trip(false, t0);
+        for (; t0 + 3 * ST + 32 <= tend; t0 += 4 * ST) trip(false, t0);
         if (t0 < tend) trip(true, t0);
     }
-    if constexpr (MODE == MFMA_KEY) return;
+    if constexpr (MODE == MFMA_PICK) {
+        if (tid < CT && j0 + tid < C) a.seg_cnt[((size_t)bkl * a.c_max + j0 + tid) * a.t_splits + blockIdx.x] = s_cnt[tid];
+    }
+    if constexpr (KEYS) return;
     // the two halves of a wave hold different keys of the same (centroid, head): merged (the same value
     // on both sides, a sum of two products), then one pair per block
 #pragma unroll
@@ -1300,6 +1389,120 @@ template <int G> __global__ __launch_bounds__(1024) void rerank_select_kernel(Se
     }
     CTKVR_STAMP(31);
     CTKVR_STAMP_BLK(3);
+}
+
+// ------------------------------------------------------------------------------
+// Matrix-core list build, candidate route (Algorithm 1 line 4 on a few thousand candidates per unit
+// instead of all s keys).
+// sample_threshold_kernel: tau[unit] = the r-th largest of the unit's sampled keys (slot i of the sample
+// row is key id (i / 32) * 32 * step_stride + i % 32; slots of ids beyond s or inside the resident window
+// do not count), with r = 2 ceil(rho / step_stride) + 16: about 2 rho + 16 step_stride of the unit's keys
+// then lie at or above tau.  Fewer samples than r: tau = 0, every key is a candidate (and the unit
+// overflows, see below).
+// cand_select_kernel: the rho largest of the unit's candidates (key, id), gathered from the segments the
+// blocks of the PICK pass filled, ties to the lowest id, written to the unit's list in ascending id order.
+// A unit with fewer than rho candidates, more than cand_cap, or a segment that ran over, raises *fail instead
+// (the caller then redoes the chunk by the route that keeps every key).
+// Both: grid = chunk units, 1024 threads.  cand_select: dynamic shared memory 2112 + 2 cand_cap +
+// 4 ceil(s_max / 64) words; cand_cap <= kCandCap.
+// ------------------------------------------------------------------------------
+constexpr int kCandCap = 8192;
+constexpr int kSampleCap = 8192;   // sampled keys per unit at most
+
+struct CandArgs {
+    Units u;
+    const int32_t *ctx_lens;
+    int rho, step_stride, sample_stride, cand_cap;
+    int n_init, n_local;
+    const uint32_t *ksamp;    // [chunk units][sample_stride]
+    uint32_t *tau;            // [chunk units]
+    const uint2 *cand;        // [chunk units][t_splits][seg_cap]
+    const uint32_t *seg_cnt;  // [chunk units][t_splits], zero where no block wrote
+    int t_splits, seg_cap;
+    int32_t *lists;           // [all units][rho]
+    uint32_t *fail;           // [1]
+};
+
+__global__ __launch_bounds__(1024) void sample_threshold_kernel(CandArgs a)
+{
+    __shared__ uint32_t s_hist[2048 + 64];
+    __shared__ uint32_t s_cnt;
+    int b, kv, j;
+    const int ul = blockIdx.x, tid = threadIdx.x;
+    if (!decode_unit(a.u, ul, b, kv, j)) return;
+    const int s = a.ctx_lens[b];
+    const int ST = 32 * a.step_stride;
+    const int n = ((s + ST - 1) / ST) * 32;   // sample slots of this unit (the last step's may reach beyond s)
+    const uint32_t *ks = a.ksamp + (size_t)ul * a.sample_stride;
+    if (tid == 0) s_cnt = 0u;
+    constexpr int KPT = kSampleCap / 1024;
+    uint32_t kreg[KPT];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int q = 0; q < KPT; ++q) {
+        const int i = q * 1024 + tid;
+        const int t = (i >> 5) * ST + (i & 31);
+        const bool valid = i < n && t < s - a.n_local && t >= a.n_init;
+        kreg[q] = ks[min(i, n - 1)];
+        if (!valid) kreg[q] = 0u;   // below the image of every real key
+        mine += valid;
+    }
+    __syncthreads();
+    mine = wave_sum_uniform(mine);
+    if ((tid & 63) == 0 && mine) atomicAdd(&s_cnt, mine);
+    __syncthreads();
+    const uint32_t n_valid = s_cnt;
+    const uint32_t r = 2u * (uint32_t)((a.rho + a.step_stride - 1) / a.step_stride) + 16u;
+    if (r > n_valid) {   // uniform
+        if (tid == 0) a.tau[ul] = 0u;
+        return;
+    }
+    auto for_slots = [&](auto f) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < KPT; ++q) f(q * 1024 + tid, kreg[q] != 0u, kreg[q]);
+    };
+    uint32_t T, need_eq;
+    block_kth_largest<1024>(for_slots, r, s_hist, T, need_eq);
+    if (tid == 0) a.tau[ul] = T;
+}
+
+__global__ __launch_bounds__(1024) void cand_select_kernel(CandArgs a)
+{
+    extern __shared__ __align__(16) uint32_t smem[];
+    int b, kv, j;
+    const int ul = blockIdx.x, tid = threadIdx.x;
+    if (!decode_unit(a.u, ul, b, kv, j)) return;
+    const int s = a.ctx_lens[b];
+    // the unit's candidates, segment after segment (every thread walks the few counts itself)
+    uint32_t n = 0;
+    bool bad = false;
+    for (int x = 0; x < a.t_splits; ++x) {
+        const uint32_t c = a.seg_cnt[(size_t)ul * a.t_splits + x];
+        bad |= c > (uint32_t)a.seg_cap;
+        n += c;
+    }
+    if (bad || n < (uint32_t)a.rho || n > (uint32_t)a.cand_cap) {   // uniform
+        if (tid == 0) atomicOr(a.fail, 1u);
+        return;
+    }
+    uint32_t *s_hist = smem;                                   // 2048 + 64
+    uint2 *l_ent = reinterpret_cast<uint2 *>(smem + 2112);     // cand_cap entries
+    const int nw32 = 2 * ((s + 63) >> 6);
+    uint32_t *s_gt = smem + 2112 + 2 * a.cand_cap;             // two bitmaps over the ids
+    uint32_t *s_eq = s_gt + nw32;
+    {
+        uint32_t at = 0;
+        for (int x = 0; x < a.t_splits; ++x) {
+            const uint32_t c = a.seg_cnt[(size_t)ul * a.t_splits + x];
+            const uint2 *src = a.cand + ((size_t)ul * a.t_splits + x) * a.seg_cap;
+            for (uint32_t e = tid; e < c; e += 1024) l_ent[at + e] = src[e];
+            at += c;
+        }
+    }
+    for (int w = tid; w < 2 * nw32; w += 1024) s_gt[w] = 0u;
+    __syncthreads();
+    int32_t *lst = a.lists + (size_t)(a.u.unit0 + ul) * a.rho;
+    block_resolve_emit<1024, kCandCap>(n, (uint32_t)a.rho, s, s_hist, s_gt, s_eq, l_ent, [&](int pos, int i) { lst[pos] = i; });
 }
 
 // ------------------------------------------------------------------------------

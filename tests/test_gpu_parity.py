@@ -376,6 +376,57 @@ def test_mfma_build_matches_oracle_up_to_ties(ck, case):
     ck.ctkvr_free(idx)
 
 
+@pytest.mark.parametrize("name,s,rho,expect_redo", [
+    ("cand_ok", 6000, 400, False),         # about 2 rho + 256 = 1056 candidates per unit: within [rho, 4 rho]
+    ("cand_overflow", 2500, 40, True),     # about 2 rho + 256 candidates against room for 4 rho = 160: handed back, same lists
+])
+def test_mfma_build_from_candidates_gives_the_lists_of_the_route_that_ranks_every_key(ck, name, s, rho, expect_redo, monkeypatch):
+    """The candidate route (threshold from a sample of the positions, exact selection among the keys above it) and
+    its hand-back when a unit has too few or too many candidates: bit-equal lists either way, since both rank the
+    same matrix-core keys; and within the derived band of the oracle's."""
+    wl = small_workload(name, "bf16", 8, 2, (s, s - 777), (620, 621), 40, 0, 4, rho, 60, 1)
+    bt = gen_batch(wl)
+    db = H.device_batch(bt)
+    lists = {}
+    for forced in ("0", "1", "redo"):
+        monkeypatch.setenv("CTKVR_BUILD_CANDIDATES", "0" if forced == "0" else "1")
+        if forced == "redo":
+            monkeypatch.setenv("CTKVR_BUILD_CANDIDATES_REDO", "1")
+        idx = ck.ctkvr_build_index(H.params_of(wl, build_algo=ck.BUILD_MFMA), db.q_prefill, db.cu_seqlens, True, db.k_pages,
+                                   db.block_table, db.ctx_lens)
+        monkeypatch.delenv("CTKVR_BUILD_CANDIDATES_REDO", raising=False)
+        by_cand, redone = ck.ctkvr_index_build_route(idx)
+        assert by_cand == (forced != "0")
+        if forced == "1":
+            assert (redone > 0) == expect_redo, f"{redone} chunks handed back"
+        if forced == "redo":
+            assert redone > 0
+        lists[forced] = ck.ctkvr_index_lists(idx)
+        ck.ctkvr_free(idx)
+    assert np.array_equal(lists["0"], lists["1"]) and np.array_equal(lists["0"], lists["redo"])
+    for b, sq in enumerate(bt.seqs):
+        n, w, wa = _check_lists_within_band(lists["1"][b, :, :40], sq, oracle.centroids_last_c(sq.q_tail, 40), wl)
+        _say(f"[mfma {name}] sequence {b}: ids that differ inside the derived band: {n}; farthest {wa:.3g} = {w:.3f} of the band")
+
+
+def test_mfma_build_from_candidates_leaves_the_resident_window_out(ck, monkeypatch):
+    n_init, n_local = 9, 300
+    wl = small_workload("cand_window", "bf16", 8, 2, (7000,), (622,), 33, 0, 4, 300, 60, 1)
+    bt = gen_batch(wl)
+    db = H.device_batch(bt)
+    got = {}
+    for forced in ("0", "1"):
+        monkeypatch.setenv("CTKVR_BUILD_CANDIDATES", forced)
+        idx = ck.ctkvr_build_index(H.params_of(wl, build_algo=ck.BUILD_MFMA, n_init=n_init, n_local=n_local), db.q_prefill,
+                                   db.cu_seqlens, True, db.k_pages, db.block_table, db.ctx_lens)
+        got[forced] = ck.ctkvr_index_lists(idx)[0]
+        if forced == "1":
+            assert ck.ctkvr_index_build_route(idx) == (True, 0)
+        ck.ctkvr_free(idx)
+    assert got["1"].min() >= n_init and got["1"].max() < 7000 - n_local
+    assert np.array_equal(got["0"], got["1"])
+
+
 def test_mfma_build_cfg2_and_128k_sampled(ck):
     for name, n_pairs in (("cfg2", 96), ("cfg5", 48)):
         wl = workload(name)
@@ -389,6 +440,7 @@ def test_mfma_build_cfg2_and_128k_sampled(ck):
         C = wl.centroids_of(sq.s)
         rng = np.random.Generator(np.random.Philox(77))
         pairs = np.stack([rng.integers(0, wl.g, n_pairs), rng.integers(0, C, n_pairs)], axis=1).astype(np.int32)
+        assert ck.ctkvr_index_build_route(idx) == (True, 0)     # long sequences: the candidate route, nothing handed back
         n_diff, worst, worst_abs = _check_lists_within_band(lists[0], sq, oracle.centroids_last_c(sq.q_tail, C), wl,
                                                             pairs=pairs)
         _say(f"[mfma {name}] {n_pairs} sampled lists agree; ids inside the derived band: {n_diff}; farthest from "
