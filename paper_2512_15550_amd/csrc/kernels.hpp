@@ -581,13 +581,14 @@ template <typename T, int G> __global__ __launch_bounds__(256) void recall_score
 // Algorithm 1 line 2 on the matrix cores (bf16 only): the same z = (c_{h,j} . k_t) *
 // scale as score_kernel in build mode, but the 128-term dot is a chain of eight
 // v_mfma_f32_32x32x16_bf16.  A block owns 8/G sub-tiles of 32 centroids of one
-// (sequence, KV head) for all G heads (8 wave work items, two per wave, their A
-// fragments resident in registers) and walks a range of keys 32 at a time: B
-// fragments are 16-byte pieces of the paged key rows, the 32x32 results go through
-// shared memory so that z leaves as G contiguous floats per (centroid, key), the
-// layout denom and rerank_select read.  grid (t_splits, tiles), 256 threads.
-// Only the accumulation order inside the MFMA differs from the fixed arithmetic;
-// on inputs whose dot products are exact in fp32 the two builds agree bit for bit.
+// (sequence, KV head) for all G heads (8 wave work items, two per wave -- two heads of the
+// same sub-tile when G >= 2 -- their A fragments resident in registers) and walks a range of
+// keys 32 at a time: B fragments are 16-byte pieces of the paged key rows; in the passes that
+// form ranking keys the 32x32 results of a head pair are reduced in registers and go through
+// shared memory, where the maximum over the pairs is taken.  grid (t_splits, tiles), 256 threads.
+// The scores differ from the fixed arithmetic in the accumulation order inside the MFMA and
+// the softmax denominators in how they are summed; on inputs whose dot products are exact in
+// fp32 only the latter is left.
 // ------------------------------------------------------------------------------
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
@@ -633,11 +634,14 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
 {
     constexpr int MT = 8 / G;        // 32-centroid sub-tiles per block
     constexpr int CT = 32 * MT;      // centroids per block
-    // KEY: the result tiles, [head][centroid][key]: a lane's four consecutive keys are one 16-byte
-    // write, a reader's four keys one 16-byte read; 36-word rows spread both over the banks
+    // The key passes: the result tiles, [head pair][centroid][key] -- a wave's two work items are two heads of
+    // the same 32 centroids (G >= 2), so the maximum over that pair is taken in registers and one plane per
+    // pair goes through shared memory; a lane's four consecutive keys are one 16-byte write, a reader's four
+    // keys one 16-byte read; 36-word rows spread both over the banks
     constexpr int ZS = 36;
+    constexpr int NPL = G >= 2 ? G / 2 : 1;    // planes
     constexpr bool KEYS = MODE != MFMA_STAT;   // the passes that form ranking keys
-    __shared__ __align__(16) float s_z[KEYS ? G * CT * ZS : 4];
+    __shared__ __align__(16) float s_z[KEYS ? NPL * CT * ZS : 4];
     // PICK: the tile's thresholds and how many candidates this block has found for each of its centroids.  A block
     // owns a segment of every unit's candidate list, so positions are handed out by shared-memory counters: no
     // atomic on device memory (on this part those are served beyond the XCD's cache, a round trip each).
@@ -674,8 +678,8 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
         int it = wv * 2 + q;
-        hh[q] = it / MT;
-        mt[q] = it - hh[q] * MT;
+        mt[q] = it / G;   // G >= 2: both items of a wave are heads of one sub-tile; G = 1: two sub-tiles
+        hh[q] = it - mt[q] * G;
         const int j = min(j0 + mt[q] * 32 + col, C - 1);   // columns beyond C repeat centroid C-1 and are dropped at the end
         const bf16_t *row = a.centroids + (((size_t)b * a.h + kv * G + hh[q]) * a.c_max + j) * kD;
 #pragma unroll
@@ -763,8 +767,8 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
                     for (int r = 0; r < w; ++r) e[r] += e[r + w];
                 lsv[q] = __fmaf_rn(lsv[q], __expf(mx[q] - m), e[0]);   // first step: 0 * exp(-inf) = 0
                 mx[q] = m;
-            } else {   // KEY, SAMPLE, PICK
-                float *zrow = &s_z[(hh[q] * CT + mt[q] * 32 + col) * ZS + 4 * half];
+            } else if constexpr (G == 1) {   // KEY, SAMPLE, PICK with one head: each item is a sub-tile of its own
+                float *zrow = &s_z[(mt[q] * 32 + col) * ZS + 4 * half];
 #pragma unroll
                 for (int rq = 0; rq < 4; ++rq) {
                     float4 v;
@@ -774,6 +778,18 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
                     v.w = (acc[4 * rq + 3] * a.scale - mx[q]) - lsv[q];
                     *reinterpret_cast<float4 *>(zrow + 8 * rq) = v;
                 }
+            }
+        }
+        if constexpr (KEYS && G >= 2) {   // the wave's two heads of the same centroids: their maximum, one plane
+            float *zrow = &s_z[((hh[0] >> 1) * CT + mt[0] * 32 + col) * ZS + 4 * half];
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                float4 v;
+                v.x = fmaxf((acc0[4 * rq + 0] * a.scale - mx[0]) - lsv[0], (acc1[4 * rq + 0] * a.scale - mx[1]) - lsv[1]);
+                v.y = fmaxf((acc0[4 * rq + 1] * a.scale - mx[0]) - lsv[0], (acc1[4 * rq + 1] * a.scale - mx[1]) - lsv[1]);
+                v.z = fmaxf((acc0[4 * rq + 2] * a.scale - mx[0]) - lsv[0], (acc1[4 * rq + 2] * a.scale - mx[1]) - lsv[1]);
+                v.w = fmaxf((acc0[4 * rq + 3] * a.scale - mx[0]) - lsv[0], (acc1[4 * rq + 3] * a.scale - mx[1]) - lsv[1]);
+                *reinterpret_cast<float4 *>(zrow + 8 * rq) = v;
             }
         }
         if constexpr (KEYS) {
@@ -786,13 +802,14 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
                 // shared-memory counter bump per (thread, centroid) for the whole group of four, then the stores.
                 constexpr int NP = CT * 8 / 256;
                 uint32_t okv[NP][4], msk[NP], at[NP];
+                const bool inner = !tail && t0 >= a.n_init && t0 + 32 <= s - a.n_local && j0 + CT <= C;
                 if (t0 < tend) {
 #pragma unroll
                     for (int it = 0; it < NP; ++it) {
                         const int p = tid + 256 * it, n4 = (p & 7) * 4, jl = p >> 3;
                         float4 best = *reinterpret_cast<const float4 *>(&s_z[jl * ZS + n4]);
 #pragma unroll
-                        for (int c = 1; c < G; ++c) {
+                        for (int c = 1; c < NPL; ++c) {
                             const float4 o = *reinterpret_cast<const float4 *>(&s_z[(c * CT + jl) * ZS + n4]);
                             best.x = fmaxf(best.x, o.x);
                             best.y = fmaxf(best.y, o.y);
@@ -806,10 +823,15 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
                         okv[it][3] = ordered_key(best.w);
                         const uint32_t tau = s_tau[jl];
                         uint32_t m = 0;
+                        if (inner) {   // the whole step lies inside the block's range and outside the window, every centroid is real
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const bool in = (t + e) < tend && (t + e) >= a.n_init && (t + e) < s - a.n_local && (j0 + jl) < C;
-                            m |= (uint32_t)(in && okv[it][e] >= tau) << e;
+                            for (int e = 0; e < 4; ++e) m |= (uint32_t)(okv[it][e] >= tau) << e;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const bool in = (t + e) < tend && (t + e) >= a.n_init && (t + e) < s - a.n_local && (j0 + jl) < C;
+                                m |= (uint32_t)(in && okv[it][e] >= tau) << e;
+                            }
                         }
                         msk[it] = m;
                     }
@@ -840,7 +862,7 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
                     if ((j0 + jl) >= C) continue;
                     float4 best = *reinterpret_cast<const float4 *>(&s_z[jl * ZS + n4]);
 #pragma unroll
-                    for (int c = 1; c < G; ++c) {
+                    for (int c = 1; c < NPL; ++c) {
                         const float4 o = *reinterpret_cast<const float4 *>(&s_z[(c * CT + jl) * ZS + n4]);
                         best.x = fmaxf(best.x, o.x);
                         best.y = fmaxf(best.y, o.y);
