@@ -165,13 +165,15 @@ int ctkvr_decode_step_window(ctkvr_index *idx, const void *q, const void *k_page
  * the same step with the same arguments, results and errors, but every intermediate buffer of
  * the step (cosines, recall bitmap, recalled ids and rows, logits, ranking keys and their
  * histogram, the selection's bitmap and list, the selected rows and logits) lives in a static
- * device array of the library, 16 MiB per GPU, instead of the workspace `idx` owns.  The call
+ * device array of the library, 32 MiB per GPU, instead of the workspace `idx` owns.  The call
  * allocates and frees nothing, on the host side of HIP or through it; the array's device
  * address is looked up on the first call on each device.
  *   - The step's buffers must fit: about
- *       units * (l_stride * (12 + 4 G) + 4 C_max + s_max / 8 + top_k * (8 + 4 G) + 30 KiB)
- *     bytes, units = batch * g (the 32K benchmark workload takes 7.6 MiB).  Larger geometries
- *     return CTKVR_EUNSUPPORTED before anything is launched.
+ *       units * (l_stride * (16 + 4 G) + 4 C_max + s_max / 8 + top_k * (8 + 4 G) + 30 KiB)
+ *     bytes, units = batch * g, plus, on geometries that allow the single-launch form (units at most
+ *     the number of compute units), units * 32 * (4 top_k + 21 KiB) for its per-block slots (the 32K
+ *     benchmark workload takes about 15 MiB).  Larger geometries return CTKVR_EUNSUPPORTED before
+ *     anything is launched.
  *   - Every call on a GPU shares that GPU's array, whichever index it serves: calls that
  *     overlap on one GPU (different streams, different threads) race.  The call clears what a
  *     step expects to find zero, so it may follow a call for any other index.
@@ -273,10 +275,11 @@ int ctkvr_index_decode_path(const ctkvr_index *idx);
  * (CTKVR_EHIP; the index must then be freed) -- CTKVR_OK otherwise. */
 int ctkvr_index_check(ctkvr_index *idx);
 /* Measurement aid for the single launch: with enable != 0 the first block of the first unit
- * stamps the 100 MHz wall clock at kernel entry and after each of its seven phases (entries 0-7:
- * when it leaves the phase's barrier) and when its own work of each of the first six phases is
- * done (entries 8-13: when it arrives at the barrier); the call synchronises and copies the 16
- * entries of the last step to ticks_host (HOST, may be NULL). */
+ * stamps the 100 MHz wall clock at kernel entry and after each of its phases (entries 0-7: when it
+ * leaves the phase's barrier), when its own work of each phase is done (entries 8-13: when it
+ * arrives at the barrier) and at points inside the phases (entries 16 and up; 0 = not stamped); the
+ * call synchronises and copies the 64 entries of the last step to ticks_host (HOST, 64 values, may
+ * be NULL). */
 int ctkvr_profile_phases(ctkvr_index *idx, int32_t enable, long long *ticks_host);
 
 /* Measurement aid: what a launch costs when the kernel does nothing.  Captures n_launches empty
