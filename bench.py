@@ -94,6 +94,11 @@ def bench_build(args, wl, emit=True):
             ck.ctkvr_free(ck.ctkvr_build_index(p, db.q_prefill, db.cu_seqlens, True, db.k_pages, db.block_table, db.ctx_lens))
         torch.cuda.synchronize()
         res[name] = (time.perf_counter() - t0) / K * 1e3
+        if name == "mfma":   # which way the lists were chosen (untimed extra build)
+            probe = ck.ctkvr_build_index(p, db.q_prefill, db.cu_seqlens, True, db.k_pages, db.block_table, db.ctx_lens)
+            by_cand, redone = ck.ctkvr_index_build_route(probe)
+            res["route"] = {"by_candidates": by_cand, "chunks_redone": redone}
+            ck.ctkvr_free(probe)
     flops = sum(2.0 * wl.h * wl.centroids_of(s) * s * wl.d for s in wl.ctx_lens)
     tf = flops / (res["mfma"] * 1e-3) / 1e12
     rec = {"metric": "index build ms (centroid table + top-rho inverted lists)", "value": res["mfma"], "unit": "ms",
@@ -101,7 +106,7 @@ def bench_build(args, wl, emit=True):
            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "config": {"workload": wl.name, "ctx_lens": wl.ctx_lens, "q_heads": wl.h, "kv_heads": wl.g,
                       "centroids": wl.n_centroids, "list_len": wl.list_len, "build_algo": "mfma"},
-           "exact_build_ms": res["exact"], "score_gemm_flops": flops, "kmeans": res.get("kmeans"),
+           "exact_build_ms": res["exact"], "score_gemm_flops": flops, "mfma_build_route": res["route"], "kmeans": res.get("kmeans"),
            "roofline": ({"kernel": "Lloyd iterations (kmeans_assign_kernel GEMM + counting-sort update)", "bound": "mfma",
                          "achieved": res["kmeans"]["lloyd_TFLOPs"], "peak": 2500.0, "unit": "TFLOP/s",
                          "frac": res["kmeans"]["lloyd_TFLOPs"] / 2500.0, "traffic": None} if args.kmeans else
@@ -110,7 +115,7 @@ def bench_build(args, wl, emit=True):
            "cpu_baseline": None}
     if not emit:
         return {"mfma_build_ms": res["mfma"], "exact_build_ms": res["exact"], "score_gemm_flops": flops,
-                "whole_build_TFLOPs": tf, "whole_build_mfma_frac": tf / 2500.0, "kmeans": res.get("kmeans"),
+                "mfma_build_route": res["route"], "whole_build_TFLOPs": tf, "whole_build_mfma_frac": tf / 2500.0, "kmeans": res.get("kmeans"),
                 "config": rec["config"]}
     print(json.dumps(rec))
 
