@@ -376,15 +376,18 @@ def test_mfma_build_matches_oracle_up_to_ties(ck, case):
     ck.ctkvr_free(idx)
 
 
-@pytest.mark.parametrize("name,s,rho,expect_redo", [
-    ("cand_ok", 6000, 400, False),         # about 2 rho + 256 = 1056 candidates per unit: within [rho, 4 rho]
-    ("cand_overflow", 2500, 40, True),     # about 2 rho + 256 candidates against room for 4 rho = 160: handed back, same lists
+@pytest.mark.parametrize("name,h,g,s,rho,expect_redo", [
+    ("cand_ok", 8, 2, 6000, 400, False),         # about 2 rho + 256 = 1056 candidates per unit: within [rho, 4 rho]
+    ("cand_overflow", 8, 2, 2500, 40, True),     # about 2 rho + 256 candidates against room for 4 rho = 160: handed back, same lists
+    ("cand_g1", 2, 2, 6100, 400, False),         # one head per group: a wave's two work items are two sub-tiles
+    ("cand_g2", 4, 2, 5900, 400, False),
+    ("cand_g8", 8, 1, 6200, 400, False),         # four head pairs meet in shared memory
 ])
-def test_mfma_build_from_candidates_gives_the_lists_of_the_route_that_ranks_every_key(ck, name, s, rho, expect_redo, monkeypatch):
+def test_mfma_build_from_candidates_gives_the_lists_of_the_route_that_ranks_every_key(ck, name, h, g, s, rho, expect_redo, monkeypatch):
     """The candidate route (threshold from a sample of the positions, exact selection among the keys above it) and
     its hand-back when a unit has too few or too many candidates: bit-equal lists either way, since both rank the
     same matrix-core keys; and within the derived band of the oracle's."""
-    wl = small_workload(name, "bf16", 8, 2, (s, s - 777), (620, 621), 40, 0, 4, rho, 60, 1)
+    wl = small_workload(name, "bf16", h, g, (s, s - 777), (620, 621), 40, 0, 4, rho, 60, 1)
     bt = gen_batch(wl)
     db = H.device_batch(bt)
     lists = {}
