@@ -119,6 +119,7 @@ struct ctkvr_index {
     bool have_step = false;
     size_t recall_lds = 0, select_lds = 0, attn_lds = 0, build_select_lds = 0;
     size_t fused_lds = 0;   // non-zero: selection and attention run as one launch (select_attn_kernel)
+    int attn_slices = 4;    // blocks per unit of the attention (head-dimension slices): 8 while each has a CU of its own
     int build_redone = 0;   // chunks of the matrix-core list build that the candidate route had to hand back
     int build_by_cand = 0;  // the matrix-core list build took the candidate route
     int score_by_rank = -1;   // how the scoring kernel splits a unit's recalled ids over its blocks: -1 chosen per batch, 0 by id range, 1 by rank
@@ -380,6 +381,7 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
     // Few enough units for every (unit, slice) block to have a CU of its own: one launch for lines 6-9.
     {
         const size_t fw = ((size_t)kSelLds + 2 * kListCap + ix->sel_bits + p->top_k + (size_t)p->top_k * ix->G) * 4;
+        ix->attn_slices = 8 * (int)U <= ix->num_cu ? 8 : 4;
         if (4 * (int)U <= ix->num_cu && fw <= 150 * 1024) ix->fused_lds = fw;
     }
     if (ix->recall_lds > 150 * 1024 || ix->select_lds > 150 * 1024 || ix->attn_lds > 128 * 1024) {
@@ -400,28 +402,44 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
     want((const void *)rerank_select_kernel<8>, sel_b);
     if (ix->fused_lds) {
         if (p->dtype == CTKVR_BF16) {
-            want((const void *)select_attn_kernel<bf16_t, 1>, ix->fused_lds);
-            want((const void *)select_attn_kernel<bf16_t, 2>, ix->fused_lds);
-            want((const void *)select_attn_kernel<bf16_t, 4>, ix->fused_lds);
-            want((const void *)select_attn_kernel<bf16_t, 8>, ix->fused_lds);
+            want((const void *)select_attn_kernel<bf16_t, 1, 4>, ix->fused_lds);
+            want((const void *)select_attn_kernel<bf16_t, 1, 8>, ix->fused_lds);
+            want((const void *)select_attn_kernel<bf16_t, 2, 4>, ix->fused_lds);
+            want((const void *)select_attn_kernel<bf16_t, 2, 8>, ix->fused_lds);
+            want((const void *)select_attn_kernel<bf16_t, 4, 4>, ix->fused_lds);
+            want((const void *)select_attn_kernel<bf16_t, 4, 8>, ix->fused_lds);
+            want((const void *)select_attn_kernel<bf16_t, 8, 4>, ix->fused_lds);
+            want((const void *)select_attn_kernel<bf16_t, 8, 8>, ix->fused_lds);
         } else {
-            want((const void *)select_attn_kernel<float, 1>, ix->fused_lds);
-            want((const void *)select_attn_kernel<float, 2>, ix->fused_lds);
-            want((const void *)select_attn_kernel<float, 4>, ix->fused_lds);
-            want((const void *)select_attn_kernel<float, 8>, ix->fused_lds);
+            want((const void *)select_attn_kernel<float, 1, 4>, ix->fused_lds);
+            want((const void *)select_attn_kernel<float, 1, 8>, ix->fused_lds);
+            want((const void *)select_attn_kernel<float, 2, 4>, ix->fused_lds);
+            want((const void *)select_attn_kernel<float, 2, 8>, ix->fused_lds);
+            want((const void *)select_attn_kernel<float, 4, 4>, ix->fused_lds);
+            want((const void *)select_attn_kernel<float, 4, 8>, ix->fused_lds);
+            want((const void *)select_attn_kernel<float, 8, 4>, ix->fused_lds);
+            want((const void *)select_attn_kernel<float, 8, 8>, ix->fused_lds);
         }
     }
     if (ix->fused_bpu && e == hipSuccess) e = fused_set_smem(p->dtype == CTKVR_BF16, ix->G, ix->fused_nt, ix->fused_smem);
     if (p->dtype == CTKVR_BF16) {
-        want((const void *)sparse_attn_kernel<bf16_t, 1>, ix->attn_lds);
-        want((const void *)sparse_attn_kernel<bf16_t, 2>, ix->attn_lds);
-        want((const void *)sparse_attn_kernel<bf16_t, 4>, ix->attn_lds);
-        want((const void *)sparse_attn_kernel<bf16_t, 8>, ix->attn_lds);
+        want((const void *)sparse_attn_kernel<bf16_t, 1, 4>, ix->attn_lds);
+        want((const void *)sparse_attn_kernel<bf16_t, 1, 8>, ix->attn_lds);
+        want((const void *)sparse_attn_kernel<bf16_t, 2, 4>, ix->attn_lds);
+        want((const void *)sparse_attn_kernel<bf16_t, 2, 8>, ix->attn_lds);
+        want((const void *)sparse_attn_kernel<bf16_t, 4, 4>, ix->attn_lds);
+        want((const void *)sparse_attn_kernel<bf16_t, 4, 8>, ix->attn_lds);
+        want((const void *)sparse_attn_kernel<bf16_t, 8, 4>, ix->attn_lds);
+        want((const void *)sparse_attn_kernel<bf16_t, 8, 8>, ix->attn_lds);
     } else {
-        want((const void *)sparse_attn_kernel<float, 1>, ix->attn_lds);
-        want((const void *)sparse_attn_kernel<float, 2>, ix->attn_lds);
-        want((const void *)sparse_attn_kernel<float, 4>, ix->attn_lds);
-        want((const void *)sparse_attn_kernel<float, 8>, ix->attn_lds);
+        want((const void *)sparse_attn_kernel<float, 1, 4>, ix->attn_lds);
+        want((const void *)sparse_attn_kernel<float, 1, 8>, ix->attn_lds);
+        want((const void *)sparse_attn_kernel<float, 2, 4>, ix->attn_lds);
+        want((const void *)sparse_attn_kernel<float, 2, 8>, ix->attn_lds);
+        want((const void *)sparse_attn_kernel<float, 4, 4>, ix->attn_lds);
+        want((const void *)sparse_attn_kernel<float, 4, 8>, ix->attn_lds);
+        want((const void *)sparse_attn_kernel<float, 8, 4>, ix->attn_lds);
+        want((const void *)sparse_attn_kernel<float, 8, 8>, ix->attn_lds);
     }
     {
         int dev = 0, cus = 0;
@@ -1027,11 +1045,17 @@ int decode_launch_group(ctkvr_index *ix, const StepWs &w_all, int b0, int nb, bo
     aa.m_key = w.m_key;
     if (ix->fused_lds) {
         if (whole) ix->mark(7, st);   // no separate selection launch: its stage reads as the cost of an event pair
-        select_attn_kernel<T, G><<<dim3(4 * U), 1024, ix->fused_lds, st>>>(se, aa);
+        if (ix->attn_slices == 8)
+            select_attn_kernel<T, G, 8><<<dim3(8 * U), 1024, ix->fused_lds, st>>>(se, aa);
+        else
+            select_attn_kernel<T, G, 4><<<dim3(4 * U), 1024, ix->fused_lds, st>>>(se, aa);
     } else {
         rerank_select_kernel<G><<<dim3(U), 1024, ix->select_lds, st>>>(se);
         if (whole) ix->mark(7, st);
-        sparse_attn_kernel<T, G><<<dim3(4 * U), 1024, ix->attn_lds, st>>>(aa);
+        if (ix->attn_slices == 8)
+            sparse_attn_kernel<T, G, 8><<<dim3(8 * U), 1024, ix->attn_lds, st>>>(aa);
+        else
+            sparse_attn_kernel<T, G, 4><<<dim3(4 * U), 1024, ix->attn_lds, st>>>(aa);
     }
     if (whole) ix->mark(8, st);
     if (whole && ix->prof_step < ix->prof_max) {   // a null kernel between two events: what the bracketing itself costs

@@ -1746,57 +1746,68 @@ __device__ __forceinline__ float merge_window(const float *win, int ul, int hh, 
     return num / den;
 }
 
-// Block id -> (unit, slice).  Workgroups go to the 8 XCDs round-robin by linear id; the four slices
-// of a unit read the same 128-byte lines, so they get ids that are congruent modulo 8: one XCD, one L2.
-__device__ __forceinline__ void attn_block_of(int &ul, int &slice)
+// Block id -> (unit, slice).  A slice is 128 / SL head dimensions of all G heads, SL = 4 or 8 (8 while every
+// block still has a CU of its own: each block then moves half the bytes and weighs half the rows; beyond that the
+// launch is oversubscribed and 4 is faster).  Workgroups go to the 8 XCDs round-robin by linear id; the slices of a
+// unit read the same 128-byte lines, so they get ids that are congruent modulo 8: one XCD, one L2.
+template <int SL> __device__ __forceinline__ void attn_block_of(int &ul, int &slice)
 {
-    const int lin = blockIdx.x, nu = gridDim.x >> 2;
+    const int lin = blockIdx.x, nu = gridDim.x / SL;
     if ((nu & 7) == 0) {
         const int xcd = lin & 7, k = lin >> 3;
-        ul = (k >> 2) * 8 + xcd;
-        slice = k & 3;
+        ul = (k / SL) * 8 + xcd;
+        slice = k % SL;
     } else {
-        ul = lin >> 2;
-        slice = lin & 3;
+        ul = lin / SL;
+        slice = lin % SL;
     }
 }
 
 // The attention of one (unit, slice).  row_of(t) = physical row of the t-th selected key (valid for
 // every t < top_k), z_of(t, zv) = its G logits, nsel_of() = how many keys were selected; nsel_of is
 // asked only after the first value rows have been requested.  s_p: top_k*G floats of shared memory.
-template <typename T, int G, typename RowFn, typename ZFn, typename NFn>
+template <typename T, int G, int SL, typename RowFn, typename ZFn, typename NFn>
 __device__ __forceinline__ void attend_unit(const AttnArgs &a, int ul, int slice, float *s_p, RowFn row_of, ZFn z_of, NFn nsel_of)
 {
-    __shared__ float s_red[16][G];
+    constexpr int kSliceDims = kD / SL;            // head dimensions per block
+    constexpr int kSliceLanes = kSliceDims / 8;    // lanes that share a value row (8 dimensions each)
+    constexpr int kSliceRows = 64 / kSliceLanes;   // rows per wave and pass
+    static_assert(kSliceRows % 16 == 0, "the sum over a wave's rows starts with a butterfly inside each 16-lane row");
+    // A wave's 64 lanes are kSliceLanes parts of kSliceRows rows: lane l works on row (l mod kSliceRows) of the
+    // pass and on the 8 values (l / kSliceRows) of the slice.  Every 16-lane row of a wave thus belongs to one part and
+    // is one producer of partial sums; kProd of them per part in the block.
+    constexpr int PASS = 16 * kSliceRows, NU = 4, kProd = kSliceRows;   // rows per pass of the block, passes in flight
+    __shared__ float s_red[kProd][G];
     __shared__ float s_m[G], s_l[G];
-    __shared__ float s_o[16][G][32];
+    __shared__ float s_o[kProd][G][kSliceDims];
     const int b = ul / a.g, kv = ul - b * a.g;
     const int tid = threadIdx.x, wv = tid >> 6, ln = tid & 63;
-    const int quad = ln >> 4, rin = wv * 16 + (ln & 15);   // 4 lanes (one per 16-lane row of the wave) share a key row
+    const int quad = ln / kSliceRows, rin = wv * kSliceRows + (ln % kSliceRows);
+    const int prod = wv * (kSliceRows / 16) + ((ln % kSliceRows) >> 4);   // this lane's 16-lane row among its part's producers
     CTKVR_STAMP(44);
     CTKVR_STAMP_BLK(4);
-    const T *V = (const T *)a.v_pages + slice * 32 + quad * 8;
-    // The first 1024 value rows are requested before anything else (rows beyond nsel are valid
+    const T *V = (const T *)a.v_pages + slice * kSliceDims + quad * 8;
+    // The first NU * PASS value rows are requested before anything else (rows beyond nsel are valid
     // stale ones whose products get weight 0).
-    // The four row numbers first, then the four rows: taken in turn, each row number would be
+    // The row numbers first, then the rows: taken in turn, each row number would be
     // waited for together with the row requested just before it.
-    Chunk<T> cv[4];
-    uint32_t vrow[4];
+    Chunk<T> cv[NU];
+    uint32_t vrow[NU];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) vrow[u] = row_of(min(u * 256 + rin, a.top_k - 1));
+    for (int u = 0; u < NU; ++u) vrow[u] = row_of(min(u * PASS + rin, a.top_k - 1));
 #pragma unroll
-    for (int u = 0; u < 4; ++u) cv[u] = load_chunk(V + (size_t)vrow[u] * kD, 0);
-    // the first 1024 keys' logits travel with their value rows
-    float zq[4][G];
+    for (int u = 0; u < NU; ++u) cv[u] = load_chunk(V + (size_t)vrow[u] * kD, 0);
+    // those keys' logits travel with their value rows
+    float zq[NU][G];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) z_of(min(u * 256 + rin, a.top_k - 1), zq[u]);
+    for (int u = 0; u < NU; ++u) z_of(min(u * PASS + rin, a.top_k - 1), zq[u]);
     const int nsel = nsel_of();
     if (nsel == 0) {   // nothing recalled: the window alone, or zeros
-        if (tid < G * 32) {
-            int hh = tid >> 5, e = tid & 31;
+        if (tid < G * kSliceDims) {
+            int hh = tid / kSliceDims, e = tid % kSliceDims;
             float lse;
-            const float o = merge_window<G>(a.win, ul, hh, slice * 32 + e, 0.0f, -__builtin_huge_valf(), 0.0f, lse);
-            a.out[((size_t)b * a.h + kv * G + hh) * kD + slice * 32 + e] = o;
+            const float o = merge_window<G>(a.win, ul, hh, slice * kSliceDims + e, 0.0f, -__builtin_huge_valf(), 0.0f, lse);
+            a.out[((size_t)b * a.h + kv * G + hh) * kD + slice * kSliceDims + e] = o;
             if (slice == 0 && e == 0 && a.out_lse) a.out_lse[(size_t)b * a.h + kv * G + hh] = lse;
         }
         return;
@@ -1813,19 +1824,19 @@ __device__ __forceinline__ void attend_unit(const AttnArgs &a, int ul, int slice
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[hh][e] = 0.0f;
     }
-    for (int r0 = 0; r0 < nsel; r0 += 1024) {
+    for (int r0 = 0; r0 < nsel; r0 += NU * PASS) {
         if (r0 > 0) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) vrow[u] = row_of(min(r0 + u * 256 + rin, a.top_k - 1));
+            for (int u = 0; u < NU; ++u) vrow[u] = row_of(min(r0 + u * PASS + rin, a.top_k - 1));
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < NU; ++u) {
                 cv[u] = load_chunk(V + (size_t)vrow[u] * kD, 0);
-                z_of(min(r0 + u * 256 + rin, a.top_k - 1), zq[u]);
+                z_of(min(r0 + u * PASS + rin, a.top_k - 1), zq[u]);
             }
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int t = r0 + u * 256 + rin;
+        for (int u = 0; u < NU; ++u) {
+            const int t = r0 + u * PASS + rin;
             if (t < nsel) {
                 float vx[8];
                 unpack(cv[u], vx);
@@ -1842,14 +1853,14 @@ __device__ __forceinline__ void attend_unit(const AttnArgs &a, int ul, int slice
     CTKVR_STAMP(48);
 #pragma unroll
     for (int hh = 0; hh < G; ++hh) {
-        const float v = group16_sum(lsum[hh]);   // rows 1-3 of the wave hold zeros
-        if (ln == 0) s_red[wv][hh] = v;
+        const float v = group16_sum(lsum[hh]);   // the lanes of the other parts hold zeros
+        if ((ln & 15) == 0 && quad == 0) s_red[prod][hh] = v;
     }
     __syncthreads();
     if (tid < G) {
         float v = 0.0f;
 #pragma unroll
-        for (int w = 0; w < 16; ++w) v += s_red[w][tid];
+        for (int w = 0; w < kProd; ++w) v += s_red[w][tid];
         s_l[tid] = v;
         s_m[tid] = mref[0];
 #pragma unroll
@@ -1930,16 +1941,16 @@ __device__ __forceinline__ void attend_unit(const AttnArgs &a, int ul, int slice
         for (int hh = 0; hh < G; ++hh)
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[hh][e] = 0.0f;
-        for (int r0 = 0; r0 < nsel; r0 += 1024) {
+        for (int r0 = 0; r0 < nsel; r0 += NU * PASS) {
             {
 #pragma unroll
-                for (int u = 0; u < 4; ++u) vrow[u] = row_of(min(r0 + u * 256 + rin, a.top_k - 1));
+                for (int u = 0; u < NU; ++u) vrow[u] = row_of(min(r0 + u * PASS + rin, a.top_k - 1));
 #pragma unroll
-                for (int u = 0; u < 4; ++u) cv[u] = load_chunk(V + (size_t)vrow[u] * kD, 0);
+                for (int u = 0; u < NU; ++u) cv[u] = load_chunk(V + (size_t)vrow[u] * kD, 0);
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                int t = r0 + u * 256 + rin;
+            for (int u = 0; u < NU; ++u) {
+                int t = r0 + u * PASS + rin;
                 if (t < nsel) {
                     float vx[8];
                     unpack(cv[u], vx);
@@ -1953,7 +1964,7 @@ __device__ __forceinline__ void attend_unit(const AttnArgs &a, int ul, int slice
             }
         }
     }
-    // sum over the 16 rows of a wave (a DPP butterfly inside each 16-lane row), then over the 16 waves in order
+    // sum inside each 16-lane row (a DPP butterfly), then over the part's kProd rows of the block in order
 #pragma unroll
     for (int hh = 0; hh < G; ++hh)
 #pragma unroll
@@ -1962,48 +1973,48 @@ __device__ __forceinline__ void attend_unit(const AttnArgs &a, int ul, int slice
 #pragma unroll
         for (int hh = 0; hh < G; ++hh)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) s_o[wv][hh][quad * 8 + e] = acc[hh][e];
+            for (int e = 0; e < 8; ++e) s_o[prod][hh][quad * 8 + e] = acc[hh][e];
     }
     __syncthreads();
     CTKVR_STAMP(46);
-    if (tid < G * 32) {
-        int hh = tid >> 5, e = tid & 31;
+    if (tid < G * kSliceDims) {
+        int hh = tid / kSliceDims, e = tid % kSliceDims;
         float v = 0.0f;
 #pragma unroll
-        for (int w = 0; w < 16; ++w) v += s_o[w][hh][e];
+        for (int w = 0; w < kProd; ++w) v += s_o[w][hh][e];
         float lse;
-        const float o = merge_window<G>(a.win, ul, hh, slice * 32 + e, v, s_m[hh], s_l[hh], lse);
-        a.out[((size_t)b * a.h + kv * G + hh) * kD + slice * 32 + e] = o;
+        const float o = merge_window<G>(a.win, ul, hh, slice * kSliceDims + e, v, s_m[hh], s_l[hh], lse);
+        a.out[((size_t)b * a.h + kv * G + hh) * kD + slice * kSliceDims + e] = o;
         if (slice == 0 && e == 0 && a.out_lse) a.out_lse[(size_t)b * a.h + kv * G + hh] = lse;
     }
     CTKVR_STAMP(47);
     CTKVR_STAMP_BLK(5);
 }
 
-template <typename T, int G> __global__ __launch_bounds__(1024) void sparse_attn_kernel(AttnArgs a)
+template <typename T, int G, int SL> __global__ __launch_bounds__(1024) void sparse_attn_kernel(AttnArgs a)
 {
     extern __shared__ __align__(16) float s_p[];   // [top_k][G]
     int ul, slice;
-    attn_block_of(ul, slice);
+    attn_block_of<SL>(ul, slice);
     const uint32_t *rb = a.srow + (size_t)ul * a.top_k;
     const float *zb = a.zsel + (size_t)ul * a.top_k * G;
-    attend_unit<T, G>(a, ul, slice, s_p, [&](int t) { return rb[t]; }, [&](int t, float(&zv)[G]) { load_z<G>(zb, t, zv); },
+    attend_unit<T, G, SL>(a, ul, slice, s_p, [&](int t) { return rb[t]; }, [&](int t, float(&zv)[G]) { load_z<G>(zb, t, zv); },
                       [&]() { return a.nsel[ul]; });
 }
 
 // ------------------------------------------------------------------------------
 // Algorithm 2 lines 6-9 in one launch, for batches small enough that every block has a CU of its
-// own: each of the four slice blocks of a unit makes the unit's selection itself (the same work
-// four times over, on four CUs, instead of a second launch and a round trip of the picks through
+// own: each of the SL slice blocks of a unit makes the unit's selection itself (the same work
+// several times over, on as many CUs, instead of a second launch and a round trip of the picks through
 // global memory) and then attends over the picks straight from the recalled ids' rows and logits.
-// Slice 0 also writes the selected ids and their number.  grid 4*batch*g, 1024 threads; dynamic
+// Slice 0 also writes the selected ids and their number.  grid SL*batch*g, 1024 threads; dynamic
 // shared memory: the selection's words, then top_k*G floats.
 // ------------------------------------------------------------------------------
-template <typename T, int G> __global__ __launch_bounds__(1024) void select_attn_kernel(SelectArgs sa, AttnArgs a)
+template <typename T, int G, int SL> __global__ __launch_bounds__(1024) void select_attn_kernel(SelectArgs sa, AttnArgs a)
 {
     extern __shared__ __align__(16) uint32_t smem[];
     int ul, slice;
-    attn_block_of(ul, slice);
+    attn_block_of<SL>(ul, slice);
     const int L = sa.ncand[ul];
     CTKVR_STAMP(28);
     const int n = select_unit<G>(sa, ul, L, smem);
@@ -2027,7 +2038,7 @@ template <typename T, int G> __global__ __launch_bounds__(1024) void select_attn
     // positions beyond n repeat the last pick; when nothing was recalled every position reads slot 0 of
     // the row table and then names row 0 of the pool (selects, not a branch: the four row numbers of a
     // pass are then requested together)
-    attend_unit<T, G>(a, ul, slice, s_p,
+    attend_unit<T, G, SL>(a, ul, slice, s_p,
                       [&](int t) {
                           const uint32_t r = rb[n > 0 ? s_idx[min(t, n - 1)] : 0];
                           return n > 0 ? r : 0u;
