@@ -180,6 +180,26 @@ def test_exact_ties_duplicated_keys_and_centroids(ck):
     ck.ctkvr_free(idx)
 
 
+@pytest.mark.parametrize("C,n_dup,n_probe", [(300, 200, 12), (1500, 1400, 40), (600, 90, 20)])
+def test_many_equal_cosines_take_the_lowest_centroid_ids(ck, C, n_dup, n_probe):
+    """n_dup of the C centroids are one and the same vector, so their cosines tie exactly, far more of them than are
+    probed: the probed ids must be the oracle's (ties to the lowest id), with 2 and with 8 keys per thread in the
+    selection."""
+    wl = small_workload(f"dupcos{C}", "bf16", 4, 2, (2000,), (430,), C, 0, n_probe, 48, 40, 2)
+    bt = gen_batch(wl)
+    sq = bt.seqs[0]
+    n_tail = sq.q_tail.shape[0]
+    sq.q_tail[n_tail - C + 5:n_tail - C + 5 + n_dup] = sq.q_tail[n_tail - 1]    # the newest query, copied over older centroids
+    bt = Batch(wl=wl, seqs=[sq], paged=paginate([sq], wl.page_size, 9))
+    oi = H.oracle_index(bt)
+    db = H.device_batch(bt)
+    cen, lst = oi.padded(wl)
+    idx = ck.ctkvr_index_load(H.params_of(wl), db.ctx_lens, cen, lst)
+    st = H.run_decode_parity(bt, oi, idx, db)
+    _say(f"[dupcos C={C} dup={n_dup}] ok {st}")
+    ck.ctkvr_free(idx)
+
+
 def test_lattice_inputs_all_scores_exact(ck):
     wl = small_workload("lattice", "bf16", 8, 2, (1200,), (500,), 16, 0, 4, 90, 60, 3)
     sq = gen_lattice_sequence(500, 1200, 8, 2, 128, 16, 3)
