@@ -119,6 +119,7 @@ struct ctkvr_index {
     bool have_step = false;
     size_t recall_lds = 0, select_lds = 0, attn_lds = 0, build_select_lds = 0;
     size_t fused_lds = 0;   // non-zero: selection and attention run as one launch (select_attn_kernel)
+    int keyclass = -1;      // key histogram + classification as one launch: -1 chosen per batch, 0 never, 1 always
     int attn_slices = 4;    // blocks per unit of the attention (head-dimension slices): 8 while each has a CU of its own
     int build_redone = 0;   // chunks of the matrix-core list build that the candidate route had to hand back
     int build_by_cand = 0;  // the matrix-core list build took the candidate route
@@ -334,6 +335,7 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
         int ng = 1;
         if (const char *e = getenv("CTKVR_DECODE_GROUPS")) ng = std::max(1, std::min(std::min(8, B), atoi(e)));
         if (const char *e = getenv("CTKVR_SCORE_BY_RANK")) ix->score_by_rank = atoi(e) != 0;
+        if (const char *e = getenv("CTKVR_KEYCLASS")) ix->keyclass = atoi(e) != 0;
         ix->n_groups = ng;
     }
     if (const char *e = getenv("CTKVR_DECODE_PATH")) {
@@ -971,10 +973,34 @@ int decode_launch_group(ctkvr_index *ix, const StepWs &w_all, int b0, int nb, bo
     da.S = w.S;
     da.gbits = w.gbits;
     da.bitmap_words = ix->bitmap_words;
+    da.gcur = w.gcur;
     const int chunks = (ix->l_stride + 1023) / 1024;
     denom_kernel<G><<<dim3(std::max(1, std::min(chunks, (4 * ix->num_cu + U - 1) / U)), U), 256, 0, st>>>(da);
     if (whole) ix->mark(4, st);
 
+    // Small batches: the key histogram and the classification pass as one launch, every block taking the unit's
+    // whole histogram itself (keyclass_kernel); otherwise two chip-wide launches.
+    const bool keyclass = ix->sel_bits && (ix->keyclass < 0 ? (long long)ix->l_stride * U <= 2048ll * ix->num_cu : ix->keyclass != 0);
+    if (keyclass) {
+        KeyClassArgs kc{};
+        kc.u = u;
+        kc.ctx_lens = d_ctx_lens;
+        kc.ncand = w.ncand;
+        kc.l_stride = ix->l_stride;
+        kc.top_k = p.top_k;
+        kc.z = w.z;
+        kc.m_key = w.m_key;
+        kc.S = w.S;
+        kc.kbuf = w.kbuf;
+        kc.bits_stride = 2 * ((ix->l_stride + 63) / 64);
+        kc.gbm = w.gbm;
+        kc.glist = w.glist;
+        kc.gcur = w.gcur;
+        kc.ginfo = w.ginfo;
+        keyclass_kernel<G><<<dim3(std::max(1, std::min((ix->l_stride + 4095) / 4096, (2 * ix->num_cu + U - 1) / U)), U), 1024, 0, st>>>(kc);
+        if (whole) ix->mark(5, st);
+        if (&w_all == &ix->ws) ix->last_step_fused = true;   // no 2048-bucket histogram is left for a second ranking
+    } else {
     KeyArgs ka{};
     ka.u = u;
     ka.ctx_lens = d_ctx_lens;
@@ -988,8 +1014,9 @@ int decode_launch_group(ctkvr_index *ix, const StepWs &w_all, int b0, int nb, bo
     ka.gcur = w.gcur;
     keyhist_kernel<G><<<dim3(std::max(1, std::min((ix->l_stride + 4095) / 4096, (2 * ix->num_cu + U - 1) / U)), U), 1024, 0, st>>>(ka);
     if (whole) ix->mark(5, st);
+    }
 
-    if (ix->sel_bits) {
+    if (ix->sel_bits && !keyclass) {
         ClassifyArgs ca{};
         ca.u = u;
         ca.ctx_lens = d_ctx_lens;

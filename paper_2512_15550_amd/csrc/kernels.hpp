@@ -979,6 +979,7 @@ struct DenomArgs {
     unsigned long long *S;
     uint32_t *gbits;          // decode only: the recall bitmap, cleared here for the next step
     int bitmap_words;
+    uint32_t *gcur;           // optional: [units] list cursors of keyclass_kernel, cleared here
 };
 
 template <int G> __global__ __launch_bounds__(256) void denom_kernel(DenomArgs a)
@@ -993,6 +994,7 @@ template <int G> __global__ __launch_bounds__(256) void denom_kernel(DenomArgs a
     for (int hh = 0; hh < G; ++hh) mk[hh] = a.m_key[ul * G + hh];
     const int s_len = a.ctx_lens[b];
     const int L = a.ncand ? a.ncand[ul] : s_len;
+    if (a.gcur && blockIdx.x == 0 && threadIdx.x == 0) a.gcur[ul] = 0u;
     if (a.gbits) {
         const int W = (s_len + 31) >> 5;
         for (int w = blockIdx.x * 256 + threadIdx.x; w < W; w += gridDim.x * 256) a.gbits[(size_t)ul * a.bitmap_words + w] = 0u;
@@ -1275,6 +1277,135 @@ __global__ __launch_bounds__(256) void classify_kernel(ClassifyArgs a)
 }
 
 // ------------------------------------------------------------------------------
+// keyhist_kernel and classify_kernel as ONE launch, for small batches (decode).  The histogram of a unit's
+// keys is needed whole before any key can be classified; here every block of the unit takes it itself, over
+// ALL the unit's ids (the same few thousand scores read by each of its blocks, from the cache; the histogram
+// stays in shared memory), finds the deciding bucket, and then writes and classifies the keys of its own share
+// as classify_kernel does.  One launch and one round trip fewer, for work that is repeated per block: only
+// where that work is small (the host's choice).  grid (nbx, units), 1024 threads; denom_kernel has cleared the
+// list cursors.  No 2048-bucket histogram is left in global memory.
+// ------------------------------------------------------------------------------
+struct KeyClassArgs {
+    Units u;
+    const int32_t *ctx_lens, *ncand;
+    int l_stride, top_k;
+    const float *z;
+    const uint32_t *m_key;
+    const unsigned long long *S;
+    uint32_t *kbuf;          // [units][l_stride]
+    int bits_stride;
+    uint32_t *gbm;           // [units][bits_stride]
+    uint2 *glist;            // [units][kListCap]
+    uint32_t *gcur;          // [units], zero on entry
+    uint32_t *ginfo;         // [units][4]
+};
+
+template <int G> __global__ __launch_bounds__(1024) void keyclass_kernel(KeyClassArgs a)
+{
+    int b, kv, j;
+    const int ul = blockIdx.y;
+    if (!decode_unit(a.u, ul, b, kv, j)) return;
+    const int tid = threadIdx.x, wv = tid >> 6, ln = lane_id();
+    uint32_t mk[G];
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) mk[hh] = a.m_key[ul * G + hh];
+    const unsigned long long S_mine = tid < G ? a.S[ul * G + tid] : 1ull;
+    const int L = a.ncand ? a.ncand[ul] : a.ctx_lens[b];
+    __shared__ uint32_t s_h[kBuckets];
+    __shared__ float s_ls[G];
+    __shared__ uint32_t s_scan[1024 / 64 + 2];
+    __shared__ uint32_t s_res[3];
+    for (int w = tid; w < kBuckets; w += 1024) s_h[w] = 0u;
+    if (tid < G) s_ls[tid] = (float)log_fixed40(S_mine);
+    if (tid == 0) s_res[2] = 0xffffffffu;
+    float m[G], ls[G];
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) m[hh] = ordered_value(mk[hh]);
+    __syncthreads();
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) ls[hh] = s_ls[hh];
+    const float *zb = a.z + (size_t)ul * a.l_stride * G;
+    auto key_of = [&](const float(&zv)[G]) __attribute__((always_inline)) {
+        float best = -__builtin_huge_valf();
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh) best = fmaxf(best, (zv[hh] - m[hh]) - ls[hh]);
+        return ordered_key(best);
+    };
+    const bool rank = a.top_k < L;   // otherwise every recalled key is kept and nothing needs classifying
+    // pass 1: the histogram of ALL the unit's keys (the last bucket, which takes every key below the range, counted
+    // per wave with a ballot)
+    for (int c0 = 0; rank && c0 < L; c0 += 4096) {
+        float zv[4][G];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) load_z<G>(zb, min(c0 + q * 1024 + tid, L - 1), zv[q]);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const bool valid = c0 + q * 1024 + tid < L;
+            const uint32_t bk = key_bucket(key_of(zv[q]));
+            const bool tail = valid && bk == (uint32_t)(kBuckets - 1);
+            const uint64_t mt = __ballot(tail);
+            if (valid && !tail) atomicAdd(&s_h[bk], 1u);
+            if (mt && ln == 0) atomicAdd(&s_h[kBuckets - 1], (uint32_t)__popcll(mt));
+        }
+    }
+    __syncthreads();
+    uint32_t bkt = 0, nb = 0xffffffffu;
+    if (rank) {
+        // thread t owns buckets 2t, 2t+1, in descending key order
+        constexpr int BPT = kBuckets / 1024;
+        uint32_t c[BPT], mine = 0;
+#pragma unroll
+        for (int q = 0; q < BPT; ++q) {
+            c[q] = s_h[BPT * tid + q];
+            mine += c[q];
+        }
+        uint32_t tot;
+        uint32_t before = block_excl_scan<1024>(mine, s_scan, &tot);
+#pragma unroll
+        for (int q = 0; q < BPT; ++q) {
+            if (before < (uint32_t)a.top_k && (uint32_t)a.top_k <= before + c[q]) {
+                s_res[0] = (uint32_t)(BPT * tid + q);
+                s_res[1] = (uint32_t)a.top_k - before;
+                s_res[2] = c[q];
+            }
+            before += c[q];
+        }
+        __syncthreads();
+        bkt = s_res[0];
+        nb = s_res[2];
+        if (blockIdx.x == 0 && tid == 0) *reinterpret_cast<uint4 *>(a.ginfo + 4 * (size_t)ul) = make_uint4(bkt, s_res[1], nb, 0u);
+    }
+    const bool classify = rank && nb <= (uint32_t)kListCap;
+    // pass 2: this block's share of the ids in groups of 64: keys written, and classified against the deciding bucket
+    uint32_t *kb = a.kbuf + (size_t)ul * a.l_stride;
+    uint32_t *bm = a.gbm + (size_t)ul * a.bits_stride;
+    uint2 *lst = a.glist + (size_t)ul * kListCap;
+    const uint64_t below = (1ull << ln) - 1ull;
+    const int nw64 = (L + 63) >> 6;
+    for (int g0 = blockIdx.x * 16 + wv; g0 < nw64; g0 += gridDim.x * 16) {
+        const int i = g0 * 64 + ln;
+        const bool valid = i < L;
+        float zv[G];
+        load_z<G>(zb, min(i, L - 1), zv);
+        const uint32_t ok = key_of(zv);
+        if (valid) kb[i] = ok;
+        if (classify) {
+            const uint32_t bk = key_bucket(ok);
+            const bool inb = valid && bk == bkt;
+            const uint64_t above = __ballot(valid && bk < bkt);
+            const uint64_t listed = __ballot(inb);
+            if (ln == 0) *reinterpret_cast<uint2 *>(bm + 2 * g0) = make_uint2((uint32_t)above, (uint32_t)(above >> 32));
+            if (listed) {
+                uint32_t at0 = 0;
+                if (ln == 0) at0 = atomicAdd(&a.gcur[ul], (uint32_t)__popcll(listed));
+                at0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)at0);
+                if (inb) lst[at0 + (uint32_t)__popcll(listed & below)] = make_uint2(ok, (uint32_t)i);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------
 // Algorithm 2 line 6 / Algorithm 1 line 4.  One block of 1024 threads per unit: the
 // top-k ids by ranking key (kbuf), ascending, helped by the key histogram.
 //   decode: sel[unit][pos] = cand[i], srow[unit][pos] = crow[i],
@@ -1528,11 +1659,11 @@ __global__ __launch_bounds__(1024) void cand_select_kernel(CandArgs a)
 }
 
 // ------------------------------------------------------------------------------
-// Algorithm 2 lines 7-9: o_h = softmax(z_sel[h]) . V_sel.  grid 4*batch*g, 1024
-// threads: block x owns head dimensions 32x .. 32x+31 of all G heads of its
-// (sequence, KV head), so no partial result crosses a block.  Four lanes share a
-// row (8 dimensions each; lane l, l+16, l+32, l+48 of a wave), 256 rows per pass.  Dynamic shared memory:
-// top_k*G floats (softmax weights) .
+// Algorithm 2 lines 7-9: o_h = softmax(z_sel[h]) . V_sel.  grid SL*batch*g, 1024
+// threads, SL = 4 or 8 slices: block x owns head dimensions (128/SL) x .. of all G heads of its
+// (sequence, KV head), so no partial result crosses a block.  16/SL lanes share a
+// row (8 dimensions each; lanes 64 SL/16 apart in a wave), 64 SL rows per pass.  Dynamic shared memory:
+// top_k*G floats (softmax weights of the two-pass fallback).
 // ------------------------------------------------------------------------------
 struct AttnArgs {
     const void *v_pages;

@@ -83,6 +83,16 @@ def test_both_ways_of_splitting_the_recalled_ids_over_blocks_match_the_oracle(ck
     _run(ck, case, ck.PATH_STAGED)
 
 
+@pytest.mark.parametrize("merged", [0, 1])
+@pytest.mark.parametrize("case", SPLIT_CASES, ids=[c[0] for c in SPLIT_CASES])
+def test_key_histogram_and_classification_as_one_launch_or_two_match_the_oracle(ck, case, merged, monkeypatch):
+    """Small batches take the ranking keys' histogram and the classification pass in one launch (every block takes its
+    unit's whole histogram itself), large ones in two chip-wide launches; here each form is forced in turn."""
+    monkeypatch.setenv("CTKVR_KEYCLASS", str(merged))
+    print(f"[paths {case[0]}] keys + classification in {'one launch' if merged else 'two launches'}", flush=True)
+    _run(ck, case, ck.PATH_STAGED)
+
+
 def test_exact_ties_through_the_single_launch(ck):
     """Duplicated keys and centroids (planted exact ties) and lattice inputs crowd the deciding
     bucket: the unit's first block then selects alone (the histogram-free route)."""
