@@ -602,7 +602,7 @@ struct MfmaScoreArgs {
     const bf16_t *centroids;   // [batch][h][c_max][128]
     Paged k;
     int l_stride;              // s_max
-    float2 *part;              // [chunk units][G][t_splits] (maximum, sum of exp(z - maximum)) over a block's keys
+    float2 *part;              // [chunk units][G][t_splits] (maximum of z log2(e), sum of 2^(z log2(e) - maximum)) over a block's keys
     uint32_t *kbuf;            // KEY: [chunk units][l_stride] ranking keys; SAMPLE: [chunk units][sample_stride]
     int n_init, n_local;       // keys of the resident window get the lowest ranking key
     float scale;
@@ -645,7 +645,8 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
     // PICK: the tile's thresholds and how many candidates this block has found for each of its centroids.  A block
     // owns a segment of every unit's candidate list, so positions are handed out by shared-memory counters: no
     // atomic on device memory (on this part those are served beyond the XCD's cache, a round trip each).
-    __shared__ uint32_t s_tau[MODE == MFMA_PICK ? CT : 1], s_cnt[MODE == MFMA_PICK ? CT : 1];
+    __shared__ float s_tauf[MODE == MFMA_PICK ? CT : 1];
+    __shared__ uint32_t s_cnt[MODE == MFMA_PICK ? CT : 1];
     __shared__ __align__(16) unsigned char s_k[2][32 * 272];
     const int tid = threadIdx.x, wv = tid >> 6, ln = tid & 63;
     const int col = ln & 31, half = ln >> 5;
@@ -663,7 +664,8 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
     if (tbeg >= tend) return;
     if constexpr (MODE == MFMA_PICK) {
         if (tid < CT) {
-            s_tau[tid] = a.tau[(size_t)bkl * a.c_max + min(j0 + tid, C - 1)];
+            const uint32_t tk = a.tau[(size_t)bkl * a.c_max + min(j0 + tid, C - 1)];
+            s_tauf[tid] = tk ? ordered_value(tk) : -__builtin_huge_valf();   // 0: no threshold, every key is a candidate
             s_cnt[tid] = 0u;
         }
     }
@@ -693,11 +695,14 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
             float m = -__builtin_huge_valf();
             for (int x = 0; x < a.t_splits && x * tper < s; ++x) m = fmaxf(m, pp[x].x);
             float S = 0.0f;
-            for (int x = 0; x < a.t_splits && x * tper < s; ++x) S += pp[x].y * __expf(pp[x].x - m);
-            mx[q] = m;
+            for (int x = 0; x < a.t_splits && x * tper < s; ++x) S += pp[x].y * __builtin_amdgcn_exp2f(pp[x].x - m);
+            mx[q] = m * 0.693147180559945309f;   // the pairs hold base-two maxima
             lsv[q] = logf(S);
         }
     }
+    const float sc2 = a.scale * 1.44269504088896341f;   // scores in base two (statistics pass)
+    // key passes: the score's offset -(m + log S), so that a key is one fused multiply-add per score
+    const float off[2] = {-(mx[0] + lsv[0]), -(mx[1] + lsv[1])};
     // The 32 key rows of a step (8 KB) go through shared memory once for the four waves, in two
     // buffers; a step's rows are requested two steps ahead and their block-table entries four
     // steps ahead, so that neither latency is waited for.  Rows beyond the sequence are clamped
@@ -749,33 +754,33 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
             if constexpr (MODE == MFMA_STAT) {
                 // the step's maximum first (repeated keys of a tail are real keys: harmless), then its sixteen
                 // terms relative to the new running maximum, summed as a tree, and the old sum rescaled
-                float zs[16];
+                // (in base two: the scores' maximum as fl(max acc * sc2), monotone since sc2 > 0, and each term
+                // 2^(acc * sc2 - m) with one fused multiply-add and the hardware's base-two exponential)
+                float am = acc[0];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) zs[r] = acc[r] * a.scale;
-                float m = mx[q];
-#pragma unroll
-                for (int r = 0; r < 16; r += 2) m = fmaxf(fmaxf(zs[r], zs[r + 1]), m);
+                for (int r = 1; r < 16; r += 2) am = fmaxf(fmaxf(acc[r], r + 1 < 16 ? acc[r + 1] : acc[r]), am);
+                const float m = fmaxf(mx[q], am * sc2);
                 float e[16];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    e[r] = __expf(zs[r] - m);
+                    e[r] = __builtin_amdgcn_exp2f(__fmaf_rn(acc[r], sc2, -m));
                     if (tail) e[r] = (t0 + 8 * (r >> 2) + 4 * half + (r & 3)) < tend ? e[r] : 0.0f;
                 }
 #pragma unroll
                 for (int w = 8; w >= 1; w >>= 1)
 #pragma unroll
                     for (int r = 0; r < w; ++r) e[r] += e[r + w];
-                lsv[q] = __fmaf_rn(lsv[q], __expf(mx[q] - m), e[0]);   // first step: 0 * exp(-inf) = 0
+                lsv[q] = __fmaf_rn(lsv[q], __builtin_amdgcn_exp2f(mx[q] - m), e[0]);   // first step: 0 * 2^(-inf) = 0
                 mx[q] = m;
             } else if constexpr (G == 1) {   // KEY, SAMPLE, PICK with one head: each item is a sub-tile of its own
                 float *zrow = &s_z[(mt[q] * 32 + col) * ZS + 4 * half];
 #pragma unroll
                 for (int rq = 0; rq < 4; ++rq) {
                     float4 v;
-                    v.x = (acc[4 * rq + 0] * a.scale - mx[q]) - lsv[q];
-                    v.y = (acc[4 * rq + 1] * a.scale - mx[q]) - lsv[q];
-                    v.z = (acc[4 * rq + 2] * a.scale - mx[q]) - lsv[q];
-                    v.w = (acc[4 * rq + 3] * a.scale - mx[q]) - lsv[q];
+                    v.x = __fmaf_rn(acc[4 * rq + 0], a.scale, off[q]);
+                    v.y = __fmaf_rn(acc[4 * rq + 1], a.scale, off[q]);
+                    v.z = __fmaf_rn(acc[4 * rq + 2], a.scale, off[q]);
+                    v.w = __fmaf_rn(acc[4 * rq + 3], a.scale, off[q]);
                     *reinterpret_cast<float4 *>(zrow + 8 * rq) = v;
                 }
             }
@@ -785,10 +790,10 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
                 float4 v;
-                v.x = fmaxf((acc0[4 * rq + 0] * a.scale - mx[0]) - lsv[0], (acc1[4 * rq + 0] * a.scale - mx[1]) - lsv[1]);
-                v.y = fmaxf((acc0[4 * rq + 1] * a.scale - mx[0]) - lsv[0], (acc1[4 * rq + 1] * a.scale - mx[1]) - lsv[1]);
-                v.z = fmaxf((acc0[4 * rq + 2] * a.scale - mx[0]) - lsv[0], (acc1[4 * rq + 2] * a.scale - mx[1]) - lsv[1]);
-                v.w = fmaxf((acc0[4 * rq + 3] * a.scale - mx[0]) - lsv[0], (acc1[4 * rq + 3] * a.scale - mx[1]) - lsv[1]);
+                v.x = fmaxf(__fmaf_rn(acc0[4 * rq + 0], a.scale, off[0]), __fmaf_rn(acc1[4 * rq + 0], a.scale, off[1]));
+                v.y = fmaxf(__fmaf_rn(acc0[4 * rq + 1], a.scale, off[0]), __fmaf_rn(acc1[4 * rq + 1], a.scale, off[1]));
+                v.z = fmaxf(__fmaf_rn(acc0[4 * rq + 2], a.scale, off[0]), __fmaf_rn(acc1[4 * rq + 2], a.scale, off[1]));
+                v.w = fmaxf(__fmaf_rn(acc0[4 * rq + 3], a.scale, off[0]), __fmaf_rn(acc1[4 * rq + 3], a.scale, off[1]));
                 *reinterpret_cast<float4 *>(zrow + 8 * rq) = v;
             }
         }
@@ -801,7 +806,8 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
                 // Few keys pass (a few per cent): the verdicts of all of a thread's keys first, then one
                 // shared-memory counter bump per (thread, centroid) for the whole group of four, then the stores.
                 constexpr int NP = CT * 8 / 256;
-                uint32_t okv[NP][4], msk[NP], at[NP];
+                float bv[NP][4];
+                uint32_t msk[NP], at[NP];
                 const bool inner = !tail && t0 >= a.n_init && t0 + 32 <= s - a.n_local && j0 + CT <= C;
                 if (t0 < tend) {
 #pragma unroll
@@ -817,20 +823,22 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
                             best.w = fmaxf(best.w, o.w);
                         }
                         const int t = t0 + n4;
-                        okv[it][0] = ordered_key(best.x);
-                        okv[it][1] = ordered_key(best.y);
-                        okv[it][2] = ordered_key(best.z);
-                        okv[it][3] = ordered_key(best.w);
-                        const uint32_t tau = s_tau[jl];
+                        bv[it][0] = best.x;
+                        bv[it][1] = best.y;
+                        bv[it][2] = best.z;
+                        bv[it][3] = best.w;
+                        // compared as floats: the same verdict as on the ordered images except that -0 passes a
+                        // threshold of +0, i.e. at most a candidate too many
+                        const float tau = s_tauf[jl];
                         uint32_t m = 0;
                         if (inner) {   // the whole step lies inside the block's range and outside the window, every centroid is real
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) m |= (uint32_t)(okv[it][e] >= tau) << e;
+                            for (int e = 0; e < 4; ++e) m |= (uint32_t)(bv[it][e] >= tau) << e;
                         } else {
 #pragma unroll
                             for (int e = 0; e < 4; ++e) {
                                 const bool in = (t + e) < tend && (t + e) >= a.n_init && (t + e) < s - a.n_local && (j0 + jl) < C;
-                                m |= (uint32_t)(in && okv[it][e] >= tau) << e;
+                                m |= (uint32_t)(in && bv[it][e] >= tau) << e;
                             }
                         }
                         msk[it] = m;
@@ -849,7 +857,7 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
 #pragma unroll
                             for (int e = 0; e < 4; ++e) {
                                 if ((msk[it] >> e) & 1u) {
-                                    if (w < (uint32_t)a.seg_cap) seg[w] = make_uint2(okv[it][e], (uint32_t)(t0 + n4 + e));
+                                    if (w < (uint32_t)a.seg_cap) seg[w] = make_uint2(ordered_key(bv[it][e]), (uint32_t)(t0 + n4 + e));
                                     ++w;
                                 }
                             }
@@ -944,7 +952,7 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
         const bool mine = half == 0 && (j0 + mt[q] * 32 + col) < C;
         const float m_o = __shfl_xor(mx[q], 32), l_o = __shfl_xor(lsv[q], 32);
         const float m = fmaxf(mx[q], m_o);
-        const float l = lsv[q] * __expf(mx[q] - m) + l_o * __expf(m_o - m);
+        const float l = lsv[q] * __builtin_amdgcn_exp2f(mx[q] - m) + l_o * __builtin_amdgcn_exp2f(m_o - m);
         if (mine) a.part[stat[q] * a.t_splits + blockIdx.x] = make_float2(m, l);
     }
 }

@@ -18,7 +18,10 @@ in fp32 (terms that matter have |x| < 32: another 32 * 2^-24), one addition and 
 with a hardware exponential) per step of 32 keys, a tree over a step's terms and the merges of lane halves and
 blocks: at most s / 32 + 64 operations deep, each within 2 u (u = 2^-24) relative.  log itself: 2^-22 absolute.
 
-KEY_ROUND covers the roundings of the key itself (three operations on magnitudes below 64)."""
+KEY_ROUND covers the roundings of the key itself (three operations on magnitudes below 64).  The matrix-core route
+forms a key as fma(acc, scale, -(m + log S)): the offset is rounded once at magnitude up to |c| max|k| scale, hence
+another 2^-23 |c| max|k| scale there, and as much again because the maximum is kept in base two and converted
+back, also on inputs whose dot products are exact."""
 import numpy as np
 
 ACC_TERMS = 129
@@ -45,7 +48,8 @@ def key_error_bound(Qc_group, K_kv, scale, u, running_fp32=False, exact_dots=Fal
     2^-40 fixed point (running_fp32=False) or as a running fp32 sum.  Qc_group [G][d], K_kv [s][d]."""
     c, k = _norms(Qc_group, K_kv)
     eps_z = 0.0 if exact_dots else ACC_TERMS * u * c * k * float(scale)
-    return 4 * eps_z + denominator_bound(len(K_kv), running_fp32) + KEY_ROUND
+    offset = 2.0 ** -22 * c * k * float(scale) if running_fp32 else 0.0
+    return 4 * eps_z + offset + denominator_bound(len(K_kv), running_fp32) + KEY_ROUND
 
 
 def key_band(Qc_group, K_kv, scale, exact_dots=False):
