@@ -543,6 +543,7 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
         if (const char *e = getenv("CTKVR_BUILD_CANDIDATES")) by_cand = atoi(e) != 0;
     }
     ix->build_by_cand = by_cand;
+    if (by_cand) chunk = std::min(chunk, 4 * ix->c_max);   // half the scratch (allocating it is a tenth of the build), as fast
     const bool redo_always = by_cand && getenv("CTKVR_BUILD_CANDIDATES_REDO") != nullptr;   // tests: take the redo path
     uint32_t *ksamp = nullptr, *tau = nullptr, *cursor = nullptr, *d_fail = nullptr;
     uint2 *cand = nullptr;
