@@ -641,7 +641,7 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
     constexpr int ZS = 36;
     constexpr int NPL = G >= 2 ? G / 2 : 1;    // planes
     constexpr bool KEYS = MODE != MFMA_STAT;   // the passes that form ranking keys
-    __shared__ __align__(16) float s_z[KEYS ? NPL * CT * ZS : 4];
+    __shared__ __align__(16) float s_z[KEYS ? 2 * NPL * CT * ZS : 4];   // two buffers: see keys_out
     // PICK: the tile's thresholds and how many candidates this block has found for each of its centroids.  A block
     // owns a segment of every unit's candidate list, so positions are handed out by shared-memory counters: no
     // atomic on device memory (on this part those are served beyond the XCD's cache, a round trip each).
@@ -731,6 +731,115 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
         dst[0] = x;
         dst[1] = y;
     };
+    bool have_prev = false, prev_tail = false;
+    int prev_t0 = 0, zb = 0;
+    // Second half of a key pass's step: the tile's keys leave shared memory (zsrc: the buffer the step's results
+    // were written to).  It runs one step late, after the NEXT step's matrix work, so that one barrier per step serves
+    // both the key rows' hand-over and this one (the result tiles are double-buffered).
+    auto keys_out = [&](const bool tail, int t0, const float *zsrc) __attribute__((always_inline)) {
+        // four consecutive keys of one centroid per thread: maximum over the heads, one 16-byte
+        // store where the key rows allow it (whole step in range, row length a multiple of four)
+        const bool wide = !tail && ((MODE == MFMA_SAMPLE ? a.sample_stride : a.l_stride) & 3) == 0;
+        if constexpr (MODE == MFMA_PICK) {
+            // Few keys pass (a few per cent): the verdicts of all of a thread's keys first, then one
+            // shared-memory counter bump per (thread, centroid) for the whole group of four, then the stores.
+            constexpr int NP = CT * 8 / 256;
+            float bv[NP][4];
+            uint32_t msk[NP], at[NP];
+            const bool inner = !tail && t0 >= a.n_init && t0 + 32 <= s - a.n_local && j0 + CT <= C;
+            if (t0 < tend) {
+#pragma unroll
+                for (int it = 0; it < NP; ++it) {
+                    const int p = tid + 256 * it, n4 = (p & 7) * 4, jl = p >> 3;
+                    float4 best = *reinterpret_cast<const float4 *>(&zsrc[jl * ZS + n4]);
+#pragma unroll
+                    for (int c = 1; c < NPL; ++c) {
+                        const float4 o = *reinterpret_cast<const float4 *>(&zsrc[(c * CT + jl) * ZS + n4]);
+                        best.x = fmaxf(best.x, o.x);
+                        best.y = fmaxf(best.y, o.y);
+                        best.z = fmaxf(best.z, o.z);
+                        best.w = fmaxf(best.w, o.w);
+                    }
+                    const int t = t0 + n4;
+                    bv[it][0] = best.x;
+                    bv[it][1] = best.y;
+                    bv[it][2] = best.z;
+                    bv[it][3] = best.w;
+                    // compared as floats: the same verdict as on the ordered images except that -0 passes a
+                    // threshold of +0, i.e. at most a candidate too many
+                    const float tau = s_tauf[jl];
+                    uint32_t m = 0;
+                    if (inner) {   // the whole step lies inside the block's range and outside the window, every centroid is real
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) m |= (uint32_t)(bv[it][e] >= tau) << e;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const bool in = (t + e) < tend && (t + e) >= a.n_init && (t + e) < s - a.n_local && (j0 + jl) < C;
+                            m |= (uint32_t)(in && bv[it][e] >= tau) << e;
+                        }
+                    }
+                    msk[it] = m;
+                }
+#pragma unroll
+                for (int it = 0; it < NP; ++it) {
+                    at[it] = 0u;
+                    if (msk[it]) at[it] = atomicAdd(&s_cnt[(tid + 256 * it) >> 3], (uint32_t)__popc(msk[it]));
+                }
+#pragma unroll
+                for (int it = 0; it < NP; ++it) {
+                    if (msk[it]) {
+                        const int p = tid + 256 * it, n4 = (p & 7) * 4, jl = p >> 3;
+                        uint2 *seg = a.cand + (((size_t)bkl * a.c_max + j0 + jl) * a.t_splits + blockIdx.x) * a.seg_cap;
+                        uint32_t w = at[it];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            if ((msk[it] >> e) & 1u) {
+                                if (w < (uint32_t)a.seg_cap) seg[w] = make_uint2(ordered_key(bv[it][e]), (uint32_t)(t0 + n4 + e));
+                                ++w;
+                            }
+                        }
+                    }
+                }
+            }
+        } else if (t0 < tend) {
+            for (int p = tid; p < CT * 8; p += 256) {
+                const int n4 = (p & 7) * 4, jl = p >> 3;
+                if ((j0 + jl) >= C) continue;
+                float4 best = *reinterpret_cast<const float4 *>(&zsrc[jl * ZS + n4]);
+#pragma unroll
+                for (int c = 1; c < NPL; ++c) {
+                    const float4 o = *reinterpret_cast<const float4 *>(&zsrc[(c * CT + jl) * ZS + n4]);
+                    best.x = fmaxf(best.x, o.x);
+                    best.y = fmaxf(best.y, o.y);
+                    best.z = fmaxf(best.z, o.z);
+                    best.w = fmaxf(best.w, o.w);
+                }
+                const int t = t0 + n4;
+                uint32_t ok[4] = {ordered_key(best.x), ordered_key(best.y), ordered_key(best.z), ordered_key(best.w)};
+                bool win[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    win[e] = (t + e) < a.n_init || (t + e) >= s - a.n_local;
+                    if (win[e]) ok[e] = 0x007fffffu;   // the image of -inf
+                }
+                const size_t unit = (size_t)bkl * a.c_max + j0 + jl;
+                {
+                    uint32_t *dst = MODE == MFMA_SAMPLE ? a.kbuf + unit * a.sample_stride + (t0 / ST) * 32 + n4
+                                                        : a.kbuf + unit * a.l_stride + t;
+                    if (wide) {
+                        // written once, read much later by other kernels: kept out of the caches that hold the keys
+                        u32x4_t v4 = {ok[0], ok[1], ok[2], ok[3]};
+                        __builtin_nontemporal_store(v4, reinterpret_cast<u32x4_t *>(dst));
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if ((t + e) < tend) dst[e] = ok[e];
+                    }
+                }
+            }
+        }
+        };
     // tail: a step whose keys may reach beyond the block's range (a literal at every call).  Such
     // keys are real keys of the sequence, repeated: harmless for a maximum, left out of a sum,
     // not written as ranking keys.
@@ -773,7 +882,7 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
                 lsv[q] = __fmaf_rn(lsv[q], __builtin_amdgcn_exp2f(mx[q] - m), e[0]);   // first step: 0 * 2^(-inf) = 0
                 mx[q] = m;
             } else if constexpr (G == 1) {   // KEY, SAMPLE, PICK with one head: each item is a sub-tile of its own
-                float *zrow = &s_z[(mt[q] * 32 + col) * ZS + 4 * half];
+                float *zrow = &s_z[zb * (NPL * CT * ZS) + (mt[q] * 32 + col) * ZS + 4 * half];
 #pragma unroll
                 for (int rq = 0; rq < 4; ++rq) {
                     float4 v;
@@ -786,7 +895,7 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
             }
         }
         if constexpr (KEYS && G >= 2) {   // the wave's two heads of the same centroids: their maximum, one plane
-            float *zrow = &s_z[((hh[0] >> 1) * CT + mt[0] * 32 + col) * ZS + 4 * half];
+            float *zrow = &s_z[zb * (NPL * CT * ZS) + ((hh[0] >> 1) * CT + mt[0] * 32 + col) * ZS + 4 * half];
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
                 float4 v;
@@ -798,109 +907,11 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
             }
         }
         if constexpr (KEYS) {
-            __syncthreads();
-            // four consecutive keys of one centroid per thread: maximum over the heads, one 16-byte
-            // store where the key rows allow it (whole step in range, row length a multiple of four)
-            const bool wide = !tail && ((MODE == MFMA_SAMPLE ? a.sample_stride : a.l_stride) & 3) == 0;
-            if constexpr (MODE == MFMA_PICK) {
-                // Few keys pass (a few per cent): the verdicts of all of a thread's keys first, then one
-                // shared-memory counter bump per (thread, centroid) for the whole group of four, then the stores.
-                constexpr int NP = CT * 8 / 256;
-                float bv[NP][4];
-                uint32_t msk[NP], at[NP];
-                const bool inner = !tail && t0 >= a.n_init && t0 + 32 <= s - a.n_local && j0 + CT <= C;
-                if (t0 < tend) {
-#pragma unroll
-                    for (int it = 0; it < NP; ++it) {
-                        const int p = tid + 256 * it, n4 = (p & 7) * 4, jl = p >> 3;
-                        float4 best = *reinterpret_cast<const float4 *>(&s_z[jl * ZS + n4]);
-#pragma unroll
-                        for (int c = 1; c < NPL; ++c) {
-                            const float4 o = *reinterpret_cast<const float4 *>(&s_z[(c * CT + jl) * ZS + n4]);
-                            best.x = fmaxf(best.x, o.x);
-                            best.y = fmaxf(best.y, o.y);
-                            best.z = fmaxf(best.z, o.z);
-                            best.w = fmaxf(best.w, o.w);
-                        }
-                        const int t = t0 + n4;
-                        bv[it][0] = best.x;
-                        bv[it][1] = best.y;
-                        bv[it][2] = best.z;
-                        bv[it][3] = best.w;
-                        // compared as floats: the same verdict as on the ordered images except that -0 passes a
-                        // threshold of +0, i.e. at most a candidate too many
-                        const float tau = s_tauf[jl];
-                        uint32_t m = 0;
-                        if (inner) {   // the whole step lies inside the block's range and outside the window, every centroid is real
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) m |= (uint32_t)(bv[it][e] >= tau) << e;
-                        } else {
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const bool in = (t + e) < tend && (t + e) >= a.n_init && (t + e) < s - a.n_local && (j0 + jl) < C;
-                                m |= (uint32_t)(in && bv[it][e] >= tau) << e;
-                            }
-                        }
-                        msk[it] = m;
-                    }
-#pragma unroll
-                    for (int it = 0; it < NP; ++it) {
-                        at[it] = 0u;
-                        if (msk[it]) at[it] = atomicAdd(&s_cnt[(tid + 256 * it) >> 3], (uint32_t)__popc(msk[it]));
-                    }
-#pragma unroll
-                    for (int it = 0; it < NP; ++it) {
-                        if (msk[it]) {
-                            const int p = tid + 256 * it, n4 = (p & 7) * 4, jl = p >> 3;
-                            uint2 *seg = a.cand + (((size_t)bkl * a.c_max + j0 + jl) * a.t_splits + blockIdx.x) * a.seg_cap;
-                            uint32_t w = at[it];
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                if ((msk[it] >> e) & 1u) {
-                                    if (w < (uint32_t)a.seg_cap) seg[w] = make_uint2(ordered_key(bv[it][e]), (uint32_t)(t0 + n4 + e));
-                                    ++w;
-                                }
-                            }
-                        }
-                    }
-                }
-            } else if (t0 < tend) {
-                for (int p = tid; p < CT * 8; p += 256) {
-                    const int n4 = (p & 7) * 4, jl = p >> 3;
-                    if ((j0 + jl) >= C) continue;
-                    float4 best = *reinterpret_cast<const float4 *>(&s_z[jl * ZS + n4]);
-#pragma unroll
-                    for (int c = 1; c < NPL; ++c) {
-                        const float4 o = *reinterpret_cast<const float4 *>(&s_z[(c * CT + jl) * ZS + n4]);
-                        best.x = fmaxf(best.x, o.x);
-                        best.y = fmaxf(best.y, o.y);
-                        best.z = fmaxf(best.z, o.z);
-                        best.w = fmaxf(best.w, o.w);
-                    }
-                    const int t = t0 + n4;
-                    uint32_t ok[4] = {ordered_key(best.x), ordered_key(best.y), ordered_key(best.z), ordered_key(best.w)};
-                    bool win[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        win[e] = (t + e) < a.n_init || (t + e) >= s - a.n_local;
-                        if (win[e]) ok[e] = 0x007fffffu;   // the image of -inf
-                    }
-                    const size_t unit = (size_t)bkl * a.c_max + j0 + jl;
-                    {
-                        uint32_t *dst = MODE == MFMA_SAMPLE ? a.kbuf + unit * a.sample_stride + (t0 / ST) * 32 + n4
-                                                            : a.kbuf + unit * a.l_stride + t;
-                        if (wide) {
-                            // written once, read much later by other kernels: kept out of the caches that hold the keys
-                            u32x4_t v4 = {ok[0], ok[1], ok[2], ok[3]};
-                            __builtin_nontemporal_store(v4, reinterpret_cast<u32x4_t *>(dst));
-                        } else {
-#pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                if ((t + e) < tend) dst[e] = ok[e];
-                        }
-                    }
-                }
-            }
+            if (have_prev) keys_out(prev_tail, prev_t0, s_z + (zb ^ 1) * (NPL * CT * ZS));
+            have_prev = true;
+            prev_tail = tail;
+            prev_t0 = t0;
+            zb ^= 1;
         }
     };
     // A step's rows are requested four steps ahead (four register sets).
@@ -941,7 +952,11 @@ template <int G, int MODE> __global__ __launch_bounds__(256, 2) void mfma_score_
         for (; t0 + 3 * ST + 32 <= tend; t0 += 4 * ST) trip(false, t0);
         if (t0 < tend) trip(true, t0);
     }
+    if constexpr (KEYS) {   // the last step's keys (the last trip ended with a barrier)
+        if (have_prev) keys_out(prev_tail, prev_t0, s_z + (zb ^ 1) * (NPL * CT * ZS));
+    }
     if constexpr (MODE == MFMA_PICK) {
+        __syncthreads();
         if (tid < CT && j0 + tid < C) a.seg_cnt[((size_t)bkl * a.c_max + j0 + tid) * a.t_splits + blockIdx.x] = s_cnt[tid];
     }
     if constexpr (KEYS) return;
