@@ -246,9 +246,11 @@ int ctkvr_profile_collect(ctkvr_index *idx, float *ms_host, int32_t capacity_ste
 /* CTKVR_BUILD_MFMA ranks either all s keys of a (KV head, centroid) unit (their 4-byte ranking keys
  * written once, read for a histogram and read again for the selection) or only the keys at or above
  * a per-unit threshold taken from a 1-in-16 sample of the positions (a few thousand candidates per
- * unit; taken when every sequence is at least 32 rho long, rho is 256..2048 and the context at most
- * 2^18).  The second route yields exactly the same lists: a chunk of units in which a unit ends
- * with fewer than rho candidates, or more than fit, is redone by the first route.
+ * unit; taken when every sequence is at least 32 rho long, rho is 256..2730 and the selection's
+ * shared memory holds a bitmap of the context, i.e. up to about 2^19 tokens).  The second route
+ * yields exactly the same lists: a chunk of units in which a unit ends with fewer than rho
+ * candidates, more than fit, or hundreds of candidates exactly equal to its rho-th key, is redone
+ * by the first route.
  * by_candidates_host: 1 if the index was built by the candidate route; chunks_redone_host: how many
  * chunks it handed back.  Both HOST, either may be NULL.  The environment variable
  * CTKVR_BUILD_CANDIDATES = 0 | 1, read at build time, forces the choice where the geometry allows it. */

@@ -534,12 +534,12 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
     const int rho = ix->p.list_len;
     const int step_stride = std::max(16, ((ix->s_max + 31) / 32 + 255) / 256);
     const int sample_stride = ((ix->s_max + 32 * step_stride - 1) / (32 * step_stride)) * 32;
-    const int cand_cap = std::min(kCandCap, 4 * rho);
-    const size_t cand_lds = ((size_t)2112 + 2 * (size_t)cand_cap + 4 * (size_t)((ix->s_max + 63) / 64)) * 4;
+    const int cand_cap = std::min(kCandCap, std::max(3 * rho, 2 * rho + 1024));   // about 2 rho + 256 are expected (+-6 % at rho = 2048)
+    const size_t cand_lds = ((size_t)2112 + 2 * (size_t)cand_cap + kCandTies + (size_t)((ix->s_max + 31) / 32)) * 4;
     bool by_cand = false;
     if (mfma && cand_lds <= 150 * 1024 && sample_stride <= kSampleCap && cand_cap >= rho) {
         const int s_min = *std::min_element(ix->ctx_lens.begin(), ix->ctx_lens.end());
-        by_cand = rho >= 256 && 4 * rho <= kCandCap && (long long)s_min >= 32ll * rho;
+        by_cand = rho >= 256 && 3 * rho <= kCandCap && (long long)s_min >= 32ll * rho;
         if (const char *e = getenv("CTKVR_BUILD_CANDIDATES")) by_cand = atoi(e) != 0;
     }
     ix->build_by_cand = by_cand;

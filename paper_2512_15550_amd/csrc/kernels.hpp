@@ -1579,8 +1579,9 @@ template <int G> __global__ __launch_bounds__(1024) void rerank_select_kernel(Se
 // blocks of the PICK pass filled, ties to the lowest id, written to the unit's list in ascending id order.
 // A unit with fewer than rho candidates, more than cand_cap, or a segment that ran over, raises *fail instead
 // (the caller then redoes the chunk by the route that keeps every key).
-// Both: grid = chunk units, 1024 threads.  cand_select: dynamic shared memory 2112 + 2 cand_cap +
-// 4 ceil(s_max / 64) words; cand_cap <= kCandCap.
+// Both: grid = chunk units, 1024 threads.  cand_select: dynamic shared memory 2112 + 2 cand_cap + kCandTies +
+// ceil(s_max / 32) words (one bitmap over the ids; the candidates that tie with the rho-th key, normally one, are
+// sorted out in a short list: more than kCandTies of them also raise *fail); cand_cap <= kCandCap.
 // ------------------------------------------------------------------------------
 constexpr int kCandCap = 8192;
 constexpr int kSampleCap = 8192;   // sampled keys per unit at most
@@ -1642,6 +1643,8 @@ __global__ __launch_bounds__(1024) void sample_threshold_kernel(CandArgs a)
     if (tid == 0) a.tau[ul] = T;
 }
 
+constexpr int kCandTies = 256;   // candidates equal to the rho-th key that cand_select_kernel sorts out itself
+
 __global__ __launch_bounds__(1024) void cand_select_kernel(CandArgs a)
 {
     extern __shared__ __align__(16) uint32_t smem[];
@@ -1663,9 +1666,10 @@ __global__ __launch_bounds__(1024) void cand_select_kernel(CandArgs a)
     }
     uint32_t *s_hist = smem;                                   // 2048 + 64
     uint2 *l_ent = reinterpret_cast<uint2 *>(smem + 2112);     // cand_cap entries
-    const int nw32 = 2 * ((s + 63) >> 6);
-    uint32_t *s_gt = smem + 2112 + 2 * a.cand_cap;             // two bitmaps over the ids
-    uint32_t *s_eq = s_gt + nw32;
+    uint32_t *s_ties = smem + 2112 + 2 * a.cand_cap;           // ids of the candidates equal to the rho-th key
+    uint32_t *s_bm = s_ties + kCandTies;                       // one bitmap over the ids
+    const int nw = (s + 31) >> 5;
+    uint32_t *s_x = s_hist + 2048 + 56;                        // [1]: tie cursor (free once the threshold is known)
     {
         uint32_t at = 0;
         for (int x = 0; x < a.t_splits; ++x) {
@@ -1675,10 +1679,53 @@ __global__ __launch_bounds__(1024) void cand_select_kernel(CandArgs a)
             at += c;
         }
     }
-    for (int w = tid; w < 2 * nw32; w += 1024) s_gt[w] = 0u;
+    for (int w = tid; w < nw; w += 1024) s_bm[w] = 0u;
     __syncthreads();
+    // T = the rho-th largest key, need_eq = how many of the candidates equal to T belong to the rho largest
+    uint32_t T, need_eq;
+    block_list_threshold<1024, kCandCap>(n, (uint32_t)a.rho, s_hist, l_ent, T, need_eq);
+    __syncthreads();
+    if (tid == 0) s_x[1] = 0u;
+    __syncthreads();
+    for (uint32_t e = tid; e < n; e += 1024) {
+        const uint2 en = l_ent[e];
+        if (en.x > T) atomicOr(&s_bm[en.y >> 5], 1u << (en.y & 31u));
+        if (en.x == T) {
+            const uint32_t at = atomicAdd(&s_x[1], 1u);
+            if (at < (uint32_t)kCandTies) s_ties[at] = en.y;
+        }
+    }
+    __syncthreads();
+    const uint32_t n_eq = s_x[1];
+    if (n_eq > (uint32_t)kCandTies) {   // uniform: more exact ties at the threshold than are sorted out here
+        if (tid == 0) atomicOr(a.fail, 1u);
+        return;
+    }
+    // the need_eq lowest ids among the ties join the bitmap
+    if ((uint32_t)tid < n_eq) {
+        const uint32_t mine = s_ties[tid];
+        uint32_t lower = 0;
+        for (uint32_t e = 0; e < n_eq; ++e) lower += s_ties[e] < mine;
+        if (lower < need_eq) atomicOr(&s_bm[mine >> 5], 1u << (mine & 31u));
+    }
+    __syncthreads();
+    // thread t owns words [t wpt, (t + 1) wpt) of the bitmap: count, scan, emit in ascending id order
+    uint32_t *s_scan = s_hist + 2048 + 4;
+    const int wpt = (nw + 1023) / 1024;
+    const int w0 = min(nw, tid * wpt), w1 = min(nw, w0 + wpt);
+    uint32_t cnt = 0;
+    for (int w = w0; w < w1; ++w) cnt += (uint32_t)__popc(s_bm[w]);
+    uint32_t tot;
+    uint32_t pos = block_excl_scan<1024>(cnt, s_scan, &tot);
     int32_t *lst = a.lists + (size_t)(a.u.unit0 + ul) * a.rho;
-    block_resolve_emit<1024, kCandCap>(n, (uint32_t)a.rho, s, s_hist, s_gt, s_eq, l_ent, [&](int pos, int i) { lst[pos] = i; });
+    for (int w = w0; w < w1; ++w) {
+        uint32_t m = s_bm[w];
+        while (m) {
+            const int bpos = __ffs((int)m) - 1;
+            m &= m - 1u;
+            lst[pos++] = w * 32 + bpos;
+        }
+    }
 }
 
 // ------------------------------------------------------------------------------

@@ -398,7 +398,7 @@ def test_mfma_build_matches_oracle_up_to_ties(ck, case):
 
 @pytest.mark.parametrize("name,h,g,s,rho,expect_redo", [
     ("cand_ok", 8, 2, 6000, 400, False),         # about 2 rho + 256 = 1056 candidates per unit: within [rho, 4 rho]
-    ("cand_overflow", 8, 2, 2500, 40, True),     # about 2 rho + 256 candidates against room for 4 rho = 160: handed back, same lists
+    ("cand_all_equal", 8, 2, 2500, 40, True),    # every key the same vector: all s keys tie with the threshold and cannot all be candidates: handed back, same lists
     ("cand_g1", 2, 2, 6100, 400, False),         # one head per group: a wave's two work items are two sub-tiles
     ("cand_g2", 4, 2, 5900, 400, False),
     ("cand_g8", 8, 1, 6200, 400, False),         # four head pairs meet in shared memory
@@ -409,6 +409,10 @@ def test_mfma_build_from_candidates_gives_the_lists_of_the_route_that_ranks_ever
     same matrix-core keys; and within the derived band of the oracle's."""
     wl = small_workload(name, "bf16", h, g, (s, s - 777), (620, 621), 40, 0, 4, rho, 60, 1)
     bt = gen_batch(wl)
+    if name == "cand_all_equal":
+        for sq in bt.seqs:
+            sq.K[:] = sq.K[:, :1]
+        bt = Batch(wl=wl, seqs=bt.seqs, paged=paginate(bt.seqs, wl.page_size, 11))
     db = H.device_batch(bt)
     lists = {}
     for forced in ("0", "1", "redo"):
