@@ -242,6 +242,19 @@ int ctkvr_profile_enable(ctkvr_index *idx, int32_t max_steps);
  * their number in *n_steps and restarts recording at step 0. */
 int ctkvr_profile_collect(ctkvr_index *idx, float *ms_host, int32_t capacity_steps, int32_t *n_steps);
 
+/* ---- environment variables ------------------------------------------------------------- */
+/* Read when an index is created (ctkvr_build_index, ctkvr_index_load); none changes a result, all
+ * exist so that each form of a launch can be measured and tested against the other:
+ *   CTKVR_DECODE_PATH        = staged | fused | auto   default of ctkvr_index_set_decode_path
+ *   CTKVR_DECODE_GROUPS      = n   sequences stepped as n forked groups (default 1)
+ *   CTKVR_SCORE_BY_RANK      = 0|1 recalled ids split over a unit's blocks by id range / by rank
+ *                                  (default: by rank for small batches)
+ *   CTKVR_KEYCLASS           = 0|1 ranking-key histogram and classification as two launches / one
+ *                                  (default: one for small batches)
+ *   CTKVR_FUSED_THREADS      = 256|1024  block size of the single-launch step
+ *   CTKVR_BUILD_CANDIDATES   = 0|1 see ctkvr_index_build_route
+ *   CTKVR_BUILD_CANDIDATES_REDO    (set: the candidate route also hands every chunk back; tests) */
+
 /* ---- how the matrix-core list build chose a unit's top-rho (Algorithm 1 line 4) ---------- */
 /* CTKVR_BUILD_MFMA ranks either all s keys of a (KV head, centroid) unit (their 4-byte ranking keys
  * written once, read for a histogram and read again for the selection) or only the keys at or above
