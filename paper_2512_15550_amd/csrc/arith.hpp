@@ -22,11 +22,11 @@ __device__ long long g_trace[128];
     do {                                                                         \
         if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) g_trace[slot] = wall_clock64(); \
     } while (0)
-__device__ long long g_blk[8][1024];
+__device__ long long g_blk[8][2048];
 #define CTKVR_STAMP_BLK(slot)                                                    \
     do {                                                                         \
         int bi_ = blockIdx.x + blockIdx.y * gridDim.x;                           \
-        if (threadIdx.x == 0 && bi_ < 1024) g_blk[slot][bi_] = wall_clock64();   \
+        if (threadIdx.x == 0 && bi_ < 2048) g_blk[slot][bi_] = wall_clock64();   \
     } while (0)
 #else
 #define CTKVR_STAMP(slot) do { } while (0)

@@ -1686,7 +1686,7 @@ int ctkvr_debug_trace_read(long long *dst_host)
 int ctkvr_debug_blk_read(long long *dst_host)
 {
     HIP_TRY(hipDeviceSynchronize());
-    HIP_TRY(hipMemcpyFromSymbol(dst_host, HIP_SYMBOL(ctkvr::g_blk), sizeof(long long) * 8 * 1024));
+    HIP_TRY(hipMemcpyFromSymbol(dst_host, HIP_SYMBOL(ctkvr::g_blk), sizeof(long long) * 8 * 2048));
     return CTKVR_OK;
 }
 #endif

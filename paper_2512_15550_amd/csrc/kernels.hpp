@@ -407,12 +407,26 @@ template <typename T, int G> __global__ __launch_bounds__(256) void recall_score
         // unit's words start on a 16-byte boundary (words from W up to the row's end are zero)
         const int wpt = ((((W + 255) >> 8) + 3) >> 2) << 2;
         const int w0 = tid * wpt;
+        const bool wide = ((reinterpret_cast<uintptr_t>(gb) | ((uintptr_t)a.bitmap_words << 2)) & 15u) == 0;
+        // up to 16 words per thread (contexts up to 128K) stay in registers, so that the two threads that
+        // name the block's edge words below need no further load
+        const bool in_regs = wide && wpt <= 16;
+        uint4 v[4] = {};
         uint32_t cnt = 0;
-        if (((reinterpret_cast<uintptr_t>(gb) | ((uintptr_t)a.bitmap_words << 2)) & 15u) == 0) {
+        if (in_regs) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int w = w0 + 4 * i;
+                const uint4 x = *reinterpret_cast<const uint4 *>(gb + min(w, a.bitmap_words - 4));
+                if (i * 4 < wpt && w < a.bitmap_words) v[i] = x;
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) cnt += (uint32_t)(__popc(v[i].x) + __popc(v[i].y) + __popc(v[i].z) + __popc(v[i].w));
+        } else if (wide) {
 #pragma unroll 4
             for (int w = w0; w < min(w0 + wpt, a.bitmap_words); w += 4) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(gb + w);
-                cnt += (uint32_t)(__popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w));
+                const uint4 x = *reinterpret_cast<const uint4 *>(gb + w);
+                cnt += (uint32_t)(__popc(x.x) + __popc(x.y) + __popc(x.z) + __popc(x.w));
             }
         } else {
 #pragma unroll 4
@@ -428,26 +442,56 @@ template <typename T, int G> __global__ __launch_bounds__(256) void recall_score
         r0 = blockIdx.x * qn;
         if (r0 >= L) return;
         r1 = min(L, r0 + qn);
-        // the threads whose stretches hold ranks r0 and r1 - 1 walk their words (cached) to the one that holds it
-        if (cnt && pre <= r0 && r0 < pre + cnt) {
-            uint32_t p = pre;
-            for (int w = w0; w < w0 + wpt; ++w) {
-                const uint32_t c = (uint32_t)__popc(gb[w]);
-                if (r0 < p + c) {
-                    s_edge[0] = (uint32_t)w;
-                    s_edge[1] = p;
-                    break;
+        // the threads whose stretches hold ranks r0 and r1 - 1 walk their words to the one that holds it
+        const bool own_first = cnt && pre <= r0 && r0 < pre + cnt;
+        const bool own_last = cnt && pre < r1 && r1 <= pre + cnt;
+        if (in_regs) {
+            if (own_first || own_last) {
+                const uint32_t wd[16] = {v[0].x, v[0].y, v[0].z, v[0].w, v[1].x, v[1].y, v[1].z, v[1].w,
+                                         v[2].x, v[2].y, v[2].z, v[2].w, v[3].x, v[3].y, v[3].z, v[3].w};
+                uint32_t p = pre, e0 = 0, e1 = 0, e2 = 0;
+                bool f0 = !own_first, f2 = !own_last;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const uint32_t c = (uint32_t)__popc(wd[i]);
+                    if (!f0 && r0 < p + c) {
+                        e0 = (uint32_t)(w0 + i);
+                        e1 = p;
+                        f0 = true;
+                    }
+                    p += c;
+                    if (!f2 && r1 <= p) {
+                        e2 = (uint32_t)(w0 + i);
+                        f2 = true;
+                    }
                 }
-                p += c;
+                if (own_first) {
+                    s_edge[0] = e0;
+                    s_edge[1] = e1;
+                }
+                if (own_last) s_edge[2] = e2;
             }
-        }
-        if (cnt && pre < r1 && r1 <= pre + cnt) {
-            uint32_t p = pre;
-            for (int w = w0; w < w0 + wpt; ++w) {
-                p += (uint32_t)__popc(gb[w]);
-                if (r1 <= p) {
-                    s_edge[2] = (uint32_t)w;
-                    break;
+        } else {
+            if (own_first) {
+                uint32_t p = pre;
+                for (int w = w0; w < w0 + wpt; ++w) {
+                    const uint32_t c = (uint32_t)__popc(gb[w]);
+                    if (r0 < p + c) {
+                        s_edge[0] = (uint32_t)w;
+                        s_edge[1] = p;
+                        break;
+                    }
+                    p += c;
+                }
+            }
+            if (own_last) {
+                uint32_t p = pre;
+                for (int w = w0; w < w0 + wpt; ++w) {
+                    p += (uint32_t)__popc(gb[w]);
+                    if (r1 <= p) {
+                        s_edge[2] = (uint32_t)w;
+                        break;
+                    }
                 }
             }
         }
