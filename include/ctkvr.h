@@ -253,7 +253,8 @@ int ctkvr_profile_collect(ctkvr_index *idx, float *ms_host, int32_t capacity_ste
  *                                  (default: one for small batches)
  *   CTKVR_FUSED_THREADS      = 256|1024  block size of the single-launch step
  *   CTKVR_BUILD_CANDIDATES   = 0|1 see ctkvr_index_build_route
- *   CTKVR_BUILD_CANDIDATES_REDO    (set: the candidate route also hands every chunk back; tests) */
+ *   CTKVR_BUILD_CANDIDATES_REDO    (set: the candidate route also hands every chunk back; tests)
+ *   CTKVR_BUILD_SCRATCH_CACHE = 0|1 see ctkvr_release_scratch (read at every build) */
 
 /* ---- how the matrix-core list build chose a unit's top-rho (Algorithm 1 line 4) ---------- */
 /* CTKVR_BUILD_MFMA ranks either all s keys of a (KV head, centroid) unit (their 4-byte ranking keys
@@ -268,6 +269,15 @@ int ctkvr_profile_collect(ctkvr_index *idx, float *ms_host, int32_t capacity_ste
  * chunks it handed back.  Both HOST, either may be NULL.  The environment variable
  * CTKVR_BUILD_CANDIDATES = 0 | 1, read at build time, forces the choice where the geometry allows it. */
 int ctkvr_index_build_route(const ctkvr_index *idx, int32_t *by_candidates_host, int32_t *chunks_redone_host);
+
+/* ---- scratch kept between index builds (Algorithm 1 runs once per prompt) ----------------- */
+/* The candidate route of CTKVR_BUILD_MFMA keeps its device scratch (about 1.1 GB for a 128K context,
+ * 32/8 heads, C = rho = 2048; never more than 2 GiB -- a build that needs more, or that finds the
+ * scratch in use by a build on another host thread, allocates and frees its own) in one allocation per
+ * device until this call, so that the next build neither allocates nor frees (0.75 ms of an 8 ms build).
+ * Frees the current device's scratch; an error if a build is using it.  The environment variable
+ * CTKVR_BUILD_SCRATCH_CACHE = 0, read at build time, switches the keeping off. */
+int ctkvr_release_scratch(void);
 
 /* ---- how a decode step is launched ----------------------------------------- */
 /* Algorithm 2 lines 1-9 run either as a sequence of launches (one per stage; any geometry) or as

@@ -12,4 +12,4 @@ from .binding import (CtkvrError, Index, Params, ctkvr_build_index, ctkvr_decode
                       BUILD_EXACT, BUILD_MFMA, ctkvr_profile_enable, ctkvr_profile_collect, ctkvr_selftest_exp, STAGE_NAMES,
                       ctkvr_centroid_update, ctkvr_decode_step_window, ctkvr_decode_step_static,
                       ctkvr_index_set_decode_path, ctkvr_index_decode_path, ctkvr_index_check, ctkvr_index_build_route, ctkvr_profile_phases,
-                      ctkvr_measure_dispatch_floor, PATH_AUTO, PATH_STAGED, PATH_FUSED)
+                      ctkvr_measure_dispatch_floor, ctkvr_release_scratch, PATH_AUTO, PATH_STAGED, PATH_FUSED)

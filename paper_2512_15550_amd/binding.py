@@ -77,7 +77,7 @@ EXPORTS = ["ctkvr_build_index", "ctkvr_index_load", "ctkvr_decode_step", "ctkvr_
            "ctkvr_index_info", "ctkvr_index_lists", "ctkvr_index_centroids", "ctkvr_index_last_candidates",
            "ctkvr_profile_enable", "ctkvr_profile_collect", "ctkvr_centroid_update", "ctkvr_decode_step_window",
            "ctkvr_selftest_exp", "ctkvr_decode_step_static", "ctkvr_index_set_decode_path", "ctkvr_index_decode_path",
-           "ctkvr_index_check", "ctkvr_profile_phases", "ctkvr_measure_dispatch_floor", "ctkvr_index_build_route"]
+           "ctkvr_index_check", "ctkvr_profile_phases", "ctkvr_measure_dispatch_floor", "ctkvr_index_build_route", "ctkvr_release_scratch"]
 PATH_AUTO, PATH_STAGED, PATH_FUSED = 0, 1, 2
 N_STAGES = 9
 STAGE_NAMES = ["centroid_cos", "recall_gather", "score", "denom", "keyhist", "classify",
@@ -129,6 +129,8 @@ def load_library() -> ctypes.CDLL:
     L.ctkvr_index_decode_path.argtypes = [vp]
     L.ctkvr_index_check.restype = ctypes.c_int
     L.ctkvr_index_check.argtypes = [vp]
+    L.ctkvr_release_scratch.restype = ctypes.c_int
+    L.ctkvr_release_scratch.argtypes = []
     L.ctkvr_index_build_route.restype = ctypes.c_int
     L.ctkvr_index_build_route.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
     L.ctkvr_profile_phases.restype = ctypes.c_int
@@ -337,6 +339,11 @@ def ctkvr_index_build_route(idx: Index):
     a, b = ctypes.c_int32(0), ctypes.c_int32(0)
     _check(load_library().ctkvr_index_build_route(idx.handle, ctypes.byref(a), ctypes.byref(b)))
     return bool(a.value), int(b.value)
+
+
+def ctkvr_release_scratch() -> None:
+    """Frees the device scratch the matrix-core list build keeps between builds (current device)."""
+    _check(load_library().ctkvr_release_scratch())
 
 
 def ctkvr_index_check(idx: Index) -> None:

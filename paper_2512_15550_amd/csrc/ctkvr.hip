@@ -76,6 +76,69 @@ int static_scratch(unsigned char **out)
     *out = g_scratch_ptr[dev];
     return CTKVR_OK;
 }
+
+// Scratch of the matrix-core list build's candidate route, kept between builds (an index is built per prompt, and
+// freeing a gigabyte costs 0.6 ms of an 8 ms build): one allocation per device, grown when a build needs more, at most
+// kBuildCacheMax bytes; a build that finds it taken (another host thread is building) or needs more than that allocates
+// its own.  ctkvr_release_scratch() frees it; CTKVR_BUILD_SCRATCH_CACHE=0 switches the cache off.
+constexpr size_t kBuildCacheMax = (size_t)2 << 30;
+struct BuildCache {
+    void *base = nullptr;
+    size_t bytes = 0;
+    bool busy = false;
+};
+std::mutex g_build_mu;
+BuildCache g_build_cache[kMaxDevices];
+
+// *cached tells build_scratch_put what to do with the pointer afterwards
+int build_scratch_get(size_t bytes, void **out, bool *cached)
+{
+    *out = nullptr;
+    *cached = false;
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    const char *env = getenv("CTKVR_BUILD_SCRATCH_CACHE");
+    const bool use = dev >= 0 && dev < kMaxDevices && bytes <= kBuildCacheMax && !(env && atoi(env) == 0);
+    if (use) {
+        std::lock_guard<std::mutex> lock(g_build_mu);
+        BuildCache &c = g_build_cache[dev];
+        if (!c.busy) {
+            if (c.bytes < bytes) {   // (no build is using it: every build ends with a synchronisation of its stream)
+                if (c.base) (void)hipFree(c.base);
+                c.base = nullptr;
+                c.bytes = 0;
+                hipError_t e = hipMalloc(&c.base, bytes);
+                if (e != hipSuccess) {
+                    c.base = nullptr;
+                    return fail(e == hipErrorOutOfMemory ? CTKVR_ENOMEM : CTKVR_EHIP, "hipMalloc(%zu): %s", bytes, hipGetErrorString(e));
+                }
+                c.bytes = bytes;
+            }
+            c.busy = true;
+            *out = c.base;
+            *cached = true;
+            return CTKVR_OK;
+        }
+    }
+    hipError_t e = hipMalloc(out, bytes ? bytes : 16);
+    if (e != hipSuccess) {
+        *out = nullptr;
+        return fail(e == hipErrorOutOfMemory ? CTKVR_ENOMEM : CTKVR_EHIP, "hipMalloc(%zu): %s", bytes, hipGetErrorString(e));
+    }
+    return CTKVR_OK;
+}
+
+void build_scratch_put(void *ptr, bool cached)
+{
+    if (!ptr) return;
+    if (!cached) {
+        (void)hipFree(ptr);
+        return;
+    }
+    std::lock_guard<std::mutex> lock(g_build_mu);
+    for (BuildCache &c : g_build_cache)
+        if (c.base == ptr) c.busy = false;
+}
 }  // namespace
 
 // Buffers of one decode step for every (sequence, KV head) unit: everything ctkvr_decode_step
@@ -519,14 +582,9 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
     float *z = nullptr;
     uint32_t *m_key = nullptr;
     unsigned long long *S = nullptr;
-    if (!mfma) HIP_TRY(hipMalloc((void **)&z, (size_t)chunk * per_unit));
-    hipError_t e1 = hipMalloc((void **)&m_key, (size_t)chunk * G * 4);
-    hipError_t e2 = hipMalloc((void **)&S, (size_t)chunk * G * 8);
     uint32_t *kbuf = nullptr, *ghist = nullptr;
     float2 *part = nullptr;   // matrix-core route: one (maximum, sum) pair per unit, head and block of the statistics pass
     constexpr int kMaxSplits = 64;
-    hipError_t e5 = hipSuccess;
-    if (mfma) e5 = hipMalloc((void **)&part, (size_t)chunk * G * kMaxSplits * sizeof(float2));
     // Matrix-core route, candidates only (see mfma_score_kernel): when every sequence is long against rho, so that
     // about 2 rho candidates are a small part of its keys and a 1-in-16 sample of the positions places the threshold
     // well, and the selection's bitmaps and candidate list fit the shared memory.  CTKVR_BUILD_CANDIDATES=0/1 forces
@@ -543,29 +601,47 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
         if (const char *e = getenv("CTKVR_BUILD_CANDIDATES")) by_cand = atoi(e) != 0;
     }
     ix->build_by_cand = by_cand;
-    if (by_cand) chunk = std::min(chunk, 4 * ix->c_max);   // half the scratch (allocating it is a tenth of the build), as fast
+    if (by_cand) chunk = std::min(chunk, 4 * ix->c_max);   // half the scratch, as fast
     const bool redo_always = by_cand && getenv("CTKVR_BUILD_CANDIDATES_REDO") != nullptr;   // tests: take the redo path
     uint32_t *ksamp = nullptr, *tau = nullptr, *cursor = nullptr, *d_fail = nullptr;
     uint2 *cand = nullptr;
-    hipError_t e3 = hipSuccess, e4 = hipSuccess;
+    hipError_t e1 = hipSuccess, e2 = hipSuccess, e3 = hipSuccess, e4 = hipSuccess, e5 = hipSuccess;
     auto alloc_full = [&]() {   // the buffers of the route that keeps every key
         if (!kbuf) e3 = hipMalloc((void **)&kbuf, (size_t)chunk * ix->s_max * 4);
         if (!ghist) e4 = hipMalloc((void **)&ghist, (size_t)chunk * kBuckets * 4);
         return e3 == hipSuccess && e4 == hipSuccess;
     };
-    if (by_cand && e5 == hipSuccess) {
+    void *block = nullptr;   // candidates route: all of its buffers in one allocation, kept between builds
+    bool block_cached = false;
+    int rc = CTKVR_OK;
+    if (by_cand) {
         // a segment per block of the statistics split: room for twice an even share, at least 256 entries
-        if (hipMalloc((void **)&ksamp, (size_t)chunk * sample_stride * 4) != hipSuccess ||
-            hipMalloc((void **)&tau, (size_t)chunk * 4) != hipSuccess ||
-            hipMalloc((void **)&cursor, (size_t)chunk * kMaxSplits * 4) != hipSuccess || hipMalloc((void **)&d_fail, 4) != hipSuccess ||
-            hipMalloc((void **)&cand, (size_t)chunk * 2 * std::max(cand_cap, 128 * kMaxSplits) * sizeof(uint2)) != hipSuccess)
-            e5 = hipErrorOutOfMemory;
-        if (e5 == hipSuccess) e5 = hipFuncSetAttribute((const void *)cand_select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)cand_lds);
+        const size_t sizes[8] = {(size_t)chunk * G * 4, (size_t)chunk * G * 8, (size_t)chunk * G * kMaxSplits * sizeof(float2),
+                                 (size_t)chunk * sample_stride * 4, (size_t)chunk * 4, (size_t)chunk * kMaxSplits * 4, 4,
+                                 (size_t)chunk * 2 * std::max(cand_cap, 128 * kMaxSplits) * sizeof(uint2)};
+        size_t off[9] = {0};
+        for (int i = 0; i < 8; ++i) off[i + 1] = off[i] + ((sizes[i] + 255) & ~(size_t)255);
+        rc = build_scratch_get(off[8], &block, &block_cached);
+        if (rc == CTKVR_OK) {
+            unsigned char *base = (unsigned char *)block;
+            m_key = (uint32_t *)(base + off[0]);
+            S = (unsigned long long *)(base + off[1]);
+            part = (float2 *)(base + off[2]);
+            ksamp = (uint32_t *)(base + off[3]);
+            tau = (uint32_t *)(base + off[4]);
+            cursor = (uint32_t *)(base + off[5]);
+            d_fail = (uint32_t *)(base + off[6]);
+            cand = (uint2 *)(base + off[7]);
+            e5 = hipFuncSetAttribute((const void *)cand_select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)cand_lds);
+        }
     } else {
+        if (!mfma) e5 = hipMalloc((void **)&z, (size_t)chunk * per_unit);
+        e1 = hipMalloc((void **)&m_key, (size_t)chunk * G * 4);
+        e2 = hipMalloc((void **)&S, (size_t)chunk * G * 8);
+        if (mfma && e5 == hipSuccess) e5 = hipMalloc((void **)&part, (size_t)chunk * G * kMaxSplits * sizeof(float2));
         alloc_full();
     }
-    int rc = CTKVR_OK;
-    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess || e4 != hipSuccess || e5 != hipSuccess)
+    if (rc == CTKVR_OK && (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess || e4 != hipSuccess || e5 != hipSuccess))
         rc = fail(CTKVR_ENOMEM, "build scratch allocation failed");
     for (int u0 = 0; rc == CTKVR_OK && u0 < total_units; u0 += chunk) {
         const int nu = std::min(chunk, total_units - u0);
@@ -726,17 +802,16 @@ int build_lists_exact(ctkvr_index *ix, const void *k_pages, const int32_t *block
     }
     hipError_t es = hipStreamSynchronize(st);
     if (rc == CTKVR_OK && es != hipSuccess) rc = fail(CTKVR_EHIP, "build: %s", hipGetErrorString(es));
-    (void)hipFree(z);
-    (void)hipFree(m_key);
-    (void)hipFree(S);
+    if (by_cand) {
+        build_scratch_put(block, block_cached);
+    } else {
+        (void)hipFree(z);
+        (void)hipFree(m_key);
+        (void)hipFree(S);
+        (void)hipFree(part);
+    }
     (void)hipFree(kbuf);
     (void)hipFree(ghist);
-    (void)hipFree(part);
-    (void)hipFree(ksamp);
-    (void)hipFree(tau);
-    (void)hipFree(cursor);
-    (void)hipFree(d_fail);
-    (void)hipFree(cand);
     return rc;
 }
 
@@ -1536,6 +1611,20 @@ int ctkvr_index_set_decode_path(ctkvr_index *idx, int32_t path)
         return fail(CTKVR_EUNSUPPORTED, "the single-launch step does not fit this geometry (%d units on %d CUs, or its shared memory)",
                     idx->units, idx->num_cu);
     idx->decode_path = path;
+    return CTKVR_OK;
+}
+
+int ctkvr_release_scratch(void)
+{
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return CTKVR_OK;
+    std::lock_guard<std::mutex> lock(g_build_mu);
+    BuildCache &c = g_build_cache[dev];
+    if (c.busy) return fail(CTKVR_EINVAL, "an index build is using the scratch");
+    if (c.base) HIP_TRY(hipFree(c.base));
+    c.base = nullptr;
+    c.bytes = 0;
     return CTKVR_OK;
 }
 

@@ -436,6 +436,37 @@ def test_mfma_build_from_candidates_gives_the_lists_of_the_route_that_ranks_ever
         _say(f"[mfma {name}] sequence {b}: ids that differ inside the derived band: {n}; farthest {wa:.3g} = {w:.3f} of the band")
 
 
+def test_scratch_kept_between_candidate_builds_changes_no_list(ck, monkeypatch):
+    """The candidate route keeps its device scratch between builds: a build that finds the scratch of a larger,
+    different build (its contents still there), one that has to grow it, and one after ctkvr_release_scratch give
+    the lists of a build with a scratch of its own."""
+    shapes = {"large": (16, 2, 12000, 300), "small": (8, 2, 9000, 256), "larger": (16, 4, 14000, 320)}
+    dbs, wls = {}, {}
+    for name, (h, g, s, rho) in shapes.items():
+        wls[name] = small_workload("scratch_" + name, "bf16", h, g, (s, s - 500), (630, 631), 40, 0, 4, rho, 60, 1)
+        dbs[name] = H.device_batch(gen_batch(wls[name]))
+
+    def build(name):
+        wl, db = wls[name], dbs[name]
+        idx = ck.ctkvr_build_index(H.params_of(wl, build_algo=ck.BUILD_MFMA), db.q_prefill, db.cu_seqlens, True, db.k_pages,
+                                   db.block_table, db.ctx_lens)
+        assert ck.ctkvr_index_build_route(idx)[0]
+        lists = ck.ctkvr_index_lists(idx)
+        ck.ctkvr_free(idx)
+        return lists
+
+    monkeypatch.setenv("CTKVR_BUILD_CANDIDATES", "1")
+    ck.ctkvr_release_scratch()
+    monkeypatch.setenv("CTKVR_BUILD_SCRATCH_CACHE", "0")
+    own = {name: build(name) for name in shapes}
+    monkeypatch.setenv("CTKVR_BUILD_SCRATCH_CACHE", "1")
+    for name in ("large", "small", "small", "larger", "large"):
+        assert np.array_equal(build(name), own[name]), name
+    ck.ctkvr_release_scratch()
+    ck.ctkvr_release_scratch()          # nothing kept: still fine
+    assert np.array_equal(build("small"), own["small"])
+
+
 def test_mfma_build_from_candidates_leaves_the_resident_window_out(ck, monkeypatch):
     n_init, n_local = 9, 300
     wl = small_workload("cand_window", "bf16", 8, 2, (7000,), (622,), 33, 0, 4, 300, 60, 1)
