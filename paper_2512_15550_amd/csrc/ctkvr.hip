@@ -878,8 +878,9 @@ int decode_launch_group(ctkvr_index *ix, const StepWs &w_all, int b0, int nb, bo
     units.n_cent = d_n_cent;
     // lines 10-11 first: the window's share depends on q, K and V only
     const bool window = p.n_init + p.n_local > 0 || cur_lens;
+    WindowArgs wa{};
+    const bool one_launch = whole && ix->fused_bpu && ix->decode_path == CTKVR_PATH_FUSED;
     if (window) {
-        WindowArgs wa{};
         wa.u = units;
         wa.q = q;
         wa.k = Paged{k_pages, bt, max_pages, ix->page_shift};
@@ -890,7 +891,9 @@ int decode_launch_group(ctkvr_index *ix, const StepWs &w_all, int b0, int nb, bo
         wa.n_local = p.n_local;
         wa.scale = ix->scale;
         wa.win = w.win;
-        window_attn_kernel<T, G><<<dim3(kWinSplit, U), 256, 0, st>>>(wa);
+        // a launch of its own before the single-launch step, and for groups of eight heads (where the window's
+        // registers would cost the scoring blocks a wave per SIMD); otherwise its blocks ride in the scoring launch below
+        if (one_launch || G > 4) window_attn_kernel<T, G><<<dim3(kWinSplit, U), 256, 0, st>>>(wa);
     }
     const bool stream_k = [&] {
         // key bytes the batch can touch per step: above 128 MiB (half of the 256 MB memory-side cache) few rows
@@ -900,7 +903,7 @@ int decode_launch_group(ctkvr_index *ix, const StepWs &w_all, int b0, int nb, bo
         for (int sl : ix->ctx_lens) kbytes += (size_t)sl * p.n_kv_heads * 128 * elem_size(p.dtype);
         return kbytes > ((size_t)128 << 20);
     }();
-    if (whole && ix->fused_bpu && ix->decode_path == CTKVR_PATH_FUSED) {
+    if (one_launch) {
         FusedArgs fa{};
         fa.g = p.n_kv_heads;
         fa.h = p.n_q_heads;
@@ -1035,7 +1038,16 @@ int decode_launch_group(ctkvr_index *ix, const StepWs &w_all, int b0, int nb, bo
             const int wpb = std::max(8, std::min(kRecallWpb, (ix->bitmap_words + target - 1) / target));
             nbx = (ix->bitmap_words + wpb - 1) / wpb;
         }
-        recall_score_kernel<T, G><<<dim3(nbx, U), 256, 0, st>>>(sa);
+        sa.nbx = nbx;
+        bool launched = false;
+        if constexpr (G <= 4) {
+            if (window) {
+                sa.win = wa;
+                recall_score_kernel<T, G, true><<<dim3(nbx + kWinSplit, U), 256, 0, st>>>(sa);
+                launched = true;
+            }
+        }
+        if (!launched) recall_score_kernel<T, G, false><<<dim3(nbx, U), 256, 0, st>>>(sa);
     }
     if (whole) ix->mark(3, st);
 

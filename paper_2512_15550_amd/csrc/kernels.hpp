@@ -346,6 +346,166 @@ template <typename T, int G, int R> __global__ __launch_bounds__(256) void score
 }
 
 // ------------------------------------------------------------------------------
+// Algorithm 2 lines 10-11: attention over the resident window -- the first n_init keys and the
+// keys from s - n_local to the current end of the cache (the tokens decoded since the index was
+// built join the local window) -- and its merge with the sparse attention.
+// window_attn_kernel: block x of a unit takes every kWinSplit-th run of 64 window rows and leaves
+// a partial result relative to its own maximum: m[G], l[G] = sum of exp(z - m), o[G][128] = sum of
+// exp(z - m) v.  Online softmax over runs of 64 rows (one row per 16-lane group and pass, four
+// passes).  It depends on q, K and V only: as a launch of its own it is the first of a step (grid (kWinSplit,
+// units), 256 threads); the step of one launch per stage runs the same blocks as kWinSplit extra blocks per
+// unit of recall_score_kernel's launch instead, where they cost no launch and run beside the scoring blocks.
+// ------------------------------------------------------------------------------
+
+struct WindowArgs {
+    Units u;
+    const void *q;            // [batch][h][128]
+    Paged k;
+    const void *v_pages;
+    const int32_t *ctx_lens;  // [batch] s: the prefix the index was built on
+    const int32_t *cur_lens;  // optional [batch]: tokens in the cache now (>= s)
+    int n_init, n_local;
+    float scale;
+    float *win;               // [units][kWinSplit][G][2 + 128]
+};
+
+// One block's share: bx of kWinSplit, unit ul; 256 threads.
+template <typename T, int G> __device__ __forceinline__ void window_attn_block(const WindowArgs &a, const int bx, const int ul)
+{
+    __shared__ float s_z[64][G];
+    __shared__ float s_part[4][G][kD];
+    __shared__ float s_ml[G];
+    const int b = ul / a.u.g, kv = ul - b * a.u.g;
+    const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4;
+    const int s = a.ctx_lens[b];
+    int cur = a.cur_lens ? a.cur_lens[b] : s;
+    cur = max(s, min(cur, a.k.max_pages << a.k.page_shift));
+    const int ni = min(a.n_init, s), nl = min(a.n_local, s - ni);
+    const int n_w = ni + nl + (cur - s);
+    auto id_of = [&](int r) { return r < ni ? r : s - nl + (r - ni); };
+    float q[G][8];
+    const T *qb = (const T *)a.q + ((size_t)b * a.u.h + kv * G) * kD;
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) unpack(load_chunk(qb + (size_t)hh * kD, lane16), q[hh]);
+    const T *K = (const T *)a.k.pages;
+    const T *V = (const T *)a.v_pages;
+    float m_run[G], l_run[G], acc[G][8];
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+        m_run[hh] = -__builtin_huge_valf();
+        l_run[hh] = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[hh][e] = 0.0f;
+    }
+    for (int r0 = bx * 64; r0 < n_w; r0 += kWinSplit * 64) {
+        const int nr = min(64, n_w - r0);
+        uint32_t row[4];
+        Chunk<T> ck[4], cv[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int r = min(p * 16 + grp, nr - 1);
+            row[p] = row_of(a.k.block_table, a.k.max_pages, a.k.page_shift, a.u.g, b, kv, id_of(r0 + r));
+        }
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            ck[p] = load_chunk(K + (size_t)row[p] * kD, lane16);
+            cv[p] = load_chunk(V + (size_t)row[p] * kD, lane16);
+        }
+        __syncthreads();   // the previous run's s_z and s_ml have been read
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            float kx[8];
+            unpack(ck[p], kx);
+#pragma unroll
+            for (int hh = 0; hh < G; ++hh) {
+                float tot = group16_sum(lane_partial(q[hh], kx)) * a.scale;
+                if (lane16 == hh) s_z[p * 16 + grp][hh] = tot;
+            }
+        }
+        __syncthreads();
+        if (tid < 64) {   // the run's maximum per head (one row per lane of the first wave)
+#pragma unroll
+            for (int hh = 0; hh < G; ++hh) {
+                float mx = tid < nr ? s_z[tid][hh] : -__builtin_huge_valf();
+#pragma unroll
+                for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+                if (tid == 0) s_ml[hh] = mx;
+            }
+        }
+        __syncthreads();
+        float corr[G];
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh) {
+            const float m_new = fmaxf(m_run[hh], s_ml[hh]);   // the same in every thread
+            corr[hh] = __expf(m_run[hh] - m_new);          // exp(-inf) = 0 on the first run
+            m_run[hh] = m_new;
+            l_run[hh] *= corr[hh];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[hh][e] *= corr[hh];
+        }
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int r = p * 16 + grp;
+            if (r < nr) {
+                float vx[8];
+                unpack(cv[p], vx);
+#pragma unroll
+                for (int hh = 0; hh < G; ++hh) {
+                    const float pr = __expf(s_z[r][hh] - m_run[hh]);
+                    if (lane16 == 0) l_run[hh] += pr;   // lane 0 of each group carries the group's share of l
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[hh][e] = __fmaf_rn(pr, vx[e], acc[hh][e]);
+                }
+            }
+        }
+    }
+    // the 16 groups hold partial sums over their rows, all relative to the same running maximum:
+    // first the four groups of a wave (lanes l, l+16, l+32, l+48), then the four waves
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float v = acc[hh][e];
+            v += __shfl_xor(v, 16);
+            v += __shfl_xor(v, 32);
+            acc[hh][e] = v;
+        }
+        float l = l_run[hh];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        l_run[hh] = l;
+    }
+    __syncthreads();
+    const int wv = tid >> 6;
+    if ((tid & 63) < 16) {
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s_part[wv][hh][lane16 * 8 + e] = acc[hh][e];
+        }
+        if (lane16 == 0) {
+#pragma unroll
+            for (int hh = 0; hh < G; ++hh) s_z[wv][hh] = l_run[hh];
+        }
+    }
+    __syncthreads();
+    float *dst = a.win + ((size_t)ul * kWinSplit + bx) * G * (2 + kD);
+    for (int i = tid; i < G * kD; i += 256) {
+        const int hh = i >> 7, e = i & 127;
+        dst[hh * (2 + kD) + 2 + e] = (s_part[0][hh][e] + s_part[1][hh][e]) + (s_part[2][hh][e] + s_part[3][hh][e]);
+    }
+    if (tid < G) {
+        dst[tid * (2 + kD)] = m_run[tid];
+        dst[tid * (2 + kD) + 1] = (s_z[0][tid] + s_z[1][tid]) + (s_z[2][tid] + s_z[3][tid]);
+    }
+}
+
+template <typename T, int G> __global__ __launch_bounds__(256) void window_attn_kernel(WindowArgs a)
+{
+    window_attn_block<T, G>(a, (int)blockIdx.x, (int)blockIdx.y);
+}
+
+// ------------------------------------------------------------------------------
 // Algorithm 2 lines 4-5 in one launch (decode).  A unit's bitmap of recalled ids is split over the
 // unit's blocks; a block turns its part into ascending ids 64 words at a time (one byte per thread,
 // positions by a block scan), writes them and their physical rows to their ranks of the recalled
@@ -361,7 +521,7 @@ template <typename T, int G, int R> __global__ __launch_bounds__(256) void score
 //     round trip to the cache, but every block then has the same number of rows: for small batches,
 //     where a block's rows are one or two round trips to memory and the slowest block is the launch.
 // The block that sees the unit's last word (by id) or block 0 (by rank) also writes L.
-// grid (nbx, units), 256 threads; by id nbx >= W_max / 64, by rank nbx >= l_stride / kRecallCap.
+// grid (nbx [+ kWinSplit], units), 256 threads; by id nbx >= W_max / 64, by rank nbx >= l_stride / kRecallCap.
 // ------------------------------------------------------------------------------
 constexpr int kRecallWpb = 64;     // by id range: at most 2048 ids per block
 constexpr int kRecallCap = 2048;   // ids per block at most
@@ -383,9 +543,11 @@ struct RecallScoreArgs {
     float scale;
     int stream_k;             // the keys of all sequences exceed what the memory-side cache holds: load them non-temporal
     int by_rank;              // how the bitmap is split over a unit's blocks
+    int nbx;                  // blocks per unit that score; with WIN blocks nbx .. nbx + kWinSplit - 1 take the resident window
+    WindowArgs win;
 };
 
-template <typename T, int G> __global__ __launch_bounds__(256) void recall_score_kernel(RecallScoreArgs a)
+template <typename T, int G, bool WIN> __global__ __launch_bounds__(256) void recall_score_kernel(RecallScoreArgs a)
 {
     constexpr int R = 8, TILE = 16 * R;
     __shared__ uint32_t s_ids[kRecallCap];        // ids of this block's ranks, then their rows
@@ -393,12 +555,18 @@ template <typename T, int G> __global__ __launch_bounds__(256) void recall_score
     __shared__ uint32_t s_tmp[8];
     __shared__ uint32_t s_edge[3];                // first word, ids before it, last word
     __shared__ uint32_t s_max[G];
+    if constexpr (WIN) {
+        if ((int)blockIdx.x >= a.nbx) {   // Algorithm 2 lines 10-11 beside lines 4-5
+            window_attn_block<T, G>(a.win, (int)blockIdx.x - a.nbx, (int)blockIdx.y);
+            return;
+        }
+    }
     const int ul = blockIdx.y, b = ul / a.u.g, kv = ul - b * a.u.g;
     const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4;
     CTKVR_STAMP_BLK(6);
     const int s_len = a.ctx_lens[b];
     const int W = (s_len + 31) >> 5;
-    for (int w = blockIdx.x * 256 + tid; w < kBuckets; w += gridDim.x * 256) a.ghist[(size_t)ul * kBuckets + w] = 0u;
+    for (int w = blockIdx.x * 256 + tid; w < kBuckets; w += (uint32_t)a.nbx * 256) a.ghist[(size_t)ul * kBuckets + w] = 0u;
     const uint32_t *gb = a.gbits + (size_t)ul * a.bitmap_words;
     if (tid < G) s_max[tid] = 0u;
     uint32_t r0, r1;   // the block's ranks
@@ -438,7 +606,7 @@ template <typename T, int G> __global__ __launch_bounds__(256) void recall_score
             a.ncand[ul] = (int32_t)L;
             if (a.out_ncand) a.out_ncand[ul] = (int32_t)L;
         }
-        const uint32_t qn = (L + gridDim.x - 1) / gridDim.x;
+        const uint32_t qn = (L + (uint32_t)a.nbx - 1) / (uint32_t)a.nbx;
         r0 = blockIdx.x * qn;
         if (r0 >= L) return;
         r1 = min(L, r0 + qn);
@@ -498,7 +666,7 @@ template <typename T, int G> __global__ __launch_bounds__(256) void recall_score
     } else {
         // the unit's own words split evenly over the blocks of its row (a short sequence of a ragged
         // batch still uses all of them)
-        const int wpb = min(kRecallWpb, (W + (int)gridDim.x - 1) / (int)gridDim.x);
+        const int wpb = min(kRecallWpb, (W + a.nbx - 1) / a.nbx);
         const int w_beg = blockIdx.x * wpb;
         if (w_beg >= W) return;
         uint32_t before = 0;
@@ -1791,158 +1959,6 @@ struct AttnArgs {
     const uint32_t *m_key;   // [units][G] ordered-key maxima of the logits over all recalled keys
 };
 
-// ------------------------------------------------------------------------------
-// Algorithm 2 lines 10-11: attention over the resident window -- the first n_init keys and the
-// keys from s - n_local to the current end of the cache (the tokens decoded since the index was
-// built join the local window) -- and its merge with the sparse attention.
-// window_attn_kernel: block x of a unit takes every kWinSplit-th run of 64 window rows and leaves
-// a partial result relative to its own maximum: m[G], l[G] = sum of exp(z - m), o[G][128] = sum of
-// exp(z - m) v.  Online softmax over runs of 64 rows (one row per 16-lane group and pass, four
-// passes).  It depends on q, K and V only, so it is the first launch of a step.
-// grid (kWinSplit, units), 256 threads.
-// ------------------------------------------------------------------------------
-
-struct WindowArgs {
-    Units u;
-    const void *q;            // [batch][h][128]
-    Paged k;
-    const void *v_pages;
-    const int32_t *ctx_lens;  // [batch] s: the prefix the index was built on
-    const int32_t *cur_lens;  // optional [batch]: tokens in the cache now (>= s)
-    int n_init, n_local;
-    float scale;
-    float *win;               // [units][kWinSplit][G][2 + 128]
-};
-
-template <typename T, int G> __global__ __launch_bounds__(256) void window_attn_kernel(WindowArgs a)
-{
-    __shared__ float s_z[64][G];
-    __shared__ float s_part[4][G][kD];
-    __shared__ float s_ml[G];
-    const int ul = blockIdx.y, b = ul / a.u.g, kv = ul - b * a.u.g;
-    const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4;
-    const int s = a.ctx_lens[b];
-    int cur = a.cur_lens ? a.cur_lens[b] : s;
-    cur = max(s, min(cur, a.k.max_pages << a.k.page_shift));
-    const int ni = min(a.n_init, s), nl = min(a.n_local, s - ni);
-    const int n_w = ni + nl + (cur - s);
-    auto id_of = [&](int r) { return r < ni ? r : s - nl + (r - ni); };
-    float q[G][8];
-    const T *qb = (const T *)a.q + ((size_t)b * a.u.h + kv * G) * kD;
-#pragma unroll
-    for (int hh = 0; hh < G; ++hh) unpack(load_chunk(qb + (size_t)hh * kD, lane16), q[hh]);
-    const T *K = (const T *)a.k.pages;
-    const T *V = (const T *)a.v_pages;
-    float m_run[G], l_run[G], acc[G][8];
-#pragma unroll
-    for (int hh = 0; hh < G; ++hh) {
-        m_run[hh] = -__builtin_huge_valf();
-        l_run[hh] = 0.0f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[hh][e] = 0.0f;
-    }
-    for (int r0 = blockIdx.x * 64; r0 < n_w; r0 += kWinSplit * 64) {
-        const int nr = min(64, n_w - r0);
-        uint32_t row[4];
-        Chunk<T> ck[4], cv[4];
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int r = min(p * 16 + grp, nr - 1);
-            row[p] = row_of(a.k.block_table, a.k.max_pages, a.k.page_shift, a.u.g, b, kv, id_of(r0 + r));
-        }
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            ck[p] = load_chunk(K + (size_t)row[p] * kD, lane16);
-            cv[p] = load_chunk(V + (size_t)row[p] * kD, lane16);
-        }
-        __syncthreads();   // the previous run's s_z and s_ml have been read
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            float kx[8];
-            unpack(ck[p], kx);
-#pragma unroll
-            for (int hh = 0; hh < G; ++hh) {
-                float tot = group16_sum(lane_partial(q[hh], kx)) * a.scale;
-                if (lane16 == hh) s_z[p * 16 + grp][hh] = tot;
-            }
-        }
-        __syncthreads();
-        if (tid < 64) {   // the run's maximum per head (one row per lane of the first wave)
-#pragma unroll
-            for (int hh = 0; hh < G; ++hh) {
-                float mx = tid < nr ? s_z[tid][hh] : -__builtin_huge_valf();
-#pragma unroll
-                for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-                if (tid == 0) s_ml[hh] = mx;
-            }
-        }
-        __syncthreads();
-        float corr[G];
-#pragma unroll
-        for (int hh = 0; hh < G; ++hh) {
-            const float m_new = fmaxf(m_run[hh], s_ml[hh]);   // the same in every thread
-            corr[hh] = __expf(m_run[hh] - m_new);          // exp(-inf) = 0 on the first run
-            m_run[hh] = m_new;
-            l_run[hh] *= corr[hh];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[hh][e] *= corr[hh];
-        }
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int r = p * 16 + grp;
-            if (r < nr) {
-                float vx[8];
-                unpack(cv[p], vx);
-#pragma unroll
-                for (int hh = 0; hh < G; ++hh) {
-                    const float pr = __expf(s_z[r][hh] - m_run[hh]);
-                    if (lane16 == 0) l_run[hh] += pr;   // lane 0 of each group carries the group's share of l
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[hh][e] = __fmaf_rn(pr, vx[e], acc[hh][e]);
-                }
-            }
-        }
-    }
-    // the 16 groups hold partial sums over their rows, all relative to the same running maximum:
-    // first the four groups of a wave (lanes l, l+16, l+32, l+48), then the four waves
-#pragma unroll
-    for (int hh = 0; hh < G; ++hh) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            float v = acc[hh][e];
-            v += __shfl_xor(v, 16);
-            v += __shfl_xor(v, 32);
-            acc[hh][e] = v;
-        }
-        float l = l_run[hh];
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
-        l_run[hh] = l;
-    }
-    __syncthreads();
-    const int wv = tid >> 6;
-    if ((tid & 63) < 16) {
-#pragma unroll
-        for (int hh = 0; hh < G; ++hh) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) s_part[wv][hh][lane16 * 8 + e] = acc[hh][e];
-        }
-        if (lane16 == 0) {
-#pragma unroll
-            for (int hh = 0; hh < G; ++hh) s_z[wv][hh] = l_run[hh];
-        }
-    }
-    __syncthreads();
-    float *dst = a.win + ((size_t)ul * kWinSplit + blockIdx.x) * G * (2 + kD);
-    for (int i = tid; i < G * kD; i += 256) {
-        const int hh = i >> 7, e = i & 127;
-        dst[hh * (2 + kD) + 2 + e] = (s_part[0][hh][e] + s_part[1][hh][e]) + (s_part[2][hh][e] + s_part[3][hh][e]);
-    }
-    if (tid < G) {
-        dst[tid * (2 + kD)] = m_run[tid];
-        dst[tid * (2 + kD) + 1] = (s_z[0][tid] + s_z[1][tid]) + (s_z[2][tid] + s_z[3][tid]);
-    }
-}
 
 // out element `dim` of head hh of a unit: the sparse part (v = sum of exp(z - m_s) * value, l_s = sum of
 // exp(z - m_s); l_s = 0 for an empty part) merged with the window's partial results, if there are any.
