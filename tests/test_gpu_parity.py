@@ -467,6 +467,46 @@ def test_scratch_kept_between_candidate_builds_changes_no_list(ck, monkeypatch):
     assert np.array_equal(build("small"), own["small"])
 
 
+def test_two_host_threads_building_at_once_each_get_their_lists(ck, monkeypatch):
+    """Only one build at a time can hold the kept scratch; a build on another host thread that finds it taken
+    allocates its own.  Two threads build different indices side by side, several times."""
+    import threading
+    import torch
+    monkeypatch.setenv("CTKVR_BUILD_CANDIDATES", "1")
+    shapes = {"a": (16, 2, 12000, 300), "b": (8, 2, 9000, 256)}
+    wls = {n: small_workload("threads_" + n, "bf16", h, g, (s,), (640 + i,), 40, 0, 4, rho, 60, 1)
+           for i, (n, (h, g, s, rho)) in enumerate(shapes.items())}
+    dbs = {n: H.device_batch(gen_batch(wls[n])) for n in shapes}
+
+    def build(name, stream=None):
+        wl, db = wls[name], dbs[name]
+        idx = ck.ctkvr_build_index(H.params_of(wl, build_algo=ck.BUILD_MFMA), db.q_prefill, db.cu_seqlens, True, db.k_pages,
+                                   db.block_table, db.ctx_lens)
+        lists = ck.ctkvr_index_lists(idx)
+        ck.ctkvr_free(idx)
+        return lists
+
+    want = {n: build(n) for n in shapes}
+    got, errors = {n: [] for n in shapes}, []
+
+    def worker(name):
+        try:
+            torch.cuda.set_device(0)
+            for _ in range(4):
+                got[name].append(build(name))
+        except Exception as e:      # noqa: BLE001  (reported below, in the test's own thread)
+            errors.append((name, repr(e)))
+
+    threads = [threading.Thread(target=worker, args=(n,)) for n in shapes]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for n in shapes:
+        assert len(got[n]) == 4 and all(np.array_equal(x, want[n]) for x in got[n]), n
+
+
 def test_mfma_build_from_candidates_leaves_the_resident_window_out(ck, monkeypatch):
     n_init, n_local = 9, 300
     wl = small_workload("cand_window", "bf16", 8, 2, (7000,), (622,), 33, 0, 4, 300, 60, 1)
