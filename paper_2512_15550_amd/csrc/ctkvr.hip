@@ -177,7 +177,7 @@ struct ctkvr_index {
     int32_t *d_ctx_lens = nullptr, *d_n_cent = nullptr;
     StepWs ws;   // decode workspace
     // dynamic centroid update
-    uint32_t *d_dcu_count = nullptr;   // updates so far (device side, so that captured graphs replay correctly)
+    uint32_t *d_dcu_count = nullptr;   // [2]: updates so far (device side, so that captured graphs replay correctly), blocks of the running update that are done
     int32_t *dsel = nullptr, *dnsel = nullptr;   // top-rho ids of the second ranking (only when rho != rho')
     bool have_step = false;
     size_t recall_lds = 0, select_lds = 0, attn_lds = 0, build_select_lds = 0;
@@ -360,7 +360,7 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
     A(&ix->lists, U * ix->c_max * p->list_len * 4);
     A(&ix->d_ctx_lens, (size_t)B * 4);
     A(&ix->d_n_cent, (size_t)B * 4);
-    A(&ix->d_dcu_count, 4);
+    A(&ix->d_dcu_count, 8);
     A(&ix->d_err, 4);
     A(&ix->d_prof, 64 * 8);
     {
@@ -513,7 +513,7 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
             ix->num_cu = cus;
     }
     if (e == hipSuccess) e = hipMemset(ix->ws.ghist, 0, U * (size_t)kBuckets * 4);
-    if (e == hipSuccess) e = hipMemset(ix->d_dcu_count, 0, 4);
+    if (e == hipSuccess) e = hipMemset(ix->d_dcu_count, 0, 8);
     if (e == hipSuccess) e = hipMemset(ix->d_err, 0, 4);
     if (e == hipSuccess) e = hipMemset(ix->d_prof, 0, 64 * 8);
     if (e == hipSuccess) e = hipMemset(ix->ws.bar, 0, U * (size_t)kFusedBarriers * 4);
@@ -1373,7 +1373,6 @@ template <typename T, int G> int update_launch(ctkvr_index *ix, const void *q, h
         da.src_stride = p.list_len;
     }
     dcu_write_kernel<T><<<dim3(U), 256, 0, st>>>(da);
-    dcu_advance_kernel<<<dim3(1), 64, 0, st>>>(ix->d_dcu_count);
     HIP_TRY(hipGetLastError());
     ix->have_step = false;
     return CTKVR_OK;

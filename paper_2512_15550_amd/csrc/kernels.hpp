@@ -2312,12 +2312,12 @@ template <typename T, int G, int SL> __global__ __launch_bounds__(1024) void sel
 // FIFO slot (updates so far mod C: the oldest mapping goes first) for the G heads of the group,
 // with its inverse norm, and the slot's list becomes src[unit][0..rho): the top-rho ids by rerank
 // score, ascending (should fewer have been recalled, the last one is repeated; none: no update).
-// grid batch*g, 256 threads.  dcu_advance_kernel then counts the update.
+// grid batch*g, 256 threads; the block that ends last counts the update.
 // ------------------------------------------------------------------------------
 struct DcuArgs {
     int g, h, G, c_max, rho, src_stride;
     const int32_t *n_cent;
-    const uint32_t *count;    // [1] updates so far
+    uint32_t *count;          // [2]: updates so far; blocks of this update that are done (zero between updates)
     const void *q;            // [batch][h][128]
     const int32_t *src;       // [units][src_stride]
     const int32_t *nsrc;      // [units]
@@ -2342,25 +2342,27 @@ template <typename T> __global__ __launch_bounds__(256) void dcu_write_kernel(Dc
     const int ul = blockIdx.x, b = ul / a.g, kv = ul - b * a.g, tid = threadIdx.x;
     const int slot = (int)(a.count[0] % (uint32_t)a.n_cent[b]);
     const int n = min(a.nsrc[ul], a.rho);
-    if (n <= 0) return;
-    const int32_t *src = a.src + (size_t)ul * a.src_stride;
-    int32_t *dst = a.lists + ((size_t)ul * a.c_max + slot) * a.rho;
-    for (int r = tid; r < a.rho; r += 256) dst[r] = src[min(r, n - 1)];
-    if (tid < 16 * a.G) {
-        const int hh = tid >> 4, lane16 = tid & 15;
-        const size_t head = (size_t)b * a.h + kv * a.G + hh;
-        Chunk<T> c = load_chunk((const T *)a.q + head * kD, lane16);
-        store_chunk((T *)a.centroids + (head * a.c_max + slot) * kD, lane16, c);
-        float x[8];
-        unpack(c, x);
-        const float n2 = group16_sum(lane_partial(x, x));
-        if (lane16 == 0) a.inv_norm_c[head * a.c_max + slot] = inv_norm_from_sq(n2);
+    if (n > 0) {
+        const int32_t *src = a.src + (size_t)ul * a.src_stride;
+        int32_t *dst = a.lists + ((size_t)ul * a.c_max + slot) * a.rho;
+        for (int r = tid; r < a.rho; r += 256) dst[r] = src[min(r, n - 1)];
+        if (tid < 16 * a.G) {
+            const int hh = tid >> 4, lane16 = tid & 15;
+            const size_t head = (size_t)b * a.h + kv * a.G + hh;
+            Chunk<T> c = load_chunk((const T *)a.q + head * kD, lane16);
+            store_chunk((T *)a.centroids + (head * a.c_max + slot) * kD, lane16, c);
+            float x[8];
+            unpack(c, x);
+            const float n2 = group16_sum(lane_partial(x, x));
+            if (lane16 == 0) a.inv_norm_c[head * a.c_max + slot] = inv_norm_from_sq(n2);
+        }
     }
-}
-
-__global__ void dcu_advance_kernel(uint32_t *count)
-{
-    if (threadIdx.x == 0 && blockIdx.x == 0) count[0] += 1u;
+    // The update is counted by the block that ends last: every block has read the count before it reports done.
+    __syncthreads();
+    if (tid == 0 && atomicAdd(&a.count[1], 1u) == gridDim.x - 1) {
+        atomicExch(&a.count[1], 0u);
+        atomicAdd(&a.count[0], 1u);
+    }
 }
 
 }  // namespace ctkvr
