@@ -1554,10 +1554,8 @@ int ctkvr_decode_step_static(ctkvr_index *idx, const void *q, const void *k_page
     // zero is cleared here (fill kernels, so that a captured call replays correctly): the recall bitmap, and
     // the selected rows (slots beyond the selection are read as valid row numbers).
     const size_t nbits = (size_t)idx->units * idx->bitmap_words, nrow = (size_t)idx->units * idx->p.top_k;
-    fill_u32_kernel<<<dim3((unsigned)((nbits + 255) / 256)), 256, 0, st>>>(w.gbits, 0u, nbits);
-    fill_u32_kernel<<<dim3((unsigned)((nrow + 255) / 256)), 256, 0, st>>>(w.srow, 0u, nrow);
     const size_t nbar = (size_t)idx->units * kFusedBarriers;
-    fill_u32_kernel<<<dim3((unsigned)((nbar + 255) / 256)), 256, 0, st>>>(w.bar, 0u, nbar);
+    zero3_u32_kernel<<<dim3((unsigned)((nbits + nrow + nbar + 255) / 256)), 256, 0, st>>>(w.gbits, nbits, w.srow, nrow, w.bar, nbar);
     if (idx->p.dtype == CTKVR_BF16)
         return decode_dispatch<bf16_t>(idx, w, q, k_pages, v_pages, block_table, max_pages, nullptr, out, out_lse, out_sel,
                                        out_ncand, out_probe, st);

@@ -57,6 +57,19 @@ __global__ void fill_u32_kernel(uint32_t *p, uint32_t v, size_t n)
     if (i < n) p[i] = v;
 }
 
+// three ranges cleared by one launch: grid ceil((n0 + n1 + n2) / blockDim.x)
+__global__ void zero3_u32_kernel(uint32_t *p0, size_t n0, uint32_t *p1, size_t n1, uint32_t *p2, size_t n2)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n0) {
+        p0[i] = 0u;
+    } else if (i < n0 + n1) {
+        p1[i - n0] = 0u;
+    } else if (i < n0 + n1 + n2) {
+        p2[i - n0 - n1] = 0u;
+    }
+}
+
 // Algorithm 1 line 1: centroid j of sequence b, head hd = prompt query at position s_b - C_b + j.
 // q_prefill rows [first_row_b + j][h][128] -> centroids [b][h][c_max][128]
 template <typename T>
