@@ -36,9 +36,8 @@
  * Pins: tests/test_oracle_*.py check this file against brute-force dense
  * attention, brute-force fp64 definitions on small inputs, closed forms the
  * paper prints, and library exp/log/sort -- none of them calls back into it.
- * The k-means centroid mode at the end of the file is pinned only through
- * invariants (see its header): "parity unpinned" bit-wise beyond one
- * iteration.
+ * The k-means centroid mode at the end of the file has pins of its own
+ * (tests/test_oracle_kmeans.py, listed in its header).
  */
 #include <math.h>
 #include <stdint.h>
@@ -382,12 +381,16 @@ void ctkvr_oracle_set_threads(int n)
 /*     values of magnitude >= 2^-13), so they do not depend on the order;      */
 /*     mean = (double)sum * 2^-20 / count, rounded to fp32 and then, for bf16  */
 /*     data, to bf16 (nearest even): the next assignment reads bf16 centres.   */
-/* Distances here are fp64; a GPU that scores in fp32 on the matrix cores may  */
-/* assign a point differently when two centres tie within rounding, after     */
-/* which the two runs drift apart: PARITY UNPINNED bit-wise beyond such ties.  */
+/* Distances here are fp64.  (A kernel that scores in fp32 on the matrix cores  */
+/* may assign a point differently when two centres tie within its rounding;    */
+/* the GPU tests therefore compare one iteration at a time from equal centres, */
+/* with such near-ties listed, and check the argmin property of the result.)   */
 /* Pins (tests/test_oracle_kmeans.py): one centre = the mean; as many centres  */
 /* as distinct points = zero inertia; inertia never increases; scipy's         */
-/* kmeans2 step from the same start.                                            */
+/* kmeans2 step from the same start; lattice points: exact means and their     */
+/* bf16 rounding; duplicated centres: every point of the tie goes to the       */
+/* lowest id; a centre without members keeps its position; explicit start      */
+/* centres = the positions they were read from.                                 */
 /* ========================================================================= */
 static float round_bf16(float x)
 {
