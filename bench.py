@@ -198,6 +198,17 @@ def main():
         a5 = copy.copy(args)
         a5.steps, a5.kmeans = 3, True
         rec["build_cfg5"] = bench_build(a5, workload("cfg5"), emit=False)
+        # the rows next on the path, as plain step times: the resident window, the dynamic centroid update, and the
+        # paper's own operating point on both head shapes and at its 4 % budget
+        rec["variants"] = {}
+        for name, wname, window, dcu in (("cfg2_window_128_512", "cfg2", "128,512", False), ("cfg2_centroid_update", "cfg2", "", True),
+                                         ("cfg3_window_128_512", "cfg3", "128,512", False), ("cfg3_centroid_update", "cfg3", "", True),
+                                         ("paper_llama", "paper_llama", "", False), ("paper_yi", "paper_yi", "", False),
+                                         ("paper_budget4", "paper_budget4", "", False)):
+            av = copy.copy(args)
+            av.window, av.dcu, av.repeats = window, dcu, 5
+            rv = bench_decode(av, workload(wname), 64, 0)
+            rec["variants"][name] = {k: rv[k] for k in ("value", "us_per_step_p95", "unit", "steps", "repeats", "config")}
     print(json.dumps(rec))
 
 
