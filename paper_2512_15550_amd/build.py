@@ -43,7 +43,7 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
-PROBES = ["sync_probe", "latency_probe", "gather_probe"]
+PROBES = ["sync_probe", "latency_probe", "gather_probe", "xcd_probe"]
 PROBE_DIR = os.path.join(HERE, "probes")
 
 

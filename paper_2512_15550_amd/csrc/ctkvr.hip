@@ -186,6 +186,8 @@ struct ctkvr_index {
     int attn_slices = 4;    // blocks per unit of the attention (head-dimension slices): 8 while each has a CU of its own
     int build_redone = 0;   // chunks of the matrix-core list build that the candidate route had to hand back
     int build_by_cand = 0;  // the matrix-core list build took the candidate route
+    int xcd_units = -1;       // a unit's blocks on one XCD in every kernel of a step (unit_block_of; the units must be a multiple of 8):
+                              // -1 for small batches, 0 never, 1 whenever possible
     int score_by_rank = -1;   // how the scoring kernel splits a unit's recalled ids over its blocks: -1 chosen per batch, 0 by id range, 1 by rank
     int sel_bits = 0, build_bits = 0;   // words for the selection's id bitmaps (0: histogram route off)
     int bitmap_words = 0, recall_split = 1, num_cu = 256;
@@ -397,6 +399,7 @@ int create_index(const ctkvr_params *p, const int32_t *ctx_lens, ctkvr_index **o
     {
         int ng = 1;
         if (const char *e = getenv("CTKVR_DECODE_GROUPS")) ng = std::max(1, std::min(std::min(8, B), atoi(e)));
+        if (const char *e = getenv("CTKVR_XCD_UNITS")) ix->xcd_units = atoi(e) != 0;
         if (const char *e = getenv("CTKVR_SCORE_BY_RANK")) ix->score_by_rank = atoi(e) != 0;
         if (const char *e = getenv("CTKVR_KEYCLASS")) ix->keyclass = atoi(e) != 0;
         ix->n_groups = ng;
@@ -876,6 +879,9 @@ int decode_launch_group(ctkvr_index *ix, const StepWs &w_all, int b0, int nb, bo
     }
     Units units = decode_units(ix);
     units.n_cent = d_n_cent;
+    // Small batches (latency-bound: a step is a chain of dependent loads of what the previous kernel wrote) keep each unit on
+    // one XCD; large ones lose more in the scoring kernel, whose blocks then cannot be handed to whichever XCD is free.
+    const int by_xcd = U % 8 == 0 && (ix->xcd_units < 0 ? (long long)ix->l_stride * U <= 2048ll * ix->num_cu : ix->xcd_units != 0);
     // lines 10-11 first: the window's share depends on q, K and V only
     const bool window = p.n_init + p.n_local > 0 || cur_lens;
     WindowArgs wa{};
@@ -891,6 +897,7 @@ int decode_launch_group(ctkvr_index *ix, const StepWs &w_all, int b0, int nb, bo
         wa.n_local = p.n_local;
         wa.scale = ix->scale;
         wa.win = w.win;
+        wa.by_xcd = by_xcd;
         // a launch of its own before the single-launch step, and for groups of eight heads (where the window's
         // registers would cost the scoring blocks a wave per SIMD); otherwise its blocks ride in the scoring launch below
         if (one_launch || G > 4) window_attn_kernel<T, G><<<dim3(kWinSplit, U), 256, 0, st>>>(wa);
@@ -977,6 +984,7 @@ int decode_launch_group(ctkvr_index *ix, const StepWs &w_all, int b0, int nb, bo
     ca.g = p.n_kv_heads;
     ca.h = p.n_q_heads;
     ca.c_max = ix->c_max;
+    ca.by_xcd = by_xcd;
     if (whole) ix->mark(0, st);
     centroid_cos_kernel<T, G><<<dim3((ix->c_max + 15) / 16, U), 256, 0, st>>>(ca);
     if (whole) ix->mark(1, st);
@@ -994,6 +1002,7 @@ int decode_launch_group(ctkvr_index *ix, const StepWs &w_all, int b0, int nb, bo
     ga.rho = p.list_len;
     ga.n_probe = p.n_probe;
     ga.bitmap_words = ix->bitmap_words;
+    ga.by_xcd = by_xcd;
     const dim3 rgrid(ix->recall_split, U);
     if (ix->c_max <= 512)
         recall_gather_kernel<2><<<rgrid, 256, ix->recall_lds, st>>>(ga);
@@ -1022,6 +1031,7 @@ int decode_launch_group(ctkvr_index *ix, const StepWs &w_all, int b0, int nb, bo
     sa.m_key = w.m_key;
     sa.ghist = w.ghist;
     sa.scale = ix->scale;
+    sa.by_xcd = by_xcd;
     {
         // Few rows per CU (a small batch): a block's rows are one round trip to memory and the slowest block
         // is the launch, so the ids are split by rank -- two blocks per CU, at least 32 per unit and 64 ranks
@@ -1062,6 +1072,7 @@ int decode_launch_group(ctkvr_index *ix, const StepWs &w_all, int b0, int nb, bo
     da.gbits = w.gbits;
     da.bitmap_words = ix->bitmap_words;
     da.gcur = w.gcur;
+    da.by_xcd = by_xcd;
     const int chunks = (ix->l_stride + 1023) / 1024;
     denom_kernel<G><<<dim3(std::max(1, std::min(chunks, (4 * ix->num_cu + U - 1) / U)), U), 256, 0, st>>>(da);
     if (whole) ix->mark(4, st);
@@ -1085,6 +1096,7 @@ int decode_launch_group(ctkvr_index *ix, const StepWs &w_all, int b0, int nb, bo
         kc.glist = w.glist;
         kc.gcur = w.gcur;
         kc.ginfo = w.ginfo;
+        kc.by_xcd = by_xcd;
         keyclass_kernel<G><<<dim3(std::max(1, std::min((ix->l_stride + 4095) / 4096, (2 * ix->num_cu + U - 1) / U)), U), 1024, 0, st>>>(kc);
         if (whole) ix->mark(5, st);
         if (&w_all == &ix->ws) ix->last_step_fused = true;   // no 2048-bucket histogram is left for a second ranking
@@ -1100,6 +1112,7 @@ int decode_launch_group(ctkvr_index *ix, const StepWs &w_all, int b0, int nb, bo
     ka.kbuf = w.kbuf;
     ka.ghist = w.ghist;
     ka.gcur = w.gcur;
+    ka.by_xcd = by_xcd;
     keyhist_kernel<G><<<dim3(std::max(1, std::min((ix->l_stride + 4095) / 4096, (2 * ix->num_cu + U - 1) / U)), U), 1024, 0, st>>>(ka);
     if (whole) ix->mark(5, st);
     }
@@ -1118,6 +1131,7 @@ int decode_launch_group(ctkvr_index *ix, const StepWs &w_all, int b0, int nb, bo
         ca.glist = w.glist;
         ca.gcur = w.gcur;
         ca.ginfo = w.ginfo;
+        ca.by_xcd = by_xcd;
         classify_kernel<<<dim3(std::max(1, std::min(chunks, (4 * ix->num_cu + U - 1) / U)), U), 256, 0, st>>>(ca);
     }
     if (whole) ix->mark(6, st);

@@ -48,6 +48,24 @@ __device__ __forceinline__ bool decode_unit(const Units &u, int local, int &b, i
     return j < u.n_cent[b];
 }
 
+// Block -> (unit, block of the unit) for grids (blocks per unit, units).  Workgroups go to the 8 XCDs round-robin by
+// linear id, every XCD has an L2 of its own, and what a kernel wrote is still in its XCD's L2 when the next kernel
+// runs (a dependent load of such a line: 87 ns on the XCD that wrote it, 220 ns on another).  With by_xcd (the host
+// sets it when the units are a multiple of 8) the blocks of unit u are those with linear id congruent u modulo the
+// number of units: all on XCD u mod 8, in every kernel of a decode step, so that a unit's intermediate results are read
+// where they were written.
+__device__ __forceinline__ void unit_block_of(const int by_xcd, int &ul, int &bx)
+{
+    if (by_xcd) {
+        const int lin = (int)(blockIdx.y * gridDim.x + blockIdx.x);
+        ul = lin % (int)gridDim.y;
+        bx = lin / (int)gridDim.y;
+    } else {
+        ul = (int)blockIdx.y;
+        bx = (int)blockIdx.x;
+    }
+}
+
 // ------------------------------------------------------------------------------
 // small utilities
 // ------------------------------------------------------------------------------
@@ -109,20 +127,22 @@ struct CosArgs {
     uint32_t *m_key;          // [batch*g][G]  cleared here
     unsigned long long *S;    // [batch*g][G]  cleared here
     int g, h, c_max;
+    int by_xcd;               // blocks -> (unit, block of the unit) by unit_block_of
 };
 
 template <typename T, int G> __global__ __launch_bounds__(256) void centroid_cos_kernel(CosArgs a)
 {
-    const int ul = blockIdx.y;
+    int ul, bx;
+    unit_block_of(a.by_xcd, ul, bx);
     const int b = ul / a.g, kv = ul - b * a.g;
     const int C = a.n_cent[b];
     const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4;
-    if (blockIdx.x == 0 && tid < G) {
+    if (bx == 0 && tid < G) {
         a.m_key[ul * G + tid] = 0u;
         a.S[ul * G + tid] = 0ull;
     }
     CTKVR_STAMP(0);
-    const int tile0 = blockIdx.x * 16;
+    const int tile0 = bx * 16;
     if (tile0 >= C) return;
     const int j = tile0 + grp;
     const int jj = j < C ? j : C - 1;
@@ -171,6 +191,7 @@ struct GatherArgs {
     int32_t *out_probe;       // optional copy for the caller
     uint32_t *gbits;          // [batch*g][bitmap_words], all zero between steps
     int g, c_max, rho, n_probe, bitmap_words;
+    int by_xcd;               // blocks -> (unit, block of the unit) by unit_block_of
 };
 
 template <int KPT> __global__ __launch_bounds__(256) void recall_gather_kernel(GatherArgs a)
@@ -179,7 +200,9 @@ template <int KPT> __global__ __launch_bounds__(256) void recall_gather_kernel(G
     uint32_t *s_sel = smem;
     int32_t *s_probe = (int32_t *)(smem + kSelLds);
     uint32_t *s_bits = smem + kSelLds + a.n_probe;
-    const int ul = blockIdx.y, tid = threadIdx.x, wv = tid >> 6, ln = tid & 63;
+    int ul, bx;
+    unit_block_of(a.by_xcd, ul, bx);
+    const int tid = threadIdx.x, wv = tid >> 6, ln = tid & 63;
     const int b = ul / a.g;
     const int C = a.n_cent[b], s = a.ctx_lens[b];
     const float *cosv = a.cos + (size_t)ul * a.c_max;
@@ -189,7 +212,7 @@ template <int KPT> __global__ __launch_bounds__(256) void recall_gather_kernel(G
     for (int w = tid; w < W; w += 256) s_bits[w] = 0u;
     auto keep = [&](int pos, int j) {
         s_probe[pos] = j;
-        if (blockIdx.x == 0) {
+        if (bx == 0) {
             a.probe[(size_t)ul * a.n_probe + pos] = j;
             if (a.out_probe) a.out_probe[(size_t)ul * a.n_probe + pos] = j;
         }
@@ -210,7 +233,7 @@ template <int KPT> __global__ __launch_bounds__(256) void recall_gather_kernel(G
     // Two lists per round and wave, all of a round's loads requested before the first id is used.
     const int pstride = gridDim.x * 4;
     auto mark = [&](int t) { atomicOr(&s_bits[t >> 5], 1u << (t & 31)); };
-    for (int p = blockIdx.x + gridDim.x * wv; p < a.n_probe; p += 2 * pstride) {
+    for (int p = bx + gridDim.x * wv; p < a.n_probe; p += 2 * pstride) {
         const bool two = p + pstride < a.n_probe;
         const int32_t *l0 = lb + (size_t)s_probe[p] * a.rho;
         const int32_t *l1 = lb + (size_t)s_probe[two ? p + pstride : p] * a.rho;
@@ -378,6 +401,7 @@ struct WindowArgs {
     const int32_t *ctx_lens;  // [batch] s: the prefix the index was built on
     const int32_t *cur_lens;  // optional [batch]: tokens in the cache now (>= s)
     int n_init, n_local;
+    int by_xcd;               // blocks -> (unit, block of the unit) by unit_block_of
     float scale;
     float *win;               // [units][kWinSplit][G][2 + 128]
 };
@@ -515,7 +539,9 @@ template <typename T, int G> __device__ __forceinline__ void window_attn_block(c
 
 template <typename T, int G> __global__ __launch_bounds__(256) void window_attn_kernel(WindowArgs a)
 {
-    window_attn_block<T, G>(a, (int)blockIdx.x, (int)blockIdx.y);
+    int ul, bx;
+    unit_block_of(a.by_xcd, ul, bx);
+    window_attn_block<T, G>(a, bx, ul);
 }
 
 // ------------------------------------------------------------------------------
@@ -556,6 +582,7 @@ struct RecallScoreArgs {
     float scale;
     int stream_k;             // the keys of all sequences exceed what the memory-side cache holds: load them non-temporal
     int by_rank;              // how the bitmap is split over a unit's blocks
+    int by_xcd;               // blocks -> (unit, block of the unit) by unit_block_of
     int nbx;                  // blocks per unit that score; with WIN blocks nbx .. nbx + kWinSplit - 1 take the resident window
     WindowArgs win;
 };
@@ -568,18 +595,20 @@ template <typename T, int G, bool WIN> __global__ __launch_bounds__(256) void re
     __shared__ uint32_t s_tmp[8];
     __shared__ uint32_t s_edge[3];                // first word, ids before it, last word
     __shared__ uint32_t s_max[G];
+    int ul, bx;
+    unit_block_of(a.by_xcd, ul, bx);
     if constexpr (WIN) {
-        if ((int)blockIdx.x >= a.nbx) {   // Algorithm 2 lines 10-11 beside lines 4-5
-            window_attn_block<T, G>(a.win, (int)blockIdx.x - a.nbx, (int)blockIdx.y);
+        if (bx >= a.nbx) {   // Algorithm 2 lines 10-11 beside lines 4-5
+            window_attn_block<T, G>(a.win, bx - a.nbx, ul);
             return;
         }
     }
-    const int ul = blockIdx.y, b = ul / a.u.g, kv = ul - b * a.u.g;
+    const int b = ul / a.u.g, kv = ul - b * a.u.g;
     const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4;
     CTKVR_STAMP_BLK(6);
     const int s_len = a.ctx_lens[b];
     const int W = (s_len + 31) >> 5;
-    for (int w = blockIdx.x * 256 + tid; w < kBuckets; w += (uint32_t)a.nbx * 256) a.ghist[(size_t)ul * kBuckets + w] = 0u;
+    for (int w = bx * 256 + tid; w < kBuckets; w += (uint32_t)a.nbx * 256) a.ghist[(size_t)ul * kBuckets + w] = 0u;
     const uint32_t *gb = a.gbits + (size_t)ul * a.bitmap_words;
     if (tid < G) s_max[tid] = 0u;
     uint32_t r0, r1;   // the block's ranks
@@ -615,12 +644,12 @@ template <typename T, int G, bool WIN> __global__ __launch_bounds__(256) void re
         }
         uint32_t L;
         const uint32_t pre = block_excl_scan<256>(cnt, s_tmp, &L);   // barriers inside
-        if (blockIdx.x == 0 && tid == 0) {
+        if (bx == 0 && tid == 0) {
             a.ncand[ul] = (int32_t)L;
             if (a.out_ncand) a.out_ncand[ul] = (int32_t)L;
         }
         const uint32_t qn = (L + (uint32_t)a.nbx - 1) / (uint32_t)a.nbx;
-        r0 = blockIdx.x * qn;
+        r0 = bx * qn;
         if (r0 >= L) return;
         r1 = min(L, r0 + qn);
         // the threads whose stretches hold ranks r0 and r1 - 1 walk their words to the one that holds it
@@ -680,7 +709,7 @@ template <typename T, int G, bool WIN> __global__ __launch_bounds__(256) void re
         // the unit's own words split evenly over the blocks of its row (a short sequence of a ragged
         // batch still uses all of them)
         const int wpb = min(kRecallWpb, (W + a.nbx - 1) / a.nbx);
-        const int w_beg = blockIdx.x * wpb;
+        const int w_beg = bx * wpb;
         if (w_beg >= W) return;
         uint32_t before = 0;
 #pragma unroll 4
@@ -1227,13 +1256,15 @@ struct DenomArgs {
     unsigned long long *S;
     uint32_t *gbits;          // decode only: the recall bitmap, cleared here for the next step
     int bitmap_words;
+    int by_xcd;               // blocks -> (unit, block of the unit) by unit_block_of
     uint32_t *gcur;           // optional: [units] list cursors of keyclass_kernel, cleared here
 };
 
 template <int G> __global__ __launch_bounds__(256) void denom_kernel(DenomArgs a)
 {
     int b, kv, j;
-    const int ul = blockIdx.y;
+    int ul, bx;
+    unit_block_of(a.by_xcd, ul, bx);
     if (!decode_unit(a.u, ul, b, kv, j)) return;
     // everything the block needs to know is requested at once (the maxima before L decides whether
     // the block has work: one round trip instead of three)
@@ -1242,12 +1273,12 @@ template <int G> __global__ __launch_bounds__(256) void denom_kernel(DenomArgs a
     for (int hh = 0; hh < G; ++hh) mk[hh] = a.m_key[ul * G + hh];
     const int s_len = a.ctx_lens[b];
     const int L = a.ncand ? a.ncand[ul] : s_len;
-    if (a.gcur && blockIdx.x == 0 && threadIdx.x == 0) a.gcur[ul] = 0u;
+    if (a.gcur && bx == 0 && threadIdx.x == 0) a.gcur[ul] = 0u;
     if (a.gbits) {
         const int W = (s_len + 31) >> 5;
-        for (int w = blockIdx.x * 256 + threadIdx.x; w < W; w += gridDim.x * 256) a.gbits[(size_t)ul * a.bitmap_words + w] = 0u;
+        for (int w = bx * 256 + threadIdx.x; w < W; w += gridDim.x * 256) a.gbits[(size_t)ul * a.bitmap_words + w] = 0u;
     }
-    if ((int)blockIdx.x * 1024 >= L) return;
+    if (bx * 1024 >= L) return;
     const int tid = threadIdx.x;
     __shared__ unsigned long long s_acc[4][G];
     float m[G];
@@ -1258,7 +1289,7 @@ template <int G> __global__ __launch_bounds__(256) void denom_kernel(DenomArgs a
         acc[hh] = 0ull;
     }
     const float *zb = a.z + (size_t)ul * a.l_stride * G;
-    for (int c0 = blockIdx.x * 1024; c0 < L; c0 += gridDim.x * 1024) {
+    for (int c0 = bx * 1024; c0 < L; c0 += gridDim.x * 1024) {
         // four terms per head as 32-bit partial sums (hi < 2^17, lo < 2^24 each), then one 64-bit add
         uint32_t shi[G], slo[G];
 #pragma unroll
@@ -1310,12 +1341,14 @@ struct KeyArgs {
     uint32_t *ghist;    // [units][kBuckets], zero on entry
     uint32_t *gcur;     // decode only: [units] list cursors of classify_kernel, cleared here
     int n_init, n_local;   // build only: ids below n_init or from L - n_local on are never listed
+    int by_xcd;              // blocks -> (unit, block of the unit) by unit_block_of
 };
 
 template <int G> __global__ __launch_bounds__(1024) void keyhist_kernel(KeyArgs a)
 {
     int b, kv, j;
-    const int ul = blockIdx.y;
+    int ul, bx;
+    unit_block_of(a.by_xcd, ul, bx);
     if (!decode_unit(a.u, ul, b, kv, j)) return;
     const int tid = threadIdx.x;
     // the unit's statistics are requested together with L, before L decides whether the block has work
@@ -1324,8 +1357,8 @@ template <int G> __global__ __launch_bounds__(1024) void keyhist_kernel(KeyArgs 
     for (int hh = 0; hh < G; ++hh) mk[hh] = a.z ? a.m_key[ul * G + hh] : 0u;
     const unsigned long long S_mine = (a.z && tid < G) ? a.S[ul * G + tid] : 1ull;
     const int L = a.ncand ? a.ncand[ul] : a.ctx_lens[b];
-    if (a.gcur && blockIdx.x == 0 && threadIdx.x == 0) a.gcur[ul] = 0u;
-    if ((int)blockIdx.x * 4096 >= L) return;
+    if (a.gcur && bx == 0 && threadIdx.x == 0) a.gcur[ul] = 0u;
+    if (bx * 4096 >= L) return;
     __shared__ uint32_t s_h[kBuckets];
     __shared__ float s_ls[G];
     for (int w = tid; w < kBuckets; w += 1024) s_h[w] = 0u;
@@ -1357,7 +1390,7 @@ template <int G> __global__ __launch_bounds__(1024) void keyhist_kernel(KeyArgs 
         // four chunks of 4096 keys per trip; when all four lie wholly below L their loads are plain
         // and go out together
         const int stride = gridDim.x * 4096;
-        for (int c0 = blockIdx.x * 4096; c0 < L; c0 += 4 * stride) {
+        for (int c0 = bx * 4096; c0 < L; c0 += 4 * stride) {
             if (wide && c0 + 3 * stride + 4096 <= L) {
                 uint4 v[4];
 #pragma unroll
@@ -1386,7 +1419,7 @@ template <int G> __global__ __launch_bounds__(1024) void keyhist_kernel(KeyArgs 
             }
         }
     }
-    for (int c0 = blockIdx.x * 4096; a.z && c0 < L; c0 += gridDim.x * 4096) {
+    for (int c0 = bx * 4096; a.z && c0 < L; c0 += gridDim.x * 4096) {
         // the four loads first (ids beyond L read entry L-1 and are dropped): see denom_kernel
         float zv[4][G];
 #pragma unroll
@@ -1437,12 +1470,14 @@ struct ClassifyArgs {
     uint2 *glist;            // [units][kListCap] (key, id) of the deciding bucket
     uint32_t *gcur;          // [units] list cursor, zero on entry
     uint32_t *ginfo;         // [units][4] deciding bucket, keys wanted from it, its population, unused
+    int by_xcd;              // blocks -> (unit, block of the unit) by unit_block_of
 };
 
 __global__ __launch_bounds__(256) void classify_kernel(ClassifyArgs a)
 {
     int b, kv, j;
-    const int ul = blockIdx.y;
+    int ul, bx;
+    unit_block_of(a.by_xcd, ul, bx);
     if (!decode_unit(a.u, ul, b, kv, j)) return;
     const int L = a.ncand ? a.ncand[ul] : a.ctx_lens[b];
     if (a.top_k >= L) return;
@@ -1450,7 +1485,7 @@ __global__ __launch_bounds__(256) void classify_kernel(ClassifyArgs a)
     __shared__ uint32_t s_res[3];
     const int tid = threadIdx.x, ln = lane_id();
     const int nw64 = (L + 63) >> 6;
-    const int wg = blockIdx.x * 4 + (tid >> 6), nwg = gridDim.x * 4;
+    const int wg = bx * 4 + (tid >> 6), nwg = gridDim.x * 4;
     const uint32_t *kb = a.kbuf + (size_t)ul * a.l_stride;
     constexpr int UNR = 4;
     // this wave's first groups of keys are requested before the histogram is looked at
@@ -1488,7 +1523,7 @@ __global__ __launch_bounds__(256) void classify_kernel(ClassifyArgs a)
     }
     __syncthreads();
     const uint32_t bkt = s_res[0], nb = s_res[2];
-    if (blockIdx.x == 0 && tid == 0)
+    if (bx == 0 && tid == 0)
         *reinterpret_cast<uint4 *>(a.ginfo + 4 * (size_t)ul) = make_uint4(bkt, s_res[1], nb, 0u);
     if (nb > (uint32_t)kListCap) return;
     uint32_t *bm = a.gbm + (size_t)ul * a.bits_stride;
@@ -1546,12 +1581,14 @@ struct KeyClassArgs {
     uint2 *glist;            // [units][kListCap]
     uint32_t *gcur;          // [units], zero on entry
     uint32_t *ginfo;         // [units][4]
+    int by_xcd;              // blocks -> (unit, block of the unit) by unit_block_of
 };
 
 template <int G> __global__ __launch_bounds__(1024) void keyclass_kernel(KeyClassArgs a)
 {
     int b, kv, j;
-    const int ul = blockIdx.y;
+    int ul, bx;
+    unit_block_of(a.by_xcd, ul, bx);
     if (!decode_unit(a.u, ul, b, kv, j)) return;
     const int tid = threadIdx.x, wv = tid >> 6, ln = lane_id();
     uint32_t mk[G];
@@ -1621,7 +1658,7 @@ template <int G> __global__ __launch_bounds__(1024) void keyclass_kernel(KeyClas
         __syncthreads();
         bkt = s_res[0];
         nb = s_res[2];
-        if (blockIdx.x == 0 && tid == 0) *reinterpret_cast<uint4 *>(a.ginfo + 4 * (size_t)ul) = make_uint4(bkt, s_res[1], nb, 0u);
+        if (bx == 0 && tid == 0) *reinterpret_cast<uint4 *>(a.ginfo + 4 * (size_t)ul) = make_uint4(bkt, s_res[1], nb, 0u);
     }
     const bool classify = rank && nb <= (uint32_t)kListCap;
     // pass 2: this block's share of the ids in groups of 64: keys written, and classified against the deciding bucket
@@ -1630,7 +1667,7 @@ template <int G> __global__ __launch_bounds__(1024) void keyclass_kernel(KeyClas
     uint2 *lst = a.glist + (size_t)ul * kListCap;
     const uint64_t below = (1ull << ln) - 1ull;
     const int nw64 = (L + 63) >> 6;
-    for (int g0 = blockIdx.x * 16 + wv; g0 < nw64; g0 += gridDim.x * 16) {
+    for (int g0 = bx * 16 + wv; g0 < nw64; g0 += gridDim.x * 16) {
         const int i = g0 * 64 + ln;
         const bool valid = i < L;
         float zv[G];

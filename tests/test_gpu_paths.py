@@ -83,6 +83,25 @@ def test_both_ways_of_splitting_the_recalled_ids_over_blocks_match_the_oracle(ck
     _run(ck, case, ck.PATH_STAGED)
 
 
+XCD_CASES = [
+    # (sequence, KV head) units a multiple of 8: 8, 16 (ragged), 8 with a group of one head
+    ("xcd_8_units", "bf16", 32, 8, (9000,), (560,), 128, 0, 16, 256, 256, 3),
+    ("xcd_16_units_ragged", "bf16", 16, 8, (5000, 2100), (561, 562), 0, 100, 6, 120, 90, 3),
+    ("xcd_8_units_g1", "f32", 4, 4, (1500, 3000), (563, 564), 24, 0, 5, 100, 70, 2),
+]
+
+
+@pytest.mark.parametrize("one_xcd", [0, 1])
+@pytest.mark.parametrize("case", XCD_CASES, ids=[c[0] for c in XCD_CASES])
+def test_units_spread_over_the_xcds_or_each_on_one_match_the_oracle(ck, case, one_xcd, monkeypatch):
+    """With a multiple of 8 units the blocks of a unit can be given linear ids that all land on one XCD, in every
+    kernel of a step (chosen for small batches); here both mappings are forced in turn (read when the index is
+    created).  (The same with the resident window's blocks in the scoring launch: tests/test_gpu_window.py.)"""
+    monkeypatch.setenv("CTKVR_XCD_UNITS", str(one_xcd))
+    print(f"[paths {case[0]}] units {'each on one XCD' if one_xcd else 'spread'}", flush=True)
+    _run(ck, case, ck.PATH_STAGED)
+
+
 @pytest.mark.parametrize("merged", [0, 1])
 @pytest.mark.parametrize("case", SPLIT_CASES, ids=[c[0] for c in SPLIT_CASES])
 def test_key_histogram_and_classification_as_one_launch_or_two_match_the_oracle(ck, case, merged, monkeypatch):

@@ -64,6 +64,21 @@ def _setup(ck, case):
     return wl, bt, db, Qc, lists
 
 
+XCD_CASES = [
+    ("units_8", "bf16", 32, 8, (1500,), 24, 4, 96, 64, 8, 100, 5, 3),
+    ("units_16_ragged", "bf16", 16, 8, (900, 1700), 16, 4, 80, 60, 4, 64, 3, 3),
+]
+
+
+@pytest.mark.parametrize("one_xcd", [0, 1])
+@pytest.mark.parametrize("case", XCD_CASES, ids=[c[0] for c in XCD_CASES])
+def test_window_with_units_spread_over_the_xcds_or_each_on_one(ck, case, one_xcd, monkeypatch):
+    """A multiple of 8 (sequence, KV head) units: both block-to-unit mappings forced in turn, the window's blocks
+    riding in the scoring launch."""
+    monkeypatch.setenv("CTKVR_XCD_UNITS", str(one_xcd))
+    test_window_build_and_decode_match_the_oracle(ck, case)
+
+
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
 def test_window_build_and_decode_match_the_oracle(ck, case):
     import torch
