@@ -50,7 +50,7 @@ __device__ __forceinline__ bool decode_unit(const Units &u, int local, int &b, i
 
 // Block -> (unit, block of the unit) for grids (blocks per unit, units).  Workgroups go to the 8 XCDs round-robin by
 // linear id, every XCD has an L2 of its own, and what a kernel wrote is still in its XCD's L2 when the next kernel
-// runs (a dependent load of such a line: 87 ns on the XCD that wrote it, 220 ns on another).  With by_xcd (the host
+// runs (a dependent load of such a line: 88 ns on the XCD that wrote it, 220 ns on another).  With by_xcd (the host
 // sets it when the units are a multiple of 8) the blocks of unit u are those with linear id congruent u modulo the
 // number of units: all on XCD u mod 8, in every kernel of a decode step, so that a unit's intermediate results are read
 // where they were written.
