@@ -248,7 +248,8 @@ int ctkvr_profile_collect(ctkvr_index *idx, float *ms_host, int32_t capacity_ste
  *   CTKVR_DECODE_PATH        = staged | fused | auto   default of ctkvr_index_set_decode_path
  *   CTKVR_DECODE_GROUPS      = n   sequences stepped as n forked groups (default 1)
  *   CTKVR_XCD_UNITS          = 0|1 the blocks of a (sequence, KV head) unit spread over the XCDs / all on one XCD in
- *                                  every kernel of a step (needs a multiple of 8 units; default: one XCD for small batches)
+ *                                  every kernel of a step (needs a multiple of 8 units; default: one XCD, except, for
+ *                                  large batches, in the two bandwidth-bound launches)
  *   CTKVR_SCORE_BY_RANK      = 0|1 recalled ids split over a unit's blocks by id range / by rank
  *                                  (default: by rank for small batches)
  *   CTKVR_KEYCLASS           = 0|1 ranking-key histogram and classification as two launches / one

@@ -879,9 +879,12 @@ int decode_launch_group(ctkvr_index *ix, const StepWs &w_all, int b0, int nb, bo
     }
     Units units = decode_units(ix);
     units.n_cent = d_n_cent;
-    // Small batches (latency-bound: a step is a chain of dependent loads of what the previous kernel wrote) keep each unit on
-    // one XCD; large ones lose more in the scoring kernel, whose blocks then cannot be handed to whichever XCD is free.
-    const int by_xcd = U % 8 == 0 && (ix->xcd_units < 0 ? (long long)ix->l_stride * U <= 2048ll * ix->num_cu : ix->xcd_units != 0);
+    // A unit's blocks on one XCD (unit_block_of; needs a multiple of 8 units): in every kernel for small batches
+    // (latency-bound: a step is a chain of dependent loads of what the previous kernel wrote); for large ones in all but
+    // the two bandwidth-bound launches -- the cosines, and the scoring, whose blocks are better handed to whichever XCD is free.
+    const bool xcd_small = ix->xcd_units < 0 ? (long long)ix->l_stride * U <= 2048ll * ix->num_cu : ix->xcd_units != 0;
+    const int by_xcd = U % 8 == 0 && ix->xcd_units != 0;
+    const int by_xcd_all = by_xcd && xcd_small;
     // lines 10-11 first: the window's share depends on q, K and V only
     const bool window = p.n_init + p.n_local > 0 || cur_lens;
     WindowArgs wa{};
@@ -984,7 +987,7 @@ int decode_launch_group(ctkvr_index *ix, const StepWs &w_all, int b0, int nb, bo
     ca.g = p.n_kv_heads;
     ca.h = p.n_q_heads;
     ca.c_max = ix->c_max;
-    ca.by_xcd = by_xcd;
+    ca.by_xcd = by_xcd_all;
     if (whole) ix->mark(0, st);
     centroid_cos_kernel<T, G><<<dim3((ix->c_max + 15) / 16, U), 256, 0, st>>>(ca);
     if (whole) ix->mark(1, st);
@@ -1031,7 +1034,7 @@ int decode_launch_group(ctkvr_index *ix, const StepWs &w_all, int b0, int nb, bo
     sa.m_key = w.m_key;
     sa.ghist = w.ghist;
     sa.scale = ix->scale;
-    sa.by_xcd = by_xcd;
+    sa.by_xcd = by_xcd_all;
     {
         // Few rows per CU (a small batch): a block's rows are one round trip to memory and the slowest block
         // is the launch, so the ids are split by rank -- two blocks per CU, at least 32 per unit and 64 ranks
